@@ -1,0 +1,132 @@
+"""ctypes access to the CPU oracle (oracle/ff_oracle.cpp).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the bench's
+cpu_baseline leg.  The product package never imports this module.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ff_oracle.cpp")
+_LIB = os.path.join(_HERE, "libff_oracle.so")
+INVALID = 2 ** 64 - 1
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """compile the oracle with g++ (plain -O2, no vector tricks)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-pthread",
+                               "-Wall", "-o", _LIB, _SRC])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
+        L.ffo_build.restype = vp
+        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp]
+        L.ffo_from_arrays.restype = vp
+        L.ffo_from_arrays.argtypes = [u32, vp, vp, u32, u32, vp, vp]
+        L.ffo_counts.restype = None
+        L.ffo_counts.argtypes = [vp, u32p, u32p, u32p, u32p]
+        L.ffo_export.restype = None
+        L.ffo_export.argtypes = [vp, vp, vp, vp, vp]
+        L.ffo_simulate.restype = C.c_uint64
+        L.ffo_simulate.argtypes = [vp, vp, vp, vp]
+        L.ffo_free.restype = None
+        L.ffo_free.argtypes = [vp]
+        L.ffo_batch.restype = None
+        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, u32, vp, u32]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _machine(m):
+    return np.array(m.as_tuple() if hasattr(m, "as_tuple") else tuple(m), dtype="<u4")
+
+
+class TaskGraph:
+    """a built task graph: exe[t], dev[t], deps (src, dst); the first n_compute tasks are
+    compute tasks in (op, part) order, the rest communication tasks in creation order."""
+
+    def __init__(self, handle):
+        self._h = handle
+        nt, nc, nd, nr = C.c_uint32(), C.c_uint32(), C.c_uint32(), C.c_uint32()
+        lib().ffo_counts(handle, C.byref(nt), C.byref(nc), C.byref(nd), C.byref(nr))
+        self.n_tasks, self.n_compute, self.n_deps, self.n_rows = nt.value, nc.value, nd.value, nr.value
+        self.exe = np.zeros(self.n_tasks, "<u8")
+        self.dev = np.zeros(self.n_tasks, "<u4")
+        self.dep_src = np.zeros(self.n_deps, "<u4")
+        self.dep_dst = np.zeros(self.n_deps, "<u4")
+        lib().ffo_export(handle, _ptr(self.exe), _ptr(self.dev), _ptr(self.dep_src), _ptr(self.dep_dst))
+
+    def simulate(self):
+        """Algorithm 1 -> (makespan, ready[], start[], end[])."""
+        r = np.zeros(self.n_tasks, "<u8")
+        s = np.zeros(self.n_tasks, "<u8")
+        e = np.zeros(self.n_tasks, "<u8")
+        mk = lib().ffo_simulate(self._h, _ptr(r), _ptr(s), _ptr(e))
+        return int(mk), r, s, e
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().ffo_free(self._h)
+            self._h = None
+
+
+def build_task_graph(ops, edges, machine, cost, cfg):
+    """Section 5.1 for one strategy (cfg: [n_ops] configs). None if the strategy is invalid."""
+    ops, edges, cost, cfg = map(np.ascontiguousarray, (ops, edges, cost, cfg))
+    m = _machine(machine)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), _ptr(cost),
+                        cost.shape[1], _ptr(cfg))
+    return TaskGraph(h) if h else None
+
+
+def task_graph_from_arrays(exe, dev, n_rows, dep_src, dep_dst):
+    exe = np.ascontiguousarray(exe, "<u8")
+    dev = np.ascontiguousarray(dev, "<u4")
+    ds = np.ascontiguousarray(dep_src, "<u4")
+    dd = np.ascontiguousarray(dep_dst, "<u4")
+    return TaskGraph(lib().ffo_from_arrays(len(exe), _ptr(exe), _ptr(dev), n_rows, len(ds), _ptr(ds), _ptr(dd)))
+
+
+def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1):
+    """makespan (ns) of every strategy in cfgs [B][n_ops]; 2^64-1 for an invalid one."""
+    ops, edges, cost, cfgs = map(np.ascontiguousarray, (ops, edges, cost, cfgs))
+    assert cfgs.ndim == 2 and cfgs.shape[1] == len(ops)
+    m = _machine(machine)
+    out = np.zeros(cfgs.shape[0], "<u8")
+    lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), _ptr(cost), cost.shape[1],
+                    _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads)
+    return out
+
+
+def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None):
+    """oracle for delta simulation: apply the single-op mutations cumulatively and fully
+    re-simulate (the definition of the delta result, Section 5.3).  mutations: [n_steps]
+    records (op, cfg).  `steps` selects which steps (0-based) to evaluate; returns their
+    makespans in order."""
+    cur = np.array(cfg0, copy=True)
+    want = set(range(len(mutations))) if steps is None else set(int(s) for s in steps)
+    last = max(want) if want else -1
+    snaps = []
+    for s in range(last + 1):
+        cur[int(mutations[s]["op"])] = mutations[s]["cfg"]
+        if s in want:
+            snaps.append(cur.copy())
+    if not snaps:
+        return np.zeros(0, "<u8")
+    return simulate_batch(ops, edges, machine, cost, np.stack(snaps))

@@ -1,0 +1,257 @@
+// CPU oracle for the execution simulator of "Beyond Data and Model Parallelism for Deep
+// Neural Networks" (FlexFlow), Section 5.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the GPU library is
+// checked against.  Only tests, the smoke check and the bench's cpu_baseline leg may call
+// it; it shares no code, header or table with the GPU path.
+//
+// What it computes
+//   build   : the task graph of Section 5.1 -- step 1 (one compute task per part of every
+//             op's configuration, Section 4) and step 2 (for every tensor edge, every
+//             producer-part / consumer-part pair that shares a sub-tensor: a dependency
+//             if both parts sit on the same device, otherwise a communication task on the
+//             link device between them, assumption A2 for its time).
+//   simulate: Algorithm 1 (full simulation) literally, with a binary-heap priority queue
+//             ordered by (readyTime, task id).
+// Delta simulation (Algorithm 2) is defined by the paper to produce the same timeline as a
+// full simulation of the changed strategy (Section 5.3), so the oracle for it is: change the
+// strategy, build, simulate.
+//
+// Readings where the paper is silent (all listed in the design notes of this repo):
+//   task id = construction order: compute tasks (op order, part index row-major with dim 0
+//   slowest), then communication tasks in (edge, producer part, consumer part) order;
+//   times are unsigned 64-bit integer ns; part p of a dim of extent E split deg ways covers
+//   [floor(p*E/deg), floor((p+1)*E/deg)); device of part k = (offset + k*stride) mod D;
+//   link device rows: D + node*G*G + ls*G + lt inside a node (one per ordered GPU pair),
+//   D + N*G*G + a*N + b between nodes a != b (one per ordered node pair);
+//   transfer time = ceil(bytes / bandwidth) + latency.
+//
+// Pins: tests/test_oracle_*.py (closed forms, bounds, brute force over task orders, a
+// timeline verifier, hand-computed cases under tests/golden/).
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <queue>
+#include <thread>
+#include <utility>
+#include <vector>
+
+namespace {
+
+struct DimMap { int8_t src_dim; uint8_t pad; uint16_t stride; int32_t a, b; };
+struct Op { uint8_t ndim; uint8_t par_mask; uint16_t type; uint32_t extent[4]; };
+struct Edge { uint32_t src_op, dst_op; DimMap map[4]; };
+struct Cfg { uint8_t deg[4]; uint16_t dev_offset; uint16_t dev_stride; };
+struct Machine { uint32_t n_nodes, gpus_per_node, intra_Bpns, inter_Bpns, intra_lat_ns, inter_lat_ns, elem_bytes; };
+static_assert(sizeof(DimMap) == 12 && sizeof(Op) == 20 && sizeof(Edge) == 56 && sizeof(Cfg) == 8, "layout");
+
+constexpr uint64_t INVALID = ~0ull;
+constexpr uint32_t MAX_PARTS = 64;
+
+struct TaskGraph {
+    std::vector<uint64_t> exe;               // exeTime
+    std::vector<uint32_t> dev;               // device row (compute device or link device)
+    std::vector<std::vector<uint32_t>> out;  // O(t)
+    std::vector<uint32_t> n_in;              // |I(t)|
+    uint32_t n_compute = 0;
+    uint32_t n_rows = 0;                     // number of device rows
+    void add_dep(uint32_t a, uint32_t b) { out[a].push_back(b); n_in[b]++; }
+    uint32_t add_task(uint64_t e, uint32_t d) {
+        exe.push_back(e); dev.push_back(d); out.emplace_back(); n_in.push_back(0);
+        return (uint32_t)exe.size() - 1;
+    }
+};
+
+struct Box { int64_t lo[4], hi[4]; };
+
+// Section 4: |c_i| = product of degrees; equal-size partitions (balanced floor split).
+uint32_t parts_of(const Cfg& c) { return (uint32_t)c.deg[0] * c.deg[1] * c.deg[2] * c.deg[3]; }
+
+bool cfg_valid(const Op& op, const Cfg& c, uint32_t n_dev, uint32_t max_parts) {
+    for (int d = 0; d < 4; d++) {
+        if (c.deg[d] < 1) return false;
+        if (d >= op.ndim || !((op.par_mask >> d) & 1)) { if (c.deg[d] != 1) return false; }
+        else if (c.deg[d] > op.extent[d]) return false;
+    }
+    if (parts_of(c) > max_parts) return false;
+    return c.dev_offset < n_dev;
+}
+
+// output box of part k (row-major over the degree tuple, dim 0 slowest)
+Box part_box(const Op& op, const Cfg& c, uint32_t k) {
+    Box b;
+    uint32_t idx[4], rem = k;
+    for (int d = 3; d >= 0; d--) { idx[d] = rem % c.deg[d]; rem /= c.deg[d]; }
+    for (int d = 0; d < 4; d++) {
+        int64_t E = d < op.ndim ? op.extent[d] : 1;
+        b.lo[d] = (int64_t)idx[d] * E / c.deg[d];
+        b.hi[d] = (int64_t)(idx[d] + 1) * E / c.deg[d];
+    }
+    return b;
+}
+
+// elements of the producer's tensor that consumer box `cb` reads and producer box `pb` holds
+uint64_t shared_elems(const Op& prod, const Edge& e, const Box& pb, const Box& cb) {
+    uint64_t elems = 1;
+    for (int d = 0; d < prod.ndim; d++) {
+        const DimMap& m = e.map[d];
+        int64_t need_lo = 0, need_hi = prod.extent[d];
+        if (m.src_dim >= 0) {
+            need_lo = cb.lo[m.src_dim] * (int64_t)m.stride + m.a;
+            need_hi = (cb.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;
+            need_lo = std::max<int64_t>(need_lo, 0);
+            need_hi = std::min<int64_t>(need_hi, prod.extent[d]);
+        }
+        int64_t lo = std::max(need_lo, pb.lo[d]), hi = std::min(need_hi, pb.hi[d]);
+        if (hi <= lo) return 0;
+        elems *= (uint64_t)(hi - lo);
+    }
+    return elems;
+}
+
+// Section 5.1: "the communication device between the devices"
+uint32_t link_row(const Machine& m, uint32_t from, uint32_t to) {
+    uint32_t G = m.gpus_per_node, N = m.n_nodes, D = N * G;
+    uint32_t na = from / G, nb = to / G;
+    if (na == nb) return D + na * G * G + (from % G) * G + (to % G);
+    return D + N * G * G + na * N + nb;
+}
+
+bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, const Machine& m,
+           const uint32_t* cost, uint32_t n_cols, const Cfg* cfg, TaskGraph& tg) {
+    const uint32_t G = m.gpus_per_node, N = m.n_nodes, D = N * G;
+    const uint32_t max_parts = std::min(MAX_PARTS, n_cols);
+    tg.n_rows = D + N * G * G + N * N;
+    std::vector<uint32_t> first(n_ops), np(n_ops);
+    // step 1: compute tasks t_{i:1..|c_i|}
+    for (uint32_t i = 0; i < n_ops; i++) {
+        if (!cfg_valid(ops[i], cfg[i], D, max_parts)) return false;
+        np[i] = parts_of(cfg[i]);
+        first[i] = (uint32_t)tg.exe.size();
+        for (uint32_t k = 0; k < np[i]; k++)
+            tg.add_task(cost[(size_t)i * n_cols + (np[i] - 1)],
+                        (uint32_t)((cfg[i].dev_offset + (uint64_t)k * cfg[i].dev_stride) % D));
+    }
+    tg.n_compute = (uint32_t)tg.exe.size();
+    // step 2: per tensor edge, per pair of tasks with a shared sub-tensor
+    for (uint32_t e = 0; e < n_edges; e++) {
+        uint32_t i = edges[e].src_op, j = edges[e].dst_op;
+        for (uint32_t kp = 0; kp < np[i]; kp++) {
+            Box pb = part_box(ops[i], cfg[i], kp);
+            for (uint32_t kc = 0; kc < np[j]; kc++) {
+                Box cb = part_box(ops[j], cfg[j], kc);
+                uint64_t elems = shared_elems(ops[i], edges[e], pb, cb);
+                if (!elems) continue;
+                uint32_t tp = first[i] + kp, tc = first[j] + kc;
+                if (tg.dev[tp] == tg.dev[tc]) { tg.add_dep(tp, tc); continue; }
+                bool same_node = tg.dev[tp] / G == tg.dev[tc] / G;
+                uint64_t bw = same_node ? m.intra_Bpns : m.inter_Bpns;
+                uint64_t lat = same_node ? m.intra_lat_ns : m.inter_lat_ns;
+                uint64_t bytes = elems * m.elem_bytes;
+                uint32_t c = tg.add_task((bytes + bw - 1) / bw + lat, link_row(m, tg.dev[tp], tg.dev[tc]));
+                tg.add_dep(tp, c);
+                tg.add_dep(c, tc);
+            }
+        }
+    }
+    return true;
+}
+
+// Algorithm 1.  ready/start/end may be null.
+uint64_t simulate(const TaskGraph& tg, uint64_t* ready_o, uint64_t* start_o, uint64_t* end_o) {
+    const size_t n = tg.exe.size();
+    std::vector<uint64_t> ready(n, 0), start(n, 0), end(n, 0), last_end(tg.n_rows, 0);
+    std::vector<uint32_t> waiting(tg.n_in);   // predecessors not yet COMPLETE
+    typedef std::pair<uint64_t, uint32_t> Key;  // (readyTime, id)
+    std::priority_queue<Key, std::vector<Key>, std::greater<Key>> ready_queue;
+    for (uint32_t t = 0; t < n; t++)
+        if (tg.n_in[t] == 0) ready_queue.push(Key(0, t));
+    uint64_t makespan = 0;
+    while (!ready_queue.empty()) {
+        uint32_t t = ready_queue.top().second;
+        ready_queue.pop();
+        uint32_t d = tg.dev[t];
+        start[t] = std::max(ready[t], last_end[d]);
+        end[t] = start[t] + tg.exe[t];
+        last_end[d] = end[t];
+        makespan = std::max(makespan, end[t]);
+        for (uint32_t s : tg.out[t]) {
+            ready[s] = std::max(ready[s], end[t]);
+            if (--waiting[s] == 0) ready_queue.push(Key(ready[s], s));
+        }
+    }
+    if (ready_o) std::memcpy(ready_o, ready.data(), n * 8);
+    if (start_o) std::memcpy(start_o, start.data(), n * 8);
+    if (end_o) std::memcpy(end_o, end.data(), n * 8);
+    return makespan;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Build the task graph of one strategy.  Returns an opaque handle or null if the strategy
+// is invalid.
+void* ffo_build(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
+                const uint32_t* cost, uint32_t n_cols, const void* cfg) {
+    TaskGraph* tg = new TaskGraph;
+    if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cost, n_cols,
+               (const Cfg*)cfg, *tg)) { delete tg; return nullptr; }
+    return tg;
+}
+
+// A task graph given directly (for pins on hand-made graphs): deps are (src, dst) pairs.
+void* ffo_from_arrays(uint32_t n_tasks, const uint64_t* exe, const uint32_t* dev, uint32_t n_rows,
+                      uint32_t n_deps, const uint32_t* dep_src, const uint32_t* dep_dst) {
+    TaskGraph* tg = new TaskGraph;
+    for (uint32_t t = 0; t < n_tasks; t++) tg->add_task(exe[t], dev[t]);
+    tg->n_compute = n_tasks;
+    tg->n_rows = n_rows;
+    for (uint32_t k = 0; k < n_deps; k++) tg->add_dep(dep_src[k], dep_dst[k]);
+    return tg;
+}
+
+void ffo_counts(const void* h, uint32_t* n_tasks, uint32_t* n_compute, uint32_t* n_deps, uint32_t* n_rows) {
+    const TaskGraph* tg = (const TaskGraph*)h;
+    uint32_t nd = 0;
+    for (auto& o : tg->out) nd += (uint32_t)o.size();
+    *n_tasks = (uint32_t)tg->exe.size(); *n_compute = tg->n_compute; *n_deps = nd; *n_rows = tg->n_rows;
+}
+
+void ffo_export(const void* h, uint64_t* exe, uint32_t* dev, uint32_t* dep_src, uint32_t* dep_dst) {
+    const TaskGraph* tg = (const TaskGraph*)h;
+    size_t k = 0;
+    for (size_t t = 0; t < tg->exe.size(); t++) {
+        exe[t] = tg->exe[t]; dev[t] = tg->dev[t];
+        for (uint32_t s : tg->out[t]) { dep_src[k] = (uint32_t)t; dep_dst[k] = s; k++; }
+    }
+}
+
+uint64_t ffo_simulate(const void* h, uint64_t* ready, uint64_t* start, uint64_t* end) {
+    return simulate(*(const TaskGraph*)h, ready, start, end);
+}
+
+void ffo_free(void* h) { delete (TaskGraph*)h; }
+
+// build + simulate for B strategies ([B][n_ops] configs); invalid strategy -> all-ones.
+// n_threads > 1 splits the candidates statically over threads (one independent oracle run each).
+void ffo_batch(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
+               const uint32_t* cost, uint32_t n_cols, const void* cfgs, uint32_t B, uint64_t* out_ns,
+               uint32_t n_threads) {
+    auto work = [&](uint32_t b0, uint32_t b1) {
+        for (uint32_t b = b0; b < b1; b++) {
+            TaskGraph tg;
+            bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cost,
+                            n_cols, (const Cfg*)cfgs + (size_t)b * n_ops, tg);
+            out_ns[b] = ok ? simulate(tg, nullptr, nullptr, nullptr) : INVALID;
+        }
+    };
+    if (n_threads <= 1) { work(0, B); return; }
+    std::vector<std::thread> th;
+    for (uint32_t t = 0; t < n_threads; t++)
+        th.emplace_back(work, (uint32_t)((uint64_t)B * t / n_threads), (uint32_t)((uint64_t)B * (t + 1) / n_threads));
+    for (auto& t : th) t.join();
+}
+
+}  // extern "C"
