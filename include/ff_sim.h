@@ -1,0 +1,174 @@
+/* ff_sim.h -- C boundary of the batched execution simulator for gfx950 (MI355X).
+ *
+ * The library predicts the per-iteration execution time of an operator graph G on a
+ * simulated device topology D under a parallelization strategy S (FlexFlow, Section 5:
+ * "takes G, D and S as inputs and predicts the execution time").  It does so for many
+ * candidate strategies at once, one candidate per wavefront.
+ *
+ * All times are unsigned 64-bit integer nanoseconds.  Results are bit-exact: the value
+ * returned for a strategy is the makespan of Algorithm 1 (full simulation) run on the task
+ * graph of Section 5.1, with tasks leaving the queue in (readyTime, task id) order, where
+ * task ids follow construction order: compute tasks by (op, part index), then
+ * communication tasks by (tensor edge, producer part, consumer part).
+ *
+ * Pointers named d_* are DEVICE pointers (e.g. a torch tensor's data_ptr()); all other
+ * pointers are HOST pointers.  The caller owns every buffer it passes.  Device buffers
+ * must stay valid until the work queued on the stream has finished.  Handles are not
+ * thread-safe; distinct handles are independent.  No function throws or aborts; every
+ * int-returning function returns FF_OK (0) or a negative FF_E* code.
+ */
+#ifndef FF_SIM_H
+#define FF_SIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    FF_OK = 0,
+    FF_EINVAL = -1,     /* malformed argument (null pointer, unsorted edges, bad field) */
+    FF_ENOMEM = -2,     /* host or device allocation failed */
+    FF_EWORKSPACE = -3, /* no workspace set, or too small for this call */
+    FF_ERANGE = -4,     /* a documented size limit is exceeded */
+    FF_EHIP = -5        /* a HIP runtime call failed */
+};
+
+#define FF_MAX_DIMS 4
+#define FF_MAX_PARTS 64          /* largest |c_i|: one wavefront lane per part */
+#define FF_MAX_OPS 4096
+#define FF_MAX_EXTENT (1u << 20)
+#define FF_MAX_DEVICES 1024
+#define FF_INVALID_NS UINT64_MAX /* result for a candidate whose strategy is invalid */
+
+/* How a consumer part's output range along one dim selects the range it reads along one
+ * PRODUCER dim ("given the output tensor of a task and its operation type, we can infer
+ * the necessary input tensors", Section 4).  src_dim = consumer output dim driving this
+ * producer dim, or -1 if every consumer part reads the producer's whole extent.  For a
+ * consumer part covering [lo, hi) along src_dim the range read is
+ * [lo*stride + a, (hi-1)*stride + b + 1), clamped to [0, extent).  stride >= 1. */
+typedef struct {
+    int8_t src_dim;
+    uint8_t reserved;
+    uint16_t stride;
+    int32_t a, b;
+} ff_dimmap_t;
+
+/* One operation o_i of the operator graph (Section 3.1): the shape of its single output
+ * tensor and which output dims may be partitioned (Table 1; bit d of par_mask). */
+typedef struct {
+    uint8_t ndim; /* 1..4 */
+    uint8_t par_mask;
+    uint16_t type; /* informational */
+    uint32_t extent[FF_MAX_DIMS]; /* 1..FF_MAX_EXTENT for d < ndim; ignored beyond */
+} ff_op_t;
+
+/* One tensor edge (o_src, o_dst); map[] is indexed by the PRODUCER (src) dim. */
+typedef struct {
+    uint32_t src_op, dst_op;
+    ff_dimmap_t map[FF_MAX_DIMS];
+} ff_edge_t;
+
+/* Operator graph.  Ops must be in topological order (src_op < dst_op for every edge) and
+ * edges sorted by (src_op, dst_op); the position in `edges` is the edge id used in
+ * communication-task ids.  n_ops <= FF_MAX_OPS. */
+typedef struct {
+    uint32_t n_ops, n_edges;
+    const ff_op_t* ops;
+    const ff_edge_t* edges;
+} ff_opgraph_t;
+
+/* Simulated machine (device topology, Section 3.1): n_nodes x gpus_per_node compute
+ * devices, device id = node*gpus_per_node + local.  Every ordered GPU pair inside a node
+ * has its own link (intra_* bandwidth in bytes/ns and latency); every ordered node pair
+ * has one network link shared by all its GPU pairs (inter_*).  Transfer time of s bytes =
+ * ceil(s / bandwidth) + latency (assumption A2 plus the edge latency label). */
+typedef struct {
+    uint32_t n_nodes, gpus_per_node;
+    uint32_t intra_Bpns, inter_Bpns;
+    uint32_t intra_lat_ns, inter_lat_ns;
+    uint32_t elem_bytes;
+} ff_machine_t;
+
+/* exeTime of a compute task (Section 5.1: measured once per op type and output size, then
+ * cached -- here handed in): ns[op*n_cols + (parts-1)] for an op split into `parts` tasks.
+ * Every entry must be >= 1.  Configurations with more than n_cols parts are invalid. */
+typedef struct {
+    uint32_t n_ops, n_cols;
+    const uint32_t* ns;
+} ff_costtable_t;
+
+/* Parallelization configuration c_i of one op (Section 4): a degree per output dim
+ * (1 on dims that are not parallelizable or beyond ndim; deg[d] <= extent[d]; product
+ * <= min(FF_MAX_PARTS, n_cols)); part k (row-major over deg, dim 0 slowest) covers
+ * [floor(p*E/deg), floor((p+1)*E/deg)) in each dim and runs on device
+ * (dev_offset + k*dev_stride) mod n_devices, dev_offset < n_devices. */
+typedef struct {
+    uint8_t deg[FF_MAX_DIMS];
+    uint16_t dev_offset;
+    uint16_t dev_stride;
+} ff_opcfg_t;
+
+/* A proposal of the search (Section 6.2): op's configuration is replaced by cfg. */
+typedef struct {
+    uint32_t op;
+    ff_opcfg_t cfg;
+} ff_mutation_t;
+
+/* Per-candidate counters written by ff_sim_batch when a stats buffer is set. */
+typedef struct {
+    uint64_t n_compute;   /* compute tasks = sum of |c_i| */
+    uint64_t n_pairs;     /* producer/consumer task pairs with a shared sub-tensor */
+    uint64_t n_comm;      /* of those, pairs on different devices (communication tasks) */
+    uint64_t sum_comm_ns; /* sum of communication-task exeTimes */
+    uint64_t n_events;    /* queue pops of the event loop */
+    uint64_t exit_code;   /* 0 = event loop ran to completion (anything else is a library bug) */
+    uint64_t n_stuck;     /* compute tasks that never ran (0 in a correct run) */
+    uint64_t reserved;
+} ff_stats_t;
+
+typedef struct ff_sim ff_sim_t;
+typedef struct ff_chains ff_chains_t;
+
+/* Validates and deep-copies graph, machine and cost table (HOST pointers; may be freed on
+ * return) and uploads them to the current HIP device.  Section 5, inputs G and D. */
+int ff_sim_create(const ff_opgraph_t* graph, const ff_machine_t* machine, const ff_costtable_t* cost,
+                  ff_sim_t** out);
+void ff_sim_destroy(ff_sim_t* sim);
+
+/* Scratch for a batch of B candidates (per-task queue keys and readyTime / pending-input
+ * counters of the resident candidates).  The workspace is caller-allocated device memory,
+ * 256-byte aligned, and may be shared by successive calls on the same stream. */
+size_t ff_sim_workspace_bytes(const ff_sim_t* sim, uint32_t B);
+int ff_sim_set_workspace(ff_sim_t* sim, void* d_ws, size_t bytes);
+
+/* Optional: d_stats[B] receives counters on every later ff_sim_batch (null to stop). */
+int ff_sim_set_stats(ff_sim_t* sim, ff_stats_t* d_stats);
+
+/* Section 5.1 + Algorithm 1 for B strategies: d_strategies is [B][n_ops] configurations,
+ * d_out_ns[b] receives the simulated execution time of candidate b, or FF_INVALID_NS if
+ * its strategy is invalid.  Asynchronous on hip_stream (a hipStream_t, null = default). */
+int ff_sim_batch(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns,
+                 void* hip_stream);
+
+/* Delta simulation (Section 5.3, Algorithm 2's contract: same timeline as a full simulation
+ * of the changed strategy).  A chain set holds C current strategies on the device;
+ * d_out_ns0[c] receives the time of the starting strategies.  The library owns the
+ * chains' state. */
+int ff_sim_chains_create(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t C, uint64_t* d_out_ns0,
+                         void* hip_stream, ff_chains_t** out);
+/* Applies d_muts[s][c] (step-major, [n_steps][C]) to chain c for s = 0..n_steps-1,
+ * cumulatively, and writes the simulated time after every step to d_out_ns[s][c]
+ * (FF_INVALID_NS while the chain's strategy is invalid). */
+int ff_sim_delta(ff_chains_t* chains, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out_ns,
+                 void* hip_stream);
+void ff_sim_chains_destroy(ff_chains_t* chains);
+
+const char* ff_sim_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FF_SIM_H */

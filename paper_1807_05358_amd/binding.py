@@ -1,0 +1,250 @@
+"""Thin ctypes binding of the C boundary in include/ff_sim.h (same names, argument
+marshalling only).  torch is used for device memory and streams, nothing else.  There is
+no CPU fallback: if libffsim.so is missing the import of the library fails loudly."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import workloads as W
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libffsim.so")
+
+FF_OK, FF_EINVAL, FF_ENOMEM, FF_EWORKSPACE, FF_ERANGE, FF_EHIP = 0, -1, -2, -3, -4, -5
+FF_INVALID_NS = 2 ** 64 - 1
+STATS_DT = np.dtype([("n_compute", "<u8"), ("n_pairs", "<u8"), ("n_comm", "<u8"), ("sum_comm_ns", "<u8"),
+                     ("n_events", "<u8"), ("exit_code", "<u8"), ("n_stuck", "<u8"), ("reserved", "<u8")])
+
+
+class ff_opgraph_t(C.Structure):
+    _fields_ = [("n_ops", C.c_uint32), ("n_edges", C.c_uint32), ("ops", C.c_void_p), ("edges", C.c_void_p)]
+
+
+class ff_machine_t(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_nodes", "gpus_per_node", "intra_Bpns", "inter_Bpns",
+                                          "intra_lat_ns", "inter_lat_ns", "elem_bytes")]
+
+
+class ff_costtable_t(C.Structure):
+    _fields_ = [("n_ops", C.c_uint32), ("n_cols", C.c_uint32), ("ns", C.c_void_p)]
+
+
+EXPORTS = ["ff_sim_create", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
+           "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_strerror"]
+
+_lib = None
+
+
+def lib():
+    """the loaded library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_1807_05358_amd.build` (hipcc, gfx950)")
+        L = C.CDLL(LIB_PATH)
+        vp, u32 = C.c_void_p, C.c_uint32
+        L.ff_sim_create.restype = C.c_int
+        L.ff_sim_create.argtypes = [C.POINTER(ff_opgraph_t), C.POINTER(ff_machine_t), C.POINTER(ff_costtable_t),
+                                    C.POINTER(vp)]
+        L.ff_sim_destroy.restype = None
+        L.ff_sim_destroy.argtypes = [vp]
+        L.ff_sim_workspace_bytes.restype = C.c_size_t
+        L.ff_sim_workspace_bytes.argtypes = [vp, u32]
+        L.ff_sim_set_workspace.restype = C.c_int
+        L.ff_sim_set_workspace.argtypes = [vp, vp, C.c_size_t]
+        L.ff_sim_set_stats.restype = C.c_int
+        L.ff_sim_set_stats.argtypes = [vp, vp]
+        L.ff_sim_batch.restype = C.c_int
+        L.ff_sim_batch.argtypes = [vp, vp, u32, vp, vp]
+        L.ff_sim_chains_create.restype = C.c_int
+        L.ff_sim_chains_create.argtypes = [vp, vp, u32, vp, vp, C.POINTER(vp)]
+        L.ff_sim_delta.restype = C.c_int
+        L.ff_sim_delta.argtypes = [vp, vp, u32, vp, vp]
+        L.ff_sim_chains_destroy.restype = None
+        L.ff_sim_chains_destroy.argtypes = [vp]
+        L.ff_sim_strerror.restype = C.c_char_p
+        L.ff_sim_strerror.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+class FFSimError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {lib().ff_sim_strerror(code).decode()} ({code})")
+
+
+def _check(code, where):
+    if code != FF_OK:
+        raise FFSimError(code, where)
+
+
+def ff_sim_create(ops, edges, machine, cost):
+    """ops / edges: numpy arrays of workloads.OP_DT / EDGE_DT; machine: 7-tuple or
+    workloads.Machine; cost: [n_ops][n_cols] uint32.  Returns an opaque handle (int)."""
+    ops = np.ascontiguousarray(ops, W.OP_DT)
+    edges = np.ascontiguousarray(edges, W.EDGE_DT)
+    cost = np.ascontiguousarray(cost, "<u4")
+    g = ff_opgraph_t(len(ops), len(edges), ops.ctypes.data, edges.ctypes.data)
+    m = ff_machine_t(*(machine.as_tuple() if hasattr(machine, "as_tuple") else tuple(machine)))
+    ct = ff_costtable_t(cost.shape[0], cost.shape[1], cost.ctypes.data)
+    h = C.c_void_p()
+    _check(lib().ff_sim_create(C.byref(g), C.byref(m), C.byref(ct), C.byref(h)), "ff_sim_create")
+    return h.value
+
+
+def ff_sim_destroy(sim):
+    lib().ff_sim_destroy(sim)
+
+
+def ff_sim_workspace_bytes(sim, B):
+    return lib().ff_sim_workspace_bytes(sim, B)
+
+
+def ff_sim_set_workspace(sim, d_ws, nbytes):
+    _check(lib().ff_sim_set_workspace(sim, d_ws, nbytes), "ff_sim_set_workspace")
+
+
+def ff_sim_set_stats(sim, d_stats):
+    _check(lib().ff_sim_set_stats(sim, d_stats), "ff_sim_set_stats")
+
+
+def ff_sim_batch(sim, d_strategies, B, d_out_ns, stream=None):
+    _check(lib().ff_sim_batch(sim, d_strategies, B, d_out_ns, stream), "ff_sim_batch")
+
+
+def ff_sim_chains_create(sim, d_strategies, C_, d_out_ns0, stream=None):
+    h = C.c_void_p()
+    _check(lib().ff_sim_chains_create(sim, d_strategies, C_, d_out_ns0, stream, C.byref(h)), "ff_sim_chains_create")
+    return h.value
+
+
+def ff_sim_delta(chains, d_muts, n_steps, d_out_ns, stream=None):
+    _check(lib().ff_sim_delta(chains, d_muts, n_steps, d_out_ns, stream), "ff_sim_delta")
+
+
+def ff_sim_chains_destroy(chains):
+    lib().ff_sim_chains_destroy(chains)
+
+
+# ---- convenience on top of the boundary: torch tensors for device memory -----------------
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("no GPU visible: the simulator has no CPU path")
+    return torch
+
+
+def to_device(arr):
+    """numpy (any dtype, incl. structured) -> uint8 torch tensor on cuda:0 holding its bytes."""
+    torch = _torch()
+    a = np.ascontiguousarray(arr)
+    return torch.from_numpy(a.view(np.uint8).reshape(-1).copy()).cuda()
+
+
+class Simulator:
+    """owns a handle, its workspace and result buffers (all torch-allocated)."""
+
+    def __init__(self, ops, edges, machine, cost):
+        _torch()
+        self.n_ops = len(ops)
+        self.handle = ff_sim_create(ops, edges, machine, cost)
+        self._ws = None
+        self._stats = None
+
+    def close(self):
+        if self.handle:
+            ff_sim_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _ensure_workspace(self, B):
+        torch = _torch()
+        need = ff_sim_workspace_bytes(self.handle, B)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            ff_sim_set_workspace(self.handle, self._ws.data_ptr(), self._ws.numel())
+
+    def upload_strategies(self, cfgs):
+        cfgs = np.ascontiguousarray(cfgs, W.CFG_DT)
+        assert cfgs.ndim == 2 and cfgs.shape[1] == self.n_ops
+        return to_device(cfgs)
+
+    def batch(self, d_strategies, B, d_out=None, stats=False):
+        """d_strategies: device tensor from upload_strategies.  Returns the device tensor of
+        B int64 (bit pattern of uint64 ns); asynchronous on the current stream."""
+        torch = _torch()
+        self._ensure_workspace(B)
+        if d_out is None:
+            d_out = torch.empty(B, dtype=torch.int64, device="cuda")
+        if stats:
+            self._stats = torch.zeros(B * STATS_DT.itemsize, dtype=torch.uint8, device="cuda")
+            ff_sim_set_stats(self.handle, self._stats.data_ptr())
+        else:
+            ff_sim_set_stats(self.handle, None)
+        ff_sim_batch(self.handle, d_strategies.data_ptr(), B, d_out.data_ptr(),
+                     torch.cuda.current_stream().cuda_stream)
+        return d_out
+
+    def simulate(self, cfgs, stats=False):
+        """host convenience: numpy configs [B][n_ops] -> numpy uint64 [B] (and stats)."""
+        d = self.upload_strategies(cfgs)
+        out = self.batch(d, len(cfgs), stats=stats)
+        res = out.cpu().numpy().view("<u8")
+        if stats:
+            return res, self._stats.cpu().numpy().view(STATS_DT)
+        return res
+
+
+class Chains:
+    """C chains of cumulative single-op mutations (delta simulation)."""
+
+    def __init__(self, sim: Simulator, cfgs0):
+        torch = _torch()
+        self.sim = sim
+        cfgs0 = np.ascontiguousarray(cfgs0, W.CFG_DT)
+        self.C = len(cfgs0)
+        d = to_device(cfgs0)
+        self.out0 = torch.empty(self.C, dtype=torch.int64, device="cuda")
+        self.handle = ff_sim_chains_create(sim.handle, d.data_ptr(), self.C, self.out0.data_ptr(),
+                                           torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+
+    def start_ns(self):
+        return self.out0.cpu().numpy().view("<u8")
+
+    def upload_mutations(self, muts):
+        muts = np.ascontiguousarray(muts, W.MUT_DT)
+        assert muts.ndim == 2 and muts.shape[1] == self.C
+        return to_device(muts)
+
+    def delta(self, d_muts, n_steps, d_out=None):
+        torch = _torch()
+        if d_out is None:
+            d_out = torch.empty((n_steps, self.C), dtype=torch.int64, device="cuda")
+        ff_sim_delta(self.handle, d_muts.data_ptr(), n_steps, d_out.data_ptr(),
+                     torch.cuda.current_stream().cuda_stream)
+        return d_out
+
+    def close(self):
+        if self.handle:
+            _torch().cuda.synchronize()
+            ff_sim_chains_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,263 @@
+// Host side of the C boundary declared in include/ff_sim.h: validation, upload of the
+// constant tables, workspace bookkeeping and kernel launches.  No torch types here.
+#include "../../include/ff_sim.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "ffsim_kernels.h"
+
+using namespace ffsim;
+
+namespace {
+
+template <typename T>
+int upload(const std::vector<T>& v, T** out) {
+    *out = nullptr;
+    size_t bytes = std::max<size_t>(v.size(), 1) * sizeof(T);
+    if (hipMalloc((void**)out, bytes) != hipSuccess) return FF_ENOMEM;
+    if (!v.empty() && hipMemcpy(*out, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return FF_EHIP;
+    return FF_OK;
+}
+
+uint32_t magic_plus1(uint32_t d) { return d <= 1 ? 0u : (uint32_t)((1ull << 32) / d) + 1u; }
+uint32_t magic_floor(uint32_t d) { return d <= 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / d); }
+
+}  // namespace
+
+struct ff_sim {
+    SimDev dev{};
+    DOp* d_ops = nullptr;
+    DEdge* d_edges = nullptr;
+    uint32_t* d_in_list = nullptr;
+    uint32_t* d_cost = nullptr;
+    uint32_t* d_magic = nullptr;
+    bool wide = false;            // some tensor has 2^32 bytes or more
+    size_t slot_bytes = 0;        // HBM scratch per resident wavefront
+    size_t lds = 0;               // dynamic LDS per wavefront
+    uint32_t max_slots = 0;       // wavefronts the device can hold at once
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    ff_stats_t* d_stats = nullptr;
+};
+
+struct ff_chains {
+    ff_sim* sim = nullptr;
+    uint32_t C = 0;
+    uint2* d_cfgs = nullptr;       // [C][n_ops] current strategies
+    unsigned char* d_slots = nullptr;
+};
+
+static void release(ff_sim* s) {
+    if (!s) return;
+    hipFree(s->d_ops); hipFree(s->d_edges); hipFree(s->d_in_list); hipFree(s->d_cost); hipFree(s->d_magic);
+    delete s;
+}
+
+extern "C" {
+
+const char* ff_sim_strerror(int code) {
+    switch (code) {
+        case FF_OK: return "ok";
+        case FF_EINVAL: return "invalid argument";
+        case FF_ENOMEM: return "out of memory";
+        case FF_EWORKSPACE: return "workspace missing or too small";
+        case FF_ERANGE: return "size limit exceeded";
+        case FF_EHIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtable_t* ct, ff_sim_t** out) {
+    if (!out) return FF_EINVAL;
+    *out = nullptr;
+    if (!g || !m || !ct || !g->ops || (g->n_edges && !g->edges) || !ct->ns) return FF_EINVAL;
+    if (g->n_ops < 1 || ct->n_ops != g->n_ops || ct->n_cols < 1) return FF_EINVAL;
+    if (g->n_ops > FF_MAX_OPS) return FF_ERANGE;
+    if (m->n_nodes < 1 || m->gpus_per_node < 1 || m->intra_Bpns < 1 || m->inter_Bpns < 1 || m->elem_bytes < 1) return FF_EINVAL;
+    const uint64_t D = (uint64_t)m->n_nodes * m->gpus_per_node;
+    if (D > FF_MAX_DEVICES) return FF_ERANGE;
+    const uint64_t n_rows = D + (uint64_t)m->n_nodes * m->gpus_per_node * m->gpus_per_node + (uint64_t)m->n_nodes * m->n_nodes;
+
+    std::vector<DOp> ops(g->n_ops);
+    unsigned __int128 max_bytes = 0;
+    for (uint32_t i = 0; i < g->n_ops; i++) {
+        const ff_op_t& o = g->ops[i];
+        if (o.ndim < 1 || o.ndim > FF_MAX_DIMS) return FF_EINVAL;
+        unsigned __int128 elems = 1;
+        for (int d = 0; d < 4; d++) {
+            uint32_t e = d < o.ndim ? o.extent[d] : 1;
+            if (e < 1) return FF_EINVAL;
+            if (e > FF_MAX_EXTENT) return FF_ERANGE;
+            ops[i].extent[d] = e;
+            elems *= e;
+        }
+        max_bytes = std::max(max_bytes, elems * m->elem_bytes);
+        ops[i].ndim = o.ndim;
+        ops[i].par_mask = o.par_mask & ((1u << o.ndim) - 1);
+        ops[i].out_begin = ops[i].out_end = 0;
+    }
+    if (max_bytes >= ((unsigned __int128)1 << 62)) return FF_ERANGE;
+
+    std::vector<DEdge> edges(g->n_edges);
+    std::vector<uint32_t> in_count(g->n_ops, 0);
+    for (uint32_t k = 0; k < g->n_edges; k++) {
+        const ff_edge_t& e = g->edges[k];
+        if (e.src_op >= g->n_ops || e.dst_op >= g->n_ops || e.src_op >= e.dst_op) return FF_EINVAL;
+        if (k > 0) {
+            const ff_edge_t& p = g->edges[k - 1];
+            if (p.src_op > e.src_op || (p.src_op == e.src_op && p.dst_op > e.dst_op)) return FF_EINVAL;
+        }
+        edges[k].src = e.src_op;
+        edges[k].dst = e.dst_op;
+        for (int d = 0; d < 4; d++) {
+            DMap& dm = edges[k].map[d];
+            const ff_dimmap_t& sm = e.map[d];
+            if (d >= g->ops[e.src_op].ndim || sm.src_dim < 0) { dm = DMap{-1, 1, 0, 0}; continue; }
+            if (sm.src_dim >= g->ops[e.dst_op].ndim || sm.stride < 1) return FF_EINVAL;
+            dm = DMap{sm.src_dim, sm.stride, sm.a, sm.b};
+        }
+        in_count[e.dst_op]++;
+    }
+    // out-edges of an op are a contiguous range (edges are sorted by producer); in-edges via a list
+    {
+        uint32_t k = 0;
+        for (uint32_t i = 0; i < g->n_ops; i++) {
+            ops[i].out_begin = k;
+            while (k < g->n_edges && edges[k].src == i) k++;
+            ops[i].out_end = k;
+        }
+    }
+    std::vector<uint32_t> in_list(g->n_edges);
+    {
+        uint32_t acc = 0;
+        for (uint32_t i = 0; i < g->n_ops; i++) { ops[i].in_begin = acc; acc += in_count[i]; ops[i].in_end = ops[i].in_begin; }
+        for (uint32_t k = 0; k < g->n_edges; k++) in_list[ops[edges[k].dst].in_end++] = k;
+    }
+    std::vector<uint32_t> cost((size_t)g->n_ops * ct->n_cols);
+    for (size_t k = 0; k < cost.size(); k++) {
+        if (ct->ns[k] < 1) return FF_EINVAL;   // every exeTime >= 1
+        cost[k] = ct->ns[k];
+    }
+    std::vector<uint32_t> magic(65, 0);
+    for (uint32_t d = 2; d <= 64; d++) magic[d] = magic_plus1(d);
+
+    ff_sim* s = new (std::nothrow) ff_sim;
+    if (!s) return FF_ENOMEM;
+    int rc;
+    if ((rc = upload(ops, &s->d_ops)) || (rc = upload(edges, &s->d_edges)) || (rc = upload(in_list, &s->d_in_list)) ||
+        (rc = upload(cost, &s->d_cost)) || (rc = upload(magic, &s->d_magic))) { release(s); return rc; }
+
+    SimDev& S = s->dev;
+    S.ops = s->d_ops; S.edges = s->d_edges; S.in_list = s->d_in_list; S.cost = s->d_cost; S.magic = s->d_magic;
+    S.n_ops = g->n_ops; S.n_edges = g->n_edges; S.n_cols = ct->n_cols;
+    S.max_parts = std::min<uint32_t>(FF_MAX_PARTS, ct->n_cols);
+    S.n_nodes = m->n_nodes; S.gpus_per_node = m->gpus_per_node; S.n_dev = (uint32_t)D; S.n_rows = (uint32_t)n_rows;
+    S.bw_intra = m->intra_Bpns; S.bw_inter = m->inter_Bpns; S.lat_intra = m->intra_lat_ns; S.lat_inter = m->inter_lat_ns;
+    S.elem_bytes = m->elem_bytes;
+    S.m_bw_intra = magic_floor(m->intra_Bpns); S.m_bw_inter = magic_floor(m->inter_Bpns);
+    S.magic_dev = magic_plus1((uint32_t)D); S.magic_gpn = magic_plus1(m->gpus_per_node);
+    S.n_ops_pad = (g->n_ops + 63) & ~63u;
+    S.n_groups = S.n_ops_pad / 64;
+    s->wide = max_bytes >= ((unsigned __int128)1 << 32);
+    s->slot_bytes = (size_t)g->n_ops * WAVE * (sizeof(TaskState) + sizeof(u64));
+    s->lds = lds_bytes(S.n_rows, S.n_ops_pad);
+    if (s->lds > 64 * 1024) { release(s); return FF_ERANGE; }
+
+    int dev_id = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev_id) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev_id) != hipSuccess) { release(s); return FF_EHIP; }
+    hipError_t e = s->wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_sim_batch<true>, WAVE, s->lds)
+                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_sim_batch<false>, WAVE, s->lds);
+    if (e != hipSuccess || per_cu < 1) per_cu = 1;
+    s->max_slots = (uint32_t)cus * (uint32_t)per_cu;
+    *out = s;
+    return FF_OK;
+}
+
+void ff_sim_destroy(ff_sim_t* s) { release(s); }
+
+size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {
+    if (!s) return 0;
+    return (size_t)std::max<uint32_t>(1, std::min(B, s->max_slots)) * s->slot_bytes;
+}
+
+int ff_sim_set_workspace(ff_sim_t* s, void* d_ws, size_t bytes) {
+    if (!s || (!d_ws && bytes) || ((uintptr_t)d_ws & 255)) return FF_EINVAL;
+    s->ws = d_ws;
+    s->ws_bytes = bytes;
+    return FF_OK;
+}
+
+int ff_sim_set_stats(ff_sim_t* s, ff_stats_t* d_stats) {
+    if (!s) return FF_EINVAL;
+    s->d_stats = d_stats;
+    return FF_OK;
+}
+
+int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns, void* hip_stream) {
+    if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
+    if (B == 0) return FF_OK;
+    const uint32_t slots = std::min(B, s->max_slots);
+    if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    static_assert(sizeof(Counters) == sizeof(ff_stats_t), "stats layout");
+    if (s->wide)
+        hipLaunchKernelGGL(k_sim_batch<true>, dim3(slots), dim3(WAVE), s->lds, st, s->dev, (const uint2*)d_strategies, B,
+                           (u64*)d_out_ns, (Counters*)s->d_stats, (unsigned char*)s->ws, s->slot_bytes);
+    else
+        hipLaunchKernelGGL(k_sim_batch<false>, dim3(slots), dim3(WAVE), s->lds, st, s->dev, (const uint2*)d_strategies, B,
+                           (u64*)d_out_ns, (Counters*)s->d_stats, (unsigned char*)s->ws, s->slot_bytes);
+    return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
+}
+
+static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out, hipStream_t st) {
+    ff_sim* s = c->sim;
+    static_assert(sizeof(ff_mutation_t) == 12, "mutation layout");
+    if (s->wide)
+        hipLaunchKernelGGL(k_sim_chain_steps<true>, dim3(c->C), dim3(WAVE), s->lds, st, s->dev, c->d_cfgs, c->C,
+                           (const uint32_t*)d_muts, n_steps, (u64*)d_out, c->d_slots, s->slot_bytes);
+    else
+        hipLaunchKernelGGL(k_sim_chain_steps<false>, dim3(c->C), dim3(WAVE), s->lds, st, s->dev, c->d_cfgs, c->C,
+                           (const uint32_t*)d_muts, n_steps, (u64*)d_out, c->d_slots, s->slot_bytes);
+    return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
+}
+
+int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C, uint64_t* d_out_ns0, void* hip_stream,
+                         ff_chains_t** out) {
+    if (!out) return FF_EINVAL;
+    *out = nullptr;
+    if (!s || !d_strategies || !d_out_ns0 || C < 1) return FF_EINVAL;
+    ff_chains* c = new (std::nothrow) ff_chains;
+    if (!c) return FF_ENOMEM;
+    c->sim = s;
+    c->C = C;
+    hipStream_t st = (hipStream_t)hip_stream;
+    size_t cfg_bytes = (size_t)C * s->dev.n_ops * sizeof(uint2);
+    if (hipMalloc((void**)&c->d_cfgs, cfg_bytes) != hipSuccess ||
+        hipMalloc((void**)&c->d_slots, (size_t)C * s->slot_bytes) != hipSuccess) { ff_sim_chains_destroy(c); return FF_ENOMEM; }
+    if (hipMemcpyAsync(c->d_cfgs, d_strategies, cfg_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) { ff_sim_chains_destroy(c); return FF_EHIP; }
+    int rc = launch_chain_steps(c, nullptr, 1, d_out_ns0, st);
+    if (rc) { ff_sim_chains_destroy(c); return rc; }
+    *out = c;
+    return FF_OK;
+}
+
+int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out_ns, void* hip_stream) {
+    if (!c || (n_steps && (!d_muts || !d_out_ns))) return FF_EINVAL;
+    if (n_steps == 0) return FF_OK;
+    return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream);
+}
+
+void ff_sim_chains_destroy(ff_chains_t* c) {
+    if (!c) return;
+    hipFree(c->d_cfgs);
+    hipFree(c->d_slots);
+    delete c;
+}
+
+}  // extern "C"

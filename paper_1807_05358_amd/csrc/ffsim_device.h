@@ -1,0 +1,106 @@
+// Device-side tables and wavefront primitives of the batched execution simulator (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ffsim {
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+constexpr u64 KEY_NONE = ~0ull;   // "no pending event" in the event tree
+constexpr u64 KEY_INTERNAL = ~0ull - 1;   // result when an internal consistency check fails
+constexpr int WAVE = 64;
+
+struct DMap { int32_t src_dim; uint32_t stride; int32_t a, b; };
+struct DEdge { uint32_t src, dst; DMap map[4]; };
+struct DOp {
+    uint32_t extent[4];          // 1 beyond ndim
+    uint32_t ndim, par_mask;
+    uint32_t out_begin, out_end; // range in edges[] (edges are sorted by producer)
+    uint32_t in_begin, in_end;   // range in in_list[]
+};
+
+// everything a kernel needs about (G, D, cost table); passed by value
+struct SimDev {
+    const DOp* ops;
+    const DEdge* edges;
+    const uint32_t* in_list;     // edge ids grouped by consumer op
+    const uint32_t* cost;        // [n_ops][n_cols]
+    const uint32_t* magic;       // magic[d] = floor(2^32/d)+1 for d in 2..64
+    uint32_t n_ops, n_edges, n_cols, max_parts;
+    uint32_t n_nodes, gpus_per_node, n_dev, n_rows;
+    uint32_t bw_intra, bw_inter, lat_intra, lat_inter, elem_bytes;
+    uint32_t m_bw_intra, m_bw_inter;   // floor(2^32 / bw) (2^32-1 for bw = 1)
+    uint32_t magic_dev, magic_gpn;     // floor(2^32/d)+1 for d = n_dev, gpus_per_node
+    uint32_t n_ops_pad;                // n_ops rounded up to a multiple of 64
+    uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
+};
+
+// per-task simulation state kept in HBM: index = op*64 + part
+struct TaskState { u64 ready; uint32_t pending; uint32_t pad; };
+
+__device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }
+
+// all lanes of the single-wave workgroup: orders LDS traffic between lanes
+__device__ __forceinline__ void wave_sync() { __syncthreads(); }
+
+// the readlane / readfirstlane builtins return int: go through uint32_t before widening
+__device__ __forceinline__ uint32_t first_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ u64 first_u64(u64 v) { return (u64)first_u32((uint32_t)v) | ((u64)first_u32((uint32_t)(v >> 32)) << 32); }
+
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = __shfl_xor(lo, m);
+    hi = __shfl_xor(hi, m);
+    return ((u64)hi << 32) | lo;
+}
+
+// minimum over the wavefront, uniform result
+__device__ __forceinline__ u64 wave_min_u64(u64 v) {
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) {
+        u64 o = shfl_xor_u64(v, m);
+        v = o < v ? o : v;
+    }
+    return first_u64(v);
+}
+
+__device__ __forceinline__ u64 wave_max_u64(u64 v) {
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) {
+        u64 o = shfl_xor_u64(v, m);
+        v = o > v ? o : v;
+    }
+    return first_u64(v);
+}
+
+__device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
+#pragma unroll
+    for (int m = 1; m < WAVE; m <<= 1) v |= __shfl_xor(v, m);
+    return first_u32(v);
+}
+
+__device__ __forceinline__ uint32_t readlane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
+__device__ __forceinline__ u64 readlane_u64(u64 v, int l) {
+    return (u64)readlane_u32((uint32_t)v, l) | ((u64)readlane_u32((uint32_t)(v >> 32), l) << 32);
+}
+
+// floor(n / d) for d in 1..64 and n <= 2^26 (part boundaries, part-index decoding)
+__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t d, const uint32_t* magic) {
+    return d == 1 ? n : __umulhi(n, magic[d]);
+}
+// floor(n / d) with a precomputed magic = floor(2^32/d)+1, valid while n*d < 2^32
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t d, uint32_t magic) {
+    return d == 1 ? n : __umulhi(n, magic);
+}
+// ceil(n / d) for any 32-bit n >= 1, m = floor(2^32/d) (one fix-up step)
+__device__ __forceinline__ uint32_t ceil_div_u32(uint32_t n, uint32_t d, uint32_t m) {
+    uint32_t x = n - 1;
+    uint32_t q = __umulhi(x, m);
+    uint32_t r = x - q * d;
+    q += (r >= d) ? 1u : 0u;
+    return q + 1;
+}
+
+}  // namespace ffsim

@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path (through the C boundary) against the CPU oracle, bit for bit,
+on the same seeded inputs.  Everything here needs an MI355X."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import graph_from_golden, load_golden
+from paper_1807_05358_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1807_05358_amd import binding
+    return binding
+
+
+_sims = {}
+
+
+def sim_for(B, config_id):
+    if config_id not in _sims:
+        w = W.workload(config_id)
+        _sims[config_id] = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    return _sims[config_id]
+
+
+def oracle_stats(w, cfg):
+    tg = oracle.build_task_graph(w.ops, w.edges, w.machine, w.cost, cfg)
+    n_comm = tg.n_tasks - tg.n_compute
+    return dict(n_compute=tg.n_compute, n_pairs=tg.n_deps - n_comm, n_comm=n_comm,
+                sum_comm_ns=int(tg.exe[tg.n_compute:].sum()))
+
+
+@pytest.mark.parametrize("name", ["build_two_ops_two_gpus.json", "build_shared_internode_link.json",
+                                  "build_part_order_row_major.json", "build_link_latency.json",
+                                  "build_intranode_latency.json"])
+def test_hand_computed_fixtures(B, golden_dir, name):
+    g = load_golden(golden_dir, name)
+    ops, edges, mach, cost, cfg = graph_from_golden(g)
+    sim = B.Simulator(ops, edges, mach, cost)
+    out, st = sim.simulate(cfg[None], stats=True)
+    assert int(out[0]) == g["makespan"]
+    n_comm = sum(1 for d in g["dev"] if d >= mach.n_devices)
+    assert int(st[0]["n_comm"]) == n_comm and int(st[0]["n_compute"]) == len(g["dev"]) - n_comm
+    sim.close()
+
+
+# (config, number of candidates compared element by element, how many get their task-graph counters compared)
+CASES = [(0, 64, 64), (1, 1024, 32), (2, 96, 4), (3, 48, 2), (4, 10, 1)]
+
+
+@pytest.mark.parametrize("config_id,n,n_stats", CASES)
+def test_batch_matches_oracle(B, config_id, n, n_stats):
+    w = W.workload(config_id)
+    cfgs = w.strategies(n)
+    print(f"config {config_id} ({w.name}): {n} candidates, sha256 {w.sha256(n)[:16]}", flush=True)
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=8)
+    got, st = sim_for(B, config_id).simulate(cfgs, stats=True)
+    assert not st["exit_code"].any() and not st["n_stuck"].any(), (st["exit_code"][:8], st["n_stuck"][:8], st["n_events"][:8])
+    for b in range(n_stats):   # localise a builder mismatch before a timeline mismatch
+        o = oracle_stats(w, cfgs[b])
+        for k, v in o.items():
+            assert int(st[b][k]) == v, f"candidate {b}: {k} gpu {int(st[b][k])} oracle {v}"
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} of {n} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+
+
+def test_full_size_batches_run_in_bench_configuration(B):
+    """configs 2 and 3 at their full B (4096), launch shape as in the bench; a strided
+    sample is compared with the oracle, and all results must respect the bounds that hold
+    for any strategy (at least the largest single task, at most the unsplit serial time...)."""
+    for config_id, n, every in ((2, 4096, 128), (3, 4096, 256)):
+        w = W.workload(config_id)
+        cfgs = w.strategies(n)
+        got = sim_for(B, config_id).simulate(cfgs)
+        idx = np.arange(0, n, every)
+        want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs[idx], n_threads=8)
+        assert np.array_equal(got[idx], want)
+        parts = cfgs["deg"].astype(np.int64).prod(-1)
+        task_ns = np.take_along_axis(np.broadcast_to(w.cost[None], (n,) + w.cost.shape), (parts - 1)[..., None], 2)[..., 0]
+        assert (got >= task_ns.max(1)).all()                      # some task runs start to end
+        assert (got < 2 ** 63).all()
+
+
+def test_repeat_is_deterministic(B):
+    w = W.workload(2)
+    cfgs = w.strategies(256)
+    sim = sim_for(B, 2)
+    a = sim.simulate(cfgs)
+    b = sim.simulate(cfgs)
+    assert np.array_equal(a, b)
+    # a different grid shape (fewer candidates per launch) gives the same bits
+    c = np.concatenate([sim.simulate(cfgs[:100]), sim.simulate(cfgs[100:])])
+    assert np.array_equal(a, c)
+
+
+def test_invalid_candidates_are_flagged_not_fatal(B):
+    w = W.workload(0)
+    cfgs = w.strategies(8).copy()
+    cfgs[1][5]["deg"] = (1, 2, 1, 1)     # softmax split in a non-parallelizable dim
+    cfgs[3][0]["deg"] = (0, 1, 1, 1)
+    cfgs[4][0]["deg"] = (8, 8, 2, 1)     # 128 parts
+    cfgs[6][2]["dev_offset"] = 4         # device 4 of 4
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs)
+    got = sim_for(B, 0).simulate(cfgs)
+    assert np.array_equal(got, want)
+    assert (got[[1, 3, 4, 6]] == B.FF_INVALID_NS).all() and (got[[0, 2, 5, 7]] != B.FF_INVALID_NS).all()
+
+
+def test_empty_batch_and_argument_errors(B):
+    sim = sim_for(B, 0)
+    assert B.lib().ff_sim_batch(sim.handle, None, 0, None, None) == B.FF_OK
+    assert B.lib().ff_sim_batch(sim.handle, None, 4, None, None) == B.FF_EINVAL
+    w = W.workload(0)
+    bad_edges = w.edges[::-1].copy()     # not sorted by producer
+    with pytest.raises(B.FFSimError):
+        B.ff_sim_create(w.ops, bad_edges, w.machine, w.cost)
+    zero_cost = w.cost.copy(); zero_cost[0, 0] = 0
+    with pytest.raises(B.FFSimError):
+        B.ff_sim_create(w.ops, w.edges, w.machine, zero_cost)
+
+
+def test_general_degrees_strides_and_small_machines(B):
+    """beyond the benchmark distribution: non-power-of-two degrees, device strides other
+    than 1 (several parts per device), more parts than devices, link latency."""
+    rng = np.random.default_rng(5)
+    w = W.workload(1)
+    mach = W.Machine(3, 2, 7, 3, 5, 9, 4)      # 6 devices
+    choices = (1, 2, 3, 4, 5, 6, 7, 12)
+    n = 200
+    cfgs = np.zeros((n, w.n_ops), W.CFG_DT)
+    for i in range(w.n_ops):
+        t = W.valid_degree_tuples(w.ops[i], 64, choices)
+        cfgs["deg"][:, i] = t[rng.integers(len(t), size=n)]
+    cfgs["dev_offset"] = rng.integers(0, 6, size=(n, w.n_ops))
+    cfgs["dev_stride"] = rng.integers(0, 9, size=(n, w.n_ops))
+    want = oracle.simulate_batch(w.ops, w.edges, mach, w.cost, cfgs, n_threads=8)
+    sim = B.Simulator(w.ops, w.edges, mach, w.cost)
+    got = sim.simulate(cfgs)
+    sim.close()
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+
+
+def test_wide_tensors_take_the_64_bit_path(B):
+    """a tensor of more than 2^32 bytes: element counts and transfer sizes need 64 bits."""
+    g = W.GraphBuilder()
+    a = g.op(W.T_ELEM, (1 << 12, 1 << 12, 1 << 9), (0, 1, 2), 1)     # 2^33 elements
+    b = g.elementwise([a])
+    g.elementwise([b])
+    ops, edges, _ = g.finish()
+    cost = np.full((3, 64), 1000, "<u4")
+    mach = W.Machine(2, 4, 20, 12, 0, 3, 4)
+    rng = np.random.default_rng(11)
+    n = 64
+    cfgs = np.zeros((n, 3), W.CFG_DT)
+    t = W.valid_degree_tuples(ops[0], 64, (1, 2, 4, 8))
+    for i in range(3):
+        cfgs["deg"][:, i] = t[rng.integers(len(t), size=n)]
+    cfgs["dev_offset"] = rng.integers(0, 8, size=(n, 3))
+    cfgs["dev_stride"] = 1
+    cfgs["deg"][0] = 1                      # candidate 0: whole tensors, 2^35 bytes per transfer,
+    cfgs["dev_offset"][0] = [0, 1, 4]       # once inside a node and once between nodes
+    want = oracle.simulate_batch(ops, edges, mach, cost, cfgs)
+    sim = B.Simulator(ops, edges, mach, cost)
+    got = sim.simulate(cfgs)
+    sim.close()
+    assert want[0] == 3 * 1000 + 2 ** 35 // 20 + 1 + (-(-2 ** 35 // 12) + 3)
+    assert np.array_equal(got, want)
+
+
+def test_delta_chain_matches_resimulation(B):
+    w = W.workload(1)
+    C, steps = 4, 40
+    cfg0 = w.strategies(C)
+    muts = w.mutations(steps, C)
+    sim = sim_for(B, 1)
+    ch = B.Chains(sim, cfg0)
+    assert np.array_equal(ch.start_ns(), oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0))
+    d_m = ch.upload_mutations(muts)
+    got = ch.delta(d_m, steps).cpu().numpy().view("<u8")
+    for c in range(C):
+        want = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], muts[:, c])
+        assert np.array_equal(got[:, c], want), f"chain {c}"
+    ch.close()
