@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched execution simulator on one MI355X.
+
+A step is one pass of the whole hot path (task-graph construction + full simulation,
+one ff_sim_batch call) over one batch of seeded synthetic candidate strategies that is
+already resident in HBM.  The headline workload is configs[1] (AlexNet-shaped graph,
+4x4 simulated devices, 1024 candidates); the other four configurations and the delta
+chain of configs[4] are measured the same way and reported in "workloads".
+
+Prints ONE JSON line.  python bench.py --gpus 1 --steps K --warmup W
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+HEADLINE = 1
+
+
+def alg_bytes(n_ops, tc, npairs):
+    """bytes the method moves per strategy if the task graph is written once and read once:
+    strategy in, 40 B per compute task, 28 B per producer/consumer pair, result out."""
+    return 8.0 * n_ops + 40.0 * tc + 28.0 * npairs + 8.0
+
+
+def time_batches(sim, d_strat, B, steps, warmup):
+    """per-launch durations (ms) from HIP events on the launch stream + wall ms per step."""
+    import torch
+    for _ in range(warmup):
+        sim.batch(d_strat, B)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    out = torch.empty(B, dtype=torch.int64, device="cuda")
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        sim.batch(d_strat, B, d_out=out)
+        b.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern_ms = [a.elapsed_time(b) for a, b in ev]
+    return sum(kern_ms) / len(kern_ms), wall_ms, out
+
+
+def oracle_rate(w, cfgs, threads):
+    import oracle
+    t0 = time.perf_counter()
+    res = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=threads)
+    return len(cfgs) / (time.perf_counter() - t0), res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--only-headline", action="store_true", help="skip the other workloads and the delta chain")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (candidates are independent; see DESIGN.md for how the "
+              "batch would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1807_05358_amd import binding, workloads as W
+
+    threads = min(os.cpu_count() or 1, 16)
+    results = {}
+    order = [HEADLINE] if args.only_headline else [HEADLINE, 0, 2, 3, 4]
+    for c in order:
+        w = W.workload(c)
+        B = w.n_candidates
+        cfgs = w.strategies(B)
+        sim = binding.Simulator(w.ops, w.edges, w.machine, w.cost)
+        d_strat = sim.upload_strategies(cfgs)
+        _, st = sim.simulate(cfgs, stats=True)          # untimed: counters for the byte model
+        steps = args.steps if c != 4 else max(2, min(args.steps, 5))
+        kern_ms, wall_ms, out = time_batches(sim, d_strat, B, steps, args.warmup if c != 4 else 1)
+        got = out.cpu().numpy().view("<u8")
+        tc, npairs = float(st["n_compute"].mean()), float(st["n_pairs"].mean())
+        ab = alg_bytes(w.n_ops, tc, npairs)
+        r = {
+            "workload": f"configs[{c}] {w.name}", "B": B, "n_ops": w.n_ops, "n_edges": int(len(w.edges)),
+            "simulated_devices": w.machine.n_devices, "steps": steps,
+            "ms_per_step": wall_ms, "kernel_ms": kern_ms, "strategies_per_s": B / (wall_ms * 1e-3),
+            "mean_compute_tasks": tc, "mean_pairs": npairs, "mean_comm_tasks": float(st["n_comm"].mean()),
+            "mean_events": float(st["n_events"].mean()),
+            "alg_bytes_per_strategy": ab,
+            "achieved_GBps": ab * B / (kern_ms * 1e-3) / 1e9,
+            "hbm_roofline_frac": ab * B / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "input_sha256": w.sha256(B),
+        }
+        if not args.no_cpu:
+            n_s = {0: 64, 1: 1024, 2: 128, 3: 64, 4: 16}[c]
+            idx = np.linspace(0, B - 1, n_s).astype(np.int64)
+            rate_t, ref = oracle_rate(w, cfgs[idx], threads)
+            r["oracle_strategies_per_s"] = rate_t
+            r["oracle_threads"] = threads
+            r["oracle_sample"] = n_s
+            r["bit_exact_on_sample"] = bool(np.array_equal(got[idx], ref))
+        results[c] = (r, sim, w, cfgs)
+
+    head, sim, w, cfgs = results[HEADLINE]
+    line = {
+        "metric": "simulated strategies/sec (build + full simulation)",
+        "value": head["strategies_per_s"],
+        "unit": "strategies/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "configs[1]: AlexNet-shaped 12-op graph, batch 256, 4 nodes x 4 simulated devices, "
+                               "1024 seeded candidate strategies per step", "B": head["B"],
+                   "candidates_per_step": head["B"]},
+        "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": head["hbm_roofline_frac"], "traffic": None,
+                     "kernel": "k_sim_batch<false>", "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
+                     "kernel_ms": head["kernel_ms"]},
+    }
+    if not args.no_cpu:
+        # the oracle as it stands on the host cores: the whole 1024-candidate batch, repeated
+        # until about 10 s of CPU work have been spent
+        one, _ = oracle_rate(w, cfgs, 1)
+        reps = max(1, int(10.0 * one / len(cfgs)))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            oracle_rate(w, cfgs, threads)
+        multi = reps * len(cfgs) / (time.perf_counter() - t0)
+        line["cpu_baseline"] = {"value": multi, "unit": "strategies/s", "cores": threads, "kind": "oracle",
+                                "sample": f"all {len(cfgs)} candidates of configs[1], {reps} repetitions, "
+                                          f"{threads} threads (static split); single thread: {one:.1f} strategies/s",
+                                "single_thread_value": one}
+    if not args.only_headline:
+        # delta simulation on configs[4]: one chain, and 256 independent chains
+        r4, sim4, w4, cfgs4 = results[4]
+        delta = []
+        for C, n_steps in ((1, 8), (256, 4)):
+            muts = w4.mutations(n_steps, C)
+            ch = binding.Chains(sim4, cfgs4[:C])
+            d_m = ch.upload_mutations(muts)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            out = ch.delta(d_m, n_steps)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            delta.append({"workload": "configs[4] nmt", "chains": C, "steps": n_steps, "ms": ms,
+                          "delta_sims_per_s": C * n_steps / (ms * 1e-3)})
+            ch.close()
+        line["delta"] = delta
+        line["workloads"] = [results[c][0] for c in sorted(results)]
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
