@@ -42,12 +42,20 @@ struct TaskState { u64 ready; uint32_t pending; uint32_t pad; };
 
 __device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }
 
-// all lanes of the single-wave workgroup: orders LDS traffic between lanes
-__device__ __forceinline__ void wave_sync() { __syncthreads(); }
+// Orders LDS traffic between the lanes of the (single-wavefront) workgroup.  LDS operations
+// of one wavefront execute in program order, so no wait and no s_barrier is needed; the
+// fence only keeps the compiler from forwarding or reordering LDS accesses across it.
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
 
 // the readlane / readfirstlane builtins return int: go through uint32_t before widening
 __device__ __forceinline__ uint32_t first_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
-__device__ __forceinline__ u64 first_u64(u64 v) { return (u64)first_u32((uint32_t)v) | ((u64)first_u32((uint32_t)(v >> 32)) << 32); }
+__device__ __forceinline__ uint32_t readlane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
+__device__ __forceinline__ u64 readlane_u64(u64 v, int l) {
+    return (u64)readlane_u32((uint32_t)v, l) | ((u64)readlane_u32((uint32_t)(v >> 32), l) << 32);
+}
 
 __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
     uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
@@ -56,35 +64,38 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
     return ((u64)hi << 32) | lo;
 }
 
-// minimum over the wavefront, uniform result
+// lane i of every row of 16 lanes reads lane perm(i) of the same row (DPP controls:
+// quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141,
+// row_mirror = 0x140); all of them are permutations, so every lane reads a valid lane
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+
+// wavefront-wide min / max of a 32-bit value, uniform result: butterfly inside each row of
+// 16 lanes with DPP, then the four row results are combined on the scalar unit
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    uint32_t t;
+    t = dpp_u32<0xB1>(v); v = t < v ? t : v;
+    t = dpp_u32<0x4E>(v); v = t < v ? t : v;
+    t = dpp_u32<0x141>(v); v = t < v ? t : v;
+    t = dpp_u32<0x140>(v); v = t < v ? t : v;
+    uint32_t a = readlane_u32(v, 0), b = readlane_u32(v, 16), c = readlane_u32(v, 32), d = readlane_u32(v, 48);
+    a = a < b ? a : b;
+    c = c < d ? c : d;
+    return a < c ? a : c;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) { return ~wave_min_u32(~v); }
+
+// minimum over the wavefront, uniform result: high words first, then the low words of the
+// lanes that hold the minimal high word
 __device__ __forceinline__ u64 wave_min_u64(u64 v) {
-#pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) {
-        u64 o = shfl_xor_u64(v, m);
-        v = o < v ? o : v;
-    }
-    return first_u64(v);
+    const uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    const uint32_t mhi = wave_min_u32(hi);
+    const uint32_t mlo = wave_min_u32(hi == mhi ? lo : 0xffffffffu);
+    return ((u64)mhi << 32) | mlo;
 }
-
-__device__ __forceinline__ u64 wave_max_u64(u64 v) {
-#pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) {
-        u64 o = shfl_xor_u64(v, m);
-        v = o > v ? o : v;
-    }
-    return first_u64(v);
-}
-
-__device__ __forceinline__ uint32_t wave_or_u32(uint32_t v) {
-#pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) v |= __shfl_xor(v, m);
-    return first_u32(v);
-}
-
-__device__ __forceinline__ uint32_t readlane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
-__device__ __forceinline__ u64 readlane_u64(u64 v, int l) {
-    return (u64)readlane_u32((uint32_t)v, l) | ((u64)readlane_u32((uint32_t)(v >> 32), l) << 32);
-}
+__device__ __forceinline__ u64 wave_max_u64(u64 v) { return ~wave_min_u64(~v); }
 
 // floor(n / d) for d in 1..64 and n <= 2^26 (part boundaries, part-index decoding)
 __device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t d, const uint32_t* magic) {

@@ -165,7 +165,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const uint2* cfgs, u64* __res
         OpCfg c = load_cfg(cfgs, i);
         if (!cfg_ok(S.ops[i], c, S)) bad = 1;
     }
-    if (wave_or_u32(bad)) return KEY_NONE;
+    if (__ballot(bad != 0)) return KEY_NONE;
 
     // ---- Section 5.1 step 1 + the start of Algorithm 1: tasks, their number of inputs, initial READY set ----
     for (uint32_t r = lane; r < S.n_rows; r += WAVE) L.free_at[r] = 0;
