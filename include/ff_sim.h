@@ -41,7 +41,13 @@ enum {
 #define FF_MAX_OPS 4096
 #define FF_MAX_EXTENT (1u << 20)
 #define FF_MAX_DEVICES 1024
+#define FF_MAX_MAP_STRIDE 1024       /* ff_dimmap_t.stride */
+#define FF_MAX_MAP_OFFSET (1 << 29)  /* |ff_dimmap_t.a|, |ff_dimmap_t.b| */
+#define FF_MAX_IN_EDGES 511          /* tensor edges into one op */
+#define FF_TIME_LIMIT_NS (1ull << 48) /* simulated times must stay below this */
 #define FF_INVALID_NS UINT64_MAX /* result for a candidate whose strategy is invalid */
+#define FF_INTERNAL_NS (UINT64_MAX - 1) /* result if an internal consistency check failed (a library bug) */
+#define FF_OVERFLOW_NS (UINT64_MAX - 2) /* result if a simulated time reached FF_TIME_LIMIT_NS */
 
 /* How a consumer part's output range along one dim selects the range it reads along one
  * PRODUCER dim ("given the output tensor of a task and its operation type, we can infer
@@ -140,7 +146,8 @@ void ff_sim_destroy(ff_sim_t* sim);
 
 /* Scratch for a batch of B candidates (per-task queue keys and readyTime / pending-input
  * counters of the resident candidates).  The workspace is caller-allocated device memory,
- * 256-byte aligned, and may be shared by successive calls on the same stream. */
+ * 256-byte aligned, and may be shared by successive calls on the same stream.  Small
+ * graphs keep this state in LDS; then 0 bytes are needed and no workspace has to be set. */
 size_t ff_sim_workspace_bytes(const ff_sim_t* sim, uint32_t B);
 int ff_sim_set_workspace(ff_sim_t* sim, void* d_ws, size_t bytes);
 

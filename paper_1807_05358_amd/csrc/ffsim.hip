@@ -33,12 +33,14 @@ struct ff_sim {
     SimDev dev{};
     DOp* d_ops = nullptr;
     DEdge* d_edges = nullptr;
-    uint32_t* d_in_list = nullptr;
+    DEdge* d_in_edges = nullptr;
     uint32_t* d_cost = nullptr;
     uint32_t* d_magic = nullptr;
     bool wide = false;            // some tensor has 2^32 bytes or more
-    size_t slot_bytes = 0;        // HBM scratch per resident wavefront
-    size_t lds = 0;               // dynamic LDS per wavefront
+    bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
+    size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
+    size_t lds = 0;               // dynamic LDS per wavefront, batch kernel
+    size_t lds_chain = 0;         // dynamic LDS per wavefront, chain kernel (words always in HBM)
     uint32_t max_slots = 0;       // wavefronts the device can hold at once
     void* ws = nullptr;
     size_t ws_bytes = 0;
@@ -49,12 +51,24 @@ struct ff_chains {
     ff_sim* sim = nullptr;
     uint32_t C = 0;
     uint2* d_cfgs = nullptr;       // [C][n_ops] current strategies
+    uint32_t* d_flags = nullptr;   // [C] nonzero once a chain saw an out-of-range mutation
     unsigned char* d_slots = nullptr;
 };
 
+typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const uint2*,
+                               uint32_t, u64*, Counters*, unsigned char*, size_t);
+typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, uint2*, uint32_t,
+                               const uint32_t*, uint32_t, u64*, uint32_t*, unsigned char*, size_t);
+
+static batch_kernel_t batch_kernel(const ff_sim* s) {
+    if (s->wide) return s->lds_words ? k_sim_batch<true, true> : k_sim_batch<true, false>;
+    return s->lds_words ? k_sim_batch<false, true> : k_sim_batch<false, false>;
+}
+static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
+
 static void release(ff_sim* s) {
     if (!s) return;
-    hipFree(s->d_ops); hipFree(s->d_edges); hipFree(s->d_in_list); hipFree(s->d_cost); hipFree(s->d_magic);
+    hipFree(s->d_ops); hipFree(s->d_edges); hipFree(s->d_in_edges); hipFree(s->d_cost); hipFree(s->d_magic);
     delete s;
 }
 
@@ -112,31 +126,44 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
             const ff_edge_t& p = g->edges[k - 1];
             if (p.src_op > e.src_op || (p.src_op == e.src_op && p.dst_op > e.dst_op)) return FF_EINVAL;
         }
-        edges[k].src = e.src_op;
-        edges[k].dst = e.dst_op;
+        DEdge& de = edges[k];
+        de.src = e.src_op;
+        de.dst = e.dst_op;
+        de.src_ndim = ops[e.src_op].ndim;
+        de.dst_ndim = ops[e.dst_op].ndim;
         for (int d = 0; d < 4; d++) {
-            DMap& dm = edges[k].map[d];
+            de.src_extent[d] = ops[e.src_op].extent[d];
+            de.dst_extent[d] = ops[e.dst_op].extent[d];
+            DMap& dm = de.map[d];
             const ff_dimmap_t& sm = e.map[d];
-            if (d >= g->ops[e.src_op].ndim || sm.src_dim < 0) { dm = DMap{-1, 1, 0, 0}; continue; }
+            if (d >= g->ops[e.src_op].ndim || sm.src_dim < 0) { dm = DMap{-1, 1, 0, 0, 1}; continue; }
             if (sm.src_dim >= g->ops[e.dst_op].ndim || sm.stride < 1) return FF_EINVAL;
-            dm = DMap{sm.src_dim, sm.stride, sm.a, sm.b};
+            if (sm.stride > FF_MAX_MAP_STRIDE || sm.a > FF_MAX_MAP_OFFSET || sm.a < -FF_MAX_MAP_OFFSET ||
+                sm.b > FF_MAX_MAP_OFFSET || sm.b < -FF_MAX_MAP_OFFSET) return FF_ERANGE;
+            dm = DMap{sm.src_dim, sm.stride, sm.a, sm.b, ops[e.dst_op].extent[sm.src_dim]};
         }
         in_count[e.dst_op]++;
     }
-    // out-edges of an op are a contiguous range (edges are sorted by producer); in-edges via a list
+    // out-edges of an op are a contiguous range (edges are sorted by producer); in-edges are a
+    // second copy of the records grouped by consumer
     {
         uint32_t k = 0;
         for (uint32_t i = 0; i < g->n_ops; i++) {
             ops[i].out_begin = k;
             while (k < g->n_edges && edges[k].src == i) k++;
             ops[i].out_end = k;
+            ops[i].first_dst = ops[i].out_end > ops[i].out_begin ? edges[ops[i].out_begin].dst : 0;
+            ops[i].pad = 0;
         }
     }
-    std::vector<uint32_t> in_list(g->n_edges);
+    std::vector<DEdge> in_edges(g->n_edges);
     {
         uint32_t acc = 0;
-        for (uint32_t i = 0; i < g->n_ops; i++) { ops[i].in_begin = acc; acc += in_count[i]; ops[i].in_end = ops[i].in_begin; }
-        for (uint32_t k = 0; k < g->n_edges; k++) in_list[ops[edges[k].dst].in_end++] = k;
+        for (uint32_t i = 0; i < g->n_ops; i++) {
+            if (in_count[i] > FF_MAX_IN_EDGES) return FF_ERANGE;   // pending-input counter has 15 bits
+            ops[i].in_begin = acc; acc += in_count[i]; ops[i].in_end = ops[i].in_begin;
+        }
+        for (uint32_t k = 0; k < g->n_edges; k++) in_edges[ops[edges[k].dst].in_end++] = edges[k];
     }
     std::vector<uint32_t> cost((size_t)g->n_ops * ct->n_cols);
     for (size_t k = 0; k < cost.size(); k++) {
@@ -149,11 +176,10 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     ff_sim* s = new (std::nothrow) ff_sim;
     if (!s) return FF_ENOMEM;
     int rc;
-    if ((rc = upload(ops, &s->d_ops)) || (rc = upload(edges, &s->d_edges)) || (rc = upload(in_list, &s->d_in_list)) ||
+    if ((rc = upload(ops, &s->d_ops)) || (rc = upload(edges, &s->d_edges)) || (rc = upload(in_edges, &s->d_in_edges)) ||
         (rc = upload(cost, &s->d_cost)) || (rc = upload(magic, &s->d_magic))) { release(s); return rc; }
 
     SimDev& S = s->dev;
-    S.ops = s->d_ops; S.edges = s->d_edges; S.in_list = s->d_in_list; S.cost = s->d_cost; S.magic = s->d_magic;
     S.n_ops = g->n_ops; S.n_edges = g->n_edges; S.n_cols = ct->n_cols;
     S.max_parts = std::min<uint32_t>(FF_MAX_PARTS, ct->n_cols);
     S.n_nodes = m->n_nodes; S.gpus_per_node = m->gpus_per_node; S.n_dev = (uint32_t)D; S.n_rows = (uint32_t)n_rows;
@@ -161,18 +187,23 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     S.elem_bytes = m->elem_bytes;
     S.m_bw_intra = magic_floor(m->intra_Bpns); S.m_bw_inter = magic_floor(m->inter_Bpns);
     S.magic_dev = magic_plus1((uint32_t)D); S.magic_gpn = magic_plus1(m->gpus_per_node);
+    S.pass_dev = D == 1 ? 0xffffffffu : 0u; S.pass_gpn = m->gpus_per_node == 1 ? 0xffffffffu : 0u;
     S.n_ops_pad = (g->n_ops + 63) & ~63u;
     S.n_groups = S.n_ops_pad / 64;
     s->wide = max_bytes >= ((unsigned __int128)1 << 32);
-    s->slot_bytes = (size_t)g->n_ops * WAVE * (sizeof(TaskState) + sizeof(u64));
-    s->lds = lds_bytes(S.n_rows, S.n_ops_pad);
-    if (s->lds > 64 * 1024) { release(s); return FF_ERANGE; }
+    s->slot_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 255) & ~(size_t)255;
+    s->lds_chain = lds_common_bytes(S.n_rows, S.n_ops_pad);
+    if (s->lds_chain > 64 * 1024) { release(s); return FF_ERANGE; }
+    // small graphs keep a candidate's task words in LDS, as long as four wavefronts (one per
+    // SIMD) still fit in a CU's 160 KB
+    const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_chain;
+    s->lds_words = lds_with_words <= 40 * 1024;
+    s->lds = s->lds_words ? lds_with_words : s->lds_chain;
 
     int dev_id = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev_id) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev_id) != hipSuccess) { release(s); return FF_EHIP; }
-    hipError_t e = s->wide ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_sim_batch<true>, WAVE, s->lds)
-                           : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_sim_batch<false>, WAVE, s->lds);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, batch_kernel(s), WAVE, s->lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_slots = (uint32_t)cus * (uint32_t)per_cu;
     *out = s;
@@ -183,6 +214,7 @@ void ff_sim_destroy(ff_sim_t* s) { release(s); }
 
 size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {
     if (!s) return 0;
+    if (s->lds_words) return 0;   // the whole per-candidate state lives in LDS
     return (size_t)std::max<uint32_t>(1, std::min(B, s->max_slots)) * s->slot_bytes;
 }
 
@@ -203,27 +235,21 @@ int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64
     if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
     if (B == 0) return FF_OK;
     const uint32_t slots = std::min(B, s->max_slots);
-    if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
+    if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes)) return FF_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     static_assert(sizeof(Counters) == sizeof(ff_stats_t), "stats layout");
-    if (s->wide)
-        hipLaunchKernelGGL(k_sim_batch<true>, dim3(slots), dim3(WAVE), s->lds, st, s->dev, (const uint2*)d_strategies, B,
-                           (u64*)d_out_ns, (Counters*)s->d_stats, (unsigned char*)s->ws, s->slot_bytes);
-    else
-        hipLaunchKernelGGL(k_sim_batch<false>, dim3(slots), dim3(WAVE), s->lds, st, s->dev, (const uint2*)d_strategies, B,
-                           (u64*)d_out_ns, (Counters*)s->d_stats, (unsigned char*)s->ws, s->slot_bytes);
+    hipLaunchKernelGGL(batch_kernel(s), dim3(slots), dim3(WAVE), s->lds, st, s->dev, s->d_ops, s->d_edges, s->d_in_edges,
+                       s->d_cost, s->d_magic, (const uint2*)d_strategies, B, (u64*)d_out_ns, (Counters*)s->d_stats,
+                       (unsigned char*)s->ws, s->slot_bytes);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
 static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out, hipStream_t st) {
     ff_sim* s = c->sim;
     static_assert(sizeof(ff_mutation_t) == 12, "mutation layout");
-    if (s->wide)
-        hipLaunchKernelGGL(k_sim_chain_steps<true>, dim3(c->C), dim3(WAVE), s->lds, st, s->dev, c->d_cfgs, c->C,
-                           (const uint32_t*)d_muts, n_steps, (u64*)d_out, c->d_slots, s->slot_bytes);
-    else
-        hipLaunchKernelGGL(k_sim_chain_steps<false>, dim3(c->C), dim3(WAVE), s->lds, st, s->dev, c->d_cfgs, c->C,
-                           (const uint32_t*)d_muts, n_steps, (u64*)d_out, c->d_slots, s->slot_bytes);
+    hipLaunchKernelGGL(chain_kernel(s), dim3(c->C), dim3(WAVE), s->lds_chain, st, s->dev, s->d_ops, s->d_edges, s->d_in_edges,
+                       s->d_cost, s->d_magic, c->d_cfgs, c->C, (const uint32_t*)d_muts, n_steps, (u64*)d_out, c->d_flags,
+                       c->d_slots, s->slot_bytes);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
@@ -238,9 +264,10 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
     c->C = C;
     hipStream_t st = (hipStream_t)hip_stream;
     size_t cfg_bytes = (size_t)C * s->dev.n_ops * sizeof(uint2);
-    if (hipMalloc((void**)&c->d_cfgs, cfg_bytes) != hipSuccess ||
+    if (hipMalloc((void**)&c->d_cfgs, cfg_bytes) != hipSuccess || hipMalloc((void**)&c->d_flags, (size_t)C * 4) != hipSuccess ||
         hipMalloc((void**)&c->d_slots, (size_t)C * s->slot_bytes) != hipSuccess) { ff_sim_chains_destroy(c); return FF_ENOMEM; }
-    if (hipMemcpyAsync(c->d_cfgs, d_strategies, cfg_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) { ff_sim_chains_destroy(c); return FF_EHIP; }
+    if (hipMemcpyAsync(c->d_cfgs, d_strategies, cfg_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
+        hipMemsetAsync(c->d_flags, 0, (size_t)C * 4, st) != hipSuccess) { ff_sim_chains_destroy(c); return FF_EHIP; }
     int rc = launch_chain_steps(c, nullptr, 1, d_out_ns0, st);
     if (rc) { ff_sim_chains_destroy(c); return rc; }
     *out = c;
@@ -256,6 +283,7 @@ int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, 
 void ff_sim_chains_destroy(ff_chains_t* c) {
     if (!c) return;
     hipFree(c->d_cfgs);
+    hipFree(c->d_flags);
     hipFree(c->d_slots);
     delete c;
 }

@@ -8,37 +8,58 @@ namespace ffsim {
 typedef unsigned long long u64;
 typedef uint32_t u32;
 
-constexpr u64 KEY_NONE = ~0ull;   // "no pending event" in the event tree
-constexpr u64 KEY_INTERNAL = ~0ull - 1;   // result when an internal consistency check fails
 constexpr int WAVE = 64;
 
-struct DMap { int32_t src_dim; uint32_t stride; int32_t a, b; };
-struct DEdge { uint32_t src, dst; DMap map[4]; };
+// ---- one 64-bit word per compute task (index op*64 + part) -----------------------------
+//   bit 63 clear: a pending event of the task, word = time*2 + kind
+//       kind 1: the task is READY and waits to be dequeued, time = readyTime
+//       kind 0: the task was dequeued, time = endTime; its successors are released then
+//   bit 63 set:  no pending event
+//       W_NONE                       unused lane, or the task is complete
+//       W_WAIT | pending<<48 | ready the task still waits for `pending` inputs; `ready` is
+//                                    the largest endTime among the inputs seen so far
+// Words with bit 63 set compare greater than every event, so a plain unsigned minimum over
+// words finds the next event.
+constexpr u64 W_NONE = ~0ull;
+constexpr u64 W_WAIT = 1ull << 63;
+constexpr u64 TIME_LIMIT = 1ull << 48;      // times must stay below this (about 78 hours)
+constexpr u32 PENDING_LIMIT = 0x7fff;       // a task may wait for fewer than this many inputs
+
+// results that are not times
+constexpr u64 RESULT_INVALID = ~0ull;        // invalid strategy
+constexpr u64 RESULT_INTERNAL = ~0ull - 1;   // internal consistency check failed (a bug)
+constexpr u64 RESULT_OVERFLOW = ~0ull - 2;   // a simulated time reached TIME_LIMIT
+
+// cext = extent of the consumer's dim src_dim (1 if src_dim < 0)
+struct DMap { int32_t src_dim; uint32_t stride; int32_t a, b; uint32_t cext; };
+// a tensor edge with the shapes of both ends inlined, so that releasing the successors of
+// a finished producer needs no second table lookup
+struct DEdge {
+    uint32_t src, dst, src_ndim, dst_ndim;
+    uint32_t src_extent[4];
+    uint32_t dst_extent[4];
+    DMap map[4];                 // indexed by producer dim
+};
 struct DOp {
     uint32_t extent[4];          // 1 beyond ndim
     uint32_t ndim, par_mask;
     uint32_t out_begin, out_end; // range in edges[] (edges are sorted by producer)
     uint32_t in_begin, in_end;   // range in in_list[]
+    uint32_t first_dst;          // consumer of edges[out_begin] (prefetch hint), 0 if none
+    uint32_t pad;
 };
 
-// everything a kernel needs about (G, D, cost table); passed by value
+// scalars describing (G, D, cost table); passed by value
 struct SimDev {
-    const DOp* ops;
-    const DEdge* edges;
-    const uint32_t* in_list;     // edge ids grouped by consumer op
-    const uint32_t* cost;        // [n_ops][n_cols]
-    const uint32_t* magic;       // magic[d] = floor(2^32/d)+1 for d in 2..64
     uint32_t n_ops, n_edges, n_cols, max_parts;
     uint32_t n_nodes, gpus_per_node, n_dev, n_rows;
     uint32_t bw_intra, bw_inter, lat_intra, lat_inter, elem_bytes;
     uint32_t m_bw_intra, m_bw_inter;   // floor(2^32 / bw) (2^32-1 for bw = 1)
-    uint32_t magic_dev, magic_gpn;     // floor(2^32/d)+1 for d = n_dev, gpus_per_node
+    uint32_t magic_dev, magic_gpn;     // floor(2^32/d)+1 for d = n_dev, gpus_per_node (0 if d = 1)
+    uint32_t pass_dev, pass_gpn;       // all ones iff the divisor is 1
     uint32_t n_ops_pad;                // n_ops rounded up to a multiple of 64
     uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
 };
-
-// per-task simulation state kept in HBM: index = op*64 + part
-struct TaskState { u64 ready; uint32_t pending; uint32_t pad; };
 
 __device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }
 
@@ -52,6 +73,7 @@ __device__ __forceinline__ void wave_sync() {
 
 // the readlane / readfirstlane builtins return int: go through uint32_t before widening
 __device__ __forceinline__ uint32_t first_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ u64 first_u64(u64 v) { return (u64)first_u32((uint32_t)v) | ((u64)first_u32((uint32_t)(v >> 32)) << 32); }
 __device__ __forceinline__ uint32_t readlane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
 __device__ __forceinline__ u64 readlane_u64(u64 v, int l) {
     return (u64)readlane_u32((uint32_t)v, l) | ((u64)readlane_u32((uint32_t)(v >> 32), l) << 32);
@@ -66,14 +88,16 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int m) {
 
 // lane i of every row of 16 lanes reads lane perm(i) of the same row (DPP controls:
 // quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141,
-// row_mirror = 0x140); all of them are permutations, so every lane reads a valid lane
+// row_mirror = 0x140); all of them are permutations, so every lane reads a valid lane.
+// Call only with all 64 lanes active.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
-    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+    // old = 0 with bound_ctrl lets the compiler fold the move into the consuming instruction
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
 }
 
-// wavefront-wide min / max of a 32-bit value, uniform result: butterfly inside each row of
-// 16 lanes with DPP, then the four row results are combined on the scalar unit
+// wavefront-wide min of a 32-bit value, uniform result: butterfly inside each row of 16
+// lanes with DPP, then the four row results are combined on the scalar unit
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
     uint32_t t;
     t = dpp_u32<0xB1>(v); v = t < v ? t : v;
@@ -85,7 +109,6 @@ __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
     c = c < d ? c : d;
     return a < c ? a : c;
 }
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) { return ~wave_min_u32(~v); }
 
 // minimum over the wavefront, uniform result: high words first, then the low words of the
 // lanes that hold the minimal high word
@@ -97,13 +120,10 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
 }
 __device__ __forceinline__ u64 wave_max_u64(u64 v) { return ~wave_min_u64(~v); }
 
-// floor(n / d) for d in 1..64 and n <= 2^26 (part boundaries, part-index decoding)
-__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t d, const uint32_t* magic) {
-    return d == 1 ? n : __umulhi(n, magic[d]);
-}
-// floor(n / d) with a precomputed magic = floor(2^32/d)+1, valid while n*d < 2^32
-__device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t d, uint32_t magic) {
-    return d == 1 ? n : __umulhi(n, magic);
+// floor(n / d) with magic = floor(2^32/d)+1 (0 if d = 1) and pass = all ones iff d = 1;
+// exact while n*d < 2^32; no branch
+__device__ __forceinline__ uint32_t div_magic(uint32_t n, uint32_t magic, uint32_t pass) {
+    return __umulhi(n, magic) + (n & pass);
 }
 // ceil(n / d) for any 32-bit n >= 1, m = floor(2^32/d) (one fix-up step)
 __device__ __forceinline__ uint32_t ceil_div_u32(uint32_t n, uint32_t d, uint32_t m) {
