@@ -38,6 +38,7 @@ struct ff_sim {
     uint32_t* d_magic = nullptr;
     bool wide = false;            // some tensor has 2^32 bytes or more
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
+    bool lds_cfgs = false;        // the candidate's configurations are staged in LDS
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
     size_t lds = 0;               // dynamic LDS per wavefront, batch kernel
     size_t lds_chain = 0;         // dynamic LDS per wavefront, chain kernel (words always in HBM)
@@ -61,8 +62,8 @@ typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, c
                                const uint32_t*, uint32_t, u64*, uint32_t*, unsigned char*, size_t);
 
 static batch_kernel_t batch_kernel(const ff_sim* s) {
-    if (s->wide) return s->lds_words ? k_sim_batch<true, true> : k_sim_batch<true, false>;
-    return s->lds_words ? k_sim_batch<false, true> : k_sim_batch<false, false>;
+    if (s->wide) return s->lds_words ? k_sim_batch<true, true, false> : (s->lds_cfgs ? k_sim_batch<true, false, true> : k_sim_batch<true, false, false>);
+    return s->lds_words ? k_sim_batch<false, true, false> : (s->lds_cfgs ? k_sim_batch<false, false, true> : k_sim_batch<false, false, false>);
 }
 static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
 
@@ -152,8 +153,9 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
             ops[i].out_begin = k;
             while (k < g->n_edges && edges[k].src == i) k++;
             ops[i].out_end = k;
-            ops[i].first_dst = ops[i].out_end > ops[i].out_begin ? edges[ops[i].out_begin].dst : 0;
-            ops[i].pad = 0;
+            ops[i].pad0 = ops[i].pad1 = 0;
+            if (ops[i].out_end > ops[i].out_begin) ops[i].first = edges[ops[i].out_begin];
+            else std::memset(&ops[i].first, 0, sizeof(DEdge));
         }
     }
     std::vector<DEdge> in_edges(g->n_edges);
@@ -196,9 +198,12 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     if (s->lds_chain > 64 * 1024) { release(s); return FF_ERANGE; }
     // small graphs keep a candidate's task words in LDS, as long as four wavefronts (one per
     // SIMD) still fit in a CU's 160 KB
+    const size_t cfg_bytes = (size_t)S.n_ops_pad * 8;
     const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_chain;
     s->lds_words = lds_with_words <= 40 * 1024;
-    s->lds = s->lds_words ? lds_with_words : s->lds_chain;
+    // configurations alone are staged if sixteen wavefronts per CU (four per SIMD) still fit
+    s->lds_cfgs = false;   // measured: no gain on MI355X (the scalar cache already serves these look-ups)
+    s->lds = s->lds_words ? lds_with_words : (s->lds_cfgs ? s->lds_chain + cfg_bytes : s->lds_chain);
 
     int dev_id = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev_id) != hipSuccess ||

@@ -45,8 +45,9 @@ struct DOp {
     uint32_t ndim, par_mask;
     uint32_t out_begin, out_end; // range in edges[] (edges are sorted by producer)
     uint32_t in_begin, in_end;   // range in in_list[]
-    uint32_t first_dst;          // consumer of edges[out_begin] (prefetch hint), 0 if none
-    uint32_t pad;
+    uint32_t pad0, pad1;
+    DEdge first;                 // copy of edges[out_begin] (most ops have one consumer): one
+                                 // scalar burst brings the op and its first out-edge
 };
 
 // scalars describing (G, D, cost table); passed by value
@@ -119,6 +120,17 @@ __device__ __forceinline__ u64 wave_min_u64(u64 v) {
     return ((u64)mhi << 32) | mlo;
 }
 __device__ __forceinline__ u64 wave_max_u64(u64 v) { return ~wave_min_u64(~v); }
+
+// Same minimum for words that are all >= base (pending events never lie before the event
+// popped last): one 32-bit reduction over the saturated distance to base; the 64-bit
+// reduction only runs if every distance is 2^32-1 or more (no event, or a far one).
+__device__ __forceinline__ u64 wave_min_from(u64 v, u64 base) {
+    const u64 d = v - base;
+    const uint32_t sat = (uint32_t)(d >> 32) ? 0xffffffffu : (uint32_t)d;
+    const uint32_t m = wave_min_u32(sat);
+    if (m != 0xffffffffu) return base + m;
+    return wave_min_u64(v);
+}
 
 // floor(n / d) with magic = floor(2^32/d)+1 (0 if d = 1) and pass = all ones iff d = 1;
 // exact while n*d < 2^32; no branch

@@ -20,6 +20,23 @@
 
 namespace ffsim {
 
+// up to this many groups of 64 ops the queue has no level 2: lanes scan level 1 directly
+constexpr uint32_t FLAT_GROUPS = 8;
+
+// Section timing for development builds (-DFFSIM_PROFILE): shader-clock ticks per section are
+// accumulated in a register array and reported through the stats record instead of the
+// usual counters.  Compiled out otherwise.
+#ifdef FFSIM_PROFILE
+#define PROF_DECL u64 prof_t[8] = {0, 0, 0, 0, 0, 0, 0, 0}; u64 prof_last = __builtin_readcyclecounter();
+#define PROF_MARK(k) { const u64 prof_now = __builtin_readcyclecounter(); prof_t[k] += prof_now - prof_last; prof_last = prof_now; }
+#define PROF_STORE(c) { c.n_compute = prof_t[0]; c.n_pairs = prof_t[1]; c.n_comm = prof_t[2]; c.sum_comm_ns = lane_id() == 0 ? prof_t[3] : 0; \
+                        c.exit_code = prof_t[4]; c.n_stuck = prof_t[5]; c.want_check = prof_t[6]; }
+#else
+#define PROF_DECL
+#define PROF_MARK(k)
+#define PROF_STORE(c)
+#endif
+
 struct Counters { u64 n_compute, n_pairs, n_comm, sum_comm_ns, n_events, exit_code, n_stuck, want_check; };
 
 // read-only tables shared by all candidates (pointers come from __restrict__ kernel
@@ -177,43 +194,51 @@ __device__ __forceinline__ uint32_t owner_part(uint32_t x, uint32_t E, uint32_t 
 
 // Serialise tasks that become ready at the same time r on device rows, in lane order
 // (= id order): end = max(r, row free time) + running sum of exeTimes on that row.
-// Lanes whose row is used by no other lane go in one parallel step; rows shared by several
-// lanes are handled one row at a time.  `may_share` = false promises distinct rows.
+// One LDS round trip: every lane writes its lane id to a one-byte tag of its row, then reads
+// the tag back together with the row's free time.  A lane that reads another lane's id
+// shares its row; the lanes of such rows are grouped and ranked with ballots (never through
+// memory), everybody else is done at once.  The last lane of every row writes the new free
+// time.  `may_share` = false promises distinct rows and skips the tags.
 __device__ __forceinline__ u64 fifo_commit(bool act, uint32_t row, u64 exe, u64 r, bool may_share, const WaveLds& L) {
     const int lane = lane_id();
-    u64 end = 0;
-    bool slow = false;
+    u64 f = 0;
+    bool lost = false;
     if (may_share) {
         if (act) L.tag[row] = (uint8_t)lane;
         wave_sync();
-        const bool lost = act && L.tag[row] != (uint8_t)lane;
-        if (__ballot(lost)) {
-            if (lost) L.tag[row] = 0xff;
-            wave_sync();
-            slow = act && L.tag[row] == 0xff;
-        }
+        if (act) { lost = L.tag[row] != (uint8_t)lane; f = L.free_at[row]; }
+    } else if (act) {
+        f = L.free_at[row];
     }
-    if (act && !slow) {
-        const u64 f = L.free_at[row];
-        end = (f > r ? f : r) + exe;
-        L.free_at[row] = end;
-    }
-    u64 todo = __ballot(slow);
+    const u64 base = f > r ? f : r;         // identical for all lanes of one row
+    u64 end = base + exe;
+    bool last = act;
+    u64 todo = __ballot(lost);
     while (todo) {
         const int l = __builtin_ctzll(todo);
         const uint32_t lrow = readlane_u32(row, l);
-        u64 peers = __ballot(slow && row == lrow);
+        const bool peer = act && row == lrow;   // includes the lane whose tag survived
+        const u64 peers = __ballot(peer);
         todo &= ~peers;
-        const u64 f = first_u64(L.free_at[lrow]);
-        u64 t = f > r ? f : r;
-        while (peers) {
-            const int p = __builtin_ctzll(peers);
-            peers &= peers - 1;
-            t += readlane_u64(exe, p);
-            if (lane == p) end = t;
+        const int first = __builtin_ctzll(peers);
+        const u64 exe_l = readlane_u64(exe, first);
+        if (!__ballot(peer && exe != exe_l)) {
+            // equal exeTimes (symmetric parts): the position in the group is enough
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u)) + 1;
+            if (peer) end = base + (u64)rank * exe;
+        } else {
+            u64 t = 0;
+            u64 pm = peers;
+            while (pm) {
+                const int p = __builtin_ctzll(pm);
+                pm &= pm - 1;
+                t += readlane_u64(exe, p);
+                if (lane == p) end = base + t;
+            }
         }
-        if (lane == l) L.free_at[lrow] = t;
+        if (peer) last = lane == 63 - __builtin_clzll(peers);
     }
+    if (last) L.free_at[row] = end;
     wave_sync();
     return end;
 }
@@ -227,6 +252,7 @@ template <bool WIDE>
 __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2* cfgs, u64* words, uint32_t* exe_of,
                                   const WaveLds& L, uint32_t magic_v, Counters& cnt) {
     const int lane = lane_id();
+    PROF_DECL
     const DOp* __restrict__ ops = T.ops;
     const DEdge* __restrict__ edges = T.edges;
     const DEdge* __restrict__ in_edges = T.in_edges;
@@ -245,12 +271,12 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
     //      waits for (in closed form per in-edge), and the initial READY set ----
     for (uint32_t r = lane; r < S.n_rows; r += WAVE) L.free_at[r] = 0;
     for (uint32_t j = 0; j < S.n_ops; j++) {
-        const DOp opj = ops[j];
+        const uint32_t in_begin = ops[j].in_begin, in_end = ops[j].in_end;
         const OpCfg cj = unpack_cfg(cfgs[j]);
         const bool mine = (uint32_t)lane < cj.parts;
         const uint32_t digits = part_digits(cj, lane, magic_v);
         uint32_t pending = 0;
-        for (uint32_t q = opj.in_begin; q < opj.in_end; q++) {
+        for (uint32_t q = in_begin; q < in_end; q++) {
             const DEdge e = in_edges[q];
             const OpCfg ci = unpack_cfg(cfgs[e.src]);
             uint32_t n = 1;
@@ -279,7 +305,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
     }
     for (uint32_t j = S.n_ops + lane; j < S.n_ops_pad; j += WAVE) L.l1[j] = W_NONE;
     wave_sync();
-    if (S.n_groups > 1) {
+    if (S.n_groups > FLAT_GROUPS) {
         for (uint32_t g = 0; g < S.n_groups; g++) {
             const u64 wmin = wave_min_u64(L.l1[g * WAVE + lane]);
             if (lane == 0) L.l2[g] = wmin;
@@ -287,29 +313,49 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
         wave_sync();
     }
 
+    PROF_MARK(0)
     // ---- Algorithm 1, main loop ----
     bool overflow = false;
+    u64 last_key = 0;
     const u64 max_events = 2ull * S.n_ops * WAVE + 8;   // every task is popped at most twice
     for (u64 ev = 0; ev < max_events; ev++) {
-        u64 kmin, k1;
-        uint32_t g = 0;
-        if (S.n_groups > 1) {
+        u64 kmin;
+        uint32_t i;
+        if (S.n_groups > FLAT_GROUPS) {
             const u64 k2 = (uint32_t)lane < S.n_groups ? L.l2[lane] : W_NONE;
-            kmin = wave_min_u64(k2);
+            kmin = wave_min_from(k2, last_key);
             if (kmin >> 63) break;
-            g = __builtin_ctzll(__ballot(k2 == kmin));
-            k1 = L.l1[g * WAVE + lane];
+            const uint32_t g = __builtin_ctzll(__ballot(k2 == kmin));
+            const u64 k1 = L.l1[g * WAVE + lane];
+            const u64 m1 = __ballot(k1 == kmin);
+            if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }   // tree inconsistent: give up, never spin
+            i = g * WAVE + __builtin_ctzll(m1);
         } else {
-            k1 = L.l1[lane];
-            kmin = wave_min_u64(k1);
+            // few ops: every lane scans its column of level 1, no level 2
+            u64 k1 = L.l1[lane];
+            uint32_t gbest = 0;
+            for (uint32_t g = 1; g < S.n_groups; g++) {
+                const u64 k = L.l1[g * WAVE + lane];
+                if (k < k1) { k1 = k; gbest = g; }
+            }
+            kmin = wave_min_from(k1, last_key);
             if (kmin >> 63) break;
+            // lowest op index among equal keys: smallest group first, then lowest lane
+            u64 m1 = __ballot(k1 == kmin);
+            if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }
+            if (m1 & (m1 - 1)) {    // several columns hold the minimum: smallest group wins
+                const uint32_t gmin = wave_min_u32(k1 == kmin ? gbest : 0xffffffffu);
+                m1 = __ballot(k1 == kmin && gbest == gmin);
+            }
+            const int col = __builtin_ctzll(m1);
+            i = readlane_u32(gbest, col) * WAVE + col;
         }
-        const u64 m1 = __ballot(k1 == kmin);
-        if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }   // tree inconsistent: give up, never spin
-        const uint32_t i = g * WAVE + __builtin_ctzll(m1);
+        last_key = kmin;
+        PROF_MARK(1)
         // everything that depends only on i is requested together
         u64 k0 = words[i * WAVE + lane];
-        const DOp opi = ops[i];
+        const DOp* __restrict__ opi_p = ops + i;
+        const uint32_t out_begin = opi_p->out_begin, out_end = opi_p->out_end;
         const OpCfg ci = unpack_cfg(cfgs[i]);
         const u64 exe = exe_of[i];
         const u64 mask = __ballot(k0 == kmin);            // parts of op i that hold the minimum
@@ -324,13 +370,15 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
             const bool may_share = !(ci.stride == 1 && ci.parts <= S.n_dev);
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
-            if (in_mask) k0 = opi.out_end > opi.out_begin ? end << 1 : W_NONE;
+            if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
+            PROF_MARK(2)
         } else {
             // the parts in `mask` finished at `now`: release their successors edge by edge
-            const Box pb = part_box(opi.extent, ci, lane, magic_v);
+            DEdge e = opi_p->first;
+            const Box pb = part_box(e.src_extent, ci, lane, magic_v);
             const uint32_t node_p = div_magic(dev_p, S.magic_gpn, S.pass_gpn);
-            for (uint32_t ei = opi.out_begin; ei < opi.out_end; ei++) {
-                const DEdge e = edges[ei];
+            for (uint32_t ei = out_begin; ei < out_end; ei++) {
+                if (ei != out_begin) e = edges[ei];
                 const uint32_t j = e.dst;
                 u64 w = words[j * WAVE + lane];
                 const OpCfg cj = unpack_cfg(cfgs[j]);
@@ -348,6 +396,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
                 bool touched = false;
                 u64 todo = mask;
+                PROF_MARK(3)
                 while (todo) {
                     const int kp = __builtin_ctzll(todo);
                     todo &= todo - 1;
@@ -403,6 +452,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
                     }
                     if (cnt.want_check) cnt.n_pairs += __popcll(hit_mask);
                 }
+                PROF_MARK(4)
                 overflow = overflow || (touched && ready >= TIME_LIMIT);
                 const bool now_ready = touched && pending == 0;
                 if (touched) {
@@ -410,25 +460,28 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
                     words[j * WAVE + lane] = w;
                 }
                 if (__ballot(now_ready)) {
-                    const u64 nmin = wave_min_u64(now_ready ? w : W_NONE);
+                    const u64 nmin = wave_min_from(now_ready ? w : W_NONE, last_key);
                     if (lane == 0) {
                         if (nmin < L.l1[j]) L.l1[j] = nmin;
-                        if (S.n_groups > 1 && nmin < L.l2[j >> 6]) L.l2[j >> 6] = nmin;
+                        if (S.n_groups > FLAT_GROUPS && nmin < L.l2[j >> 6]) L.l2[j >> 6] = nmin;
                     }
                 }
+                PROF_MARK(5)
             }
             if (in_mask) k0 = W_NONE;
         }
         if (in_mask) words[i * WAVE + lane] = k0;
-        const u64 new_l1 = wave_min_u64(k0);
+        const u64 new_l1 = wave_min_from(k0, last_key);
         wave_sync();
         if (lane == 0) L.l1[i] = new_l1;
         wave_sync();
-        if (S.n_groups > 1) {
-            const u64 new_l2 = wave_min_u64(L.l1[g * WAVE + lane]);
+        if (S.n_groups > FLAT_GROUPS) {
+            const uint32_t g = i >> 6;
+            const u64 new_l2 = wave_min_from(L.l1[g * WAVE + lane], last_key);
             if (lane == 0) L.l2[g] = new_l2;
             wave_sync();
         }
+        PROF_MARK(6)
     }
     if (__ballot(overflow)) return RESULT_OVERFLOW;
 
@@ -439,6 +492,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
     // later, so the makespan is the largest free time over the compute device rows.
     u64 mk = 0;
     for (uint32_t d = lane; d < S.n_dev; d += WAVE) mk = L.free_at[d] > mk ? L.free_at[d] : mk;
+    PROF_STORE(cnt)
     return wave_max_u64(mk);
 }
 
@@ -453,8 +507,10 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 // lane l gets the multiply-high constant of the divisor l+1
 __device__ __forceinline__ uint32_t load_magic(const uint32_t* __restrict__ magic) { return magic[lane_id() + 1]; }
 
-// LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs)
-template <bool WIDE, bool LDSW>
+// LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
+// CFGL: the candidate's configurations are copied to LDS first (graphs of moderate size), so
+// that the many uniform look-ups of a configuration do not go to memory.
+template <bool WIDE, bool LDSW, bool CFGL>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -474,12 +530,22 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
         words = (u64*)slot;
         exe_of = (uint32_t*)(slot + (size_t)S.n_ops * WAVE * 8);
     }
+    uint2* cfg_lds = (uint2*)lds_rest;
+    if (CFGL) lds_rest += (size_t)S.n_ops_pad * 8;
     const WaveLds L = carve_lds(lds_rest, S);
     const uint32_t magic_v = load_magic(magic);
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
         cnt.want_check = stats != nullptr;
-        const u64 mk = simulate_candidate<WIDE>(S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, cnt);
+        const uint2* cfgs = strategies + (size_t)b * S.n_ops;
+        u64 mk;
+        if (CFGL) {
+            for (uint32_t i = lane_id(); i < S.n_ops; i += WAVE) cfg_lds[i] = cfgs[i];
+            wave_sync();
+            mk = simulate_candidate<WIDE>(S, T, cfg_lds, words, exe_of, L, magic_v, cnt);
+        } else {
+            mk = simulate_candidate<WIDE>(S, T, cfgs, words, exe_of, L, magic_v, cnt);
+        }
         if (lane_id() == 0) out_ns[b] = mk;
         if (stats) store_counters(cnt, stats + b);
         wave_sync();
