@@ -163,7 +163,9 @@ int ff_sim_batch(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t B, uint
 /* Delta simulation (Section 5.3, Algorithm 2's contract: same timeline as a full simulation
  * of the changed strategy).  A chain set holds C current strategies on the device;
  * d_out_ns0[c] receives the time of the starting strategies.  The library owns the
- * chains' state. */
+ * chains' state and allocates it here with hipMalloc: per chain the strategy, one word and
+ * one endTime per possible task, and 32 snapshots of the simulation state (about
+ * 34 * 512 * n_ops bytes).  Destroy only after the work queued on the stream has finished. */
 int ff_sim_chains_create(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t C, uint64_t* d_out_ns0,
                          void* hip_stream, ff_chains_t** out);
 /* Applies d_muts[s][c] (step-major, [n_steps][C]) to chain c for s = 0..n_steps-1,
@@ -172,6 +174,15 @@ int ff_sim_chains_create(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t
 int ff_sim_delta(ff_chains_t* chains, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out_ns,
                  void* hip_stream);
 void ff_sim_chains_destroy(ff_chains_t* chains);
+
+/* Telemetry of the chains (HOST array of C records; synchronises the device): how many
+ * mutations were applied, how many of them resumed from a stored snapshot of the timeline
+ * instead of simulating from time 0, how many queue pops they took in total, and how many
+ * pops the last simulation from time 0 took. */
+typedef struct {
+    uint64_t n_steps, n_resumed, n_events, n_events_full;
+} ff_chain_stats_t;
+int ff_sim_chains_get_stats(ff_chains_t* chains, ff_chain_stats_t* h_out);
 
 const char* ff_sim_strerror(int code);
 

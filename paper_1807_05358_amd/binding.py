@@ -33,7 +33,9 @@ class ff_costtable_t(C.Structure):
 
 
 EXPORTS = ["ff_sim_create", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
-           "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_strerror"]
+           "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
+           "ff_sim_strerror"]
+CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8")])
 
 _lib = None
 
@@ -66,6 +68,8 @@ def lib():
         L.ff_sim_delta.argtypes = [vp, vp, u32, vp, vp]
         L.ff_sim_chains_destroy.restype = None
         L.ff_sim_chains_destroy.argtypes = [vp]
+        L.ff_sim_chains_get_stats.restype = C.c_int
+        L.ff_sim_chains_get_stats.argtypes = [vp, vp]
         L.ff_sim_strerror.restype = C.c_char_p
         L.ff_sim_strerror.argtypes = [C.c_int]
         _lib = L
@@ -129,6 +133,12 @@ def ff_sim_delta(chains, d_muts, n_steps, d_out_ns, stream=None):
 
 def ff_sim_chains_destroy(chains):
     lib().ff_sim_chains_destroy(chains)
+
+
+def ff_sim_chains_get_stats(chains, n_chains):
+    out = np.zeros(n_chains, CHAIN_STATS_DT)
+    _check(lib().ff_sim_chains_get_stats(chains, out.ctypes.data), "ff_sim_chains_get_stats")
+    return out
 
 
 # ---- convenience on top of the boundary: torch tensors for device memory -----------------
@@ -236,6 +246,9 @@ class Chains:
         ff_sim_delta(self.handle, d_muts.data_ptr(), n_steps, d_out.data_ptr(),
                      torch.cuda.current_stream().cuda_stream)
         return d_out
+
+    def stats(self):
+        return ff_sim_chains_get_stats(self.handle, self.C)
 
     def close(self):
         if self.handle:

@@ -38,10 +38,10 @@ struct ff_sim {
     uint32_t* d_magic = nullptr;
     bool wide = false;            // some tensor has 2^32 bytes or more
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
-    bool lds_cfgs = false;        // the candidate's configurations are staged in LDS
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
     size_t lds = 0;               // dynamic LDS per wavefront, batch kernel
-    size_t lds_chain = 0;         // dynamic LDS per wavefront, chain kernel (words always in HBM)
+    size_t lds_common = 0;        // device rows + queue levels 1 and 2
+    size_t lds_chain = 0;         // dynamic LDS per wavefront, chain kernel (adds the strategy; words in HBM)
     uint32_t max_slots = 0;       // wavefronts the device can hold at once
     void* ws = nullptr;
     size_t ws_bytes = 0;
@@ -51,19 +51,22 @@ struct ff_sim {
 struct ff_chains {
     ff_sim* sim = nullptr;
     uint32_t C = 0;
-    uint2* d_cfgs = nullptr;       // [C][n_ops] current strategies
+    uint32_t n_snaps = 0;
+    size_t stride = 0;             // bytes per chain
+    unsigned char* d_mem = nullptr; // [C] chain blocks: strategy, task words, endTimes, snapshots
     uint32_t* d_flags = nullptr;   // [C] nonzero once a chain saw an out-of-range mutation
-    unsigned char* d_slots = nullptr;
 };
+
+constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 
 typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const uint2*,
                                uint32_t, u64*, Counters*, unsigned char*, size_t);
-typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, uint2*, uint32_t,
-                               const uint32_t*, uint32_t, u64*, uint32_t*, unsigned char*, size_t);
+typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
+                               uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*);
 
 static batch_kernel_t batch_kernel(const ff_sim* s) {
-    if (s->wide) return s->lds_words ? k_sim_batch<true, true, false> : (s->lds_cfgs ? k_sim_batch<true, false, true> : k_sim_batch<true, false, false>);
-    return s->lds_words ? k_sim_batch<false, true, false> : (s->lds_cfgs ? k_sim_batch<false, false, true> : k_sim_batch<false, false, false>);
+    if (s->wide) return s->lds_words ? k_sim_batch<true, true> : k_sim_batch<true, false>;
+    return s->lds_words ? k_sim_batch<false, true> : k_sim_batch<false, false>;
 }
 static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
 
@@ -194,16 +197,14 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     S.n_groups = S.n_ops_pad / 64;
     s->wide = max_bytes >= ((unsigned __int128)1 << 32);
     s->slot_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 255) & ~(size_t)255;
-    s->lds_chain = lds_common_bytes(S.n_rows, S.n_ops_pad);
+    s->lds_common = lds_common_bytes(S.n_rows, S.n_ops_pad);
+    s->lds_chain = s->lds_common + (size_t)S.n_ops_pad * 8;
     if (s->lds_chain > 64 * 1024) { release(s); return FF_ERANGE; }
     // small graphs keep a candidate's task words in LDS, as long as four wavefronts (one per
     // SIMD) still fit in a CU's 160 KB
-    const size_t cfg_bytes = (size_t)S.n_ops_pad * 8;
-    const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_chain;
+    const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_common;
     s->lds_words = lds_with_words <= 40 * 1024;
-    // configurations alone are staged if sixteen wavefronts per CU (four per SIMD) still fit
-    s->lds_cfgs = false;   // measured: no gain on MI355X (the scalar cache already serves these look-ups)
-    s->lds = s->lds_words ? lds_with_words : (s->lds_cfgs ? s->lds_chain + cfg_bytes : s->lds_chain);
+    s->lds = s->lds_words ? lds_with_words : s->lds_common;
 
     int dev_id = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev_id) != hipSuccess ||
@@ -253,8 +254,8 @@ static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_
     ff_sim* s = c->sim;
     static_assert(sizeof(ff_mutation_t) == 12, "mutation layout");
     hipLaunchKernelGGL(chain_kernel(s), dim3(c->C), dim3(WAVE), s->lds_chain, st, s->dev, s->d_ops, s->d_edges, s->d_in_edges,
-                       s->d_cost, s->d_magic, c->d_cfgs, c->C, (const uint32_t*)d_muts, n_steps, (u64*)d_out, c->d_flags,
-                       c->d_slots, s->slot_bytes);
+                       s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, n_steps,
+                       (u64*)d_out, c->d_flags);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
@@ -267,12 +268,20 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
     if (!c) return FF_ENOMEM;
     c->sim = s;
     c->C = C;
+    c->n_snaps = CHAIN_SNAPSHOTS;
+    c->stride = chain_bytes(s->dev.n_ops, s->dev.n_ops_pad, s->dev.n_rows, c->n_snaps);
     hipStream_t st = (hipStream_t)hip_stream;
-    size_t cfg_bytes = (size_t)C * s->dev.n_ops * sizeof(uint2);
-    if (hipMalloc((void**)&c->d_cfgs, cfg_bytes) != hipSuccess || hipMalloc((void**)&c->d_flags, (size_t)C * 4) != hipSuccess ||
-        hipMalloc((void**)&c->d_slots, (size_t)C * s->slot_bytes) != hipSuccess) { ff_sim_chains_destroy(c); return FF_ENOMEM; }
-    if (hipMemcpyAsync(c->d_cfgs, d_strategies, cfg_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess ||
-        hipMemsetAsync(c->d_flags, 0, (size_t)C * 4, st) != hipSuccess) { ff_sim_chains_destroy(c); return FF_EHIP; }
+    const size_t row_bytes = (size_t)s->dev.n_ops * sizeof(uint2);
+    if (hipMalloc((void**)&c->d_mem, (size_t)C * c->stride) != hipSuccess ||
+        hipMalloc((void**)&c->d_flags, (size_t)C * 4) != hipSuccess) { ff_sim_chains_destroy(c); return FF_ENOMEM; }
+    // zero everything (snapshot bookkeeping starts empty), then drop each chain's strategy at
+    // the head of its block
+    if (hipMemsetAsync(c->d_mem, 0, (size_t)C * c->stride, st) != hipSuccess ||
+        hipMemsetAsync(c->d_flags, 0, (size_t)C * 4, st) != hipSuccess ||
+        hipMemcpy2DAsync(c->d_mem, c->stride, d_strategies, row_bytes, row_bytes, C, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+        ff_sim_chains_destroy(c);
+        return FF_EHIP;
+    }
     int rc = launch_chain_steps(c, nullptr, 1, d_out_ns0, st);
     if (rc) { ff_sim_chains_destroy(c); return rc; }
     *out = c;
@@ -285,11 +294,26 @@ int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, 
     return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream);
 }
 
+int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
+    if (!c || !h_out) return FF_EINVAL;
+    if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;
+    static_assert(sizeof(ChainMeta) == 16 + sizeof(ff_chain_stats_t), "chain stats layout");
+    for (uint32_t k = 0; k < c->C; k++) {
+        ChainMeta meta;
+        const unsigned char* p = c->d_mem + (size_t)k * c->stride + chain_meta_offset(c->sim->dev.n_ops, c->sim->dev.n_ops_pad, c->sim->dev.n_rows, c->n_snaps);
+        if (hipMemcpy(&meta, p, sizeof(meta), hipMemcpyDeviceToHost) != hipSuccess) return FF_EHIP;
+        h_out[k].n_steps = meta.n_steps;
+        h_out[k].n_resumed = meta.n_resumed;
+        h_out[k].n_events = meta.n_events;
+        h_out[k].n_events_full = meta.n_events_full;
+    }
+    return FF_OK;
+}
+
 void ff_sim_chains_destroy(ff_chains_t* c) {
     if (!c) return;
-    hipFree(c->d_cfgs);
+    hipFree(c->d_mem);
     hipFree(c->d_flags);
-    hipFree(c->d_slots);
     delete c;
 }
 

@@ -243,80 +243,165 @@ __device__ __forceinline__ u64 fifo_commit(bool act, uint32_t row, u64 exe, u64 
     return end;
 }
 
-// One candidate: build + simulate.  cfgs = its n_ops configurations; words / exe_of = this
-// wavefront's task words [n_ops*64] and per-op exeTime [n_ops] (LDS or HBM).  Returns the
-// makespan or one of the RESULT_* codes.  cfgs is deliberately not __restrict__: the chain
-// kernel rewrites it between calls, so loads from it must not be treated as invariant.
-// WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
-template <bool WIDE>
-__device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2* cfgs, u64* words, uint32_t* exe_of,
-                                  const WaveLds& L, uint32_t magic_v, Counters& cnt) {
-    const int lane = lane_id();
-    PROF_DECL
-    const DOp* __restrict__ ops = T.ops;
-    const DEdge* __restrict__ edges = T.edges;
-    const DEdge* __restrict__ in_edges = T.in_edges;
-    const uint32_t* __restrict__ cost = T.cost;
+// Everything one wavefront needs to simulate its candidate.  cfgs is deliberately not
+// __restrict__: the chain kernel rewrites a configuration between simulations, so loads
+// from it must not be treated as invariant.
+struct Sim {
+    const SimDev& S;
+    const Tables& T;
+    const uint2* cfgs;       // the candidate's n_ops configurations
+    u64* words;              // [n_ops*64] task words (LDS or HBM)
+    uint32_t* exe_of;        // [n_ops] exeTime of the op's tasks under its configuration
+    const WaveLds& L;
+    uint32_t magic_v;
+    u64 last_key;            // lower bound of every pending event word
+    bool overflow;
+};
 
-    // ---- validate the strategy (lanes over ops) ----
-    bool bad = false;
-    for (uint32_t i = lane; i < S.n_ops; i += WAVE) {
-        OpCfg c = unpack_cfg_lane(cfgs[i]);
-        if (!cfg_ok(ops[i], c, S)) bad = true;
-        else exe_of[i] = cost[(size_t)i * S.n_cols + (c.parts - 1)];
-    }
-    if (__ballot(bad)) return RESULT_INVALID;
+// Optional recording for delta simulation: endTime of every task, and snapshots of the
+// simulation state whenever the event time crosses a multiple of `step`.
+struct Recorder {
+    u64* end_of;             // [n_ops*64]
+    u64* snap_words;         // [n_snaps][n_ops*64]
+    u64* snap_l1;            // [n_snaps][n_ops_pad]
+    u64* snap_free;          // [n_snaps][n_rows]
+    u64 step;                // snapshot k holds the state before the first event with word >= k*step
+    uint32_t n_snaps;        // capacity (snapshot 0 is the initial state and is never stored)
+    uint32_t next;           // next snapshot index to write
+};
 
-    // ---- Section 5.1 step 1 and the start of Algorithm 1: the tasks, how many inputs each
-    //      waits for (in closed form per in-edge), and the initial READY set ----
-    for (uint32_t r = lane; r < S.n_rows; r += WAVE) L.free_at[r] = 0;
-    for (uint32_t j = 0; j < S.n_ops; j++) {
-        const uint32_t in_begin = ops[j].in_begin, in_end = ops[j].in_end;
-        const OpCfg cj = unpack_cfg(cfgs[j]);
-        const bool mine = (uint32_t)lane < cj.parts;
-        const uint32_t digits = part_digits(cj, lane, magic_v);
-        uint32_t pending = 0;
-        for (uint32_t q = in_begin; q < in_end; q++) {
-            const DEdge e = in_edges[q];
-            const OpCfg ci = unpack_cfg(cfgs[e.src]);
-            uint32_t n = 1;
+// how many parts of the producer (configuration cp) a consumer part reads through edge e:
+// the product over the producer's dims of the number of producer parts its range touches
+__device__ __forceinline__ uint32_t count_inputs(const DEdge& e, const OpCfg& cp, uint32_t cons_cfg_x, uint32_t digits, uint32_t magic_v) {
+    uint32_t n = 1;
 #pragma unroll
-            for (int d = 0; d < 4; d++) {
-                if ((uint32_t)d < e.src_ndim) {
-                    if (e.map[d].src_dim < 0) {
-                        n *= ci.deg[d];
-                    } else {
-                        int32_t lo, hi;
-                        needed_range(e.map[d], e.src_extent[d], cj.x, digits, magic_v, lo, hi);
-                        uint32_t c = 0;
-                        if (hi > lo) c = owner_part(hi - 1, e.src_extent[d], ci.deg[d]) - owner_part(lo, e.src_extent[d], ci.deg[d]) + 1;
-                        n *= c;
-                    }
-                }
+    for (int d = 0; d < 4; d++) {
+        if ((uint32_t)d < e.src_ndim) {
+            if (e.map[d].src_dim < 0) {
+                n *= cp.deg[d];
+            } else {
+                int32_t lo, hi;
+                needed_range(e.map[d], e.src_extent[d], cons_cfg_x, digits, magic_v, lo, hi);
+                uint32_t c = 0;
+                if (hi > lo) c = owner_part(hi - 1, e.src_extent[d], cp.deg[d]) - owner_part(lo, e.src_extent[d], cp.deg[d]) + 1;
+                n *= c;
             }
-            pending += n;
         }
-        // pending < PENDING_LIMIT is guaranteed by ff_sim_create (at most 511 in-edges per op)
-        const u64 w = !mine ? W_NONE : (pending == 0 ? 1ull : (W_WAIT | ((u64)pending << 48)));
-        words[j * WAVE + lane] = w;
-        const u64 wmin = wave_min_u64(w);
-        if (lane == 0) L.l1[j] = wmin;
-        cnt.n_compute += cj.parts;
     }
-    for (uint32_t j = S.n_ops + lane; j < S.n_ops_pad; j += WAVE) L.l1[j] = W_NONE;
-    wave_sync();
-    if (S.n_groups > FLAT_GROUPS) {
-        for (uint32_t g = 0; g < S.n_groups; g++) {
-            const u64 wmin = wave_min_u64(L.l1[g * WAVE + lane]);
-            if (lane == 0) L.l2[g] = wmin;
+    return n;
+}
+
+// number of inputs every part of op j waits for (Section 5.1 step 2, counted in closed form)
+__device__ __forceinline__ uint32_t count_pending(const Sim& m, uint32_t j, const OpCfg& cj) {
+    const uint32_t in_begin = m.T.ops[j].in_begin, in_end = m.T.ops[j].in_end;
+    const uint32_t digits = part_digits(cj, lane_id(), m.magic_v);
+    uint32_t pending = 0;
+    for (uint32_t q = in_begin; q < in_end; q++) {
+        const DEdge e = m.T.in_edges[q];
+        const OpCfg ci = unpack_cfg(m.cfgs[e.src]);
+        pending += count_inputs(e, ci, cj.x, digits, m.magic_v);
+    }
+    return pending;
+}
+
+// Section 4: every configuration valid?  Also fills exe_of.
+__device__ __forceinline__ bool validate_strategy(const Sim& m) {
+    bool bad = false;
+    for (uint32_t i = lane_id(); i < m.S.n_ops; i += WAVE) {
+        OpCfg c = unpack_cfg_lane(m.cfgs[i]);
+        if (!cfg_ok(m.T.ops[i], c, m.S)) bad = true;
+        else m.exe_of[i] = m.T.cost[(size_t)i * m.S.n_cols + (c.parts - 1)];
+    }
+    return !__ballot(bad);
+}
+
+__device__ __forceinline__ void rebuild_l2(const Sim& m) {
+    if (m.S.n_groups > FLAT_GROUPS) {
+        for (uint32_t g = 0; g < m.S.n_groups; g++) {
+            const u64 wmin = wave_min_u64(m.L.l1[g * WAVE + lane_id()]);
+            if (lane_id() == 0) m.L.l2[g] = wmin;
         }
         wave_sync();
     }
+}
 
-    PROF_MARK(0)
-    // ---- Algorithm 1, main loop ----
-    bool overflow = false;
-    u64 last_key = 0;
+// Section 5.1 step 1 and the start of Algorithm 1: the tasks, how many inputs each waits
+// for, the initial READY set, idle devices.
+__device__ __forceinline__ void init_state(Sim& m, Counters& cnt) {
+    const int lane = lane_id();
+    for (uint32_t r = lane; r < m.S.n_rows; r += WAVE) m.L.free_at[r] = 0;
+    for (uint32_t j = 0; j < m.S.n_ops; j++) {
+        const OpCfg cj = unpack_cfg(m.cfgs[j]);
+        const uint32_t pending = count_pending(m, j, cj);
+        // pending < PENDING_LIMIT is guaranteed by ff_sim_create (at most 511 in-edges per op)
+        const u64 w = (uint32_t)lane >= cj.parts ? W_NONE : (pending == 0 ? 1ull : (W_WAIT | ((u64)pending << 48)));
+        m.words[j * WAVE + lane] = w;
+        const u64 wmin = wave_min_u64(w);
+        if (lane == 0) m.L.l1[j] = wmin;
+        cnt.n_compute += cj.parts;
+    }
+    for (uint32_t j = m.S.n_ops + lane; j < m.S.n_ops_pad; j += WAVE) m.L.l1[j] = W_NONE;
+    wave_sync();
+    rebuild_l2(m);
+    m.last_key = 0;
+    m.overflow = false;
+}
+
+// wavefront-wide copy of n 64-bit words between 16-byte aligned HBM buffers, n a multiple of
+// 64: 16 bytes per lane and eight loads in flight before the first store
+__device__ __forceinline__ void copy_words(u64* __restrict__ dst, const u64* __restrict__ src, uint32_t n) {
+    const uint4* __restrict__ s4 = (const uint4*)src;
+    uint4* __restrict__ d4 = (uint4*)dst;
+    const uint32_t n4 = n / 2;          // multiple of 32
+    uint32_t t = lane_id();
+    for (; t + 7 * WAVE < n4; t += 8 * WAVE) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = s4[t + u * WAVE];
+#pragma unroll
+        for (int u = 0; u < 8; u++) d4[t + u * WAVE] = v[u];
+    }
+    for (; t < n4; t += WAVE) d4[t] = s4[t];
+}
+
+__device__ __forceinline__ void save_snapshot(const Sim& m, Recorder& rec) {
+    const int lane = lane_id();
+    const size_t k = rec.next;
+    copy_words(rec.snap_words + k * (size_t)m.S.n_ops * WAVE, m.words, m.S.n_ops * WAVE);
+    u64* l1 = rec.snap_l1 + k * (size_t)m.S.n_ops_pad;
+    for (uint32_t t = lane; t < m.S.n_ops_pad; t += WAVE) l1[t] = m.L.l1[t];
+    u64* fr = rec.snap_free + k * (size_t)m.S.n_rows;
+    for (uint32_t t = lane; t < m.S.n_rows; t += WAVE) fr[t] = m.L.free_at[t];
+    rec.next++;
+}
+
+__device__ __forceinline__ void load_snapshot(Sim& m, const Recorder& rec, uint32_t k) {
+    const int lane = lane_id();
+    copy_words(m.words, rec.snap_words + (size_t)k * m.S.n_ops * WAVE, m.S.n_ops * WAVE);
+    const u64* l1 = rec.snap_l1 + (size_t)k * m.S.n_ops_pad;
+    for (uint32_t t = lane; t < m.S.n_ops_pad; t += WAVE) m.L.l1[t] = l1[t];
+    const u64* fr = rec.snap_free + (size_t)k * m.S.n_rows;
+    for (uint32_t t = lane; t < m.S.n_rows; t += WAVE) m.L.free_at[t] = fr[t];
+    wave_sync();
+    m.last_key = (u64)k * rec.step;
+    m.overflow = false;
+}
+
+// Algorithm 1, main loop, from the current state to the end.  RECORD: keep endTimes and
+// snapshots for delta simulation.  Returns 0 or a RESULT_* code.
+template <bool WIDE, bool RECORD>
+__device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
+    const int lane = lane_id();
+    PROF_DECL
+    const SimDev& S = m.S;
+    const WaveLds& L = m.L;
+    const DOp* __restrict__ ops = m.T.ops;
+    const DEdge* __restrict__ edges = m.T.edges;
+    const uint2* cfgs = m.cfgs;
+    u64* words = m.words;
+    const uint32_t magic_v = m.magic_v;
+    u64 last_key = m.last_key;
+    bool overflow = m.overflow;
     const u64 max_events = 2ull * S.n_ops * WAVE + 8;   // every task is popped at most twice
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
@@ -350,6 +435,10 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
             const int col = __builtin_ctzll(m1);
             i = readlane_u32(gbest, col) * WAVE + col;
         }
+        if (RECORD) {
+            // the state before the first event at or after a multiple of `step` is a snapshot
+            while (rec.next < rec.n_snaps && kmin >= (u64)rec.next * rec.step) save_snapshot(m, rec);
+        }
         last_key = kmin;
         PROF_MARK(1)
         // everything that depends only on i is requested together
@@ -357,7 +446,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
         const DOp* __restrict__ opi_p = ops + i;
         const uint32_t out_begin = opi_p->out_begin, out_end = opi_p->out_end;
         const OpCfg ci = unpack_cfg(cfgs[i]);
-        const u64 exe = exe_of[i];
+        const u64 exe = m.exe_of[i];
         const u64 mask = __ballot(k0 == kmin);            // parts of op i that hold the minimum
         if (!mask) { cnt.exit_code = 2; return RESULT_INTERNAL; }
         cnt.n_events++;
@@ -371,6 +460,7 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
             if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
+            if (RECORD) { if (in_mask) rec.end_of[i * WAVE + lane] = end; }
             PROF_MARK(2)
         } else {
             // the parts in `mask` finished at `now`: release their successors edge by edge
@@ -483,23 +573,38 @@ __device__ u64 simulate_candidate(const SimDev& S, const Tables& T, const uint2*
         }
         PROF_MARK(6)
     }
-    if (__ballot(overflow)) return RESULT_OVERFLOW;
-
-    if (cnt.want_check) {   // diagnostics: tasks that never ran (0 in a correct run)
-        for (uint32_t j = 0; j < S.n_ops; j++) cnt.n_stuck += __popcll(__ballot(words[j * WAVE + lane] != W_NONE));
-    }
-    // Algorithm 1, result (largest endTime): every transfer feeds a compute task that ends
-    // later, so the makespan is the largest free time over the compute device rows.
-    u64 mk = 0;
-    for (uint32_t d = lane; d < S.n_dev; d += WAVE) mk = L.free_at[d] > mk ? L.free_at[d] : mk;
+    m.last_key = last_key;
     PROF_STORE(cnt)
+    if (__ballot(overflow)) return RESULT_OVERFLOW;
+    return 0;
+}
+
+// Algorithm 1, result (largest endTime): every transfer feeds a compute task that ends
+// later, so the makespan is the largest free time over the compute device rows.
+__device__ __forceinline__ u64 makespan(const Sim& m) {
+    u64 mk = 0;
+    for (uint32_t d = lane_id(); d < m.S.n_dev; d += WAVE) mk = m.L.free_at[d] > mk ? m.L.free_at[d] : mk;
     return wave_max_u64(mk);
+}
+
+// One candidate: build + simulate.  Returns the makespan or one of the RESULT_* codes.
+// WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
+template <bool WIDE, bool RECORD>
+__device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
+    if (!validate_strategy(m)) return RESULT_INVALID;
+    init_state(m, cnt);
+    const u64 rc = run_events<WIDE, RECORD>(m, cnt, rec);
+    if (rc) return rc;
+    if (cnt.want_check) {   // diagnostics: tasks that never ran (0 in a correct run)
+        for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(__ballot(m.words[j * WAVE + lane_id()] != W_NONE));
+    }
+    return makespan(m);
 }
 
 __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
     u64 s = c.sum_comm_ns;   // accumulated per lane
 #pragma unroll
-    for (int m = 1; m < WAVE; m <<= 1) s += shfl_xor_u64(s, m);
+    for (int k = 1; k < WAVE; k <<= 1) s += shfl_xor_u64(s, k);
     c.sum_comm_ns = s;
     if (lane_id() == 0) *out = c;
 }
@@ -508,9 +613,7 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 __device__ __forceinline__ uint32_t load_magic(const uint32_t* __restrict__ magic) { return magic[lane_id() + 1]; }
 
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
-// CFGL: the candidate's configurations are copied to LDS first (graphs of moderate size), so
-// that the many uniform look-ups of a configuration do not go to memory.
-template <bool WIDE, bool LDSW, bool CFGL>
+template <bool WIDE, bool LDSW>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -530,69 +633,251 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
         words = (u64*)slot;
         exe_of = (uint32_t*)(slot + (size_t)S.n_ops * WAVE * 8);
     }
-    uint2* cfg_lds = (uint2*)lds_rest;
-    if (CFGL) lds_rest += (size_t)S.n_ops_pad * 8;
     const WaveLds L = carve_lds(lds_rest, S);
     const uint32_t magic_v = load_magic(magic);
+    Recorder none = {};
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
         cnt.want_check = stats != nullptr;
-        const uint2* cfgs = strategies + (size_t)b * S.n_ops;
-        u64 mk;
-        if (CFGL) {
-            for (uint32_t i = lane_id(); i < S.n_ops; i += WAVE) cfg_lds[i] = cfgs[i];
-            wave_sync();
-            mk = simulate_candidate<WIDE>(S, T, cfg_lds, words, exe_of, L, magic_v, cnt);
-        } else {
-            mk = simulate_candidate<WIDE>(S, T, cfgs, words, exe_of, L, magic_v, cnt);
-        }
+        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false};
+        const u64 mk = simulate_candidate<WIDE, false>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (stats) store_counters(cnt, stats + b);
         wave_sync();
     }
 }
 
-// Delta entry, first form: every step applies the mutation to the chain's strategy and
-// re-runs build + Algorithm 1 (the definition of the delta result, Section 5.3).  A
-// mutation that names an op outside the graph makes this and all later results of the
-// chain RESULT_INVALID.
+// ---- delta simulation (Section 5.3) ---------------------------------------------------
+//
+// A chain keeps, in HBM, its current strategy, the task words, the endTime of every task of
+// the last simulation and up to n_snaps snapshots of the simulation state taken whenever
+// the event time crossed a multiple of `step`.  When the configuration of one op changes,
+// nothing can differ before the first producer of that op finishes (its transfers are the
+// first tasks that depend on the op's configuration), so the simulation is resumed from
+// the last snapshot before that time: the op's own tasks are rebuilt, the input counts of
+// its consumers are corrected, and Algorithm 1 continues from there, rewriting the later
+// snapshots.  The resulting timeline is the one a full simulation produces.
+struct ChainMeta {
+    u64 step;           // event-word distance between snapshots (2 * time)
+    uint32_t n_valid;   // snapshots 1..n_valid-1 are usable (0 = none; index 0 is the initial state)
+    uint32_t stale;     // the stored timeline does not belong to the current strategy
+    // telemetry (ff_sim_chains_get_stats)
+    u64 n_steps;        // mutations applied
+    u64 n_resumed;      // of those, resumed from a snapshot instead of simulated from time 0
+    u64 n_events;       // queue pops spent in mutation steps
+    u64 n_events_full;  // queue pops of the last simulation from time 0 (one full simulation)
+};
+
+struct ChainMem {       // all pointers are per chain
+    uint2* cfgs;
+    u64* words;
+    uint32_t* exe_of;
+    u64* end_of;
+    u64* snap_words;
+    u64* snap_l1;
+    u64* snap_free;
+    ChainMeta* meta;
+};
+
+// byte offset of the ChainMeta record inside a chain block (it comes last)
+__host__ __device__ inline size_t chain_meta_offset(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps) {
+    size_t b = (size_t)n_ops_pad * 8;                       // cfgs
+    b += (size_t)n_ops * WAVE * 8 * 2;                      // words, end_of
+    b += (size_t)n_snaps * ((size_t)n_ops * WAVE * 8 + (size_t)n_ops_pad * 8 + (size_t)((n_rows + 1) & ~1u) * 8);
+    b += (size_t)n_ops_pad * 4;                             // exe_of
+    return b;
+}
+__host__ __device__ inline size_t chain_bytes(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps) {
+    return (chain_meta_offset(n_ops, n_ops_pad, n_rows, n_snaps) + sizeof(ChainMeta) + 255) & ~(size_t)255;
+}
+
+__device__ __forceinline__ ChainMem carve_chain(unsigned char* base, const SimDev& S, uint32_t n_snaps) {
+    ChainMem c;
+    const size_t nw = (size_t)S.n_ops * WAVE;
+    c.cfgs = (uint2*)base; base += (size_t)S.n_ops_pad * 8;
+    c.words = (u64*)base; base += nw * 8;
+    c.end_of = (u64*)base; base += nw * 8;
+    c.snap_words = (u64*)base; base += (size_t)n_snaps * nw * 8;
+    c.snap_l1 = (u64*)base; base += (size_t)n_snaps * S.n_ops_pad * 8;
+    c.snap_free = (u64*)base; base += (size_t)n_snaps * ((S.n_rows + 1) & ~1u) * 8;
+    c.exe_of = (uint32_t*)base; base += (size_t)S.n_ops_pad * 4;
+    c.meta = (ChainMeta*)base;
+    return c;
+}
+
+// Decides where a simulation of the chain's current strategy may start after op `mo` went
+// from configuration `ocfg` to the one now in m.cfgs: returns the snapshot index to resume
+// from (0 = start from time 0) and rewrites, in every snapshot that stays valid, what the
+// snapshots hold about op mo.
+__device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, const ChainMeta& meta, uint32_t mo, uint2 ocfg) {
+    const int lane = lane_id();
+    const SimDev& S = m.S;
+    // earliest time at which the old and the new simulation can differ: the first producer
+    // task of op mo to finish; time 0 if op mo has no producer or has a part without inputs
+    const OpCfg cn = unpack_cfg(m.cfgs[mo]);
+    const OpCfg co = unpack_cfg(ocfg);
+    const uint32_t in_begin = m.T.ops[mo].in_begin, in_end = m.T.ops[mo].in_end;
+    u64 tau = in_end > in_begin ? W_NONE : 0;
+    for (uint32_t q = in_begin; q < in_end; q++) {
+        const uint32_t p = m.T.in_edges[q].src;
+        const OpCfg cp = unpack_cfg(m.cfgs[p]);
+        const u64 t = wave_min_u64((uint32_t)lane < cp.parts ? rec.end_of[p * WAVE + lane] : W_NONE);
+        tau = t < tau ? t : tau;
+    }
+    const uint32_t pend_new = count_pending(m, mo, cn);
+    uint32_t pend_old = 0;
+    {
+        const uint32_t digits = part_digits(co, lane, m.magic_v);
+        for (uint32_t q = in_begin; q < in_end; q++) {
+            const DEdge e = m.T.in_edges[q];
+            pend_old += count_inputs(e, unpack_cfg(m.cfgs[e.src]), co.x, digits, m.magic_v);
+        }
+    }
+    if (__ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
+    u64 k64 = (2 * tau) / meta.step;
+    if (k64 > meta.n_valid - 1) k64 = meta.n_valid - 1;
+    const uint32_t k = (uint32_t)k64;
+    if (k == 0) return 0;
+
+    // Snapshots 1..k were taken before anything depended on op mo's configuration.  What they
+    // hold about it is static: the op's own tasks (all still waiting for all inputs) and, in
+    // its consumers' waiting tasks, how many inputs come from op mo.  Rewrite both for the new
+    // configuration in every snapshot that stays valid.
+    const uint32_t ob = m.T.ops[mo].out_begin, oe = m.T.ops[mo].out_end;
+    const u64 w_own = (uint32_t)lane >= cn.parts ? W_NONE : (W_WAIT | ((u64)pend_new << 48));
+    const u64 w_own_min = wave_min_u64(w_own);
+    for (uint32_t sn = 1; sn <= k; sn++) {
+        u64* sw = rec.snap_words + (size_t)sn * S.n_ops * WAVE;
+        sw[mo * WAVE + lane] = w_own;
+        if (lane == 0) rec.snap_l1[(size_t)sn * S.n_ops_pad + mo] = w_own_min;
+    }
+    for (uint32_t ei = ob; ei < oe; ei++) {
+        const DEdge e = m.T.edges[ei];
+        const uint32_t j = e.dst;
+        const OpCfg cj = unpack_cfg(m.cfgs[j]);
+        const uint32_t digits = part_digits(cj, lane, m.magic_v);
+        const uint32_t was = count_inputs(e, co, cj.x, digits, m.magic_v);
+        const uint32_t is = count_inputs(e, cn, cj.x, digits, m.magic_v);
+        if (!__ballot((uint32_t)lane < cj.parts && was != is)) continue;
+        for (uint32_t sn = 1; sn <= k; sn++) {
+            u64* sw = rec.snap_words + (size_t)sn * S.n_ops * WAVE;
+            u64 w = sw[j * WAVE + lane];
+            // a part of op j that reads op mo at all is still waiting in these snapshots
+            const bool waiting = (uint32_t)lane < cj.parts && (w >> 63) && w != W_NONE;
+            if (waiting && was != is) {
+                const uint32_t pending = ((uint32_t)(w >> 48) & PENDING_LIMIT) - was + is;
+                sw[j * WAVE + lane] = W_WAIT | ((u64)pending << 48) | (w & (TIME_LIMIT - 1));
+            }
+            // level 1 of op j is unaffected: waiting words are not events
+        }
+    }
+    __threadfence_block();
+    wave_sync();
+    return k;
+}
+
+// Simulates the chain's current strategy, from snapshot k if k > 0, else from time 0, and
+// records endTimes and snapshots.  When no snapshot spacing is set yet, a first pass
+// without snapshots finds the makespan that fixes it.
+template <bool WIDE>
+__device__ u64 chain_simulate(Sim& m, Recorder& rec, ChainMeta& meta, uint32_t k, Counters& cnt) {
+    u64 mk = 0;
+    const uint32_t capacity = rec.n_snaps;
+    for (int pass = (k == 0 && meta.step == 0) ? 0 : 1; pass < 2; pass++) {
+        const u64 before = cnt.n_events;
+        rec.step = meta.step;
+        rec.n_snaps = pass == 0 ? 0 : capacity;
+        rec.next = k + 1;
+        if (k == 0) {
+            init_state(m, cnt);
+        } else {
+            load_snapshot(m, rec, k);
+            rebuild_l2(m);
+            meta.n_resumed++;
+        }
+        const u64 rc = run_events<WIDE, true>(m, cnt, rec);
+        rec.n_snaps = capacity;
+        if (rc) { meta.stale = 1; meta.n_valid = 0; return rc; }
+        mk = makespan(m);
+        if (pass == 0) meta.step = (2 * mk) / capacity + 1;
+        if (k == 0) meta.n_events_full = cnt.n_events - before;
+    }
+    meta.stale = 0;
+    meta.n_valid = rec.next;
+    return mk;
+}
+
+// muts == nullptr: simulate the chains' starting strategies (n_steps is 1).  Otherwise
+// muts is [n_steps][C] records {op, cfg.x, cfg.y}; a mutation that names an op outside the
+// graph poisons the chain: this and all later results are RESULT_INVALID.
 template <bool WIDE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
-                                                          const uint32_t* __restrict__ magic, uint2* chain_cfgs, uint32_t C,
+                                                          const uint32_t* __restrict__ magic, unsigned char* chain_mem,
+                                                          size_t chain_stride, uint32_t n_snaps, uint32_t C,
                                                           const uint32_t* __restrict__ muts, uint32_t n_steps,
-                                                          u64* __restrict__ out_ns, uint32_t* chain_flags,
-                                                          unsigned char* __restrict__ ws, size_t slot_stride) {
+                                                          u64* __restrict__ out_ns, uint32_t* chain_flags) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const Tables T{ops, edges, in_edges, cost};
-    const WaveLds L = carve_lds(lds_raw, S);
+    // the chain's strategy is worked on in LDS (and written through to HBM), so that the many
+    // uniform configuration look-ups do not queue behind the wavefront's stores to HBM
+    uint2* cfg_lds = (uint2*)lds_raw;
+    const WaveLds L = carve_lds(lds_raw + (size_t)S.n_ops_pad * 8, S);
     const uint32_t c = blockIdx.x;
     if (c >= C) return;
-    unsigned char* slot = ws + (size_t)c * slot_stride;
-    u64* words = (u64*)slot;
-    uint32_t* exe_of = (uint32_t*)(slot + (size_t)S.n_ops * WAVE * 8);
-    uint2* cfgs = chain_cfgs + (size_t)c * S.n_ops;
+    const ChainMem cm = carve_chain(chain_mem + (size_t)c * chain_stride, S, n_snaps);
     const uint32_t magic_v = load_magic(magic);
+    for (uint32_t i = lane_id(); i < S.n_ops; i += WAVE) cfg_lds[i] = cm.cfgs[i];
+    wave_sync();
     bool poisoned = first_u32(chain_flags[c]) != 0;
+    ChainMeta meta = *cm.meta;
+    meta.step = first_u64(meta.step);
+    meta.n_valid = first_u32(meta.n_valid);
+    meta.stale = first_u32(meta.stale);
+    meta.n_steps = first_u64(meta.n_steps);
+    meta.n_resumed = first_u64(meta.n_resumed);
+    meta.n_events = first_u64(meta.n_events);
+    meta.n_events_full = first_u64(meta.n_events_full);
+    Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
+    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false};
     for (uint32_t s = 0; s < n_steps; s++) {
-        if (muts) {   // muts: [n_steps][C] records of {op, cfg.x, cfg.y}
-            const uint32_t* m = muts + ((size_t)s * C + c) * 3;
-            const uint32_t op = first_u32(m[0]);
-            if (op < S.n_ops) {
-                if (lane_id() == 0) cfgs[op] = make_uint2(m[1], m[2]);
-            } else {
-                poisoned = true;
-            }
-            __threadfence_block();
-            wave_sync();
-        }
         Counters cnt = {};
         u64 mk = RESULT_INVALID;
-        if (!poisoned) mk = simulate_candidate<WIDE>(S, T, cfgs, words, exe_of, L, magic_v, cnt);
+        bool run = false;
+        uint32_t k = 0;
+        if (!muts) {
+            run = validate_strategy(m);
+            if (!run) meta.stale = 1;
+        } else {
+            const uint32_t* mu = muts + ((size_t)s * C + c) * 3;
+            const uint32_t op = first_u32(mu[0]);
+            if (op >= S.n_ops) poisoned = true;
+            if (!poisoned) {
+                const uint2 ocfg = cfg_lds[op];
+                wave_sync();
+                if (lane_id() == 0) {
+                    const uint2 ncfg = make_uint2(mu[1], mu[2]);
+                    cfg_lds[op] = ncfg;
+                    cm.cfgs[op] = ncfg;
+                }
+                wave_sync();
+                run = validate_strategy(m);
+                if (!run) meta.stale = 1;
+                else if (!meta.stale && meta.n_valid > 1 && meta.step != 0) k = chain_prepare_resume(m, rec, meta, op, ocfg);
+                meta.n_steps++;
+            }
+        }
+        if (run) {
+            mk = chain_simulate<WIDE>(m, rec, meta, k, cnt);
+            if (muts) meta.n_events += cnt.n_events;
+        }
         if (lane_id() == 0) out_ns[(size_t)s * C + c] = mk;
         wave_sync();
     }
-    if (lane_id() == 0) chain_flags[c] = poisoned ? 1u : 0u;
+    if (lane_id() == 0) {
+        chain_flags[c] = poisoned ? 1u : 0u;
+        *cm.meta = meta;
+    }
 }
 
 }  // namespace ffsim

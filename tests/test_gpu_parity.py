@@ -171,17 +171,69 @@ def test_wide_tensors_take_the_64_bit_path(B):
     assert np.array_equal(got, want)
 
 
-def test_delta_chain_matches_resimulation(B):
-    w = W.workload(1)
-    C, steps = 4, 40
+@pytest.mark.parametrize("config_id,C,steps", [(0, 8, 60), (1, 4, 80), (2, 3, 40), (3, 2, 12), (4, 1, 6)])
+def test_delta_chain_matches_resimulation(B, config_id, C, steps):
+    """Section 5.3: after every single-op mutation the delta result equals a full
+    simulation of the mutated strategy (here: the oracle's)."""
+    w = W.workload(config_id)
     cfg0 = w.strategies(C)
     muts = w.mutations(steps, C)
-    sim = sim_for(B, 1)
+    print(f"delta: config {config_id}, {C} chains x {steps} steps", flush=True)
+    sim = sim_for(B, config_id)
     ch = B.Chains(sim, cfg0)
     assert np.array_equal(ch.start_ns(), oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0))
     d_m = ch.upload_mutations(muts)
     got = ch.delta(d_m, steps).cpu().numpy().view("<u8")
     for c in range(C):
         want = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], muts[:, c])
-        assert np.array_equal(got[:, c], want), f"chain {c}"
+        bad = np.nonzero(got[:, c] != want)[0]
+        assert len(bad) == 0, f"chain {c}: first differing step {bad[0]} (op {int(muts[bad[0], c]['op'])}): gpu {got[bad[0], c]} oracle {want[bad[0]]}"
+    ch.close()
+
+
+def test_delta_in_several_calls_and_inverse_mutation(B):
+    """the chain state survives between ff_sim_delta calls; a mutation followed by its
+    inverse restores the previous value; mutating the first and the last op works."""
+    w = W.workload(2)
+    cfg0 = w.strategies(2)
+    sim = sim_for(B, 2)
+    ch = B.Chains(sim, cfg0)
+    start = ch.start_ns().copy()
+    m = w.mutations(6, 2)
+    m["op"][0] = 0
+    m["op"][2] = w.n_ops - 1
+    fwd = np.zeros((12, 2), W.MUT_DT)
+    fwd[0::2] = m
+    for s in range(6):           # odd steps undo the even ones
+        prev = cfg0.copy()
+        fwd[2 * s + 1]["op"] = m[s]["op"]
+        for c in range(2):
+            fwd[2 * s + 1, c]["cfg"] = prev[c, int(m[s, c]["op"])]
+    got = np.concatenate([ch.delta(ch.upload_mutations(fwd[a:b]), b - a).cpu().numpy().view("<u8")
+                          for a, b in ((0, 5), (5, 6), (6, 12))])
+    for c in range(2):
+        want = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], fwd[:, c])
+        assert np.array_equal(got[:, c], want)
+        assert (got[1::2, c] == start[c]).all()
+    ch.close()
+
+
+def test_delta_invalid_mutations(B):
+    """an invalid configuration gives FF_INVALID_NS until a later mutation repairs it; a
+    mutation naming an op outside the graph poisons the chain for good."""
+    w = W.workload(1)
+    cfg0 = w.strategies(2)
+    sim = sim_for(B, 1)
+    ch = B.Chains(sim, cfg0)
+    muts = w.mutations(6, 2)
+    muts[1, 0]["cfg"]["deg"] = (64, 64, 1, 1)          # chain 0: too many parts at step 1
+    muts[2, 0]["op"] = muts[1, 0]["op"]                # ... repaired at step 2
+    muts[3, 1]["op"] = w.n_ops + 5                     # chain 1: poisoned from step 3 on
+    got = ch.delta(ch.upload_mutations(muts), 6).cpu().numpy().view("<u8")
+    want0 = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[0], muts[:, 0])
+    assert want0[1] == oracle.INVALID and want0[2] != oracle.INVALID
+    assert np.array_equal(got[:, 0], want0)
+    want1 = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[1], muts[:3, 1])
+    assert np.array_equal(got[:3, 1], want1)
+    assert (got[3:, 1] == B.FF_INVALID_NS).all()
     ch.close()
