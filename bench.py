@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
 HEADLINE = 1
+# HBM bytes per launch of the batch kernel (fetch + write), from rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this script, scaled by what the same counters read for a 256 MiB
+# device-to-device copy (profiles/k_sim_batch_hbm_traffic.txt).  Not measured live.
+MEASURED_TRAFFIC_BYTES = {1: 528384, 2: 847.7e6, 3: 2147.5e6, 4: 4456.8e6}
 
 
 def alg_bytes(n_ops, tc, npairs):
@@ -60,6 +64,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--only-headline", action="store_true", help="skip the other workloads and the delta chain")
+    ap.add_argument("--workloads", default="", help="comma-separated config ids to run instead of all five (profiling runs)")
+    ap.add_argument("--no-delta", action="store_true", help="skip the delta chains")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first run three device-to-device copies of 256 MiB (a kernel of known traffic, to scale "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -71,9 +80,19 @@ def main():
     import torch
     from paper_1807_05358_amd import binding, workloads as W
 
+    if args.calibration_copy:
+        src = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     threads = min(os.cpu_count() or 1, 16)
     results = {}
     order = [HEADLINE] if args.only_headline else [HEADLINE, 0, 2, 3, 4]
+    if args.workloads:
+        order = [HEADLINE] + [int(x) for x in args.workloads.split(",") if int(x) != HEADLINE]
     for c in order:
         w = W.workload(c)
         B = w.n_candidates
@@ -95,6 +114,7 @@ def main():
             "alg_bytes_per_strategy": ab,
             "achieved_GBps": ab * B / (kern_ms * 1e-3) / 1e9,
             "hbm_roofline_frac": ab * B / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "hbm_traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get(c),
             "input_sha256": w.sha256(B),
         }
         if not args.no_cpu:
@@ -120,7 +140,7 @@ def main():
                                "1024 seeded candidate strategies per step", "B": head["B"],
                    "candidates_per_step": head["B"]},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": head["hbm_roofline_frac"], "traffic": None,
+                     "frac": head["hbm_roofline_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE),
                      "kernel": "k_sim_batch<false>", "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
                      "kernel_ms": head["kernel_ms"]},
     }
@@ -137,11 +157,11 @@ def main():
                                 "sample": f"all {len(cfgs)} candidates of configs[1], {reps} repetitions, "
                                           f"{threads} threads (static split); single thread: {one:.1f} strategies/s",
                                 "single_thread_value": one}
-    if not args.only_headline:
+    if not args.only_headline and not args.no_delta and 4 in results:
         # delta simulation on configs[4]: one chain, and 256 independent chains
         r4, sim4, w4, cfgs4 = results[4]
         delta = []
-        for C, n_steps in ((1, 8), (256, 4)):
+        for C, n_steps in ((1, 24), (256, 6)):
             muts = w4.mutations(n_steps, C)
             ch = binding.Chains(sim4, cfgs4[:C])
             d_m = ch.upload_mutations(muts)
@@ -152,10 +172,21 @@ def main():
             b.record()
             torch.cuda.synchronize()
             ms = a.elapsed_time(b)
-            delta.append({"workload": "configs[4] nmt", "chains": C, "steps": n_steps, "ms": ms,
-                          "delta_sims_per_s": C * n_steps / (ms * 1e-3)})
+            st = ch.stats()
+            d = {"workload": "configs[4] nmt", "chains": C, "steps": n_steps, "ms": ms,
+                 "delta_sims_per_s": C * n_steps / (ms * 1e-3),
+                 "steps_resumed_from_snapshot": int(st["n_resumed"].sum()), "steps_total": int(st["n_steps"].sum()),
+                 "mean_events_per_step": float(st["n_events"].sum() / max(1, st["n_steps"].sum())),
+                 "events_of_a_full_simulation": float(st["n_events_full"].mean())}
+            if not args.no_cpu and C == 1:
+                import oracle
+                sel = [0, n_steps // 2, n_steps - 1]
+                ref = oracle.simulate_delta_chain(w4.ops, w4.edges, w4.machine, w4.cost, cfgs4[0], muts[:, 0], steps=sel)
+                d["bit_exact_on_sampled_steps"] = bool(np.array_equal(out.cpu().numpy().view("<u8")[sel, 0], ref))
+            delta.append(d)
             ch.close()
         line["delta"] = delta
+    if not args.only_headline:
         line["workloads"] = [results[c][0] for c in sorted(results)]
     print(json.dumps(line))
 
