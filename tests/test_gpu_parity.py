@@ -237,3 +237,115 @@ def test_delta_invalid_mutations(B):
     assert np.array_equal(got[:3, 1], want1)
     assert (got[3:, 1] == B.FF_INVALID_NS).all()
     ch.close()
+
+
+def test_more_candidates_than_resident_wavefronts(B):
+    """B larger than the number of wavefronts the device holds at once: wavefronts stride
+    over the batch and reuse their state."""
+    w = W.workload(1)
+    n = 9000
+    cfgs = w.strategies(n)
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=8)
+    got = sim_for(B, 1).simulate(cfgs)
+    assert np.array_equal(got, want)
+    w = W.workload(2)            # task words in HBM: one workspace slot per resident wavefront
+    sim = sim_for(B, 2)
+    n = 9000
+    cfgs = w.strategies(n)
+    got = sim.simulate(cfgs)
+    idx = np.arange(0, n, 150)
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs[idx], n_threads=8)
+    assert B.ff_sim_workspace_bytes(sim.handle, n) < n * 64 * 8 * w.n_ops   # fewer slots than candidates
+    assert np.array_equal(got[idx], want)
+
+
+def test_graphs_without_edges_and_single_op(B):
+    g = W.GraphBuilder()
+    for _ in range(5):
+        g.op(W.T_ELEM, (64, 32), (0, 1), 1)
+    ops, edges, _ = g.finish()
+    cost = np.tile(np.arange(100, 164, dtype="<u4"), (5, 1))
+    mach = W.Machine(2, 2)
+    cfgs = W.strategies(ops, 40, 3, 4, 16, (1, 2, 4, 8, 16))
+    sim = B.Simulator(ops, edges, mach, cost)
+    assert np.array_equal(sim.simulate(cfgs), oracle.simulate_batch(ops, edges, mach, cost, cfgs))
+    sim.close()
+    sim = B.Simulator(ops[:1], edges, mach, cost[:1])
+    assert np.array_equal(sim.simulate(cfgs[:, :1]), oracle.simulate_batch(ops[:1], edges, mach, cost[:1], cfgs[:, :1]))
+    sim.close()
+
+
+def test_many_parts_on_few_devices_and_wide_fan_in(B):
+    """64 parts per op on a 1x2 machine (32 tasks per device queue up in id order) and an op
+    with 40 producers."""
+    g = W.GraphBuilder()
+    srcs = [g.op(W.T_ELEM, (64, 64), (0, 1), 1) for _ in range(40)]
+    mids = [g.elementwise([s]) for s in srcs]
+    top = g.op(W.T_STACK, (64, 40, 64), (0, 2), 1)
+    for m in mids:
+        g.edge(m, top, [W.ident(0), W.ident(2)])
+    g.softmax(top)
+    ops, edges, _ = g.finish()
+    rng = np.random.default_rng(2)
+    cost = rng.integers(1, 5000, size=(len(ops), 64)).astype("<u4")
+    for mach in (W.Machine(1, 2, 5, 3, 1, 2, 4), W.Machine(16, 4)):
+        cfgs = W.strategies(ops, 48, 9, mach.n_devices, 64, (1, 2, 4, 8, 16, 32, 64))
+        cfgs["dev_stride"] = rng.integers(0, 4, size=cfgs.shape)
+        sim = B.Simulator(ops, edges, mach, cost)
+        got, st = sim.simulate(cfgs, stats=True)
+        want = oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8)
+        assert not st["exit_code"].any() and not st["n_stuck"].any()
+        assert np.array_equal(got, want)
+        sim.close()
+
+
+def test_time_limit_is_reported_not_wrapped(B):
+    """simulated times are limited to 2^48 ns; a candidate that gets there returns
+    FF_OVERFLOW_NS (the oracle, with full 64-bit times, confirms the true value is beyond)."""
+    g = W.GraphBuilder()
+    x = g.op(W.T_ELEM, (64, 64), (0, 1), 1)
+    for _ in range(1099):
+        x = g.elementwise([x])
+    ops, edges, _ = g.finish()
+    cost = np.full((1100, 64), 2 ** 32 - 1, "<u4")
+    cost[:, 0] = 1000
+    mach = W.Machine(1, 2)
+    cfgs = np.zeros((2, 1100), W.CFG_DT)
+    cfgs["deg"] = 1
+    cfgs["deg"][1, :, 0] = 64          # candidate 1: 64 parts per op, all on device 0, 2^32-1 ns each
+    cfgs["dev_stride"] = 0
+    want = oracle.simulate_batch(ops, edges, mach, cost, cfgs)
+    sim = B.Simulator(ops, edges, mach, cost)
+    got = sim.simulate(cfgs)
+    sim.close()
+    assert want[0] == 1100 * 1000 and got[0] == want[0]
+    assert want[1] >= 2 ** 48 and got[1] == 2 ** 64 - 3
+
+
+def test_workspace_errors_and_other_stream(B):
+    import torch
+    w = W.workload(2)
+    h = B.ff_sim_create(w.ops, w.edges, w.machine, w.cost)
+    cfgs = w.strategies(16)
+    d = B.to_device(cfgs)
+    out = torch.empty(16, dtype=torch.int64, device="cuda")
+    L = B.lib()
+    assert L.ff_sim_batch(h, d.data_ptr(), 16, out.data_ptr(), None) == B.FF_EWORKSPACE     # none set
+    need = B.ff_sim_workspace_bytes(h, 16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    assert L.ff_sim_set_workspace(h, ws.data_ptr() + 8, need - 8) == B.FF_EINVAL             # misaligned
+    assert L.ff_sim_set_workspace(h, ws.data_ptr(), need // 2) == B.FF_OK
+    assert L.ff_sim_batch(h, d.data_ptr(), 16, out.data_ptr(), None) == B.FF_EWORKSPACE     # too small
+    assert L.ff_sim_set_workspace(h, ws.data_ptr(), need) == B.FF_OK
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        assert L.ff_sim_batch(h, d.data_ptr(), 16, out.data_ptr(), s.cuda_stream) == B.FF_OK
+    s.synchronize()
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs)
+    assert np.array_equal(out.cpu().numpy().view("<u8"), want)
+    B.ff_sim_destroy(h)
+    # limits are reported at creation
+    big = w.ops.copy(); big[0]["extent"][2] = 2 ** 21
+    with pytest.raises(B.FFSimError) as e:
+        B.ff_sim_create(big, w.edges, w.machine, w.cost)
+    assert e.value.code == B.FF_ERANGE
