@@ -45,8 +45,13 @@ def lib():
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
-                               "`python -m paper_1807_05358_amd.build` (hipcc, gfx950)")
+            # nothing built yet: build once (hipcc); there is no other implementation to fall back to
+            try:
+                from . import build as _build
+                _build.build_library(force=True)
+            except Exception as exc:
+                raise RuntimeError(f"{LIB_PATH} is missing and could not be built with hipcc "
+                                   "(`python -m paper_1807_05358_amd.build`): " + str(exc)) from exc
         L = C.CDLL(LIB_PATH)
         vp, u32 = C.c_void_p, C.c_uint32
         L.ff_sim_create.restype = C.c_int

@@ -173,13 +173,20 @@ __device__ __forceinline__ void needed_range(const DMap& m, uint32_t extent, uin
                                              uint32_t magic_v, int32_t& lo, int32_t& hi) {
     if (m.src_dim < 0) { lo = 0; hi = (int32_t)extent; return; }   // uniform
     const uint32_t sh = 8u * (uint32_t)m.src_dim;
-    const Divisor dv = divisor((cfg_x >> sh) & 0xff, magic_v);
-    const uint32_t idx = (digits >> sh) & 0xff;
-    const int32_t clo = (int32_t)div_by(idx * m.cext, dv);
-    const int32_t chi = (int32_t)div_by((idx + 1) * m.cext, dv);
+    const uint32_t degc = (cfg_x >> sh) & 0xff;
+    const int32_t E = (int32_t)extent;
+    int32_t clo, chi;
+    if (degc == 1) {      // uniform: the consumer is not split along this dim, every part reads the same range
+        clo = 0;
+        chi = (int32_t)m.cext;
+    } else {
+        const Divisor dv = divisor(degc, magic_v);
+        const uint32_t idx = (digits >> sh) & 0xff;
+        clo = (int32_t)div_by(idx * m.cext, dv);
+        chi = (int32_t)div_by((idx + 1) * m.cext, dv);
+    }
     int32_t l = clo * (int32_t)m.stride + m.a;
     int32_t h = (chi - 1) * (int32_t)m.stride + m.b + 1;
-    const int32_t E = (int32_t)extent;
     l = l < 0 ? 0 : (l > E ? E : l);
     h = h < 0 ? 0 : (h > E ? E : h);
     lo = l;
@@ -485,16 +492,28 @@ __device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
                 bool touched = false;
-                u64 todo = mask;
+                // dims along which the producer is not split overlap the same way for every
+                // producer part: take them out of the loop over parts
+                bool base_hit = mine;
+                u64 base_elems = 1;
+#pragma unroll
+                for (int d = 0; d < 4; d++) {
+                    if ((uint32_t)d < e.src_ndim && ci.deg[d] == 1) {
+                        base_hit = base_hit && nhi[d] > nlo[d];
+                        if (WIDE) base_elems *= (u64)(uint32_t)(nhi[d] - nlo[d]);
+                        else base_elems = (uint32_t)base_elems * (uint32_t)(nhi[d] - nlo[d]);
+                    }
+                }
+                u64 todo = __ballot(base_hit) ? mask : 0;
                 PROF_MARK(3)
                 while (todo) {
                     const int kp = __builtin_ctzll(todo);
                     todo &= todo - 1;
-                    bool hit = mine;
-                    u64 elems = 1;
+                    bool hit = base_hit;
+                    u64 elems = base_elems;
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
-                        if ((uint32_t)d < e.src_ndim) {
+                        if ((uint32_t)d < e.src_ndim && ci.deg[d] != 1) {
                             const int32_t plo = (int32_t)readlane_u32(pb.lo[d], kp), phi = (int32_t)readlane_u32(pb.hi[d], kp);
                             const int32_t lo = nlo[d] > plo ? nlo[d] : plo;
                             const int32_t hi = nhi[d] < phi ? nhi[d] : phi;

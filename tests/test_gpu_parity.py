@@ -349,3 +349,71 @@ def test_workspace_errors_and_other_stream(B):
     with pytest.raises(B.FFSimError) as e:
         B.ff_sim_create(big, w.edges, w.machine, w.cost)
     assert e.value.code == B.FF_ERANGE
+
+
+def random_graph(rng, n_ops):
+    """random DAG with random shapes and random affine input maps (not a DNN: it only has to
+    be a valid input of the boundary)."""
+    g = W.GraphBuilder()
+    for i in range(n_ops):
+        ndim = int(rng.integers(1, 5))
+        ext = [int(rng.choice([1, 2, 3, 5, 8, 12, 17, 32, 64, 100])) for _ in range(ndim)]
+        par = [d for d in range(ndim) if rng.random() < 0.8] or [0]
+        g.op(W.T_ELEM, ext, par, 1)
+        n_in = 0 if i == 0 else int(rng.integers(0, min(i, 3) + 1))
+        for src in sorted(rng.choice(i, size=n_in, replace=False).tolist()) if n_in else []:
+            sext = g.extent(src)
+            maps = []
+            for d in range(len(sext)):
+                if rng.random() < 0.3:
+                    maps.append(W.ALL)
+                else:
+                    c = int(rng.integers(0, ndim))
+                    stride = int(rng.choice([1, 1, 1, 2, 3]))
+                    a = int(rng.integers(-3, 4))
+                    b = a + int(rng.integers(0, 4))
+                    maps.append((c, stride, a, b))
+            g.edge(src, i, maps)
+    return g.finish()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_graphs_machines_and_strategies(B, seed):
+    rng = np.random.default_rng(1000 + seed)
+    n_ops = int(rng.integers(3, 90))
+    ops, edges, _ = random_graph(rng, n_ops)
+    n_nodes, gpn = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+    mach = W.Machine(n_nodes, gpn, int(rng.integers(1, 30)), int(rng.integers(1, 30)),
+                     int(rng.integers(0, 50)), int(rng.integers(0, 50)), int(rng.choice([1, 2, 4, 8])))
+    cost = rng.integers(1, 3000, size=(n_ops, 64)).astype("<u4")
+    n = 160
+    cfgs = np.zeros((n, n_ops), W.CFG_DT)
+    for i in range(n_ops):
+        t = W.valid_degree_tuples(ops[i], 64, (1, 2, 3, 4, 5, 7, 8, 16, 32, 64))
+        cfgs["deg"][:, i] = t[rng.integers(len(t), size=n)]
+    cfgs["dev_offset"] = rng.integers(0, mach.n_devices, size=(n, n_ops))
+    cfgs["dev_stride"] = rng.integers(0, 5, size=(n, n_ops))
+    print(f"seed {seed}: {n_ops} ops, {len(edges)} edges, machine {mach.as_tuple()}", flush=True)
+    want = oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8)
+    sim = B.Simulator(ops, edges, mach, cost)
+    got, st = sim.simulate(cfgs, stats=True)
+    assert not st["exit_code"].any() and not st["n_stuck"].any()
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+    # and a mutation chain on the same graph
+    muts = np.zeros((30, 2), W.MUT_DT)
+    muts["op"] = rng.integers(0, n_ops, size=(30, 2))
+    for s in range(30):
+        for c in range(2):
+            i = int(muts[s, c]["op"])
+            t = W.valid_degree_tuples(ops[i], 64, (1, 2, 3, 4, 8, 16))
+            muts[s, c]["cfg"]["deg"] = t[rng.integers(len(t))]
+            muts[s, c]["cfg"]["dev_offset"] = rng.integers(0, mach.n_devices)
+            muts[s, c]["cfg"]["dev_stride"] = rng.integers(0, 3)
+    ch = B.Chains(sim, cfgs[:2])
+    d = ch.delta(ch.upload_mutations(muts), 30).cpu().numpy().view("<u8")
+    for c in range(2):
+        ref = oracle.simulate_delta_chain(ops, edges, mach, cost, cfgs[c], muts[:, c])
+        assert np.array_equal(d[:, c], ref), f"chain {c}: steps {np.nonzero(d[:, c] != ref)[0][:5]}"
+    ch.close()
+    sim.close()
