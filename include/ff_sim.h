@@ -175,6 +175,18 @@ int ff_sim_delta(ff_chains_t* chains, const ff_mutation_t* d_muts, uint32_t n_st
                  void* hip_stream);
 void ff_sim_chains_destroy(ff_chains_t* chains);
 
+/* Trial mutations: the proposals of the search before acceptance (Section 6.2).  Evaluates M
+ * alternative single-op mutations per chain -- d_muts is [M][C], proposal-major -- each against
+ * the chain's current strategy and stored timeline, and writes the simulated times to
+ * d_out_ns[M][C].  The chains are NOT changed (commit an accepted proposal with
+ * ff_sim_delta).  Results equal a full simulation of the mutated strategy (Section 5.3).
+ * Needs the handle's workspace (ff_sim_set_workspace) to hold
+ * ff_sim_delta_try_workspace_bytes(chains, M) bytes.  Asynchronous on hip_stream; must not
+ * overlap with ff_sim_delta on the same chains or with other users of the workspace. */
+size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* chains, uint32_t M);
+int ff_sim_delta_try(ff_chains_t* chains, const ff_mutation_t* d_muts, uint32_t M, uint64_t* d_out_ns,
+                     void* hip_stream);
+
 /* Telemetry of the chains (HOST array of C records; synchronises the device): how many
  * mutations were applied, how many of them resumed from a stored snapshot of the timeline
  * instead of simulating from time 0, how many queue pops they took in total, and how many

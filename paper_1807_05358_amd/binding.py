@@ -34,6 +34,7 @@ class ff_costtable_t(C.Structure):
 
 EXPORTS = ["ff_sim_create", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
+           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8")])
 
@@ -73,6 +74,10 @@ def lib():
         L.ff_sim_delta.argtypes = [vp, vp, u32, vp, vp]
         L.ff_sim_chains_destroy.restype = None
         L.ff_sim_chains_destroy.argtypes = [vp]
+        L.ff_sim_delta_try.restype = C.c_int
+        L.ff_sim_delta_try.argtypes = [vp, vp, u32, vp, vp]
+        L.ff_sim_delta_try_workspace_bytes.restype = C.c_size_t
+        L.ff_sim_delta_try_workspace_bytes.argtypes = [vp, u32]
         L.ff_sim_chains_get_stats.restype = C.c_int
         L.ff_sim_chains_get_stats.argtypes = [vp, vp]
         L.ff_sim_strerror.restype = C.c_char_p
@@ -138,6 +143,14 @@ def ff_sim_delta(chains, d_muts, n_steps, d_out_ns, stream=None):
 
 def ff_sim_chains_destroy(chains):
     lib().ff_sim_chains_destroy(chains)
+
+
+def ff_sim_delta_try_workspace_bytes(chains, M):
+    return lib().ff_sim_delta_try_workspace_bytes(chains, M)
+
+
+def ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream=None):
+    _check(lib().ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream), "ff_sim_delta_try")
 
 
 def ff_sim_chains_get_stats(chains, n_chains):
@@ -250,6 +263,20 @@ class Chains:
             d_out = torch.empty((n_steps, self.C), dtype=torch.int64, device="cuda")
         ff_sim_delta(self.handle, d_muts.data_ptr(), n_steps, d_out.data_ptr(),
                      torch.cuda.current_stream().cuda_stream)
+        return d_out
+
+    def try_mutations(self, d_muts, M, d_out=None):
+        """evaluate M proposals per chain ([M][C] mutations) without changing the chains."""
+        torch = _torch()
+        need = ff_sim_delta_try_workspace_bytes(self.handle, M)
+        sim = self.sim
+        if sim._ws is None or sim._ws.numel() < need:
+            sim._ws = None
+            sim._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            ff_sim_set_workspace(sim.handle, sim._ws.data_ptr(), sim._ws.numel())
+        if d_out is None:
+            d_out = torch.empty((M, self.C), dtype=torch.int64, device="cuda")
+        ff_sim_delta_try(self.handle, d_muts.data_ptr(), M, d_out.data_ptr(), torch.cuda.current_stream().cuda_stream)
         return d_out
 
     def stats(self):

@@ -42,7 +42,8 @@ struct ff_sim {
     size_t lds = 0;               // dynamic LDS per wavefront, batch kernel
     size_t lds_common = 0;        // device rows + queue levels 1 and 2
     size_t lds_chain = 0;         // dynamic LDS per wavefront, chain kernel (adds the strategy; words in HBM)
-    uint32_t max_slots = 0;       // wavefronts the device can hold at once
+    uint32_t max_slots = 0;       // wavefronts the device can hold at once (batch kernel)
+    uint32_t max_try_slots = 0;   // same for the trial-mutation kernel
     void* ws = nullptr;
     size_t ws_bytes = 0;
     ff_stats_t* d_stats = nullptr;
@@ -69,6 +70,9 @@ static batch_kernel_t batch_kernel(const ff_sim* s) {
     return s->lds_words ? k_sim_batch<false, true> : k_sim_batch<false, false>;
 }
 static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
+typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
+                             uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, unsigned char*, size_t);
+static try_kernel_t try_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_try<true> : k_sim_chain_try<false>; }
 
 static void release(ff_sim* s) {
     if (!s) return;
@@ -212,6 +216,10 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, batch_kernel(s), WAVE, s->lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_slots = (uint32_t)cus * (uint32_t)per_cu;
+    per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, try_kernel(s), WAVE, s->lds_chain);
+    if (e != hipSuccess || per_cu < 1) per_cu = 1;
+    s->max_try_slots = (uint32_t)cus * (uint32_t)per_cu;
     *out = s;
     return FF_OK;
 }
@@ -292,6 +300,26 @@ int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, 
     if (!c || (n_steps && (!d_muts || !d_out_ns))) return FF_EINVAL;
     if (n_steps == 0) return FF_OK;
     return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream);
+}
+
+size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* c, uint32_t M) {
+    if (!c) return 0;
+    const uint64_t total = (uint64_t)M * c->C;
+    return (size_t)std::max<uint64_t>(1, std::min<uint64_t>(total, c->sim->max_try_slots)) * c->sim->slot_bytes;
+}
+
+int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, uint64_t* d_out_ns, void* hip_stream) {
+    if (!c || (M && (!d_muts || !d_out_ns))) return FF_EINVAL;
+    if (M == 0) return FF_OK;
+    if ((uint64_t)M * c->C > 0xffffffffull) return FF_ERANGE;
+    ff_sim* s = c->sim;
+    const uint32_t total = M * c->C;
+    const uint32_t slots = std::min(total, s->max_try_slots);
+    if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
+    hipLaunchKernelGGL(try_kernel(s), dim3(slots), dim3(WAVE), s->lds_chain, (hipStream_t)hip_stream, s->dev, s->d_ops, s->d_edges,
+                       s->d_in_edges, s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, M,
+                       (u64*)d_out_ns, c->d_flags, (unsigned char*)s->ws, s->slot_bytes);
+    return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
 int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {

@@ -724,15 +724,15 @@ __device__ __forceinline__ ChainMem carve_chain(unsigned char* base, const SimDe
     return c;
 }
 
-// Decides where a simulation of the chain's current strategy may start after op `mo` went
-// from configuration `ocfg` to the one now in m.cfgs: returns the snapshot index to resume
-// from (0 = start from time 0) and rewrites, in every snapshot that stays valid, what the
-// snapshots hold about op mo.
-__device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, const ChainMeta& meta, uint32_t mo, uint2 ocfg) {
+// Where may a simulation start after op `mo` went from configuration `ocfg` to the one now
+// in m.cfgs?  Nothing can differ before the first task of a producer of op mo finishes (the
+// transfers released then are the first tasks that depend on op mo's configuration); time 0
+// if op mo has no producer or has a part without inputs.  Returns the index of the last
+// snapshot at or before that time (0 = start from time 0) and, in pend_new, the number of
+// inputs every part of op mo waits for under the new configuration.
+__device__ __forceinline__ uint32_t resume_point(const Sim& m, const u64* end_of, const ChainMeta& meta, uint32_t mo, uint2 ocfg,
+                                                 uint32_t& pend_new) {
     const int lane = lane_id();
-    const SimDev& S = m.S;
-    // earliest time at which the old and the new simulation can differ: the first producer
-    // task of op mo to finish; time 0 if op mo has no producer or has a part without inputs
     const OpCfg cn = unpack_cfg(m.cfgs[mo]);
     const OpCfg co = unpack_cfg(ocfg);
     const uint32_t in_begin = m.T.ops[mo].in_begin, in_end = m.T.ops[mo].in_end;
@@ -740,10 +740,10 @@ __device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, 
     for (uint32_t q = in_begin; q < in_end; q++) {
         const uint32_t p = m.T.in_edges[q].src;
         const OpCfg cp = unpack_cfg(m.cfgs[p]);
-        const u64 t = wave_min_u64((uint32_t)lane < cp.parts ? rec.end_of[p * WAVE + lane] : W_NONE);
+        const u64 t = wave_min_u64((uint32_t)lane < cp.parts ? end_of[p * WAVE + lane] : W_NONE);
         tau = t < tau ? t : tau;
     }
-    const uint32_t pend_new = count_pending(m, mo, cn);
+    pend_new = count_pending(m, mo, cn);
     uint32_t pend_old = 0;
     {
         const uint32_t digits = part_digits(co, lane, m.magic_v);
@@ -755,21 +755,22 @@ __device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, 
     if (__ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
     u64 k64 = (2 * tau) / meta.step;
     if (k64 > meta.n_valid - 1) k64 = meta.n_valid - 1;
-    const uint32_t k = (uint32_t)k64;
-    if (k == 0) return 0;
+    return (uint32_t)k64;
+}
 
-    // Snapshots 1..k were taken before anything depended on op mo's configuration.  What they
-    // hold about it is static: the op's own tasks (all still waiting for all inputs) and, in
-    // its consumers' waiting tasks, how many inputs come from op mo.  Rewrite both for the new
-    // configuration in every snapshot that stays valid.
-    const uint32_t ob = m.T.ops[mo].out_begin, oe = m.T.ops[mo].out_end;
+// A simulation state taken before anything depended on op mo's configuration holds two static
+// things about it: the op's own tasks (all still waiting for all their inputs) and, in its
+// consumers' waiting tasks, how many inputs come from op mo.  Rewrites both for the new
+// configuration.  words / l1: the state to patch (a stored snapshot, or live state).
+__device__ __forceinline__ void patch_state_for_op(const Sim& m, u64* words, u64* l1, uint32_t mo, uint2 ocfg, uint32_t pend_new) {
+    const int lane = lane_id();
+    const OpCfg cn = unpack_cfg(m.cfgs[mo]);
+    const OpCfg co = unpack_cfg(ocfg);
     const u64 w_own = (uint32_t)lane >= cn.parts ? W_NONE : (W_WAIT | ((u64)pend_new << 48));
+    words[mo * WAVE + lane] = w_own;
     const u64 w_own_min = wave_min_u64(w_own);
-    for (uint32_t sn = 1; sn <= k; sn++) {
-        u64* sw = rec.snap_words + (size_t)sn * S.n_ops * WAVE;
-        sw[mo * WAVE + lane] = w_own;
-        if (lane == 0) rec.snap_l1[(size_t)sn * S.n_ops_pad + mo] = w_own_min;
-    }
+    if (lane == 0) l1[mo] = w_own_min;
+    const uint32_t ob = m.T.ops[mo].out_begin, oe = m.T.ops[mo].out_end;
     for (uint32_t ei = ob; ei < oe; ei++) {
         const DEdge e = m.T.edges[ei];
         const uint32_t j = e.dst;
@@ -778,18 +779,24 @@ __device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, 
         const uint32_t was = count_inputs(e, co, cj.x, digits, m.magic_v);
         const uint32_t is = count_inputs(e, cn, cj.x, digits, m.magic_v);
         if (!__ballot((uint32_t)lane < cj.parts && was != is)) continue;
-        for (uint32_t sn = 1; sn <= k; sn++) {
-            u64* sw = rec.snap_words + (size_t)sn * S.n_ops * WAVE;
-            u64 w = sw[j * WAVE + lane];
-            // a part of op j that reads op mo at all is still waiting in these snapshots
-            const bool waiting = (uint32_t)lane < cj.parts && (w >> 63) && w != W_NONE;
-            if (waiting && was != is) {
-                const uint32_t pending = ((uint32_t)(w >> 48) & PENDING_LIMIT) - was + is;
-                sw[j * WAVE + lane] = W_WAIT | ((u64)pending << 48) | (w & (TIME_LIMIT - 1));
-            }
-            // level 1 of op j is unaffected: waiting words are not events
+        const u64 w = words[j * WAVE + lane];
+        // a part of op j that reads op mo at all is still waiting in such a state
+        const bool waiting = (uint32_t)lane < cj.parts && (w >> 63) && w != W_NONE;
+        if (waiting && was != is) {
+            const uint32_t pending = ((uint32_t)(w >> 48) & PENDING_LIMIT) - was + is;
+            words[j * WAVE + lane] = W_WAIT | ((u64)pending << 48) | (w & (TIME_LIMIT - 1));
         }
+        // level 1 of op j is unaffected: waiting words are not events
     }
+}
+
+// The committed form of a mutation: every stored snapshot that stays valid is rewritten for
+// the new configuration of op mo.  Returns the snapshot index to resume from.
+__device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, const ChainMeta& meta, uint32_t mo, uint2 ocfg) {
+    uint32_t pend_new;
+    const uint32_t k = resume_point(m, rec.end_of, meta, mo, ocfg, pend_new);
+    for (uint32_t sn = 1; sn <= k; sn++)
+        patch_state_for_op(m, rec.snap_words + (size_t)sn * m.S.n_ops * WAVE, rec.snap_l1 + (size_t)sn * m.S.n_ops_pad, mo, ocfg, pend_new);
     __threadfence_block();
     wave_sync();
     return k;
@@ -896,6 +903,68 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     if (lane_id() == 0) {
         chain_flags[c] = poisoned ? 1u : 0u;
         *cm.meta = meta;
+    }
+}
+
+// Trial mutations (the proposals of Section 6.2 before acceptance): evaluates M alternative
+// single-op mutations per chain, each against the chain's current strategy and stored
+// timeline, without changing the chain.  One wavefront per (proposal, chain); its task words
+// live in a private workspace slot, the chain's snapshots are only read.
+template <bool WIDE>
+__global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
+                                                        const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
+                                                        const uint32_t* __restrict__ magic, const unsigned char* chain_mem,
+                                                        size_t chain_stride, uint32_t n_snaps, uint32_t C,
+                                                        const uint32_t* __restrict__ muts, uint32_t M, u64* __restrict__ out_ns,
+                                                        const uint32_t* __restrict__ chain_flags, unsigned char* __restrict__ ws,
+                                                        size_t slot_stride) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const Tables T{ops, edges, in_edges, cost};
+    uint2* cfg_lds = (uint2*)lds_raw;
+    const WaveLds L = carve_lds(lds_raw + (size_t)S.n_ops_pad * 8, S);
+    const uint32_t magic_v = load_magic(magic);
+    unsigned char* slot = ws + (size_t)blockIdx.x * slot_stride;
+    u64* words = (u64*)slot;
+    uint32_t* exe_of = (uint32_t*)(slot + (size_t)S.n_ops * WAVE * 8);
+    const uint32_t total = M * C;
+    for (uint32_t id = blockIdx.x; id < total; id += gridDim.x) {
+        const uint32_t c = id % C;
+        const ChainMem cm = carve_chain(const_cast<unsigned char*>(chain_mem) + (size_t)c * chain_stride, S, n_snaps);
+        ChainMeta meta = *cm.meta;
+        meta.step = first_u64(meta.step);
+        meta.n_valid = first_u32(meta.n_valid);
+        meta.stale = first_u32(meta.stale);
+        wave_sync();
+        for (uint32_t i = lane_id(); i < S.n_ops; i += WAVE) cfg_lds[i] = cm.cfgs[i];
+        wave_sync();
+        const uint32_t* mu = muts + (size_t)id * 3;     // [M][C] records {op, cfg.x, cfg.y}
+        const uint32_t op = first_u32(mu[0]);
+        u64 mk = RESULT_INVALID;
+        if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
+            const uint2 ocfg = cfg_lds[op];
+            wave_sync();
+            if (lane_id() == 0) cfg_lds[op] = make_uint2(mu[1], mu[2]);
+            wave_sync();
+            Sim m{S, T, cfg_lds, words, exe_of, L, magic_v, 0, false};
+            if (validate_strategy(m)) {
+                Counters cnt = {};
+                Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
+                uint32_t k = 0, pend_new = 0;
+                if (!meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
+                if (k == 0) {
+                    init_state(m, cnt);
+                } else {
+                    load_snapshot(m, rec, k);
+                    patch_state_for_op(m, m.words, L.l1, op, ocfg, pend_new);
+                    wave_sync();
+                    rebuild_l2(m);
+                }
+                const u64 rc = run_events<WIDE, false>(m, cnt, rec);
+                mk = rc ? rc : makespan(m);
+            }
+        }
+        if (lane_id() == 0) out_ns[id] = mk;
+        wave_sync();
     }
 }
 

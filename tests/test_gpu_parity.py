@@ -417,3 +417,39 @@ def test_random_graphs_machines_and_strategies(B, seed):
         assert np.array_equal(d[:, c], ref), f"chain {c}: steps {np.nonzero(d[:, c] != ref)[0][:5]}"
     ch.close()
     sim.close()
+
+
+@pytest.mark.parametrize("config_id,C,M", [(1, 3, 40), (2, 2, 24), (4, 1, 6)])
+def test_trial_mutations_do_not_change_the_chain(B, config_id, C, M):
+    """ff_sim_delta_try: M proposals per chain, each equal to a full simulation of the
+    chain's current strategy with that one op changed; the chains continue afterwards as
+    if nothing had been tried."""
+    w = W.workload(config_id)
+    sim = sim_for(B, config_id)
+    cfg0 = w.strategies(C)
+    ch = B.Chains(sim, cfg0)
+    warm = w.mutations(5, C)
+    ch.delta(ch.upload_mutations(warm), 5)
+    cur = cfg0.copy()
+    for s in range(5):
+        for c in range(C):
+            cur[c, int(warm[s, c]["op"])] = warm[s, c]["cfg"]
+    props = w.mutations(5 + M, C)[5:]
+    props["op"][0] = 0                       # a source op: nothing of the old timeline can be kept
+    props["op"][1] = w.n_ops - 1
+    props[2, 0]["cfg"]["deg"] = (64, 64, 1, 1)   # an invalid proposal
+    got = ch.try_mutations(ch.upload_mutations(props), M).cpu().numpy().view("<u8")
+    for c in range(C):
+        cand = np.repeat(cur[c][None], M, 0)
+        for p in range(M):
+            cand[p, int(props[p, c]["op"])] = props[p, c]["cfg"]
+        want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cand, n_threads=8)
+        bad = np.nonzero(got[:, c] != want)[0]
+        assert len(bad) == 0, f"chain {c}: proposals {bad[:5]} gpu {got[bad[:5], c]} oracle {want[bad[:5]]}"
+    assert got[2, 0] == B.FF_INVALID_NS
+    more = w.mutations(9, C)[5:]
+    after = ch.delta(ch.upload_mutations(more), 4).cpu().numpy().view("<u8")
+    for c in range(C):
+        ref = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cur[c], more[:, c])
+        assert np.array_equal(after[:, c], ref)
+    ch.close()
