@@ -184,6 +184,33 @@ def main():
                 ref = oracle.simulate_delta_chain(w4.ops, w4.edges, w4.machine, w4.cost, cfgs4[0], muts[:, 0], steps=sel)
                 d["bit_exact_on_sampled_steps"] = bool(np.array_equal(out.cpu().numpy().view("<u8")[sel, 0], ref))
             delta.append(d)
+            if C == 1:
+                # proposals evaluated side by side against the chain's stored timeline (not committed)
+                M = 1024
+                props = w4.mutations(n_steps + M, 1)[n_steps:]
+                d_p = ch.upload_mutations(props)
+                ch.try_mutations(d_p, 8)
+                torch.cuda.synchronize()
+                a.record()
+                tried = ch.try_mutations(d_p, M)
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b)
+                t = {"workload": "configs[4] nmt", "chains": 1, "proposals": M, "ms": ms,
+                     "kind": "trial mutations (ff_sim_delta_try), all against the same current strategy",
+                     "delta_sims_per_s": M / (ms * 1e-3)}
+                if not args.no_cpu:
+                    import oracle
+                    cur = cfgs4[0].copy()
+                    for s_ in range(n_steps):
+                        cur[int(muts[s_, 0]["op"])] = muts[s_, 0]["cfg"]
+                    sel = [0, M // 2, M - 1]
+                    cand = np.repeat(cur[None], len(sel), 0)
+                    for q, p_ in enumerate(sel):
+                        cand[q, int(props[p_, 0]["op"])] = props[p_, 0]["cfg"]
+                    ref = oracle.simulate_batch(w4.ops, w4.edges, w4.machine, w4.cost, cand, n_threads=threads)
+                    t["bit_exact_on_sampled_proposals"] = bool(np.array_equal(tried.cpu().numpy().view("<u8")[sel, 0], ref))
+                delta.append(t)
             ch.close()
         line["delta"] = delta
     if not args.only_headline:

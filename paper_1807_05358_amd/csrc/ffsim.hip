@@ -56,6 +56,7 @@ struct ff_chains {
     size_t stride = 0;             // bytes per chain
     unsigned char* d_mem = nullptr; // [C] chain blocks: strategy, task words, endTimes, snapshots
     uint32_t* d_flags = nullptr;   // [C] nonzero once a chain saw an out-of-range mutation
+    uint32_t* d_counter = nullptr; // work counter of the trial-mutation kernel
 };
 
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
@@ -71,7 +72,7 @@ static batch_kernel_t batch_kernel(const ff_sim* s) {
 }
 static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
 typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
-                             uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, unsigned char*, size_t);
+                             uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);
 static try_kernel_t try_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_try<true> : k_sim_chain_try<false>; }
 
 static void release(ff_sim* s) {
@@ -217,7 +218,7 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_slots = (uint32_t)cus * (uint32_t)per_cu;
     per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, try_kernel(s), WAVE, s->lds_chain);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, try_kernel(s), WAVE, s->lds_common);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_try_slots = (uint32_t)cus * (uint32_t)per_cu;
     *out = s;
@@ -281,7 +282,8 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t row_bytes = (size_t)s->dev.n_ops * sizeof(uint2);
     if (hipMalloc((void**)&c->d_mem, (size_t)C * c->stride) != hipSuccess ||
-        hipMalloc((void**)&c->d_flags, (size_t)C * 4) != hipSuccess) { ff_sim_chains_destroy(c); return FF_ENOMEM; }
+        hipMalloc((void**)&c->d_flags, (size_t)C * 4) != hipSuccess ||
+        hipMalloc((void**)&c->d_counter, 256) != hipSuccess) { ff_sim_chains_destroy(c); return FF_ENOMEM; }
     // zero everything (snapshot bookkeeping starts empty), then drop each chain's strategy at
     // the head of its block
     if (hipMemsetAsync(c->d_mem, 0, (size_t)C * c->stride, st) != hipSuccess ||
@@ -316,9 +318,10 @@ int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, ui
     const uint32_t total = M * c->C;
     const uint32_t slots = std::min(total, s->max_try_slots);
     if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
-    hipLaunchKernelGGL(try_kernel(s), dim3(slots), dim3(WAVE), s->lds_chain, (hipStream_t)hip_stream, s->dev, s->d_ops, s->d_edges,
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(WAVE), 0, (hipStream_t)hip_stream, c->d_counter);
+    hipLaunchKernelGGL(try_kernel(s), dim3(slots), dim3(WAVE), s->lds_common, (hipStream_t)hip_stream, s->dev, s->d_ops, s->d_edges,
                        s->d_in_edges, s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, M,
-                       (u64*)d_out_ns, c->d_flags, (unsigned char*)s->ws, s->slot_bytes);
+                       (u64*)d_out_ns, c->d_flags, c->d_counter, (unsigned char*)s->ws, s->slot_bytes);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
@@ -342,6 +345,7 @@ void ff_sim_chains_destroy(ff_chains_t* c) {
     if (!c) return;
     hipFree(c->d_mem);
     hipFree(c->d_flags);
+    hipFree(c->d_counter);
     delete c;
 }
 

@@ -173,18 +173,11 @@ __device__ __forceinline__ void needed_range(const DMap& m, uint32_t extent, uin
                                              uint32_t magic_v, int32_t& lo, int32_t& hi) {
     if (m.src_dim < 0) { lo = 0; hi = (int32_t)extent; return; }   // uniform
     const uint32_t sh = 8u * (uint32_t)m.src_dim;
-    const uint32_t degc = (cfg_x >> sh) & 0xff;
+    const Divisor dv = divisor((cfg_x >> sh) & 0xff, magic_v);
+    const uint32_t idx = (digits >> sh) & 0xff;
+    const int32_t clo = (int32_t)div_by(idx * m.cext, dv);
+    const int32_t chi = (int32_t)div_by((idx + 1) * m.cext, dv);
     const int32_t E = (int32_t)extent;
-    int32_t clo, chi;
-    if (degc == 1) {      // uniform: the consumer is not split along this dim, every part reads the same range
-        clo = 0;
-        chi = (int32_t)m.cext;
-    } else {
-        const Divisor dv = divisor(degc, magic_v);
-        const uint32_t idx = (digits >> sh) & 0xff;
-        clo = (int32_t)div_by(idx * m.cext, dv);
-        chi = (int32_t)div_by((idx + 1) * m.cext, dv);
-    }
     int32_t l = clo * (int32_t)m.stride + m.a;
     int32_t h = (chi - 1) * (int32_t)m.stride + m.b + 1;
     l = l < 0 ? 0 : (l > E ? E : l);
@@ -253,7 +246,10 @@ __device__ __forceinline__ u64 fifo_commit(bool act, uint32_t row, u64 exe, u64 
 // Everything one wavefront needs to simulate its candidate.  cfgs is deliberately not
 // __restrict__: the chain kernel rewrites a configuration between simulations, so loads
 // from it must not be treated as invariant.
-struct Sim {
+// OVR: one op's configuration may be overridden (trial mutations); the plain form does not
+// pay for the comparison.
+template <bool OVR>
+struct SimT {
     const SimDev& S;
     const Tables& T;
     const uint2* cfgs;       // the candidate's n_ops configurations
@@ -263,7 +259,19 @@ struct Sim {
     uint32_t magic_v;
     u64 last_key;            // lower bound of every pending event word
     bool overflow;
+    // a trial mutation: op ov_op is simulated with configuration ov_cfg instead of cfgs[ov_op]
+    uint32_t ov_op;          // 0xffffffff = none
+    uint2 ov_cfg;
+    __device__ __forceinline__ uint2 cfg_raw(uint32_t j) const {
+        uint2 c = cfgs[j];
+        if (OVR && j == ov_op) c = ov_cfg;
+        return c;
+    }
+    __device__ __forceinline__ OpCfg cfg(uint32_t j) const { return unpack_cfg(cfg_raw(j)); }
 };
+constexpr uint32_t NO_OVERRIDE = 0xffffffffu;
+typedef SimT<false> Sim;
+typedef SimT<true> SimTrial;
 
 // Optional recording for delta simulation: endTime of every task, and snapshots of the
 // simulation state whenever the event time crosses a multiple of `step`.
@@ -299,30 +307,33 @@ __device__ __forceinline__ uint32_t count_inputs(const DEdge& e, const OpCfg& cp
 }
 
 // number of inputs every part of op j waits for (Section 5.1 step 2, counted in closed form)
-__device__ __forceinline__ uint32_t count_pending(const Sim& m, uint32_t j, const OpCfg& cj) {
+template <class SimX>
+__device__ __forceinline__ uint32_t count_pending(const SimX& m, uint32_t j, const OpCfg& cj) {
     const uint32_t in_begin = m.T.ops[j].in_begin, in_end = m.T.ops[j].in_end;
     const uint32_t digits = part_digits(cj, lane_id(), m.magic_v);
     uint32_t pending = 0;
     for (uint32_t q = in_begin; q < in_end; q++) {
         const DEdge e = m.T.in_edges[q];
-        const OpCfg ci = unpack_cfg(m.cfgs[e.src]);
+        const OpCfg ci = m.cfg(e.src);
         pending += count_inputs(e, ci, cj.x, digits, m.magic_v);
     }
     return pending;
 }
 
 // Section 4: every configuration valid?  Also fills exe_of.
-__device__ __forceinline__ bool validate_strategy(const Sim& m) {
+template <class SimX>
+__device__ __forceinline__ bool validate_strategy(const SimX& m) {
     bool bad = false;
     for (uint32_t i = lane_id(); i < m.S.n_ops; i += WAVE) {
-        OpCfg c = unpack_cfg_lane(m.cfgs[i]);
+        OpCfg c = unpack_cfg_lane(m.cfg_raw(i));
         if (!cfg_ok(m.T.ops[i], c, m.S)) bad = true;
         else m.exe_of[i] = m.T.cost[(size_t)i * m.S.n_cols + (c.parts - 1)];
     }
     return !__ballot(bad);
 }
 
-__device__ __forceinline__ void rebuild_l2(const Sim& m) {
+template <class SimX>
+__device__ __forceinline__ void rebuild_l2(const SimX& m) {
     if (m.S.n_groups > FLAT_GROUPS) {
         for (uint32_t g = 0; g < m.S.n_groups; g++) {
             const u64 wmin = wave_min_u64(m.L.l1[g * WAVE + lane_id()]);
@@ -334,11 +345,12 @@ __device__ __forceinline__ void rebuild_l2(const Sim& m) {
 
 // Section 5.1 step 1 and the start of Algorithm 1: the tasks, how many inputs each waits
 // for, the initial READY set, idle devices.
-__device__ __forceinline__ void init_state(Sim& m, Counters& cnt) {
+template <class SimX>
+__device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
     const int lane = lane_id();
     for (uint32_t r = lane; r < m.S.n_rows; r += WAVE) m.L.free_at[r] = 0;
     for (uint32_t j = 0; j < m.S.n_ops; j++) {
-        const OpCfg cj = unpack_cfg(m.cfgs[j]);
+        const OpCfg cj = m.cfg(j);
         const uint32_t pending = count_pending(m, j, cj);
         // pending < PENDING_LIMIT is guaranteed by ff_sim_create (at most 511 in-edges per op)
         const u64 w = (uint32_t)lane >= cj.parts ? W_NONE : (pending == 0 ? 1ull : (W_WAIT | ((u64)pending << 48)));
@@ -371,7 +383,8 @@ __device__ __forceinline__ void copy_words(u64* __restrict__ dst, const u64* __r
     for (; t < n4; t += WAVE) d4[t] = s4[t];
 }
 
-__device__ __forceinline__ void save_snapshot(const Sim& m, Recorder& rec) {
+template <class SimX>
+__device__ __forceinline__ void save_snapshot(const SimX& m, Recorder& rec) {
     const int lane = lane_id();
     const size_t k = rec.next;
     copy_words(rec.snap_words + k * (size_t)m.S.n_ops * WAVE, m.words, m.S.n_ops * WAVE);
@@ -382,7 +395,8 @@ __device__ __forceinline__ void save_snapshot(const Sim& m, Recorder& rec) {
     rec.next++;
 }
 
-__device__ __forceinline__ void load_snapshot(Sim& m, const Recorder& rec, uint32_t k) {
+template <class SimX>
+__device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint32_t k) {
     const int lane = lane_id();
     copy_words(m.words, rec.snap_words + (size_t)k * m.S.n_ops * WAVE, m.S.n_ops * WAVE);
     const u64* l1 = rec.snap_l1 + (size_t)k * m.S.n_ops_pad;
@@ -396,15 +410,14 @@ __device__ __forceinline__ void load_snapshot(Sim& m, const Recorder& rec, uint3
 
 // Algorithm 1, main loop, from the current state to the end.  RECORD: keep endTimes and
 // snapshots for delta simulation.  Returns 0 or a RESULT_* code.
-template <bool WIDE, bool RECORD>
-__device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
+template <bool WIDE, bool RECORD, class SimX>
+__device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const int lane = lane_id();
     PROF_DECL
     const SimDev& S = m.S;
     const WaveLds& L = m.L;
     const DOp* __restrict__ ops = m.T.ops;
     const DEdge* __restrict__ edges = m.T.edges;
-    const uint2* cfgs = m.cfgs;
     u64* words = m.words;
     const uint32_t magic_v = m.magic_v;
     u64 last_key = m.last_key;
@@ -452,7 +465,7 @@ __device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
         u64 k0 = words[i * WAVE + lane];
         const DOp* __restrict__ opi_p = ops + i;
         const uint32_t out_begin = opi_p->out_begin, out_end = opi_p->out_end;
-        const OpCfg ci = unpack_cfg(cfgs[i]);
+        const OpCfg ci = m.cfg(i);
         const u64 exe = m.exe_of[i];
         const u64 mask = __ballot(k0 == kmin);            // parts of op i that hold the minimum
         if (!mask) { cnt.exit_code = 2; return RESULT_INTERNAL; }
@@ -478,7 +491,7 @@ __device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
                 if (ei != out_begin) e = edges[ei];
                 const uint32_t j = e.dst;
                 u64 w = words[j * WAVE + lane];
-                const OpCfg cj = unpack_cfg(cfgs[j]);
+                const OpCfg cj = m.cfg(j);
                 const bool mine = (uint32_t)lane < cj.parts;
                 const uint32_t digits = part_digits(cj, lane, magic_v);
                 int32_t nlo[4], nhi[4];
@@ -492,28 +505,16 @@ __device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
                 bool touched = false;
-                // dims along which the producer is not split overlap the same way for every
-                // producer part: take them out of the loop over parts
-                bool base_hit = mine;
-                u64 base_elems = 1;
-#pragma unroll
-                for (int d = 0; d < 4; d++) {
-                    if ((uint32_t)d < e.src_ndim && ci.deg[d] == 1) {
-                        base_hit = base_hit && nhi[d] > nlo[d];
-                        if (WIDE) base_elems *= (u64)(uint32_t)(nhi[d] - nlo[d]);
-                        else base_elems = (uint32_t)base_elems * (uint32_t)(nhi[d] - nlo[d]);
-                    }
-                }
-                u64 todo = __ballot(base_hit) ? mask : 0;
+                u64 todo = mask;
                 PROF_MARK(3)
                 while (todo) {
                     const int kp = __builtin_ctzll(todo);
                     todo &= todo - 1;
-                    bool hit = base_hit;
-                    u64 elems = base_elems;
+                    bool hit = mine;
+                    u64 elems = 1;
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
-                        if ((uint32_t)d < e.src_ndim && ci.deg[d] != 1) {
+                        if ((uint32_t)d < e.src_ndim) {
                             const int32_t plo = (int32_t)readlane_u32(pb.lo[d], kp), phi = (int32_t)readlane_u32(pb.hi[d], kp);
                             const int32_t lo = nlo[d] > plo ? nlo[d] : plo;
                             const int32_t hi = nhi[d] < phi ? nhi[d] : phi;
@@ -600,7 +601,8 @@ __device__ u64 run_events(Sim& m, Counters& cnt, Recorder& rec) {
 
 // Algorithm 1, result (largest endTime): every transfer feeds a compute task that ends
 // later, so the makespan is the largest free time over the compute device rows.
-__device__ __forceinline__ u64 makespan(const Sim& m) {
+template <class SimX>
+__device__ __forceinline__ u64 makespan(const SimX& m) {
     u64 mk = 0;
     for (uint32_t d = lane_id(); d < m.S.n_dev; d += WAVE) mk = m.L.free_at[d] > mk ? m.L.free_at[d] : mk;
     return wave_max_u64(mk);
@@ -658,7 +660,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
         cnt.want_check = stats != nullptr;
-        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false};
+        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
         const u64 mk = simulate_candidate<WIDE, false>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (stats) store_counters(cnt, stats + b);
@@ -730,16 +732,17 @@ __device__ __forceinline__ ChainMem carve_chain(unsigned char* base, const SimDe
 // if op mo has no producer or has a part without inputs.  Returns the index of the last
 // snapshot at or before that time (0 = start from time 0) and, in pend_new, the number of
 // inputs every part of op mo waits for under the new configuration.
-__device__ __forceinline__ uint32_t resume_point(const Sim& m, const u64* end_of, const ChainMeta& meta, uint32_t mo, uint2 ocfg,
+template <class SimX>
+__device__ __forceinline__ uint32_t resume_point(const SimX& m, const u64* end_of, const ChainMeta& meta, uint32_t mo, uint2 ocfg,
                                                  uint32_t& pend_new) {
     const int lane = lane_id();
-    const OpCfg cn = unpack_cfg(m.cfgs[mo]);
+    const OpCfg cn = m.cfg(mo);
     const OpCfg co = unpack_cfg(ocfg);
     const uint32_t in_begin = m.T.ops[mo].in_begin, in_end = m.T.ops[mo].in_end;
     u64 tau = in_end > in_begin ? W_NONE : 0;
     for (uint32_t q = in_begin; q < in_end; q++) {
         const uint32_t p = m.T.in_edges[q].src;
-        const OpCfg cp = unpack_cfg(m.cfgs[p]);
+        const OpCfg cp = m.cfg(p);
         const u64 t = wave_min_u64((uint32_t)lane < cp.parts ? end_of[p * WAVE + lane] : W_NONE);
         tau = t < tau ? t : tau;
     }
@@ -749,7 +752,7 @@ __device__ __forceinline__ uint32_t resume_point(const Sim& m, const u64* end_of
         const uint32_t digits = part_digits(co, lane, m.magic_v);
         for (uint32_t q = in_begin; q < in_end; q++) {
             const DEdge e = m.T.in_edges[q];
-            pend_old += count_inputs(e, unpack_cfg(m.cfgs[e.src]), co.x, digits, m.magic_v);
+            pend_old += count_inputs(e, m.cfg(e.src), co.x, digits, m.magic_v);
         }
     }
     if (__ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
@@ -762,9 +765,10 @@ __device__ __forceinline__ uint32_t resume_point(const Sim& m, const u64* end_of
 // things about it: the op's own tasks (all still waiting for all their inputs) and, in its
 // consumers' waiting tasks, how many inputs come from op mo.  Rewrites both for the new
 // configuration.  words / l1: the state to patch (a stored snapshot, or live state).
-__device__ __forceinline__ void patch_state_for_op(const Sim& m, u64* words, u64* l1, uint32_t mo, uint2 ocfg, uint32_t pend_new) {
+template <class SimX>
+__device__ __forceinline__ void patch_state_for_op(const SimX& m, u64* words, u64* l1, uint32_t mo, uint2 ocfg, uint32_t pend_new) {
     const int lane = lane_id();
-    const OpCfg cn = unpack_cfg(m.cfgs[mo]);
+    const OpCfg cn = m.cfg(mo);
     const OpCfg co = unpack_cfg(ocfg);
     const u64 w_own = (uint32_t)lane >= cn.parts ? W_NONE : (W_WAIT | ((u64)pend_new << 48));
     words[mo * WAVE + lane] = w_own;
@@ -774,7 +778,7 @@ __device__ __forceinline__ void patch_state_for_op(const Sim& m, u64* words, u64
     for (uint32_t ei = ob; ei < oe; ei++) {
         const DEdge e = m.T.edges[ei];
         const uint32_t j = e.dst;
-        const OpCfg cj = unpack_cfg(m.cfgs[j]);
+        const OpCfg cj = m.cfg(j);
         const uint32_t digits = part_digits(cj, lane, m.magic_v);
         const uint32_t was = count_inputs(e, co, cj.x, digits, m.magic_v);
         const uint32_t is = count_inputs(e, cn, cj.x, digits, m.magic_v);
@@ -865,7 +869,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.n_events = first_u64(meta.n_events);
     meta.n_events_full = first_u64(meta.n_events_full);
     Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
-    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false};
+    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
     for (uint32_t s = 0; s < n_steps; s++) {
         Counters cnt = {};
         u64 mk = RESULT_INVALID;
@@ -913,39 +917,39 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 template <bool WIDE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                         const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
-                                                        const uint32_t* __restrict__ magic, const unsigned char* chain_mem,
+                                                        const uint32_t* __restrict__ magic, const unsigned char* __restrict__ chain_mem,
                                                         size_t chain_stride, uint32_t n_snaps, uint32_t C,
                                                         const uint32_t* __restrict__ muts, uint32_t M, u64* __restrict__ out_ns,
-                                                        const uint32_t* __restrict__ chain_flags, unsigned char* __restrict__ ws,
-                                                        size_t slot_stride) {
+                                                        const uint32_t* __restrict__ chain_flags, uint32_t* __restrict__ next_item,
+                                                        unsigned char* __restrict__ ws, size_t slot_stride) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const Tables T{ops, edges, in_edges, cost};
-    uint2* cfg_lds = (uint2*)lds_raw;
-    const WaveLds L = carve_lds(lds_raw + (size_t)S.n_ops_pad * 8, S);
+    const WaveLds L = carve_lds(lds_raw, S);
     const uint32_t magic_v = load_magic(magic);
     unsigned char* slot = ws + (size_t)blockIdx.x * slot_stride;
     u64* words = (u64*)slot;
     uint32_t* exe_of = (uint32_t*)(slot + (size_t)S.n_ops * WAVE * 8);
     const uint32_t total = M * C;
-    for (uint32_t id = blockIdx.x; id < total; id += gridDim.x) {
+    // proposals differ a lot in cost (how much of the timeline they keep): wavefronts draw the
+    // next one from a counter instead of striding
+    for (;;) {
+        uint32_t id = 0;
+        if (lane_id() == 0) id = atomicAdd(next_item, 1u);
+        id = first_u32(id);
+        if (id >= total) break;
         const uint32_t c = id % C;
+        // the chain is only read here
         const ChainMem cm = carve_chain(const_cast<unsigned char*>(chain_mem) + (size_t)c * chain_stride, S, n_snaps);
         ChainMeta meta = *cm.meta;
         meta.step = first_u64(meta.step);
         meta.n_valid = first_u32(meta.n_valid);
         meta.stale = first_u32(meta.stale);
-        wave_sync();
-        for (uint32_t i = lane_id(); i < S.n_ops; i += WAVE) cfg_lds[i] = cm.cfgs[i];
-        wave_sync();
         const uint32_t* mu = muts + (size_t)id * 3;     // [M][C] records {op, cfg.x, cfg.y}
         const uint32_t op = first_u32(mu[0]);
         u64 mk = RESULT_INVALID;
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
-            const uint2 ocfg = cfg_lds[op];
-            wave_sync();
-            if (lane_id() == 0) cfg_lds[op] = make_uint2(mu[1], mu[2]);
-            wave_sync();
-            Sim m{S, T, cfg_lds, words, exe_of, L, magic_v, 0, false};
+            const uint2 ocfg = cm.cfgs[op];
+            SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2]))};
             if (validate_strategy(m)) {
                 Counters cnt = {};
                 Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
@@ -967,5 +971,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         wave_sync();
     }
 }
+
+// clears the work counter of k_sim_chain_try (a kernel, so that a captured stream sees a node)
+__global__ void k_zero_u32(uint32_t* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
 
 }  // namespace ffsim
