@@ -834,6 +834,11 @@ __device__ u64 chain_simulate(Sim& m, Recorder& rec, ChainMeta& meta, uint32_t k
     }
     meta.stale = 0;
     meta.n_valid = rec.next;
+    // the spacing was fixed by an earlier makespan; if the timeline has become more than twice
+    // shorter or longer, re-space: the snapshots just written are dropped and the next
+    // simulation starts from time 0 with the new spacing
+    const u64 ideal = (2 * mk) / capacity + 1;
+    if (ideal * 2 < meta.step || ideal > meta.step * 2) { meta.step = ideal; meta.n_valid = 1; }
     return mk;
 }
 

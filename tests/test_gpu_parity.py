@@ -453,3 +453,50 @@ def test_trial_mutations_do_not_change_the_chain(B, config_id, C, M):
         ref = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cur[c], more[:, c])
         assert np.array_equal(after[:, c], ref)
     ch.close()
+
+
+def test_delta_respaces_snapshots_when_the_timeline_shrinks(B):
+    """a chain that starts unsplit on one device (long timeline) and is then mutated op by op
+    to 16-way splits: the makespan falls by an order of magnitude; results stay exact."""
+    w = W.workload(1)
+    sim = sim_for(B, 1)
+    cfg0 = np.zeros((1, w.n_ops), W.CFG_DT)
+    cfg0["deg"] = 1
+    cfg0["dev_stride"] = 1
+    P = 16
+    muts = np.zeros((3 * w.n_ops, 1), W.MUT_DT)
+    for s in range(3 * w.n_ops):
+        i = s % w.n_ops
+        muts[s, 0]["op"] = i
+        muts[s, 0]["cfg"]["deg"] = (min(P, int(w.ops[i]["extent"][0])) if s < 2 * w.n_ops else 1, 1, 1, 1)
+        muts[s, 0]["cfg"]["dev_offset"] = s % 3
+        muts[s, 0]["cfg"]["dev_stride"] = 1
+    ch = B.Chains(sim, cfg0)
+    got = ch.delta(ch.upload_mutations(muts), len(muts)).cpu().numpy().view("<u8")
+    want = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[0], muts[:, 0])
+    assert want.max() > 4 * want.min()
+    assert np.array_equal(got[:, 0], want)
+    ch.close()
+
+
+def test_trial_mutations_need_a_workspace(B):
+    import torch
+    w = W.workload(0)
+    h = B.ff_sim_create(w.ops, w.edges, w.machine, w.cost)
+    cfg0 = w.strategies(2)
+    d = B.to_device(cfg0)
+    out0 = torch.empty(2, dtype=torch.int64, device="cuda")
+    ch = B.ff_sim_chains_create(h, d.data_ptr(), 2, out0.data_ptr())
+    props = B.to_device(w.mutations(4, 2))
+    out = torch.empty((4, 2), dtype=torch.int64, device="cuda")
+    L = B.lib()
+    assert L.ff_sim_delta_try(ch, props.data_ptr(), 4, out.data_ptr(), None) == B.FF_EWORKSPACE
+    need = B.ff_sim_delta_try_workspace_bytes(ch, 4)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    B.ff_sim_set_workspace(h, ws.data_ptr(), need)
+    assert L.ff_sim_delta_try(ch, props.data_ptr(), 4, out.data_ptr(), None) == B.FF_OK
+    assert L.ff_sim_delta_try(ch, None, 0, None, None) == B.FF_OK
+    torch.cuda.synchronize()
+    B.ff_sim_chains_destroy(ch)
+    B.ff_sim_destroy(h)
