@@ -117,6 +117,14 @@ def main():
             "hbm_traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get(c),
             "input_sha256": w.sha256(B),
         }
+        if not args.workloads and not args.only_headline:
+            # saturation: the same graph with four times as many candidates per launch
+            cfgs4x = w.strategies(4 * B)
+            d4 = sim.upload_strategies(cfgs4x)
+            k4, w4ms, _ = time_batches(sim, d4, 4 * B, 2, 1)
+            r["saturation_B"] = 4 * B
+            r["saturation_strategies_per_s"] = 4 * B / (w4ms * 1e-3)
+            del d4
         if not args.no_cpu:
             n_s = {0: 64, 1: 1024, 2: 128, 3: 64, 4: 16}[c]
             idx = np.linspace(0, B - 1, n_s).astype(np.int64)
