@@ -187,6 +187,39 @@ size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* chains, uint32_t M);
 int ff_sim_delta_try(ff_chains_t* chains, const ff_mutation_t* d_muts, uint32_t M, uint64_t* d_out_ns,
                      void* hip_stream);
 
+/* The search loop of Section 6 on the device, one Markov chain per chain: per step one
+ * proposal (Section 6.2: a random op gets a random configuration) is simulated as a trial
+ * and accepted by the Metropolis rule of Section 6.1, min(1, exp(beta*(cost - cost*))), which
+ * the caller supplies in integers so that every decision is reproducible: a proposal that is
+ * not slower is always accepted; one that is slower by delta ns is accepted iff
+ * (draw >> 32) < d_accept[min(delta / bucket_ns, n_buckets - 1)], i.e. d_accept holds
+ * probabilities scaled by 2^32.  Draws are counter based: with K = 0xD6E8FEB86659FD93 and
+ * mix64 = the SplitMix64 finaliser (x += 0x9E3779B97F4A7C15; x = (x ^ x>>30) * 0xBF58476D1CE4E5B9;
+ * x = (x ^ x>>27) * 0x94D049BB133111EB; x ^= x>>31),
+ *   draw(purpose, chain, step) = mix64(mix64(mix64(mix64(seed) ^ purpose*K) ^ chain*K) ^ step*K),
+ * step counted from first_step; op = draw(10) mod n_ops; the configuration is entry
+ * draw(11) mod (number of entries) of the op's list d_tuples[d_tuple_ptr[op] .. d_tuple_ptr[op+1])
+ * (four degrees, one byte each, deg[0] lowest), dev_offset = draw(12) mod n_devices,
+ * dev_stride = 1; the acceptance draw is draw(13).  An invalid proposal is rejected.
+ * d_trace_ns[s][c] receives the time of chain c's strategy after step s; d_best_ns[c] /
+ * d_best[c][n_ops] are updated whenever a step ends with a better time than d_best_ns[c]
+ * (initialise it to UINT64_MAX).  All d_* are device pointers.  The call copies n_ops+1
+ * integers back to validate d_tuple_ptr (it synchronises the stream's device). */
+typedef struct {
+    uint64_t seed;
+    uint64_t first_step;
+    uint64_t bucket_ns;
+    uint32_t n_buckets;
+    uint32_t n_tuples;              /* entries in d_tuples */
+    const uint32_t* d_accept;       /* [n_buckets] */
+    const uint32_t* d_tuple_ptr;    /* [n_ops + 1] */
+    const uint32_t* d_tuples;       /* [n_tuples] */
+    uint64_t* d_best_ns;            /* [C] in/out */
+    ff_opcfg_t* d_best;             /* [C][n_ops] out */
+} ff_search_t;
+int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_steps, uint64_t* d_trace_ns,
+                  void* hip_stream);
+
 /* Telemetry of the chains (HOST array of C records; synchronises the device): how many
  * mutations were applied, how many of them resumed from a stored snapshot of the timeline
  * instead of simulating from time 0, how many queue pops they took in total, and how many

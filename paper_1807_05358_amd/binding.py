@@ -34,9 +34,18 @@ class ff_costtable_t(C.Structure):
 
 EXPORTS = ["ff_sim_create", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
-           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes",
+           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8")])
+
+
+
+class ff_search_t(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("first_step", C.c_uint64), ("bucket_ns", C.c_uint64),
+                ("n_buckets", C.c_uint32), ("n_tuples", C.c_uint32),
+                ("d_accept", C.c_void_p), ("d_tuple_ptr", C.c_void_p), ("d_tuples", C.c_void_p),
+                ("d_best_ns", C.c_void_p), ("d_best", C.c_void_p)]
+
 
 _lib = None
 
@@ -78,6 +87,8 @@ def lib():
         L.ff_sim_delta_try.argtypes = [vp, vp, u32, vp, vp]
         L.ff_sim_delta_try_workspace_bytes.restype = C.c_size_t
         L.ff_sim_delta_try_workspace_bytes.argtypes = [vp, u32]
+        L.ff_sim_search.restype = C.c_int
+        L.ff_sim_search.argtypes = [vp, C.POINTER(ff_search_t), u32, vp, vp]
         L.ff_sim_chains_get_stats.restype = C.c_int
         L.ff_sim_chains_get_stats.argtypes = [vp, vp]
         L.ff_sim_strerror.restype = C.c_char_p
@@ -151,6 +162,10 @@ def ff_sim_delta_try_workspace_bytes(chains, M):
 
 def ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream=None):
     _check(lib().ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream), "ff_sim_delta_try")
+
+
+def ff_sim_search(chains, params: ff_search_t, n_steps, d_trace_ns, stream=None):
+    _check(lib().ff_sim_search(chains, C.byref(params), n_steps, d_trace_ns, stream), "ff_sim_search")
 
 
 def ff_sim_chains_get_stats(chains, n_chains):
@@ -278,6 +293,39 @@ class Chains:
             d_out = torch.empty((M, self.C), dtype=torch.int64, device="cuda")
         ff_sim_delta_try(self.handle, d_muts.data_ptr(), M, d_out.data_ptr(), torch.cuda.current_stream().cuda_stream)
         return d_out
+
+    def search_setup(self, tuple_ptr, tuples, accept, bucket_ns, seed):
+        """uploads the proposal lists (workloads.search_space) and the acceptance table
+        (probabilities scaled by 2^32, one per bucket of bucket_ns) and resets the best-so-far
+        record.  Steps are numbered from 0 across the search() calls that follow."""
+        torch = _torch()
+        self._sp = dict(
+            tuple_ptr=to_device(np.ascontiguousarray(tuple_ptr, "<u4")),
+            tuples=to_device(np.ascontiguousarray(tuples, "<u4")),
+            accept=to_device(np.ascontiguousarray(accept, "<u4")),
+            best_ns=torch.full((self.C,), -1, dtype=torch.int64, device="cuda"),
+            best=torch.zeros(self.C * self.sim.n_ops * W.CFG_DT.itemsize, dtype=torch.uint8, device="cuda"),
+            n_tuples=len(tuples), n_buckets=len(accept), bucket_ns=int(bucket_ns), seed=int(seed), step=0)
+
+    def search(self, n_steps, d_trace=None):
+        """n_steps Metropolis steps on every chain; returns the device tensor [n_steps][C] of the
+        chains' times after each step (asynchronous apart from the argument check)."""
+        torch = _torch()
+        sp = self._sp
+        if d_trace is None:
+            d_trace = torch.empty((n_steps, self.C), dtype=torch.int64, device="cuda")
+        p = ff_search_t(sp["seed"], sp["step"], sp["bucket_ns"], sp["n_buckets"], sp["n_tuples"],
+                        sp["accept"].data_ptr(), sp["tuple_ptr"].data_ptr(), sp["tuples"].data_ptr(),
+                        sp["best_ns"].data_ptr(), sp["best"].data_ptr())
+        ff_sim_search(self.handle, p, n_steps, d_trace.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        sp["step"] += n_steps
+        return d_trace
+
+    def best(self):
+        """(best times [C] uint64, best strategies [C][n_ops] of workloads.CFG_DT) so far."""
+        sp = self._sp
+        return (sp["best_ns"].cpu().numpy().view("<u8"),
+                sp["best"].cpu().numpy().view(W.CFG_DT).reshape(self.C, self.sim.n_ops))
 
     def stats(self):
         return ff_sim_chains_get_stats(self.handle, self.C)

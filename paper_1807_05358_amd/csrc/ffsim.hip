@@ -64,7 +64,7 @@ constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const uint2*,
                                uint32_t, u64*, Counters*, unsigned char*, size_t);
 typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
-                               uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*);
+                               uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
 
 static batch_kernel_t batch_kernel(const ff_sim* s) {
     if (s->wide) return s->lds_words ? k_sim_batch<true, true> : k_sim_batch<true, false>;
@@ -259,12 +259,13 @@ int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
-static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out, hipStream_t st) {
+static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out, hipStream_t st,
+                              const SearchDev& search) {
     ff_sim* s = c->sim;
     static_assert(sizeof(ff_mutation_t) == 12, "mutation layout");
     hipLaunchKernelGGL(chain_kernel(s), dim3(c->C), dim3(WAVE), s->lds_chain, st, s->dev, s->d_ops, s->d_edges, s->d_in_edges,
                        s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, n_steps,
-                       (u64*)d_out, c->d_flags);
+                       (u64*)d_out, c->d_flags, search);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
@@ -292,7 +293,7 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
         ff_sim_chains_destroy(c);
         return FF_EHIP;
     }
-    int rc = launch_chain_steps(c, nullptr, 1, d_out_ns0, st);
+    int rc = launch_chain_steps(c, nullptr, 1, d_out_ns0, st, SearchDev{});
     if (rc) { ff_sim_chains_destroy(c); return rc; }
     *out = c;
     return FF_OK;
@@ -301,7 +302,26 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
 int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out_ns, void* hip_stream) {
     if (!c || (n_steps && (!d_muts || !d_out_ns))) return FF_EINVAL;
     if (n_steps == 0) return FF_OK;
-    return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream);
+    return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream, SearchDev{});
+}
+
+int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64_t* d_trace_ns, void* hip_stream) {
+    if (!c || !p || (n_steps && !d_trace_ns)) return FF_EINVAL;
+    if (!p->d_accept || !p->d_tuple_ptr || !p->d_tuples || !p->d_best_ns || !p->d_best || p->n_buckets < 1 || p->bucket_ns < 1 ||
+        p->n_tuples < 1) return FF_EINVAL;
+    if (n_steps == 0) return FF_OK;
+    // the per-op ranges index the tuple list on the device: check them here, once per call
+    const uint32_t n_ops = c->sim->dev.n_ops;
+    std::vector<uint32_t> ptr(n_ops + 1);
+    if (hipMemcpy(ptr.data(), p->d_tuple_ptr, ptr.size() * 4, hipMemcpyDeviceToHost) != hipSuccess) return FF_EHIP;
+    for (uint32_t i = 0; i < n_ops; i++)
+        if (ptr[i] > ptr[i + 1] || ptr[i + 1] > p->n_tuples) return FF_EINVAL;
+    SearchDev sd{};
+    sd.seed = p->seed; sd.first_step = p->first_step; sd.bucket_ns = p->bucket_ns;
+    sd.accept = p->d_accept; sd.tuple_ptr = p->d_tuple_ptr; sd.tuples = p->d_tuples;
+    sd.n_buckets = p->n_buckets; sd.enabled = 1;
+    sd.best_ns = (u64*)p->d_best_ns; sd.best_cfgs = (uint2*)p->d_best;
+    return launch_chain_steps(c, nullptr, n_steps, d_trace_ns, (hipStream_t)hip_stream, sd);
 }
 
 size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* c, uint32_t M) {
@@ -328,7 +348,7 @@ int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, ui
 int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
     if (!c || !h_out) return FF_EINVAL;
     if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;
-    static_assert(sizeof(ChainMeta) == 16 + sizeof(ff_chain_stats_t), "chain stats layout");
+    static_assert(sizeof(ChainMeta) == 24 + sizeof(ff_chain_stats_t), "chain stats layout");
     for (uint32_t k = 0; k < c->C; k++) {
         ChainMeta meta;
         const unsigned char* p = c->d_mem + (size_t)k * c->stride + chain_meta_offset(c->sim->dev.n_ops, c->sim->dev.n_ops_pad, c->sim->dev.n_rows, c->n_snaps);

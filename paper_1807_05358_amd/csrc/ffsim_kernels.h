@@ -480,7 +480,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
             if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
-            if (RECORD) { if (in_mask) rec.end_of[i * WAVE + lane] = end; }
+            if (RECORD) { if (in_mask && rec.end_of) rec.end_of[i * WAVE + lane] = end; }
             PROF_MARK(2)
         } else {
             // the parts in `mask` finished at `now`: release their successors edge by edge
@@ -687,6 +687,7 @@ struct ChainMeta {
     u64 n_resumed;      // of those, resumed from a snapshot instead of simulated from time 0
     u64 n_events;       // queue pops spent in mutation steps
     u64 n_events_full;  // queue pops of the last simulation from time 0 (one full simulation)
+    u64 cur_ns;         // simulated time of the chain's current strategy (result code if it has none)
 };
 
 struct ChainMem {       // all pointers are per chain
@@ -794,64 +795,58 @@ __device__ __forceinline__ void patch_state_for_op(const SimX& m, u64* words, u6
     }
 }
 
-// The committed form of a mutation: every stored snapshot that stays valid is rewritten for
-// the new configuration of op mo.  Returns the snapshot index to resume from.
-__device__ __forceinline__ uint32_t chain_prepare_resume(Sim& m, Recorder& rec, const ChainMeta& meta, uint32_t mo, uint2 ocfg) {
-    uint32_t pend_new;
-    const uint32_t k = resume_point(m, rec.end_of, meta, mo, ocfg, pend_new);
-    for (uint32_t sn = 1; sn <= k; sn++)
-        patch_state_for_op(m, rec.snap_words + (size_t)sn * m.S.n_ops * WAVE, rec.snap_l1 + (size_t)sn * m.S.n_ops_pad, mo, ocfg, pend_new);
-    __threadfence_block();
-    wave_sync();
-    return k;
+// ---- search (Section 6): proposals and Metropolis acceptance, all in integers ------------
+//
+// Counter-based draws: SplitMix64's finaliser chained over (seed, purpose, chain, step), the
+// same generator the input generators use, so a host reference can reproduce every decision.
+__device__ __forceinline__ u64 mix64(u64 x) {
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+__device__ __forceinline__ u64 draw64(u64 seed, u64 purpose, u64 chain, u64 step) {
+    const u64 K = 0xD6E8FEB86659FD93ull;
+    u64 h = mix64(seed);
+    h = mix64(h ^ (purpose * K));
+    h = mix64(h ^ (chain * K));
+    h = mix64(h ^ (step * K));
+    return h;
 }
 
-// Simulates the chain's current strategy, from snapshot k if k > 0, else from time 0, and
-// records endTimes and snapshots.  When no snapshot spacing is set yet, a first pass
-// without snapshots finds the makespan that fixes it.
-template <bool WIDE>
-__device__ u64 chain_simulate(Sim& m, Recorder& rec, ChainMeta& meta, uint32_t k, Counters& cnt) {
-    u64 mk = 0;
-    const uint32_t capacity = rec.n_snaps;
-    for (int pass = (k == 0 && meta.step == 0) ? 0 : 1; pass < 2; pass++) {
-        const u64 before = cnt.n_events;
-        rec.step = meta.step;
-        rec.n_snaps = pass == 0 ? 0 : capacity;
-        rec.next = k + 1;
-        if (k == 0) {
-            init_state(m, cnt);
-        } else {
-            load_snapshot(m, rec, k);
-            rebuild_l2(m);
-            meta.n_resumed++;
-        }
-        const u64 rc = run_events<WIDE, true>(m, cnt, rec);
-        rec.n_snaps = capacity;
-        if (rc) { meta.stale = 1; meta.n_valid = 0; return rc; }
-        mk = makespan(m);
-        if (pass == 0) meta.step = (2 * mk) / capacity + 1;
-        if (k == 0) meta.n_events_full = cnt.n_events - before;
-    }
-    meta.stale = 0;
-    meta.n_valid = rec.next;
-    // the spacing was fixed by an earlier makespan; if the timeline has become more than twice
-    // shorter or longer, re-space: the snapshots just written are dropped and the next
-    // simulation starts from time 0 with the new spacing
-    const u64 ideal = (2 * mk) / capacity + 1;
-    if (ideal * 2 < meta.step || ideal > meta.step * 2) { meta.step = ideal; meta.n_valid = 1; }
-    return mk;
-}
+// what ff_sim_search hands to the kernel (device pointers)
+struct SearchDev {
+    u64 seed;
+    u64 first_step;              // draws use first_step + s, so that consecutive calls continue one sequence
+    u64 bucket_ns;               // width of an acceptance bucket
+    const uint32_t* accept;      // [n_buckets] acceptance probability * 2^32 for a proposal worse by that bucket
+    const uint32_t* tuple_ptr;   // [n_ops+1] ranges into tuples[]
+    const uint32_t* tuples;      // degree tuples (four bytes each) a proposal may pick for each op
+    uint32_t n_buckets;
+    uint32_t enabled;
+    u64* best_ns;                // [C] best simulated time seen (in/out)
+    uint2* best_cfgs;            // [C][n_ops] the strategy that achieved it (in/out)
+};
 
-// muts == nullptr: simulate the chains' starting strategies (n_steps is 1).  Otherwise
-// muts is [n_steps][C] records {op, cfg.x, cfg.y}; a mutation that names an op outside the
-// graph poisons the chain: this and all later results are RESULT_INVALID.
+// One kernel drives a chain through a sequence of steps.  Three sources of steps:
+//   muts == nullptr and no search: simulate the chain's starting strategy (n_steps is 1);
+//   muts: forced mutations, [n_steps][C] records {op, cfg.x, cfg.y}, each committed;
+//   search: per step one proposal (random op, random configuration from its list, random
+//           device offset) is simulated as a trial and committed only if accepted:
+//           always when it is not slower, else with the tabulated probability.
+// Every simulation of a step goes through the single run_events call below: the trial
+// (nothing recorded), an optional pass that only finds the makespan when no snapshot spacing
+// is set yet, and the recorded run of the committed strategy.
+// A forced mutation that names an op outside the graph poisons the chain: this and all
+// later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
+// step s.
 template <bool WIDE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                           const uint32_t* __restrict__ magic, unsigned char* chain_mem,
                                                           size_t chain_stride, uint32_t n_snaps, uint32_t C,
                                                           const uint32_t* __restrict__ muts, uint32_t n_steps,
-                                                          u64* __restrict__ out_ns, uint32_t* chain_flags) {
+                                                          u64* __restrict__ out_ns, uint32_t* chain_flags, SearchDev search) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const Tables T{ops, edges, in_edges, cost};
     // the chain's strategy is worked on in LDS (and written through to HBM), so that the many
@@ -860,9 +855,10 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     const WaveLds L = carve_lds(lds_raw + (size_t)S.n_ops_pad * 8, S);
     const uint32_t c = blockIdx.x;
     if (c >= C) return;
+    const int lane = lane_id();
     const ChainMem cm = carve_chain(chain_mem + (size_t)c * chain_stride, S, n_snaps);
     const uint32_t magic_v = load_magic(magic);
-    for (uint32_t i = lane_id(); i < S.n_ops; i += WAVE) cfg_lds[i] = cm.cfgs[i];
+    for (uint32_t i = lane; i < S.n_ops; i += WAVE) cfg_lds[i] = cm.cfgs[i];
     wave_sync();
     bool poisoned = first_u32(chain_flags[c]) != 0;
     ChainMeta meta = *cm.meta;
@@ -873,45 +869,157 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.n_resumed = first_u64(meta.n_resumed);
     meta.n_events = first_u64(meta.n_events);
     meta.n_events_full = first_u64(meta.n_events_full);
+    meta.cur_ns = first_u64(meta.cur_ns);
     Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
     Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
+    u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
+    if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
+        // the strategy the search starts from counts as seen
+        best = meta.cur_ns;
+        for (uint32_t i = lane; i < S.n_ops; i += WAVE) search.best_cfgs[(size_t)c * S.n_ops + i] = cfg_lds[i];
+    }
+
     for (uint32_t s = 0; s < n_steps; s++) {
         Counters cnt = {};
-        u64 mk = RESULT_INVALID;
-        bool run = false;
-        uint32_t k = 0;
-        if (!muts) {
-            run = validate_strategy(m);
-            if (!run) meta.stale = 1;
-        } else {
+        bool trial = false, valid = true;
+        uint32_t op = 0;
+        uint2 ocfg = make_uint2(0, 0);
+        if (search.enabled) {
+            if (!poisoned && !meta.stale) {
+                const u64 st = search.first_step + s;
+                op = first_u32((uint32_t)(draw64(search.seed, 10, c, st) % S.n_ops));
+                const uint32_t t0 = first_u32(search.tuple_ptr[op]), t1 = first_u32(search.tuple_ptr[op + 1]);
+                if (t1 > t0) {   // an op without a list gets no proposals
+                    const uint32_t deg = search.tuples[t0 + (uint32_t)(draw64(search.seed, 11, c, st) % (t1 - t0))];
+                    const uint32_t off = (uint32_t)(draw64(search.seed, 12, c, st) % S.n_dev);
+                    ocfg = cfg_lds[op];
+                    wave_sync();
+                    if (lane == 0) cfg_lds[op] = make_uint2(first_u32(deg), first_u32(off) | (1u << 16));   // stride 1
+                    wave_sync();
+                    trial = true;
+                }
+            }
+        } else if (muts) {
             const uint32_t* mu = muts + ((size_t)s * C + c) * 3;
-            const uint32_t op = first_u32(mu[0]);
+            op = first_u32(mu[0]);
             if (op >= S.n_ops) poisoned = true;
             if (!poisoned) {
-                const uint2 ocfg = cfg_lds[op];
+                ocfg = cfg_lds[op];
                 wave_sync();
-                if (lane_id() == 0) {
+                if (lane == 0) {
                     const uint2 ncfg = make_uint2(mu[1], mu[2]);
                     cfg_lds[op] = ncfg;
                     cm.cfgs[op] = ncfg;
                 }
                 wave_sync();
-                run = validate_strategy(m);
-                if (!run) meta.stale = 1;
-                else if (!meta.stale && meta.n_valid > 1 && meta.step != 0) k = chain_prepare_resume(m, rec, meta, op, ocfg);
-                meta.n_steps++;
             }
         }
-        if (run) {
-            mk = chain_simulate<WIDE>(m, rec, meta, k, cnt);
-            if (muts) meta.n_events += cnt.n_events;
+        u64 mk = RESULT_INVALID;
+        if (!poisoned) valid = validate_strategy(m);
+        if (!poisoned && !valid && !trial) { meta.stale = 1; meta.cur_ns = RESULT_INVALID; }
+        const bool changed = muts != nullptr || trial;
+        if (changed && !poisoned) meta.n_steps++;
+
+        if (search.enabled && !trial && !poisoned && !meta.stale) {
+            mk = meta.cur_ns;   // no proposal this step: nothing to simulate
+        } else if (!poisoned && valid) {
+            // where the simulation may start (0 = time 0)
+            uint32_t k = 0, pend_new = 0;
+            if (changed && !meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, rec.end_of, meta, op, ocfg, pend_new);
+            if (!trial && k > 0) {
+                // a forced mutation is committed at once: rewrite the snapshots that stay valid
+                for (uint32_t sn = 1; sn <= k; sn++)
+                    patch_state_for_op(m, cm.snap_words + (size_t)sn * S.n_ops * WAVE, cm.snap_l1 + (size_t)sn * S.n_ops_pad, op, ocfg, pend_new);
+                __threadfence_block();
+                wave_sync();
+            }
+            const uint32_t capacity = n_snaps;
+            // phase 0: trial of a proposal; phase 1: makespan only (to fix the snapshot spacing);
+            // phase 2: the recorded simulation of the committed strategy
+            int phase = trial ? 0 : ((k == 0 && meta.step == 0) ? 1 : 2);
+            while (phase < 3) {
+                const bool record = phase == 2;
+                const u64 before = cnt.n_events;
+                rec.step = meta.step;
+                rec.n_snaps = record ? capacity : 0;
+                rec.end_of = record ? cm.end_of : nullptr;
+                rec.next = k + 1;
+                if (k == 0) {
+                    init_state(m, cnt);
+                } else {
+                    load_snapshot(m, rec, k);
+                    // a trial patches its private copy of the state; a committed mutation has
+                    // already rewritten the stored snapshots
+                    if (phase == 0) { patch_state_for_op(m, m.words, L.l1, op, ocfg, pend_new); wave_sync(); }
+                    rebuild_l2(m);
+                    if (record) meta.n_resumed++;
+                }
+                const u64 rc = run_events<WIDE, true>(m, cnt, rec);
+                rec.n_snaps = capacity;
+                rec.end_of = cm.end_of;
+                mk = rc ? rc : makespan(m);
+                if (phase == 0) {
+                    // Metropolis acceptance (Section 6.1) with tabulated probabilities
+                    bool accept = false;
+                    if (mk < RESULT_OVERFLOW) {
+                        if (mk <= meta.cur_ns) {
+                            accept = true;
+                        } else {
+                            u64 b = (mk - meta.cur_ns) / search.bucket_ns;
+                            if (b >= search.n_buckets) b = search.n_buckets - 1;
+                            const uint32_t u = (uint32_t)(draw64(search.seed, 13, c, search.first_step + s) >> 32);
+                            accept = u < search.accept[b];
+                        }
+                    }
+                    if (!accept) {
+                        wave_sync();
+                        if (lane == 0) cfg_lds[op] = ocfg;
+                        wave_sync();
+                        mk = meta.cur_ns;
+                        break;
+                    }
+                    if (lane == 0) cm.cfgs[op] = cfg_lds[op];
+                    // commit: rewrite what the snapshots that stay valid hold about the op
+                    for (uint32_t sn = 1; sn <= k; sn++)
+                        patch_state_for_op(m, cm.snap_words + (size_t)sn * S.n_ops * WAVE, cm.snap_l1 + (size_t)sn * S.n_ops_pad, op, ocfg, pend_new);
+                    __threadfence_block();
+                    wave_sync();
+                    phase = (k == 0 && meta.step == 0) ? 1 : 2;
+                    continue;
+                }
+                if (rc) { meta.stale = 1; meta.n_valid = 0; break; }
+                if (phase == 1) { meta.step = (2 * mk) / capacity + 1; phase = 2; continue; }
+                // phase 2 done
+                if (k == 0) meta.n_events_full = cnt.n_events - before;
+                meta.stale = 0;
+                meta.n_valid = rec.next;
+                meta.cur_ns = mk;
+                // the spacing was fixed by an earlier makespan; if the timeline has become more than
+                // twice shorter or longer, re-space: the snapshots just written are dropped and the
+                // next simulation starts from time 0 with the new spacing
+                const u64 ideal = (2 * mk) / capacity + 1;
+                if (ideal * 2 < meta.step || ideal > meta.step * 2) { meta.step = ideal; meta.n_valid = 1; }
+                break;
+            }
+            if (changed) meta.n_events += cnt.n_events;
+        } else if (trial && !valid) {
+            // an invalid proposal is rejected
+            wave_sync();
+            if (lane == 0) cfg_lds[op] = ocfg;
+            wave_sync();
+            mk = meta.cur_ns;
         }
-        if (lane_id() == 0) out_ns[(size_t)s * C + c] = mk;
+        if (search.enabled && !poisoned && mk < RESULT_OVERFLOW && mk < best) {
+            best = mk;
+            for (uint32_t i = lane; i < S.n_ops; i += WAVE) search.best_cfgs[(size_t)c * S.n_ops + i] = cfg_lds[i];
+        }
+        if (lane == 0) out_ns[(size_t)s * C + c] = mk;
         wave_sync();
     }
-    if (lane_id() == 0) {
+    if (lane == 0) {
         chain_flags[c] = poisoned ? 1u : 0u;
         *cm.meta = meta;
+        if (search.enabled) search.best_ns[c] = best;
     }
 }
 

@@ -491,6 +491,18 @@ def mutation_chains(ops, n_steps, n_chains, seed, n_dev, max_parts, choices):
     return out
 
 
+def search_space(ops, max_parts, choices):
+    """the proposal lists of a search: (tuple_ptr [n_ops+1] uint32, tuples uint32), the valid
+    degree tuples of every op, four bytes each (degree of dim 0 in the lowest byte)."""
+    ptr = np.zeros(len(ops) + 1, np.uint32)
+    chunks = []
+    for i, o in enumerate(ops):
+        t = valid_degree_tuples(o, max_parts, choices).astype(np.uint32)
+        chunks.append(t[:, 0] | (t[:, 1] << 8) | (t[:, 2] << 16) | (t[:, 3] << 24))
+        ptr[i + 1] = ptr[i] + len(t)
+    return ptr, np.concatenate(chunks).astype(np.uint32)
+
+
 def data_parallel_strategy(ops, n_dev, max_parts=MAX_PARTS):
     """every op split in the sample dim only, as far as the device count allows."""
     cfg = np.zeros(len(ops), CFG_DT)
@@ -536,6 +548,9 @@ class Workload:
     def mutations(self, n_steps, n_chains=1):
         return mutation_chains(self.ops, n_steps, n_chains, self.seed, self.machine.n_devices,
                                self.max_parts, self.choices)
+
+    def search_space(self):
+        return search_space(self.ops, self.max_parts, self.choices)
 
     def sha256(self, n=None):
         h = hashlib.sha256()

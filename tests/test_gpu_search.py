@@ -1,0 +1,149 @@
+"""GPU parity of the on-device search loop (ff_sim_search) against the search oracle: the same
+proposals, the same acceptance decisions, the same times after every step, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import search as S
+from paper_1807_05358_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1807_05358_amd import binding
+    return binding
+
+
+def _run_both(B, config_id, C, calls, beta_rel, seed, n_buckets=64):
+    """beta_rel: beta * (start time of chain 0); the bucket is 1/256 of that time."""
+    w = W.workload(config_id)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    cfg0 = w.strategies(C)
+    tp, tu = w.search_space()
+    t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[:1])[0])
+    bucket = max(1, t0 // 256)
+    table = S.metropolis_table(beta_rel / t0, bucket, n_buckets)
+    ch = B.Chains(sim, cfg0)
+    ch.search_setup(tp, tu, table, bucket, seed)
+    got = np.concatenate([ch.search(n).cpu().numpy().view("<u8") for n in calls])
+    best_ns, best = ch.best()
+    n_acc_total = 0
+    for c in range(C):
+        print(f"search: config {config_id} chain {c}", flush=True)
+        tr, cur, want_best_ns, want_best, n_acc = S.metropolis_chain(
+            w.ops, w.edges, w.machine, w.cost, cfg0[c], tp, tu, table, bucket, seed, c, 0, sum(calls))
+        bad = np.nonzero(got[:, c] != tr)[0]
+        assert len(bad) == 0, f"chain {c}: first differing step {bad[0]}: gpu {got[bad[0], c]} oracle {tr[bad[0]]}"
+        assert int(best_ns[c]) == want_best_ns
+        assert np.array_equal(best[c], want_best)
+        n_acc_total += n_acc
+    st = ch.stats()
+    ch.close()
+    sim.close()
+    return got, n_acc_total, st
+
+
+@pytest.mark.parametrize("config_id,C,calls,beta_rel", [
+    (0, 4, (40, 25), 20.0),
+    (1, 6, (50, 30), 40.0),
+    (2, 3, (14, 10), 60.0),
+    (3, 2, (12,), 60.0),
+    (4, 1, (6,), 100.0),
+])
+def test_search_matches_oracle(B, config_id, C, calls, beta_rel):
+    got, n_acc, st = _run_both(B, config_id, C, calls, beta_rel, seed=4242 + config_id)
+    n = sum(calls) * C
+    print(f"accepted {n_acc} of {n} proposals; resumed {int(st['n_resumed'].sum())} recorded runs", flush=True)
+    assert n_acc > 0
+    if n >= 24:
+        assert n_acc < n      # the case exercises both outcomes
+
+
+def test_pure_descent_and_always_accept(B):
+    w = W.workload(1)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    cfg0 = w.strategies(3)
+    tp, tu = w.search_space()
+    for table in (np.zeros(2, np.uint32), np.full(2, 2 ** 32 - 1, np.uint32)):
+        ch = B.Chains(sim, cfg0)
+        ch.search_setup(tp, tu, table, 1000, 11)
+        got = ch.search(40).cpu().numpy().view("<u8")
+        for c in range(3):
+            tr = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], tp, tu, table, 1000, 11, c, 0, 40)[0]
+            assert np.array_equal(got[:, c], tr)
+        if table[0] == 0:
+            assert np.all(np.diff(got.astype(np.int64), axis=0) <= 0)
+        ch.close()
+    sim.close()
+
+
+def test_search_then_forced_mutations_then_search(B):
+    """the three ways of stepping a chain share its state: a search, forced mutations
+    (ff_sim_delta), trial proposals (ff_sim_delta_try) and a search again."""
+    w = W.workload(2)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    cfg0 = w.strategies(2)
+    tp, tu = w.search_space()
+    t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[:1])[0])
+    bucket = t0 // 128
+    table = S.metropolis_table(30.0 / t0, bucket, 32)
+    ch = B.Chains(sim, cfg0)
+    ch.search_setup(tp, tu, table, bucket, 99)
+    got1 = ch.search(8).cpu().numpy().view("<u8")
+    muts = w.mutations(3, 2)
+    got2 = ch.delta(ch.upload_mutations(muts), 3).cpu().numpy().view("<u8")
+    props = w.mutations(7, 2)[3:]
+    got3 = ch.try_mutations(ch.upload_mutations(props), 4).cpu().numpy().view("<u8")
+    got4 = ch.search(6).cpu().numpy().view("<u8")
+    for c in range(2):
+        a = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], tp, tu, table, bucket, 99, c, 0, 8)
+        assert np.array_equal(got1[:, c], a[0])
+        cur = a[1].copy()
+        want2 = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cur, muts[:, c])
+        assert np.array_equal(got2[:, c], want2)
+        for s in range(3):
+            cur[int(muts[s, c]["op"])] = muts[s, c]["cfg"]
+        cand = np.repeat(cur[None], 4, 0)
+        for p in range(4):
+            cand[p, int(props[p, c]["op"])] = props[p, c]["cfg"]
+        assert np.array_equal(got3[:, c], oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cand))
+        b = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cur, tp, tu, table, bucket, 99, c, 8, 6)
+        assert np.array_equal(got4[:, c], b[0])
+    ch.close()
+    sim.close()
+
+
+def test_search_argument_errors(B):
+    import torch
+    w = W.workload(0)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    ch = B.Chains(sim, w.strategies(2))
+    tp, tu = w.search_space()
+    ch.search_setup(tp, tu, np.zeros(2, np.uint32), 10, 1)
+    L = B.lib()
+    sp = ch._sp
+    out = torch.empty((2, 2), dtype=torch.int64, device="cuda")
+
+    def params(**kw):
+        d = dict(seed=1, first_step=0, bucket_ns=10, n_buckets=2, n_tuples=len(tu), d_accept=sp["accept"].data_ptr(),
+                 d_tuple_ptr=sp["tuple_ptr"].data_ptr(), d_tuples=sp["tuples"].data_ptr(),
+                 d_best_ns=sp["best_ns"].data_ptr(), d_best=sp["best"].data_ptr())
+        d.update(kw)
+        return B.ff_search_t(**d)
+
+    import ctypes
+    assert L.ff_sim_search(ch.handle, None, 2, out.data_ptr(), None) == B.FF_EINVAL
+    assert L.ff_sim_search(None, ctypes.byref(params()), 2, out.data_ptr(), None) == B.FF_EINVAL
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params()), 2, None, None) == B.FF_EINVAL
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params(bucket_ns=0)), 2, out.data_ptr(), None) == B.FF_EINVAL
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params(n_buckets=0)), 2, out.data_ptr(), None) == B.FF_EINVAL
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params(d_accept=None)), 2, out.data_ptr(), None) == B.FF_EINVAL
+    # a list that reaches beyond the tuples handed over is refused before anything is launched
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params(n_tuples=len(tu) - 1)), 2, out.data_ptr(), None) == B.FF_EINVAL
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params()), 0, None, None) == B.FF_OK
+    assert L.ff_sim_search(ch.handle, ctypes.byref(params()), 2, out.data_ptr(), None) == B.FF_OK
+    torch.cuda.synchronize()
+    ch.close()
+    sim.close()
