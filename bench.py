@@ -221,6 +221,34 @@ def main():
                 delta.append(t)
             ch.close()
         line["delta"] = delta
+        # the search loop on the device (ff_sim_search): independent Metropolis chains
+        search = []
+        for cid, C, n_steps in ((4, 256, 8), (2, 1024, 16)):
+            if cid not in results:
+                continue
+            _, sim_s, w_s, cfgs_s = results[cid]
+            C = min(C, len(cfgs_s))
+            ch = binding.Chains(sim_s, cfgs_s[:C])
+            start = ch.start_ns().copy()
+            bucket = max(1, int(np.median(start)) // 256)
+            tp, tu = w_s.search_space()
+            ch.search_setup(tp, tu, binding.metropolis_table(50.0 / float(np.median(start)), bucket, 256), bucket, 1807)
+            ch.search(1)
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            trace = ch.search(n_steps)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            best_ns, _ = ch.best()
+            tr = trace.cpu().numpy().view("<u8")
+            search.append({"workload": f"configs[{cid}] {w_s.name}", "chains": C, "steps": n_steps, "ms": ms,
+                           "proposals_per_s": C * n_steps / (ms * 1e-3),
+                           "steps_that_changed_the_time": int((np.diff(tr.astype(np.int64), axis=0) != 0).sum()),
+                           "median_start_ns": float(np.median(start)), "median_best_ns": float(np.median(best_ns))})
+            ch.close()
+        line["search"] = search
     if not args.only_headline:
         line["workloads"] = [results[c][0] for c in sorted(results)]
     print(json.dumps(line))

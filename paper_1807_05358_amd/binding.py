@@ -190,6 +190,13 @@ def to_device(arr):
     return torch.from_numpy(a.view(np.uint8).reshape(-1).copy()).cuda()
 
 
+def metropolis_table(beta_per_ns, bucket_ns, n_buckets):
+    """acceptance probabilities of Section 6.1 for ff_sim_search, scaled by 2^32: entry b is
+    exp(-beta * b * bucket_ns), the value at the lower edge of the bucket."""
+    p = np.exp(-float(beta_per_ns) * float(bucket_ns) * np.arange(n_buckets, dtype=np.float64))
+    return np.minimum(np.floor(p * 4294967296.0), 4294967295.0).astype(np.uint32)
+
+
 class Simulator:
     """owns a handle, its workspace and result buffers (all torch-allocated)."""
 
