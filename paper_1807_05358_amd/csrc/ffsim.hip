@@ -201,6 +201,13 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     S.n_ops_pad = (g->n_ops + 63) & ~63u;
     S.n_groups = S.n_ops_pad / 64;
     s->wide = max_bytes >= ((unsigned __int128)1 << 32);
+    {
+        // longest transfer of a tensor below 2^32 bytes, times the most transfers one link row can
+        // take from one producer part (one per GPU of the consumer's node)
+        const uint64_t bw_min = std::min(m->intra_Bpns, m->inter_Bpns);
+        const uint64_t ns_max = (0xffffffffull + bw_min - 1) / bw_min + std::max(m->intra_lat_ns, m->inter_lat_ns);
+        S.run_sum32 = (!s->wide && ns_max * m->gpus_per_node < (1ull << 32)) ? 1u : 0u;
+    }
     s->slot_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 255) & ~(size_t)255;
     s->lds_common = lds_common_bytes(S.n_rows, S.n_ops_pad);
     s->lds_chain = s->lds_common + (size_t)S.n_ops_pad * 8;

@@ -60,6 +60,7 @@ struct SimDev {
     uint32_t pass_dev, pass_gpn;       // all ones iff the divisor is 1
     uint32_t n_ops_pad;                // n_ops rounded up to a multiple of 64
     uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
+    uint32_t run_sum32;                // gpus_per_node transfer times of tensors below 2^32 bytes add up to less than 2^32 ns
 };
 
 __device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }
@@ -71,6 +72,10 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 }
+
+// mask of the lanes where p holds.  (The toolkit's __ballot takes an int: a bool costs a
+// select and a compare before the mask exists.)
+__device__ __forceinline__ u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
 // the readlane / readfirstlane builtins return int: go through uint32_t before widening
 __device__ __forceinline__ uint32_t first_u32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
@@ -95,6 +100,17 @@ template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
     // old = 0 with bound_ctrl lets the compiler fold the move into the consuming instruction
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+
+// lane l reads lane l-1 of the whole wavefront, lane 0 reads 0 (DPP wave_shr:1).  Call only
+// with all 64 lanes active.
+__device__ __forceinline__ uint32_t wave_shr1_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x138, 0xf, 0xf, true);
+}
+__device__ __forceinline__ u64 wave_shr1_u64(u64 v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, 0x138, 0xf, 0xf, true);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), 0x138, 0xf, 0xf, true);
+    return ((u64)hi << 32) | lo;
 }
 
 // wavefront-wide min of a 32-bit value, uniform result: butterfly inside each row of 16

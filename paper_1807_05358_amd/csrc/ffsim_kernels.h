@@ -22,6 +22,9 @@ namespace ffsim {
 
 // up to this many groups of 64 ops the queue has no level 2: lanes scan level 1 directly
 constexpr uint32_t FLAT_GROUPS = 8;
+// GPUs per node up to which transfers are serialised on their link rows by a running sum
+// along consecutive lanes (one shift per GPU); beyond, the general search for equal rows runs
+constexpr uint32_t MAX_RUN = 8;
 
 // Section timing for development builds (-DFFSIM_PROFILE): shader-clock ticks per section are
 // accumulated in a register array and reported through the stats record instead of the
@@ -213,16 +216,16 @@ __device__ __forceinline__ u64 fifo_commit(bool act, uint32_t row, u64 exe, u64 
     const u64 base = f > r ? f : r;         // identical for all lanes of one row
     u64 end = base + exe;
     bool last = act;
-    u64 todo = __ballot(lost);
+    u64 todo = ballot(lost);
     while (todo) {
         const int l = __builtin_ctzll(todo);
         const uint32_t lrow = readlane_u32(row, l);
         const bool peer = act && row == lrow;   // includes the lane whose tag survived
-        const u64 peers = __ballot(peer);
+        const u64 peers = ballot(peer);
         todo &= ~peers;
         const int first = __builtin_ctzll(peers);
         const u64 exe_l = readlane_u64(exe, first);
-        if (!__ballot(peer && exe != exe_l)) {
+        if (!ballot(peer && exe != exe_l)) {
             // equal exeTimes (symmetric parts): the position in the group is enough
             const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u)) + 1;
             if (peer) end = base + (u64)rank * exe;
@@ -320,16 +323,21 @@ __device__ __forceinline__ uint32_t count_pending(const SimX& m, uint32_t j, con
     return pending;
 }
 
-// Section 4: every configuration valid?  Also fills exe_of.
+// Section 4: every configuration valid?  Also fills exe_of.  A valid strategy is REGULAR if
+// every op puts its parts on consecutive, distinct devices (stride 1, no more parts than
+// devices) and a node has at most MAX_RUN GPUs: the event loop has a faster form for those.
+enum StrategyClass : uint32_t { STRATEGY_INVALID = 0, STRATEGY_GENERAL = 1, STRATEGY_REGULAR = 2 };
 template <class SimX>
-__device__ __forceinline__ bool validate_strategy(const SimX& m) {
-    bool bad = false;
+__device__ __forceinline__ StrategyClass validate_strategy(const SimX& m) {
+    bool bad = false, irregular = false;
     for (uint32_t i = lane_id(); i < m.S.n_ops; i += WAVE) {
         OpCfg c = unpack_cfg_lane(m.cfg_raw(i));
         if (!cfg_ok(m.T.ops[i], c, m.S)) bad = true;
         else m.exe_of[i] = m.T.cost[(size_t)i * m.S.n_cols + (c.parts - 1)];
+        irregular = irregular || c.stride != 1 || c.parts > m.S.n_dev;
     }
-    return !__ballot(bad);
+    if (ballot(bad)) return STRATEGY_INVALID;
+    return (ballot(irregular) || m.S.gpus_per_node > MAX_RUN) ? STRATEGY_GENERAL : STRATEGY_REGULAR;
 }
 
 template <class SimX>
@@ -410,7 +418,8 @@ __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint
 
 // Algorithm 1, main loop, from the current state to the end.  RECORD: keep endTimes and
 // snapshots for delta simulation.  Returns 0 or a RESULT_* code.
-template <bool WIDE, bool RECORD, class SimX>
+// REG: the strategy is STRATEGY_REGULAR.
+template <bool WIDE, bool RECORD, bool REG, class SimX>
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const int lane = lane_id();
     PROF_DECL
@@ -422,6 +431,12 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const uint32_t magic_v = m.magic_v;
     u64 last_key = m.last_key;
     bool overflow = m.overflow;
+    // Values chosen per lane between two of these (same node or not) must sit in registers: a
+    // select between two fields of the argument block is otherwise turned into a per-lane load
+    // from that block, a vector memory round trip for every producer part.
+    const uint32_t bw_intra = first_u32(S.bw_intra), bw_inter = first_u32(S.bw_inter);
+    const uint32_t m_bw_intra = first_u32(S.m_bw_intra), m_bw_inter = first_u32(S.m_bw_inter);
+    const uint32_t lat_intra = first_u32(S.lat_intra), lat_inter = first_u32(S.lat_inter);
     const u64 max_events = 2ull * S.n_ops * WAVE + 8;   // every task is popped at most twice
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
@@ -430,9 +445,9 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const u64 k2 = (uint32_t)lane < S.n_groups ? L.l2[lane] : W_NONE;
             kmin = wave_min_from(k2, last_key);
             if (kmin >> 63) break;
-            const uint32_t g = __builtin_ctzll(__ballot(k2 == kmin));
+            const uint32_t g = __builtin_ctzll(ballot(k2 == kmin));
             const u64 k1 = L.l1[g * WAVE + lane];
-            const u64 m1 = __ballot(k1 == kmin);
+            const u64 m1 = ballot(k1 == kmin);
             if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }   // tree inconsistent: give up, never spin
             i = g * WAVE + __builtin_ctzll(m1);
         } else {
@@ -446,11 +461,11 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             kmin = wave_min_from(k1, last_key);
             if (kmin >> 63) break;
             // lowest op index among equal keys: smallest group first, then lowest lane
-            u64 m1 = __ballot(k1 == kmin);
+            u64 m1 = ballot(k1 == kmin);
             if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }
             if (m1 & (m1 - 1)) {    // several columns hold the minimum: smallest group wins
                 const uint32_t gmin = wave_min_u32(k1 == kmin ? gbest : 0xffffffffu);
-                m1 = __ballot(k1 == kmin && gbest == gmin);
+                m1 = ballot(k1 == kmin && gbest == gmin);
             }
             const int col = __builtin_ctzll(m1);
             i = readlane_u32(gbest, col) * WAVE + col;
@@ -467,7 +482,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         const uint32_t out_begin = opi_p->out_begin, out_end = opi_p->out_end;
         const OpCfg ci = m.cfg(i);
         const u64 exe = m.exe_of[i];
-        const u64 mask = __ballot(k0 == kmin);            // parts of op i that hold the minimum
+        const u64 mask = ballot(k0 == kmin);            // parts of op i that hold the minimum
         if (!mask) { cnt.exit_code = 2; return RESULT_INTERNAL; }
         cnt.n_events++;
         const u64 now = kmin >> 1;
@@ -476,7 +491,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
 
         if (kmin & 1) {
             // dequeue READY compute tasks: start = max(readyTime, device free), end = start + exeTime
-            const bool may_share = !(ci.stride == 1 && ci.parts <= S.n_dev);
+            const bool may_share = REG ? false : !(ci.stride == 1 && ci.parts <= S.n_dev);
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
             if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
@@ -502,6 +517,27 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 }
                 const uint32_t dev_c = part_device(cj, lane, S);
                 const uint32_t node_c = div_magic(dev_c, S.magic_gpn, S.pass_gpn);
+                // REG: consumer parts sit on consecutive, distinct devices, so the transfers from
+                // one producer part can share a link row only when their consumers sit on the
+                // same remote node, and those consumers are a run of consecutive lanes (the node
+                // of lane 0 may come back once more at the end, after the device numbers wrapped
+                // around).  The FIFO order on every shared row is then a running sum along the
+                // run, and no search for lanes with equal rows is needed.
+                const uint32_t G = S.gpus_per_node;
+                uint32_t pos = 0, first_len = 0, last_run_mask = 0;
+                bool run_end = false, wrapped = false;
+                if (REG) {
+                    const uint32_t node0 = div_magic(cj.off, S.magic_gpn, S.pass_gpn);
+                    const uint32_t room = G - (cj.off - node0 * G);              // lanes of the first run
+                    first_len = cj.parts < room ? cj.parts : room;
+                    const uint32_t local_c = dev_c - node_c * G;
+                    pos = (uint32_t)lane < first_len ? (uint32_t)lane : local_c;    // index inside the run
+                    const uint32_t last = cj.off + cj.parts - 1;
+                    wrapped = last >= S.n_dev && div_magic(last - S.n_dev, S.magic_gpn, S.pass_gpn) == node0;
+                    last_run_mask = (wrapped && (uint32_t)lane >= first_len && node_c == node0) ? 0xffffffffu : 0u;
+                    run_end = mine && ((uint32_t)lane == cj.parts - 1 || local_c == G - 1) &&
+                              !(wrapped && (uint32_t)lane == first_len - 1);
+                }
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
                 bool touched = false;
@@ -523,32 +559,64 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             else elems = (uint32_t)elems * (uint32_t)(hi > lo ? hi - lo : 0);
                         }
                     }
-                    const u64 hit_mask = __ballot(hit);
+                    const u64 hit_mask = ballot(hit);
                     if (!hit_mask) continue;
                     const uint32_t dev_a = readlane_u32(dev_p, kp);
                     const uint32_t node_a = readlane_u32(node_p, kp);
                     const bool comm = hit && dev_c != dev_a;
-                    const u64 comm_mask = __ballot(comm);
+                    const u64 comm_mask = ballot(comm);
                     u64 arrive = now;
                     if (comm_mask) {
                         const bool same_node = node_c == node_a;
                         // Section 5.1: the link device between the two devices
-                        const uint32_t G = S.gpus_per_node;
                         const uint32_t row = same_node
                             ? S.n_dev + node_a * G * G + (dev_a - node_a * G) * G + (dev_c - node_c * G)
                             : S.n_dev + S.n_nodes * G * G + node_a * S.n_nodes + node_c;
                         // assumption A2: transfer time = size / bandwidth (rounded up) + latency
-                        const uint32_t bw = same_node ? S.bw_intra : S.bw_inter;
+                        const uint32_t bw = same_node ? bw_intra : bw_inter;
                         u64 ns;
                         if (WIDE) {
                             const u64 bytes = elems * S.elem_bytes;
                             ns = (bytes + bw - 1) / bw;
                         } else {
                             const uint32_t bytes = (uint32_t)elems * S.elem_bytes;
-                            ns = ceil_div_u32(comm ? bytes : 1u, bw, same_node ? S.m_bw_intra : S.m_bw_inter);
+                            ns = ceil_div_u32(comm ? bytes : 1u, bw, same_node ? m_bw_intra : m_bw_inter);
                         }
-                        ns += same_node ? S.lat_intra : S.lat_inter;
-                        const u64 end = fifo_commit(comm, row, ns, now, true, L);
+                        ns += same_node ? lat_intra : lat_inter;
+                        u64 end;
+                        if (REG) {
+                            const u64 f = L.free_at[row];                  // in range for every lane
+                            const u64 base = f > now ? f : now;            // the same for all lanes of a row
+                            const bool chained = comm && !same_node;       // rows between GPUs of one node are private
+                            u64 incl;
+                            if (S.run_sum32) {
+                                // a row's running sum of transfer times cannot reach 2^32
+                                uint32_t acc = chained ? (uint32_t)ns : 0u, t = acc;
+                                for (uint32_t sft = 1; sft < G; sft++) {
+                                    t = wave_shr1_u32(t);
+                                    if (pos < sft) t = 0;
+                                    acc += t;
+                                }
+                                if (wrapped) acc += readlane_u32(acc, (int)first_len - 1) & last_run_mask;
+                                incl = acc;
+                            } else {
+                                u64 t = incl = chained ? ns : 0;
+                                for (uint32_t sft = 1; sft < G; sft++) {
+                                    t = wave_shr1_u64(t);
+                                    if (pos < sft) t = 0;
+                                    incl += t;
+                                }
+                                if (wrapped) {
+                                    const u64 first_total = readlane_u64(incl, (int)first_len - 1);
+                                    if (last_run_mask) incl += first_total;
+                                }
+                            }
+                            end = base + (same_node ? ns : incl);
+                            if (same_node ? comm : (run_end && incl != 0)) L.free_at[row] = end;
+                            wave_sync();
+                        } else {
+                            end = fifo_commit(comm, row, ns, now, true, L);
+                        }
                         if (comm) arrive = end;
                         if (cnt.want_check) {
                             cnt.n_comm += __popcll(comm_mask);
@@ -569,7 +637,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     w = now_ready ? ((ready << 1) | 1) : (W_WAIT | ((u64)pending << 48) | (ready & (TIME_LIMIT - 1)));
                     words[j * WAVE + lane] = w;
                 }
-                if (__ballot(now_ready)) {
+                if (ballot(now_ready)) {
                     const u64 nmin = wave_min_from(now_ready ? w : W_NONE, last_key);
                     if (lane == 0) {
                         if (nmin < L.l1[j]) L.l1[j] = nmin;
@@ -595,7 +663,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     }
     m.last_key = last_key;
     PROF_STORE(cnt)
-    if (__ballot(overflow)) return RESULT_OVERFLOW;
+    if (ballot(overflow)) return RESULT_OVERFLOW;
     return 0;
 }
 
@@ -612,12 +680,13 @@ __device__ __forceinline__ u64 makespan(const SimX& m) {
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
 template <bool WIDE, bool RECORD>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
-    if (!validate_strategy(m)) return RESULT_INVALID;
+    const StrategyClass cls = validate_strategy(m);
+    if (cls == STRATEGY_INVALID) return RESULT_INVALID;
     init_state(m, cnt);
-    const u64 rc = run_events<WIDE, RECORD>(m, cnt, rec);
+    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true>(m, cnt, rec) : run_events<WIDE, RECORD, false>(m, cnt, rec);
     if (rc) return rc;
     if (cnt.want_check) {   // diagnostics: tasks that never ran (0 in a correct run)
-        for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(__ballot(m.words[j * WAVE + lane_id()] != W_NONE));
+        for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));
     }
     return makespan(m);
 }
@@ -756,7 +825,7 @@ __device__ __forceinline__ uint32_t resume_point(const SimX& m, const u64* end_o
             pend_old += count_inputs(e, m.cfg(e.src), co.x, digits, m.magic_v);
         }
     }
-    if (__ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
+    if (ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
     u64 k64 = (2 * tau) / meta.step;
     if (k64 > meta.n_valid - 1) k64 = meta.n_valid - 1;
     return (uint32_t)k64;
@@ -783,7 +852,7 @@ __device__ __forceinline__ void patch_state_for_op(const SimX& m, u64* words, u6
         const uint32_t digits = part_digits(cj, lane, m.magic_v);
         const uint32_t was = count_inputs(e, co, cj.x, digits, m.magic_v);
         const uint32_t is = count_inputs(e, cn, cj.x, digits, m.magic_v);
-        if (!__ballot((uint32_t)lane < cj.parts && was != is)) continue;
+        if (!ballot((uint32_t)lane < cj.parts && was != is)) continue;
         const u64 w = words[j * WAVE + lane];
         // a part of op j that reads op mo at all is still waiting in such a state
         const bool waiting = (uint32_t)lane < cj.parts && (w >> 63) && w != W_NONE;
@@ -915,7 +984,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
             }
         }
         u64 mk = RESULT_INVALID;
-        if (!poisoned) valid = validate_strategy(m);
+        if (!poisoned) valid = validate_strategy(m) != STRATEGY_INVALID;
         if (!poisoned && !valid && !trial) { meta.stale = 1; meta.cur_ns = RESULT_INVALID; }
         const bool changed = muts != nullptr || trial;
         if (changed && !poisoned) meta.n_steps++;
@@ -954,7 +1023,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     rebuild_l2(m);
                     if (record) meta.n_resumed++;
                 }
-                const u64 rc = run_events<WIDE, true>(m, cnt, rec);
+                const u64 rc = run_events<WIDE, true, false>(m, cnt, rec);
                 rec.n_snaps = capacity;
                 rec.end_of = cm.end_of;
                 mk = rc ? rc : makespan(m);
@@ -1063,7 +1132,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
             const uint2 ocfg = cm.cfgs[op];
             SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2]))};
-            if (validate_strategy(m)) {
+            if (validate_strategy(m) != STRATEGY_INVALID) {
                 Counters cnt = {};
                 Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
                 uint32_t k = 0, pend_new = 0;
@@ -1076,7 +1145,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = run_events<WIDE, false>(m, cnt, rec);
+                const u64 rc = run_events<WIDE, false, false>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
