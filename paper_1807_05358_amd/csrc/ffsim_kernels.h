@@ -984,7 +984,9 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
             }
         }
         u64 mk = RESULT_INVALID;
-        if (!poisoned) valid = validate_strategy(m) != STRATEGY_INVALID;
+        StrategyClass cls = STRATEGY_INVALID;
+        if (!poisoned) cls = validate_strategy(m);
+        valid = cls != STRATEGY_INVALID;
         if (!poisoned && !valid && !trial) { meta.stale = 1; meta.cur_ns = RESULT_INVALID; }
         const bool changed = muts != nullptr || trial;
         if (changed && !poisoned) meta.n_steps++;
@@ -1023,7 +1025,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     rebuild_l2(m);
                     if (record) meta.n_resumed++;
                 }
-                const u64 rc = run_events<WIDE, true, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true>(m, cnt, rec) : run_events<WIDE, true, false>(m, cnt, rec);
                 rec.n_snaps = capacity;
                 rec.end_of = cm.end_of;
                 mk = rc ? rc : makespan(m);
@@ -1132,7 +1134,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
             const uint2 ocfg = cm.cfgs[op];
             SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2]))};
-            if (validate_strategy(m) != STRATEGY_INVALID) {
+            const StrategyClass cls = validate_strategy(m);
+            if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
                 Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
                 uint32_t k = 0, pend_new = 0;
@@ -1145,7 +1148,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = run_events<WIDE, false, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true>(m, cnt, rec) : run_events<WIDE, false, false>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
