@@ -176,11 +176,21 @@ __device__ __forceinline__ void needed_range(const DMap& m, uint32_t extent, uin
                                              uint32_t magic_v, int32_t& lo, int32_t& hi) {
     if (m.src_dim < 0) { lo = 0; hi = (int32_t)extent; return; }   // uniform
     const uint32_t sh = 8u * (uint32_t)m.src_dim;
-    const Divisor dv = divisor((cfg_x >> sh) & 0xff, magic_v);
+    const uint32_t deg = (cfg_x >> sh) & 0xff;
+    const int32_t E = (int32_t)extent;
+    if (deg == 1) {
+        // the consumer does not split this dim: every part reads the same range (scalar unit)
+        int32_t l = m.a, h = ((int32_t)m.cext - 1) * (int32_t)m.stride + m.b + 1;
+        l = l < 0 ? 0 : (l > E ? E : l);
+        h = h < 0 ? 0 : (h > E ? E : h);
+        lo = l;
+        hi = h < l ? l : h;
+        return;
+    }
+    const Divisor dv = divisor(deg, magic_v);
     const uint32_t idx = (digits >> sh) & 0xff;
     const int32_t clo = (int32_t)div_by(idx * m.cext, dv);
     const int32_t chi = (int32_t)div_by((idx + 1) * m.cext, dv);
-    const int32_t E = (int32_t)extent;
     int32_t l = clo * (int32_t)m.stride + m.a;
     int32_t h = (chi - 1) * (int32_t)m.stride + m.b + 1;
     l = l < 0 ? 0 : (l > E ? E : l);
