@@ -66,10 +66,13 @@ typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, c
 typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
                                uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
 
-static batch_kernel_t batch_kernel(const ff_sim* s) {
-    if (s->wide) return s->lds_words ? k_sim_batch<true, true> : k_sim_batch<true, false>;
-    return s->lds_words ? k_sim_batch<false, true> : k_sim_batch<false, false>;
+template <bool STATS>
+static batch_kernel_t batch_kernel_of(const ff_sim* s) {
+    if (s->wide) return s->lds_words ? k_sim_batch<true, true, STATS> : k_sim_batch<true, false, STATS>;
+    return s->lds_words ? k_sim_batch<false, true, STATS> : k_sim_batch<false, false, STATS>;
 }
+// the variant that also fills the per-candidate counters is only launched when they are asked for
+static batch_kernel_t batch_kernel(const ff_sim* s) { return s->d_stats ? batch_kernel_of<true>(s) : batch_kernel_of<false>(s); }
 static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
 typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
                              uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);

@@ -146,7 +146,13 @@ __device__ __forceinline__ Box part_box(const uint32_t extent[4], const OpCfg& c
     return b;
 }
 
+// REG: stride 1 and k < parts <= n_dev, so off + k wraps around at most once
+template <bool REG = false>
 __device__ __forceinline__ uint32_t part_device(const OpCfg& c, uint32_t k, const SimDev& S) {
+    if (REG) {
+        const uint32_t n = c.off + (k < S.n_dev ? k : 0u);   // lanes beyond the parts stay in range
+        return n >= S.n_dev ? n - S.n_dev : n;
+    }
     uint32_t n = c.off + k * c.stride;
     return n - div_magic(n, S.magic_dev, S.pass_dev) * S.n_dev;
 }
@@ -428,8 +434,9 @@ __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint
 
 // Algorithm 1, main loop, from the current state to the end.  RECORD: keep endTimes and
 // snapshots for delta simulation.  Returns 0 or a RESULT_* code.
-// REG: the strategy is STRATEGY_REGULAR.
-template <bool WIDE, bool RECORD, bool REG, class SimX>
+// REG: the strategy is STRATEGY_REGULAR.  STATS: also count pairs and transfers (the optional
+// per-candidate record); a compile-time switch so that the counters cost the timed path nothing.
+template <bool WIDE, bool RECORD, bool REG, bool STATS, class SimX>
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const int lane = lane_id();
     PROF_DECL
@@ -497,7 +504,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         cnt.n_events++;
         const u64 now = kmin >> 1;
         const bool in_mask = (mask >> lane) & 1;
-        const uint32_t dev_p = part_device(ci, lane, S);
+        const uint32_t dev_p = part_device<REG>(ci, lane, S);
 
         if (kmin & 1) {
             // dequeue READY compute tasks: start = max(readyTime, device free), end = start + exeTime
@@ -525,7 +532,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     nlo[d] = 0; nhi[d] = 1;
                     if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, magic_v, nlo[d], nhi[d]);
                 }
-                const uint32_t dev_c = part_device(cj, lane, S);
+                const uint32_t dev_c = part_device<REG>(cj, lane, S);
                 const uint32_t node_c = div_magic(dev_c, S.magic_gpn, S.pass_gpn);
                 // REG: consumer parts sit on consecutive, distinct devices, so the transfers from
                 // one producer part can share a link row only when their consumers sit on the
@@ -628,7 +635,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             end = fifo_commit(comm, row, ns, now, true, L);
                         }
                         if (comm) arrive = end;
-                        if (cnt.want_check) {
+                        if (STATS) {
                             cnt.n_comm += __popcll(comm_mask);
                             if (comm) cnt.sum_comm_ns += ns;   // per-lane partial sums, reduced by the caller
                         }
@@ -638,7 +645,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         pending -= 1;
                         touched = true;
                     }
-                    if (cnt.want_check) cnt.n_pairs += __popcll(hit_mask);
+                    if (STATS) cnt.n_pairs += __popcll(hit_mask);
                 }
                 PROF_MARK(4)
                 overflow = overflow || (touched && ready >= TIME_LIMIT);
@@ -688,14 +695,15 @@ __device__ __forceinline__ u64 makespan(const SimX& m) {
 
 // One candidate: build + simulate.  Returns the makespan or one of the RESULT_* codes.
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
-template <bool WIDE, bool RECORD>
+template <bool WIDE, bool RECORD, bool STATS>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
     init_state(m, cnt);
-    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true>(m, cnt, rec) : run_events<WIDE, RECORD, false>(m, cnt, rec);
+    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS>(m, cnt, rec)
+                                            : run_events<WIDE, RECORD, false, STATS>(m, cnt, rec);
     if (rc) return rc;
-    if (cnt.want_check) {   // diagnostics: tasks that never ran (0 in a correct run)
+    if (STATS) {   // diagnostics: tasks that never ran (0 in a correct run)
         for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));
     }
     return makespan(m);
@@ -713,7 +721,7 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 __device__ __forceinline__ uint32_t load_magic(const uint32_t* __restrict__ magic) { return magic[lane_id() + 1]; }
 
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
-template <bool WIDE, bool LDSW>
+template <bool WIDE, bool LDSW, bool STATS>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -738,11 +746,10 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     Recorder none = {};
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
-        cnt.want_check = stats != nullptr;
         Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
-        const u64 mk = simulate_candidate<WIDE, false>(m, cnt, none);
+        const u64 mk = simulate_candidate<WIDE, false, STATS>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
-        if (stats) store_counters(cnt, stats + b);
+        if (STATS) store_counters(cnt, stats + b);
         wave_sync();
     }
 }
@@ -1035,7 +1042,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     rebuild_l2(m);
                     if (record) meta.n_resumed++;
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true>(m, cnt, rec) : run_events<WIDE, true, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false>(m, cnt, rec) : run_events<WIDE, true, false, false>(m, cnt, rec);
                 rec.n_snaps = capacity;
                 rec.end_of = cm.end_of;
                 mk = rc ? rc : makespan(m);
@@ -1158,7 +1165,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true>(m, cnt, rec) : run_events<WIDE, false, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false>(m, cnt, rec) : run_events<WIDE, false, false, false>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
