@@ -66,17 +66,29 @@ typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, c
 typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
                                uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
 
-template <bool STATS>
+// three layouts: task words in LDS (small graphs; never a level 2), in HBM without, and with level 2
+template <bool WIDE, bool STATS>
 static batch_kernel_t batch_kernel_of(const ff_sim* s) {
-    if (s->wide) return s->lds_words ? k_sim_batch<true, true, STATS> : k_sim_batch<true, false, STATS>;
-    return s->lds_words ? k_sim_batch<false, true, STATS> : k_sim_batch<false, false, STATS>;
+    if (s->lds_words) return k_sim_batch<WIDE, true, STATS, false>;
+    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, true> : k_sim_batch<WIDE, false, STATS, false>;
 }
 // the variant that also fills the per-candidate counters is only launched when they are asked for
-static batch_kernel_t batch_kernel(const ff_sim* s) { return s->d_stats ? batch_kernel_of<true>(s) : batch_kernel_of<false>(s); }
-static chain_kernel_t chain_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_steps<true> : k_sim_chain_steps<false>; }
+static batch_kernel_t batch_kernel(const ff_sim* s) {
+    if (s->wide) return s->d_stats ? batch_kernel_of<true, true>(s) : batch_kernel_of<true, false>(s);
+    return s->d_stats ? batch_kernel_of<false, true>(s) : batch_kernel_of<false, false>(s);
+}
+static chain_kernel_t chain_kernel(const ff_sim* s) {
+    const bool tree = s->dev.n_groups > FLAT_GROUPS;
+    if (s->wide) return tree ? k_sim_chain_steps<true, true> : k_sim_chain_steps<true, false>;
+    return tree ? k_sim_chain_steps<false, true> : k_sim_chain_steps<false, false>;
+}
 typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
                              uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);
-static try_kernel_t try_kernel(const ff_sim* s) { return s->wide ? k_sim_chain_try<true> : k_sim_chain_try<false>; }
+static try_kernel_t try_kernel(const ff_sim* s) {
+    const bool tree = s->dev.n_groups > FLAT_GROUPS;
+    if (s->wide) return tree ? k_sim_chain_try<true, true> : k_sim_chain_try<true, false>;
+    return tree ? k_sim_chain_try<false, true> : k_sim_chain_try<false, false>;
+}
 
 static void release(ff_sim* s) {
     if (!s) return;
@@ -203,13 +215,14 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     S.pass_dev = D == 1 ? 0xffffffffu : 0u; S.pass_gpn = m->gpus_per_node == 1 ? 0xffffffffu : 0u;
     S.n_ops_pad = (g->n_ops + 63) & ~63u;
     S.n_groups = S.n_ops_pad / 64;
-    s->wide = max_bytes >= ((unsigned __int128)1 << 32);
     {
-        // longest transfer of a tensor below 2^32 bytes, times the most transfers one link row can
-        // take from one producer part (one per GPU of the consumer's node)
+        // The narrow kernels count elements, bytes and a link row's running sum of transfer
+        // times in 32 bits: every tensor must stay below 2^32 bytes, and gpus_per_node of the
+        // longest possible transfers (the most one producer part can queue on one row) below
+        // 2^32 ns.  Everything else runs in the 64-bit (WIDE) kernels.
         const uint64_t bw_min = std::min(m->intra_Bpns, m->inter_Bpns);
         const uint64_t ns_max = (0xffffffffull + bw_min - 1) / bw_min + std::max(m->intra_lat_ns, m->inter_lat_ns);
-        S.run_sum32 = (!s->wide && ns_max * m->gpus_per_node < (1ull << 32)) ? 1u : 0u;
+        s->wide = max_bytes >= ((unsigned __int128)1 << 32) || ns_max * m->gpus_per_node >= (1ull << 32);
     }
     s->slot_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 255) & ~(size_t)255;
     s->lds_common = lds_common_bytes(S.n_rows, S.n_ops_pad);

@@ -60,7 +60,6 @@ struct SimDev {
     uint32_t pass_dev, pass_gpn;       // all ones iff the divisor is 1
     uint32_t n_ops_pad;                // n_ops rounded up to a multiple of 64
     uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
-    uint32_t run_sum32;                // gpus_per_node transfer times of tensors below 2^32 bytes add up to less than 2^32 ns
 };
 
 __device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }

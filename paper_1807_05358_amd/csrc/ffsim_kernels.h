@@ -436,7 +436,8 @@ __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint
 // snapshots for delta simulation.  Returns 0 or a RESULT_* code.
 // REG: the strategy is STRATEGY_REGULAR.  STATS: also count pairs and transfers (the optional
 // per-candidate record); a compile-time switch so that the counters cost the timed path nothing.
-template <bool WIDE, bool RECORD, bool REG, bool STATS, class SimX>
+// TREE: more than FLAT_GROUPS groups of 64 ops, the queue has its level 2.
+template <bool WIDE, bool RECORD, bool REG, bool STATS, bool TREE, class SimX>
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const int lane = lane_id();
     PROF_DECL
@@ -458,7 +459,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
         uint32_t i;
-        if (S.n_groups > FLAT_GROUPS) {
+        if (TREE) {
             const u64 k2 = (uint32_t)lane < S.n_groups ? L.l2[lane] : W_NONE;
             kmin = wave_min_from(k2, last_key);
             if (kmin >> 63) break;
@@ -606,8 +607,9 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             const u64 base = f > now ? f : now;            // the same for all lanes of a row
                             const bool chained = comm && !same_node;       // rows between GPUs of one node are private
                             u64 incl;
-                            if (S.run_sum32) {
-                                // a row's running sum of transfer times cannot reach 2^32
+                            if (!WIDE) {
+                                // a row's running sum of transfer times cannot reach 2^32 (the host
+                                // selects the WIDE kernels otherwise)
                                 uint32_t acc = chained ? (uint32_t)ns : 0u, t = acc;
                                 for (uint32_t sft = 1; sft < G; sft++) {
                                     t = wave_shr1_u32(t);
@@ -658,7 +660,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     const u64 nmin = wave_min_from(now_ready ? w : W_NONE, last_key);
                     if (lane == 0) {
                         if (nmin < L.l1[j]) L.l1[j] = nmin;
-                        if (S.n_groups > FLAT_GROUPS && nmin < L.l2[j >> 6]) L.l2[j >> 6] = nmin;
+                        if (TREE && nmin < L.l2[j >> 6]) L.l2[j >> 6] = nmin;
                     }
                 }
                 PROF_MARK(5)
@@ -670,7 +672,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         wave_sync();
         if (lane == 0) L.l1[i] = new_l1;
         wave_sync();
-        if (S.n_groups > FLAT_GROUPS) {
+        if (TREE) {
             const uint32_t g = i >> 6;
             const u64 new_l2 = wave_min_from(L.l1[g * WAVE + lane], last_key);
             if (lane == 0) L.l2[g] = new_l2;
@@ -695,13 +697,13 @@ __device__ __forceinline__ u64 makespan(const SimX& m) {
 
 // One candidate: build + simulate.  Returns the makespan or one of the RESULT_* codes.
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
-template <bool WIDE, bool RECORD, bool STATS>
+template <bool WIDE, bool RECORD, bool STATS, bool TREE>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
     init_state(m, cnt);
-    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS>(m, cnt, rec)
-                                            : run_events<WIDE, RECORD, false, STATS>(m, cnt, rec);
+    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, TREE>(m, cnt, rec)
+                                            : run_events<WIDE, RECORD, false, STATS, TREE>(m, cnt, rec);
     if (rc) return rc;
     if (STATS) {   // diagnostics: tasks that never ran (0 in a correct run)
         for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));
@@ -721,7 +723,7 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 __device__ __forceinline__ uint32_t load_magic(const uint32_t* __restrict__ magic) { return magic[lane_id() + 1]; }
 
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
-template <bool WIDE, bool LDSW, bool STATS>
+template <bool WIDE, bool LDSW, bool STATS, bool TREE>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -747,7 +749,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
         Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
-        const u64 mk = simulate_candidate<WIDE, false, STATS>(m, cnt, none);
+        const u64 mk = simulate_candidate<WIDE, false, STATS, TREE>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (STATS) store_counters(cnt, stats + b);
         wave_sync();
@@ -926,7 +928,7 @@ struct SearchDev {
 // A forced mutation that names an op outside the graph poisons the chain: this and all
 // later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
 // step s.
-template <bool WIDE>
+template <bool WIDE, bool TREE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                           const uint32_t* __restrict__ magic, unsigned char* chain_mem,
@@ -1042,7 +1044,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     rebuild_l2(m);
                     if (record) meta.n_resumed++;
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false>(m, cnt, rec) : run_events<WIDE, true, false, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE>(m, cnt, rec) : run_events<WIDE, true, false, false, TREE>(m, cnt, rec);
                 rec.n_snaps = capacity;
                 rec.end_of = cm.end_of;
                 mk = rc ? rc : makespan(m);
@@ -1115,7 +1117,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 // single-op mutations per chain, each against the chain's current strategy and stored
 // timeline, without changing the chain.  One wavefront per (proposal, chain); its task words
 // live in a private workspace slot, the chain's snapshots are only read.
-template <bool WIDE>
+template <bool WIDE, bool TREE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                         const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                         const uint32_t* __restrict__ magic, const unsigned char* __restrict__ chain_mem,
@@ -1165,7 +1167,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false>(m, cnt, rec) : run_events<WIDE, false, false, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
