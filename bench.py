@@ -249,6 +249,19 @@ def main():
                            "median_start_ns": float(np.median(start)), "median_best_ns": float(np.median(best_ns))})
             ch.close()
         line["search"] = search
+        # neighbour sweep (local-optimality check): all single-op neighbours of one strategy
+        if 1 in results:
+            _, sim_n, w_n, cfgs_n = results[1]
+            ch = binding.Chains(sim_n, cfgs_n[:1])
+            tp, tu = w_n.search_space()
+            t0 = time.perf_counter()
+            muts_n, ns_n, best_n, idx_n = ch.neighbours(tp, tu)
+            dt = time.perf_counter() - t0
+            line["neighbour_sweep"] = {"workload": f"configs[1] {w_n.name}", "neighbours": int(ns_n.shape[0]),
+                                       "wall_ms_including_copies_back": dt * 1e3,
+                                       "neighbours_per_s": ns_n.shape[0] / dt,
+                                       "start_ns": int(ch.start_ns()[0]), "best_neighbour_ns": int(best_n[0])}
+            ch.close()
     if not args.only_headline:
         line["workloads"] = [results[c][0] for c in sorted(results)]
     print(json.dumps(line))

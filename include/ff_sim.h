@@ -187,6 +187,23 @@ size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* chains, uint32_t M);
 int ff_sim_delta_try(ff_chains_t* chains, const ff_mutation_t* d_muts, uint32_t M, uint64_t* d_out_ns,
                      void* hip_stream);
 
+/* Neighbour sweep (Section 8.4's check that a strategy is locally optimal: compare it with all
+ * of its neighbours, the strategies that differ in the configuration of one op).  For every
+ * chain, simulates every neighbour of its current strategy for the ops op_begin..op_end-1:
+ * neighbour index k runs over the ops in order, per op over the degree tuples of its list
+ * (d_tuple_ptr / d_tuples as in ff_search_t, list order), per tuple over dev_offset
+ * 0..n_devices-1, dev_stride 1 (the op's current configuration is among them).
+ * ff_sim_neighbour_count gives their number M.  d_muts[M][C] receives the list itself,
+ * d_out_ns[M][C] the simulated times, d_best_ns[c] / d_best_index[c] the smallest time of
+ * chain c and the lowest neighbour index that reaches it.  The chains are not changed.
+ * Workspace as for ff_sim_delta_try with the same M.  Both calls copy n_ops+1 integers back
+ * and ff_sim_neighbours returns only when the stream has finished the work. */
+int ff_sim_neighbour_count(const ff_chains_t* chains, const uint32_t* d_tuple_ptr, uint32_t n_tuples,
+                           uint32_t op_begin, uint32_t op_end, uint32_t* out_count);
+int ff_sim_neighbours(ff_chains_t* chains, const uint32_t* d_tuple_ptr, const uint32_t* d_tuples, uint32_t n_tuples,
+                      uint32_t op_begin, uint32_t op_end, ff_mutation_t* d_muts, uint64_t* d_out_ns,
+                      uint64_t* d_best_ns, uint32_t* d_best_index, void* hip_stream);
+
 /* The search loop of Section 6 on the device, one Markov chain per chain: per step one
  * proposal (Section 6.2: a random op gets a random configuration) is simulated as a trial
  * and accepted by the Metropolis rule of Section 6.1, min(1, exp(beta*(cost - cost*))), which

@@ -35,6 +35,7 @@ class ff_costtable_t(C.Structure):
 EXPORTS = ["ff_sim_create", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
+           "ff_sim_neighbour_count", "ff_sim_neighbours",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8")])
 
@@ -89,6 +90,10 @@ def lib():
         L.ff_sim_delta_try_workspace_bytes.argtypes = [vp, u32]
         L.ff_sim_search.restype = C.c_int
         L.ff_sim_search.argtypes = [vp, C.POINTER(ff_search_t), u32, vp, vp]
+        L.ff_sim_neighbour_count.restype = C.c_int
+        L.ff_sim_neighbour_count.argtypes = [vp, vp, u32, u32, u32, C.POINTER(u32)]
+        L.ff_sim_neighbours.restype = C.c_int
+        L.ff_sim_neighbours.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp, vp, vp]
         L.ff_sim_chains_get_stats.restype = C.c_int
         L.ff_sim_chains_get_stats.argtypes = [vp, vp]
         L.ff_sim_strerror.restype = C.c_char_p
@@ -166,6 +171,18 @@ def ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream=None):
 
 def ff_sim_search(chains, params: ff_search_t, n_steps, d_trace_ns, stream=None):
     _check(lib().ff_sim_search(chains, C.byref(params), n_steps, d_trace_ns, stream), "ff_sim_search")
+
+
+def ff_sim_neighbour_count(chains, d_tuple_ptr, n_tuples, op_begin, op_end):
+    n = C.c_uint32()
+    _check(lib().ff_sim_neighbour_count(chains, d_tuple_ptr, n_tuples, op_begin, op_end, C.byref(n)), "ff_sim_neighbour_count")
+    return n.value
+
+
+def ff_sim_neighbours(chains, d_tuple_ptr, d_tuples, n_tuples, op_begin, op_end, d_muts, d_out_ns, d_best_ns,
+                      d_best_index, stream=None):
+    _check(lib().ff_sim_neighbours(chains, d_tuple_ptr, d_tuples, n_tuples, op_begin, op_end, d_muts, d_out_ns,
+                                   d_best_ns, d_best_index, stream), "ff_sim_neighbours")
 
 
 def ff_sim_chains_get_stats(chains, n_chains):
@@ -333,6 +350,29 @@ class Chains:
         sp = self._sp
         return (sp["best_ns"].cpu().numpy().view("<u8"),
                 sp["best"].cpu().numpy().view(W.CFG_DT).reshape(self.C, self.sim.n_ops))
+
+    def neighbours(self, tuple_ptr, tuples, op_begin=0, op_end=None):
+        """every single-op neighbour of every chain's strategy for ops [op_begin, op_end).
+        Returns (mutations [M][C] MUT_DT, times [M][C] uint64, best time [C], best index [C])."""
+        torch = _torch()
+        op_end = self.sim.n_ops if op_end is None else op_end
+        d_ptr = to_device(np.ascontiguousarray(tuple_ptr, "<u4"))
+        d_tup = to_device(np.ascontiguousarray(tuples, "<u4"))
+        M = ff_sim_neighbour_count(self.handle, d_ptr.data_ptr(), len(tuples), op_begin, op_end)
+        need = ff_sim_delta_try_workspace_bytes(self.handle, M)
+        sim = self.sim
+        if sim._ws is None or sim._ws.numel() < need:
+            sim._ws = None
+            sim._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+            ff_sim_set_workspace(sim.handle, sim._ws.data_ptr(), sim._ws.numel())
+        d_muts = torch.empty(M * self.C * W.MUT_DT.itemsize, dtype=torch.uint8, device="cuda")
+        d_out = torch.empty((M, self.C), dtype=torch.int64, device="cuda")
+        d_best = torch.empty(self.C, dtype=torch.int64, device="cuda")
+        d_idx = torch.empty(self.C, dtype=torch.int32, device="cuda")
+        ff_sim_neighbours(self.handle, d_ptr.data_ptr(), d_tup.data_ptr(), len(tuples), op_begin, op_end, d_muts.data_ptr(),
+                          d_out.data_ptr(), d_best.data_ptr(), d_idx.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        return (d_muts.cpu().numpy().view(W.MUT_DT).reshape(M, self.C), d_out.cpu().numpy().view("<u8"),
+                d_best.cpu().numpy().view("<u8"), d_idx.cpu().numpy().view("<u4"))
 
     def stats(self):
         return ff_sim_chains_get_stats(self.handle, self.C)

@@ -347,6 +347,68 @@ int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64
     return launch_chain_steps(c, nullptr, n_steps, d_trace_ns, (hipStream_t)hip_stream, sd);
 }
 
+// host copy of the per-op tuple ranges, validated; first[o - op_begin] = index of op o's first neighbour
+static int neighbour_ranges(const ff_chains_t* c, const uint32_t* d_tuple_ptr, uint32_t n_tuples, uint32_t op_begin, uint32_t op_end,
+                            std::vector<uint32_t>* first, uint64_t* total) {
+    const uint32_t n_ops = c->sim->dev.n_ops;
+    if (op_begin > op_end || op_end > n_ops) return FF_EINVAL;
+    std::vector<uint32_t> ptr(n_ops + 1);
+    if (hipMemcpy(ptr.data(), d_tuple_ptr, ptr.size() * 4, hipMemcpyDeviceToHost) != hipSuccess) return FF_EHIP;
+    for (uint32_t i = 0; i < n_ops; i++)
+        if (ptr[i] > ptr[i + 1] || ptr[i + 1] > n_tuples) return FF_EINVAL;
+    first->assign(op_end - op_begin + 1, 0);
+    uint64_t acc = 0;
+    for (uint32_t o = op_begin; o < op_end; o++) {
+        (*first)[o - op_begin] = (uint32_t)acc;
+        acc += (uint64_t)(ptr[o + 1] - ptr[o]) * c->sim->dev.n_dev;
+        if (acc > 0xffffffffull) return FF_ERANGE;
+    }
+    (*first)[op_end - op_begin] = (uint32_t)acc;
+    *total = acc;
+    return FF_OK;
+}
+
+int ff_sim_neighbour_count(const ff_chains_t* c, const uint32_t* d_tuple_ptr, uint32_t n_tuples, uint32_t op_begin, uint32_t op_end,
+                           uint32_t* out_count) {
+    if (!c || !d_tuple_ptr || !out_count) return FF_EINVAL;
+    std::vector<uint32_t> first;
+    uint64_t total = 0;
+    const int rc = neighbour_ranges(c, d_tuple_ptr, n_tuples, op_begin, op_end, &first, &total);
+    if (rc) return rc;
+    *out_count = (uint32_t)total;
+    return FF_OK;
+}
+
+int ff_sim_neighbours(ff_chains_t* c, const uint32_t* d_tuple_ptr, const uint32_t* d_tuples, uint32_t n_tuples, uint32_t op_begin,
+                      uint32_t op_end, ff_mutation_t* d_muts, uint64_t* d_out_ns, uint64_t* d_best_ns, uint32_t* d_best_index,
+                      void* hip_stream) {
+    if (!c || !d_tuple_ptr || !d_tuples || !d_muts || !d_out_ns || !d_best_ns || !d_best_index) return FF_EINVAL;
+    std::vector<uint32_t> first;
+    uint64_t total = 0;
+    int rc = neighbour_ranges(c, d_tuple_ptr, n_tuples, op_begin, op_end, &first, &total);
+    if (rc) return rc;
+    if (total == 0) return FF_EINVAL;
+    if (total * c->C > 0xffffffffull) return FF_ERANGE;
+    const uint32_t M = (uint32_t)total;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the index ranges of the ops: a small allocation of the library's for the duration of the call
+    uint32_t* d_first = nullptr;
+    if (hipMalloc(&d_first, first.size() * 4) != hipSuccess) return FF_ENOMEM;
+    if (hipMemcpyAsync(d_first, first.data(), first.size() * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) { hipFree(d_first); return FF_EHIP; }   // `first` is pageable host memory
+    hipLaunchKernelGGL(k_neighbour_list, dim3((M + WAVE - 1) / WAVE), dim3(WAVE), 0, st, d_tuple_ptr, d_tuples, d_first, op_begin,
+                       op_end, c->sim->dev.n_dev, M, c->C, (uint32_t*)d_muts);
+    rc = ff_sim_delta_try(c, d_muts, M, d_out_ns, hip_stream);
+    if (rc == FF_OK) {
+        hipLaunchKernelGGL(k_best_of, dim3(c->C), dim3(WAVE), 0, st, (const u64*)d_out_ns, M, c->C, (u64*)d_best_ns, d_best_index);
+        if (hipGetLastError() != hipSuccess) rc = FF_EHIP;
+    }
+    // the list kernel is the only reader of d_first
+    if (hipStreamSynchronize(st) != hipSuccess && rc == FF_OK) rc = FF_EHIP;
+    hipFree(d_first);
+    return rc;
+}
+
 size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* c, uint32_t M) {
     if (!c) return 0;
     const uint64_t total = (uint64_t)M * c->C;

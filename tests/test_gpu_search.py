@@ -147,3 +147,74 @@ def test_search_argument_errors(B):
     torch.cuda.synchronize()
     ch.close()
     sim.close()
+
+
+@pytest.mark.parametrize("config_id,C,ops_range", [(0, 3, None), (1, 2, None), (2, 1, (118, 121))])
+def test_neighbour_sweep_matches_oracle(B, config_id, C, ops_range):
+    """Section 8.4's local-optimality check: every strategy that differs from the chain's in one
+    op's configuration, each equal to a full simulation by the oracle; the list is enumerated
+    here independently (ops, then tuples in list order, then device offsets)."""
+    w = W.workload(config_id)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    cfg0 = w.strategies(C)
+    ch = B.Chains(sim, cfg0)
+    warm = w.mutations(3, C)
+    ch.delta(ch.upload_mutations(warm), 3)
+    cur = cfg0.copy()
+    for s in range(3):
+        for c in range(C):
+            cur[c, int(warm[s, c]["op"])] = warm[s, c]["cfg"]
+    tp, tu = w.search_space()
+    ob, oe = ops_range if ops_range else (0, w.n_ops)
+    muts, got, best_ns, best_idx = ch.neighbours(tp, tu, ob, oe)
+    want_list = [(op, int(tu[t]), off) for op in range(ob, oe) for t in range(tp[op], tp[op + 1])
+                 for off in range(w.machine.n_devices)]
+    M = len(want_list)
+    assert muts.shape == (M, C) and got.shape == (M, C)
+    print(f"neighbours: config {config_id}, {M} per chain", flush=True)
+    for c in range(C):
+        assert [int(x) for x in muts[:, c]["op"]] == [m[0] for m in want_list]
+        deg = muts[:, c]["cfg"]["deg"].astype(np.uint32)
+        assert np.array_equal(deg[:, 0] | (deg[:, 1] << 8) | (deg[:, 2] << 16) | (deg[:, 3] << 24),
+                              np.array([m[1] for m in want_list], np.uint32))
+        assert [int(x) for x in muts[:, c]["cfg"]["dev_offset"]] == [m[2] for m in want_list]
+        assert np.all(muts[:, c]["cfg"]["dev_stride"] == 1)
+        cand = np.repeat(cur[c][None], M, 0)
+        for k in range(M):
+            cand[k, int(muts[k, c]["op"])] = muts[k, c]["cfg"]
+        want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cand, n_threads=8)
+        bad = np.nonzero(got[:, c] != want)[0]
+        assert len(bad) == 0, f"chain {c}: neighbours {bad[:5]} gpu {got[bad[:5], c]} oracle {want[bad[:5]]}"
+        assert int(best_ns[c]) == int(want.min()) and int(best_idx[c]) == int(np.argmin(want))
+        # the current strategy is its own neighbour: never better than the best
+        own = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cur[c][None])[0])
+        assert int(best_ns[c]) <= own
+    # the chains were only read
+    more = w.mutations(5, C)[3:]
+    after = ch.delta(ch.upload_mutations(more), 2).cpu().numpy().view("<u8")
+    for c in range(C):
+        assert np.array_equal(after[:, c], oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cur[c], more[:, c]))
+    ch.close()
+    sim.close()
+
+
+def test_neighbour_sweep_argument_errors(B):
+    import torch
+    w = W.workload(0)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    ch = B.Chains(sim, w.strategies(1))
+    tp, tu = w.search_space()
+    d_ptr, d_tu = B.to_device(tp), B.to_device(tu)
+    assert B.ff_sim_neighbour_count(ch.handle, d_ptr.data_ptr(), len(tu), 0, w.n_ops) == len(tu) * w.machine.n_devices
+    assert B.ff_sim_neighbour_count(ch.handle, d_ptr.data_ptr(), len(tu), 2, 2) == 0
+    import ctypes
+    n = ctypes.c_uint32()
+    L = B.lib()
+    assert L.ff_sim_neighbour_count(ch.handle, d_ptr.data_ptr(), len(tu), 3, 2, ctypes.byref(n)) == B.FF_EINVAL
+    assert L.ff_sim_neighbour_count(ch.handle, d_ptr.data_ptr(), len(tu), 0, w.n_ops + 1, ctypes.byref(n)) == B.FF_EINVAL
+    assert L.ff_sim_neighbour_count(ch.handle, d_ptr.data_ptr(), len(tu) - 1, 0, w.n_ops, ctypes.byref(n)) == B.FF_EINVAL
+    assert L.ff_sim_neighbour_count(ch.handle, None, len(tu), 0, w.n_ops, ctypes.byref(n)) == B.FF_EINVAL
+    assert L.ff_sim_neighbours(ch.handle, d_ptr.data_ptr(), d_tu.data_ptr(), len(tu), 0, w.n_ops, None, None, None, None, None) == B.FF_EINVAL
+    torch.cuda.synchronize()
+    ch.close()
+    sim.close()
