@@ -500,3 +500,54 @@ def test_trial_mutations_need_a_workspace(B):
     torch.cuda.synchronize()
     B.ff_sim_chains_destroy(ch)
     B.ff_sim_destroy(h)
+
+
+@pytest.mark.parametrize("seed,n_nodes,gpn", [(0, 1, 4), (1, 3, 1), (2, 2, 2), (3, 5, 3), (4, 4, 4), (5, 3, 5),
+                                               (6, 2, 8), (7, 7, 8), (8, 2, 9), (9, 6, 2)])
+def test_random_graphs_with_regular_strategies(B, seed, n_nodes, gpn):
+    """every op on consecutive, distinct devices (stride 1, parts <= devices): the form of the
+    event loop that serialises transfers on shared link rows with a running sum along the lanes.
+    Machine shapes cover one GPU per node, non-powers of two, eight and nine GPUs per node (nine
+    is beyond that form's limit) and offsets that make the device numbers wrap around."""
+    rng = np.random.default_rng(7000 + seed)
+    n_ops = int(rng.integers(3, 70))
+    ops, edges, _ = random_graph(rng, n_ops)
+    mach = W.Machine(n_nodes, gpn, int(rng.integers(1, 30)), int(rng.integers(1, 30)),
+                     int(rng.integers(0, 50)), int(rng.integers(0, 50)), int(rng.choice([1, 2, 4, 8])))
+    D = mach.n_devices
+    cost = rng.integers(1, 3000, size=(n_ops, 64)).astype("<u4")
+    n = 200
+    cfgs = np.zeros((n, n_ops), W.CFG_DT)
+    for i in range(n_ops):
+        t = W.valid_degree_tuples(ops[i], min(64, D), (1, 2, 3, 4, 5, 6, 7, 8, 16, 32, 64))
+        cfgs["deg"][:, i] = t[rng.integers(len(t), size=n)]
+    cfgs["dev_offset"] = rng.integers(0, D, size=(n, n_ops))
+    cfgs["dev_offset"][: n // 4] = D - 1          # many wrap-arounds
+    cfgs["dev_stride"] = 1
+    cfgs["dev_stride"][-1, 0] = 2                 # one candidate that needs the general form
+    print(f"seed {seed}: {n_ops} ops, {len(edges)} edges, machine {mach.as_tuple()}", flush=True)
+    want = oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8)
+    sim = B.Simulator(ops, edges, mach, cost)
+    got, st = sim.simulate(cfgs, stats=True)
+    assert not st["exit_code"].any() and not st["n_stuck"].any()
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+    assert np.array_equal(sim.simulate(cfgs), want)          # and the kernel without the counters
+    # chains that stay regular, with one irregular mutation in the middle
+    muts = np.zeros((24, 2), W.MUT_DT)
+    muts["op"] = rng.integers(0, n_ops, size=(24, 2))
+    for s in range(24):
+        for c in range(2):
+            i = int(muts[s, c]["op"])
+            t = W.valid_degree_tuples(ops[i], min(64, D), (1, 2, 3, 4, 8, 16))
+            muts[s, c]["cfg"]["deg"] = t[rng.integers(len(t))]
+            muts[s, c]["cfg"]["dev_offset"] = rng.integers(0, D)
+            muts[s, c]["cfg"]["dev_stride"] = 1
+    muts[11, 0]["cfg"]["dev_stride"] = 3
+    ch = B.Chains(sim, cfgs[:2])
+    d = ch.delta(ch.upload_mutations(muts), 24).cpu().numpy().view("<u8")
+    for c in range(2):
+        ref = oracle.simulate_delta_chain(ops, edges, mach, cost, cfgs[c], muts[:, c])
+        assert np.array_equal(d[:, c], ref), f"chain {c}: steps {np.nonzero(d[:, c] != ref)[0][:5]}"
+    ch.close()
+    sim.close()
