@@ -23,7 +23,13 @@ HEADLINE = 1
 # HBM bytes per launch of the batch kernel (fetch + write), from rocprofv3 --pmc FETCH_SIZE and
 # --pmc WRITE_SIZE runs of this script, scaled by what the same counters read for a 256 MiB
 # device-to-device copy (profiles/k_sim_batch_hbm_traffic.txt).  Not measured live.
-MEASURED_TRAFFIC_BYTES = {1: 528384, 2: 847.7e6, 3: 2147.5e6, 4: 4456.8e6}
+MEASURED_TRAFFIC_BYTES = {1: 504832, 2: 782.7e6, 3: 1961.4e6, 4: 4162.1e6}
+# Vector instructions per candidate (SQ_INSTS_VALU / B, profiles/k_sim_batch_sq_counters.txt) and the
+# chip's vector issue peak: 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per 64-lane instruction.  The
+# kernel is bound by instruction issue and latency, not by HBM; this second view says how busy the
+# vector units are.  Not measured live.
+MEASURED_VALU_PER_STRATEGY = {1: 35263.0, 2: 1383214.0, 4: 17966790.0}
+VALU_PEAK_G_PER_S = 256 * 4 * 2.4e9 / 4 / 1e9
 
 
 def alg_bytes(n_ops, tc, npairs):
@@ -115,6 +121,8 @@ def main():
             "achieved_GBps": ab * B / (kern_ms * 1e-3) / 1e9,
             "hbm_roofline_frac": ab * B / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "hbm_traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get(c),
+            "valu_issue_frac": (MEASURED_VALU_PER_STRATEGY[c] * B / (kern_ms * 1e-3) / 1e9 / VALU_PEAK_G_PER_S
+                                if c in MEASURED_VALU_PER_STRATEGY else None),
             "input_sha256": w.sha256(B),
         }
         if not args.workloads and not args.only_headline:
@@ -149,8 +157,13 @@ def main():
                    "candidates_per_step": head["B"]},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": head["hbm_roofline_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE),
-                     "kernel": "k_sim_batch<false>", "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
+                     "kernel": "k_sim_batch<WIDE=false, LDSW=true, STATS=false, TREE=false>",
+                     "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
                      "kernel_ms": head["kernel_ms"]},
+        # the same launch against the vector-issue peak (64-lane integer instructions per second)
+        "roofline_alu": {"bound": "alu", "achieved": MEASURED_VALU_PER_STRATEGY[HEADLINE] * head["B"] / (head["kernel_ms"] * 1e-3) / 1e9,
+                         "peak": VALU_PEAK_G_PER_S, "unit": "G wavefront-instructions/s", "frac": head["valu_issue_frac"],
+                         "note": "instruction count from rocprofv3 SQ_INSTS_VALU (profiles/), kernel time live"},
     }
     if not args.no_cpu:
         # the oracle as it stands on the host cores: the whole 1024-candidate batch, repeated
