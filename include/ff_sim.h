@@ -218,6 +218,10 @@ int ff_sim_neighbours(ff_chains_t* chains, const uint32_t* d_tuple_ptr, const ui
  * draw(11) mod (number of entries) of the op's list d_tuples[d_tuple_ptr[op] .. d_tuple_ptr[op+1])
  * (four degrees, one byte each, deg[0] lowest), dev_offset = draw(12) mod n_devices,
  * dev_stride = 1; the acceptance draw is draw(13).  An invalid proposal is rejected.
+ * Section 6.2 ends the search from one initial strategy when its budget is spent (n_steps, the
+ * caller's) or when the best discovered strategy has not improved for half of the search time:
+ * a chain that has gone `patience` steps without a new best makes no further proposals (its
+ * time repeats in the trace); the count carries over between calls on the same chains.
  * d_trace_ns[s][c] receives the time of chain c's strategy after step s; d_best_ns[c] /
  * d_best[c][n_ops] are updated whenever a step ends with a better time than d_best_ns[c]
  * (initialise it to UINT64_MAX).  All d_* are device pointers.  The call copies n_ops+1
@@ -226,6 +230,7 @@ typedef struct {
     uint64_t seed;
     uint64_t first_step;
     uint64_t bucket_ns;
+    uint64_t patience;              /* steps without a new best after which a chain stops proposing; 0 = never */
     uint32_t n_buckets;
     uint32_t n_tuples;              /* entries in d_tuples */
     const uint32_t* d_accept;       /* [n_buckets] */

@@ -50,8 +50,10 @@ def metropolis_table(beta_per_ns: float, bucket_ns: int, n_buckets: int) -> np.n
 
 
 def metropolis_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept, bucket_ns, seed,
-                     chain, first_step, n_steps):
-    """runs n_steps of one chain starting from the valid strategy cfg0.
+                     chain, first_step, n_steps, patience=0, idle_steps=0, best_so_far=None):
+    """runs n_steps of one chain starting from the valid strategy cfg0.  patience > 0: the
+    stopping rule of Section 6.2 -- after `patience` steps without a new best the chain makes
+    no further proposals (idle_steps / best_so_far carry the state of an earlier call over).
     Returns (trace [n_steps] of the chain's time after each step, final strategy, best time,
     best strategy, number of accepted proposals)."""
     n_ops = len(ops)
@@ -60,13 +62,16 @@ def metropolis_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept,
     cur_ns = int(simulate_batch(ops, edges, machine, cost, cur[None])[0])
     assert cur_ns != INVALID, "the chain must start from a valid strategy"
     best_ns, best = cur_ns, cur.copy()
+    if best_so_far is not None and best_so_far < best_ns:
+        best_ns, best = best_so_far, None
+    idle = idle_steps
     trace = np.zeros(n_steps, "<u8")
     n_acc = 0
     for s in range(n_steps):
         st = first_step + s
         op = draw(seed, OP, chain, st) % n_ops
         t0, t1 = int(tuple_ptr[op]), int(tuple_ptr[op + 1])
-        if t1 > t0:
+        if t1 > t0 and not (patience and idle >= patience):
             word = int(tuples[t0 + draw(seed, TUPLE, chain, st) % (t1 - t0)])
             prop = cur.copy()
             prop[op]["deg"] = [(word >> (8 * d)) & 0xFF for d in range(4)]
@@ -84,6 +89,8 @@ def metropolis_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept,
                 cur, cur_ns = prop, new_ns
                 n_acc += 1
         trace[s] = cur_ns
+        idle += 1
         if cur_ns < best_ns:
             best_ns, best = cur_ns, cur.copy()
+            idle = 0
     return trace, cur, best_ns, best, n_acc

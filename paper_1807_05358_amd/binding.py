@@ -42,7 +42,7 @@ CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events"
 
 
 class ff_search_t(C.Structure):
-    _fields_ = [("seed", C.c_uint64), ("first_step", C.c_uint64), ("bucket_ns", C.c_uint64),
+    _fields_ = [("seed", C.c_uint64), ("first_step", C.c_uint64), ("bucket_ns", C.c_uint64), ("patience", C.c_uint64),
                 ("n_buckets", C.c_uint32), ("n_tuples", C.c_uint32),
                 ("d_accept", C.c_void_p), ("d_tuple_ptr", C.c_void_p), ("d_tuples", C.c_void_p),
                 ("d_best_ns", C.c_void_p), ("d_best", C.c_void_p)]
@@ -318,7 +318,7 @@ class Chains:
         ff_sim_delta_try(self.handle, d_muts.data_ptr(), M, d_out.data_ptr(), torch.cuda.current_stream().cuda_stream)
         return d_out
 
-    def search_setup(self, tuple_ptr, tuples, accept, bucket_ns, seed):
+    def search_setup(self, tuple_ptr, tuples, accept, bucket_ns, seed, patience=0):
         """uploads the proposal lists (workloads.search_space) and the acceptance table
         (probabilities scaled by 2^32, one per bucket of bucket_ns) and resets the best-so-far
         record.  Steps are numbered from 0 across the search() calls that follow."""
@@ -329,7 +329,8 @@ class Chains:
             accept=to_device(np.ascontiguousarray(accept, "<u4")),
             best_ns=torch.full((self.C,), -1, dtype=torch.int64, device="cuda"),
             best=torch.zeros(self.C * self.sim.n_ops * W.CFG_DT.itemsize, dtype=torch.uint8, device="cuda"),
-            n_tuples=len(tuples), n_buckets=len(accept), bucket_ns=int(bucket_ns), seed=int(seed), step=0)
+            n_tuples=len(tuples), n_buckets=len(accept), bucket_ns=int(bucket_ns), seed=int(seed), step=0,
+            patience=int(patience))
 
     def search(self, n_steps, d_trace=None):
         """n_steps Metropolis steps on every chain; returns the device tensor [n_steps][C] of the
@@ -338,7 +339,7 @@ class Chains:
         sp = self._sp
         if d_trace is None:
             d_trace = torch.empty((n_steps, self.C), dtype=torch.int64, device="cuda")
-        p = ff_search_t(sp["seed"], sp["step"], sp["bucket_ns"], sp["n_buckets"], sp["n_tuples"],
+        p = ff_search_t(sp["seed"], sp["step"], sp["bucket_ns"], sp["patience"], sp["n_buckets"], sp["n_tuples"],
                         sp["accept"].data_ptr(), sp["tuple_ptr"].data_ptr(), sp["tuples"].data_ptr(),
                         sp["best_ns"].data_ptr(), sp["best"].data_ptr())
         ff_sim_search(self.handle, p, n_steps, d_trace.data_ptr(), torch.cuda.current_stream().cuda_stream)

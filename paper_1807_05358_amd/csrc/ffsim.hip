@@ -342,7 +342,7 @@ int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64
     SearchDev sd{};
     sd.seed = p->seed; sd.first_step = p->first_step; sd.bucket_ns = p->bucket_ns;
     sd.accept = p->d_accept; sd.tuple_ptr = p->d_tuple_ptr; sd.tuples = p->d_tuples;
-    sd.n_buckets = p->n_buckets; sd.enabled = 1;
+    sd.n_buckets = p->n_buckets; sd.enabled = 1; sd.patience = p->patience;
     sd.best_ns = (u64*)p->d_best_ns; sd.best_cfgs = (uint2*)p->d_best;
     return launch_chain_steps(c, nullptr, n_steps, d_trace_ns, (hipStream_t)hip_stream, sd);
 }
@@ -433,7 +433,7 @@ int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, ui
 int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
     if (!c || !h_out) return FF_EINVAL;
     if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;
-    static_assert(sizeof(ChainMeta) == 24 + sizeof(ff_chain_stats_t), "chain stats layout");
+    static_assert(sizeof(ChainMeta) == 32 + sizeof(ff_chain_stats_t), "chain stats layout");
     for (uint32_t k = 0; k < c->C; k++) {
         ChainMeta meta;
         const unsigned char* p = c->d_mem + (size_t)k * c->stride + chain_meta_offset(c->sim->dev.n_ops, c->sim->dev.n_ops_pad, c->sim->dev.n_rows, c->n_snaps);

@@ -776,6 +776,7 @@ struct ChainMeta {
     u64 n_events;       // queue pops spent in mutation steps
     u64 n_events_full;  // queue pops of the last simulation from time 0 (one full simulation)
     u64 cur_ns;         // simulated time of the chain's current strategy (result code if it has none)
+    u64 idle_steps;     // search steps since the chain's best time last improved
 };
 
 struct ChainMem {       // all pointers are per chain
@@ -912,6 +913,7 @@ struct SearchDev {
     const uint32_t* tuples;      // degree tuples (four bytes each) a proposal may pick for each op
     uint32_t n_buckets;
     uint32_t enabled;
+    u64 patience;                // a chain stops proposing after this many steps without a new best (0 = never)
     u64* best_ns;                // [C] best simulated time seen (in/out)
     uint2* best_cfgs;            // [C][n_ops] the strategy that achieved it (in/out)
 };
@@ -958,6 +960,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.n_events = first_u64(meta.n_events);
     meta.n_events_full = first_u64(meta.n_events_full);
     meta.cur_ns = first_u64(meta.cur_ns);
+    meta.idle_steps = first_u64(meta.idle_steps);
     Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
     Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
@@ -973,7 +976,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         uint32_t op = 0;
         uint2 ocfg = make_uint2(0, 0);
         if (search.enabled) {
-            if (!poisoned && !meta.stale) {
+            if (!poisoned && !meta.stale && !(search.patience && meta.idle_steps >= search.patience)) {
                 const u64 st = search.first_step + s;
                 op = first_u32((uint32_t)(draw64(search.seed, 10, c, st) % S.n_ops));
                 const uint32_t t0 = first_u32(search.tuple_ptr[op]), t1 = first_u32(search.tuple_ptr[op + 1]);
@@ -1099,8 +1102,10 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
             wave_sync();
             mk = meta.cur_ns;
         }
+        if (search.enabled) meta.idle_steps++;
         if (search.enabled && !poisoned && mk < RESULT_OVERFLOW && mk < best) {
             best = mk;
+            meta.idle_steps = 0;
             for (uint32_t i = lane; i < S.n_ops; i += WAVE) search.best_cfgs[(size_t)c * S.n_ops + i] = cfg_lds[i];
         }
         if (lane == 0) out_ns[(size_t)s * C + c] = mk;

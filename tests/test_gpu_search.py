@@ -218,3 +218,27 @@ def test_neighbour_sweep_argument_errors(B):
     torch.cuda.synchronize()
     ch.close()
     sim.close()
+
+
+def test_search_stopping_rule(B):
+    """patience: chains stop proposing after that many steps without a new best; the count and
+    the best so far carry over between calls."""
+    w = W.workload(1)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    C = 5
+    cfg0 = w.strategies(C)
+    tp, tu = w.search_space()
+    table = S.metropolis_table(40.0 / 4.0e7, 150000, 64)
+    ch = B.Chains(sim, cfg0)
+    ch.search_setup(tp, tu, table, 150000, 21, patience=7)
+    got = np.concatenate([ch.search(n).cpu().numpy().view("<u8") for n in (30, 50)])
+    stopped = 0
+    for c in range(C):
+        a = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], tp, tu, table, 150000, 21, c, 0, 80, patience=7)
+        assert np.array_equal(got[:, c], a[0]), f"chain {c}: step {np.nonzero(got[:, c] != a[0])[0][:3]}"
+        stopped += int(np.all(a[0][-8:] == a[0][-1]))
+    assert stopped == C           # with patience 7 every chain has come to rest within 80 steps
+    best_ns, _ = ch.best()
+    assert np.array_equal(best_ns, got.min(axis=0).clip(max=ch.start_ns()))
+    ch.close()
+    sim.close()

@@ -104,3 +104,29 @@ def test_steps_continue_across_calls():
     b = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, a[1], tp, tu, table, 1000, 9, 2, 12, 18)
     assert np.array_equal(whole[0], np.concatenate([a[0], b[0]]))
     assert np.array_equal(whole[1], b[1])
+
+
+def test_stopping_rule_freezes_the_chain_after_patience_steps_without_a_new_best():
+    """Section 6.2: the search from one initial strategy ends when the best strategy has not
+    improved for the given number of steps; until then it is the same chain."""
+    w = W.workload(1)
+    tp, tu = w.search_space()
+    cfg0 = w.strategies(1)[0]
+    table = S.metropolis_table(40.0 / 4.0e7, 150000, 64)
+    free = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0, tp, tu, table, 150000, 21, 0, 0, 300)[0]
+    for patience in (3, 10, 40):
+        tr = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0, tp, tu, table, 150000, 21, 0, 0, 300,
+                                patience=patience)[0]
+        # running best of the unrestricted chain, with the start strategy counted
+        start = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[None])[0])
+        best, idle, stop = start, 0, None
+        for s in range(300):
+            if idle >= patience:
+                stop = s
+                break
+            idle += 1
+            if free[s] < best:
+                best, idle = int(free[s]), 0
+        assert stop is not None and stop < 300
+        assert np.array_equal(tr[:stop], free[:stop])
+        assert np.all(tr[stop:] == tr[stop - 1])
