@@ -163,9 +163,9 @@ int ff_sim_batch(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t B, uint
 /* Delta simulation (Section 5.3, Algorithm 2's contract: same timeline as a full simulation
  * of the changed strategy).  A chain set holds C current strategies on the device;
  * d_out_ns0[c] receives the time of the starting strategies.  The library owns the
- * chains' state and allocates it here with hipMalloc: per chain the strategy, one word and
- * one endTime per possible task, and 32 snapshots of the simulation state (about
- * 34 * 512 * n_ops bytes).  Destroy only after the work queued on the stream has finished. */
+ * chains' state and allocates it here with hipMalloc: per chain the strategy, one word and two
+ * endTimes per possible task, and two places for each of 32 snapshots of the simulation state
+ * (about 67 * 512 * n_ops bytes: 80 MB for a 2321-op graph).  Destroy only after the work queued on the stream has finished. */
 int ff_sim_chains_create(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t C, uint64_t* d_out_ns0,
                          void* hip_stream, ff_chains_t** out);
 /* Applies d_muts[s][c] (step-major, [n_steps][C]) to chain c for s = 0..n_steps-1,

@@ -60,6 +60,7 @@ struct ff_chains {
 };
 
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
+static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMeta::loc");
 
 typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const uint2*,
                                uint32_t, u64*, Counters*, unsigned char*, size_t);
@@ -433,7 +434,6 @@ int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, ui
 int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
     if (!c || !h_out) return FF_EINVAL;
     if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;
-    static_assert(sizeof(ChainMeta) == 32 + sizeof(ff_chain_stats_t), "chain stats layout");
     for (uint32_t k = 0; k < c->C; k++) {
         ChainMeta meta;
         const unsigned char* p = c->d_mem + (size_t)k * c->stride + chain_meta_offset(c->sim->dev.n_ops, c->sim->dev.n_ops_pad, c->sim->dev.n_rows, c->n_snaps);

@@ -294,15 +294,24 @@ typedef SimT<true> SimTrial;
 
 // Optional recording for delta simulation: endTime of every task, and snapshots of the
 // simulation state whenever the event time crosses a multiple of `step`.
+//
+// Every snapshot index has two storage places (set 0 and set 1).  Bit k of `loc` says which of
+// them holds snapshot k of the chain's ACCEPTED timeline; a recorded run writes snapshot k into
+// the other place, and endTimes into their own array, marked with the run's tag.  Nothing of
+// the accepted timeline is touched until the run is committed (the bits of the snapshots it
+// wrote are flipped, its endTimes are copied over); a run that is not committed leaves no trace.
 struct Recorder {
-    u64* end_of;             // [n_ops*64]
-    u64* snap_words;         // [n_snaps][n_ops*64]
-    u64* snap_l1;            // [n_snaps][n_ops_pad]
-    u64* snap_free;          // [n_snaps][n_rows]
+    u64* end_try;            // [n_ops*64] tag<<48 | endTime of the tasks the run committed (null: not recorded)
+    u64* snap_words;         // [2][n_snaps][n_ops*64]
+    u64* snap_l1;            // [2][n_snaps][n_ops_pad]
+    u64* snap_free;          // [2][n_snaps][n_rows]
     u64 step;                // snapshot k holds the state before the first event with word >= k*step
+    u64 tag;                 // this run's tag, already shifted (tag << 48)
+    uint32_t loc;            // see above
     uint32_t n_snaps;        // capacity (snapshot 0 is the initial state and is never stored)
     uint32_t next;           // next snapshot index to write
 };
+constexpr uint32_t MAX_SNAPSHOTS = 32;   // bits of loc
 
 // how many parts of the producer (configuration cp) a consumer part reads through edge e:
 // the product over the producer's dims of the number of producer parts its range touches
@@ -410,7 +419,7 @@ __device__ __forceinline__ void copy_words(u64* __restrict__ dst, const u64* __r
 template <class SimX>
 __device__ __forceinline__ void save_snapshot(const SimX& m, Recorder& rec) {
     const int lane = lane_id();
-    const size_t k = rec.next;
+    const size_t k = (size_t)((((rec.loc >> rec.next) & 1u) ^ 1u) * rec.n_snaps + rec.next);   // the place the accepted timeline does not use
     copy_words(rec.snap_words + k * (size_t)m.S.n_ops * WAVE, m.words, m.S.n_ops * WAVE);
     u64* l1 = rec.snap_l1 + k * (size_t)m.S.n_ops_pad;
     for (uint32_t t = lane; t < m.S.n_ops_pad; t += WAVE) l1[t] = m.L.l1[t];
@@ -419,13 +428,15 @@ __device__ __forceinline__ void save_snapshot(const SimX& m, Recorder& rec) {
     rec.next++;
 }
 
+// snapshot k of the accepted timeline
 template <class SimX>
 __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint32_t k) {
     const int lane = lane_id();
-    copy_words(m.words, rec.snap_words + (size_t)k * m.S.n_ops * WAVE, m.S.n_ops * WAVE);
-    const u64* l1 = rec.snap_l1 + (size_t)k * m.S.n_ops_pad;
+    const size_t at = (size_t)(((rec.loc >> k) & 1u) * rec.n_snaps + k);
+    copy_words(m.words, rec.snap_words + at * m.S.n_ops * WAVE, m.S.n_ops * WAVE);
+    const u64* l1 = rec.snap_l1 + at * m.S.n_ops_pad;
     for (uint32_t t = lane; t < m.S.n_ops_pad; t += WAVE) m.L.l1[t] = l1[t];
-    const u64* fr = rec.snap_free + (size_t)k * m.S.n_rows;
+    const u64* fr = rec.snap_free + at * m.S.n_rows;
     for (uint32_t t = lane; t < m.S.n_rows; t += WAVE) m.L.free_at[t] = fr[t];
     wave_sync();
     m.last_key = (u64)k * rec.step;
@@ -513,7 +524,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
             if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
-            if (RECORD) { if (in_mask && rec.end_of) rec.end_of[i * WAVE + lane] = end; }
+            if (RECORD) { if (in_mask && rec.end_try) rec.end_try[i * WAVE + lane] = rec.tag | end; }
             PROF_MARK(2)
         } else {
             // the parts in `mask` finished at `now`: release their successors edge by edge
@@ -758,14 +769,16 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
 
 // ---- delta simulation (Section 5.3) ---------------------------------------------------
 //
-// A chain keeps, in HBM, its current strategy, the task words, the endTime of every task of
-// the last simulation and up to n_snaps snapshots of the simulation state taken whenever
-// the event time crossed a multiple of `step`.  When the configuration of one op changes,
-// nothing can differ before the first producer of that op finishes (its transfers are the
-// first tasks that depend on the op's configuration), so the simulation is resumed from
-// the last snapshot before that time: the op's own tasks are rebuilt, the input counts of
-// its consumers are corrected, and Algorithm 1 continues from there, rewriting the later
-// snapshots.  The resulting timeline is the one a full simulation produces.
+// A chain keeps, in HBM, its current strategy, the endTime of every task of the simulation of
+// that strategy (the accepted timeline) and up to n_snaps snapshots of the simulation state
+// taken whenever the event time crossed a multiple of `step`.  When the configuration of one
+// op changes, nothing can differ before the first producer of that op finishes (its transfers
+// are the first tasks that depend on the op's configuration), so the simulation is resumed
+// from the last snapshot before that time: the op's own tasks are rebuilt, the input counts of
+// its consumers are corrected, and Algorithm 1 continues from there.  The resulting timeline is
+// the one a full simulation produces.  Every such run is recorded beside the accepted timeline
+// (see Recorder) and becomes the accepted one only when it is committed, so a search proposal
+// costs one resumed simulation whether it is accepted or not.
 struct ChainMeta {
     u64 step;           // event-word distance between snapshots (2 * time)
     uint32_t n_valid;   // snapshots 1..n_valid-1 are usable (0 = none; index 0 is the initial state)
@@ -777,24 +790,27 @@ struct ChainMeta {
     u64 n_events_full;  // queue pops of the last simulation from time 0 (one full simulation)
     u64 cur_ns;         // simulated time of the chain's current strategy (result code if it has none)
     u64 idle_steps;     // search steps since the chain's best time last improved
+    uint32_t loc;       // bit k: which of its two places holds snapshot k of the accepted timeline
+    uint32_t tag;       // tag of the last recorded run (1..0xffff; 0 marks entries never written)
 };
 
 struct ChainMem {       // all pointers are per chain
     uint2* cfgs;
     u64* words;
     uint32_t* exe_of;
-    u64* end_of;
-    u64* snap_words;
-    u64* snap_l1;
-    u64* snap_free;
+    u64* end_of;        // accepted timeline
+    u64* end_try;       // tag<<48 | endTime, written by recorded runs
+    u64* snap_words;    // [2][n_snaps][n_ops*64]
+    u64* snap_l1;       // [2][n_snaps][n_ops_pad]
+    u64* snap_free;     // [2][n_snaps][n_rows, padded to even]
     ChainMeta* meta;
 };
 
 // byte offset of the ChainMeta record inside a chain block (it comes last)
 __host__ __device__ inline size_t chain_meta_offset(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps) {
     size_t b = (size_t)n_ops_pad * 8;                       // cfgs
-    b += (size_t)n_ops * WAVE * 8 * 2;                      // words, end_of
-    b += (size_t)n_snaps * ((size_t)n_ops * WAVE * 8 + (size_t)n_ops_pad * 8 + (size_t)((n_rows + 1) & ~1u) * 8);
+    b += (size_t)n_ops * WAVE * 8 * 3;                      // words, end_of, end_try
+    b += 2 * (size_t)n_snaps * ((size_t)n_ops * WAVE * 8 + (size_t)n_ops_pad * 8 + (size_t)((n_rows + 1) & ~1u) * 8);
     b += (size_t)n_ops_pad * 4;                             // exe_of
     return b;
 }
@@ -808,9 +824,10 @@ __device__ __forceinline__ ChainMem carve_chain(unsigned char* base, const SimDe
     c.cfgs = (uint2*)base; base += (size_t)S.n_ops_pad * 8;
     c.words = (u64*)base; base += nw * 8;
     c.end_of = (u64*)base; base += nw * 8;
-    c.snap_words = (u64*)base; base += (size_t)n_snaps * nw * 8;
-    c.snap_l1 = (u64*)base; base += (size_t)n_snaps * S.n_ops_pad * 8;
-    c.snap_free = (u64*)base; base += (size_t)n_snaps * ((S.n_rows + 1) & ~1u) * 8;
+    c.end_try = (u64*)base; base += nw * 8;
+    c.snap_words = (u64*)base; base += 2 * (size_t)n_snaps * nw * 8;
+    c.snap_l1 = (u64*)base; base += 2 * (size_t)n_snaps * S.n_ops_pad * 8;
+    c.snap_free = (u64*)base; base += 2 * (size_t)n_snaps * ((S.n_rows + 1) & ~1u) * 8;
     c.exe_of = (uint32_t*)base; base += (size_t)S.n_ops_pad * 4;
     c.meta = (ChainMeta*)base;
     return c;
@@ -918,15 +935,30 @@ struct SearchDev {
     uint2* best_cfgs;            // [C][n_ops] the strategy that achieved it (in/out)
 };
 
+// Makes a recorded run the chain's accepted timeline: the snapshots it wrote (first..next-1)
+// take the place of the old ones, the endTimes it wrote are copied over the old ones.
+__device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, const Recorder& rec, uint32_t first, uint32_t n_words) {
+    const uint32_t written = rec.next > first ? (uint32_t)(((1ull << rec.next) - 1) & ~((1ull << first) - 1)) : 0u;
+    meta.loc ^= written;
+    meta.n_valid = rec.next;
+    const u64 tag = rec.tag;
+    for (uint32_t t = lane_id(); t < n_words; t += WAVE) {
+        const u64 v = cm.end_try[t];
+        if ((v & ~(TIME_LIMIT - 1)) == tag) cm.end_of[t] = v & (TIME_LIMIT - 1);
+    }
+    __threadfence_block();
+    wave_sync();
+}
+
 // One kernel drives a chain through a sequence of steps.  Three sources of steps:
 //   muts == nullptr and no search: simulate the chain's starting strategy (n_steps is 1);
-//   muts: forced mutations, [n_steps][C] records {op, cfg.x, cfg.y}, each committed;
+//   muts: forced mutations, [n_steps][C] records {op, cfg.x, cfg.y}, always committed;
 //   search: per step one proposal (random op, random configuration from its list, random
-//           device offset) is simulated as a trial and committed only if accepted:
-//           always when it is not slower, else with the tabulated probability.
-// Every simulation of a step goes through the single run_events call below: the trial
-// (nothing recorded), an optional pass that only finds the makespan when no snapshot spacing
-// is set yet, and the recorded run of the committed strategy.
+//           device offset), committed if it is not slower, else with the tabulated probability.
+// A step is one recorded simulation (resumed from the last snapshot before the change can
+// matter), then either commit_run or nothing.  Every simulation goes through the single
+// run_events call site below, including the pass that only finds the makespan when no
+// snapshot spacing is set yet.
 // A forced mutation that names an op outside the graph poisons the chain: this and all
 // later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
 // step s.
@@ -948,6 +980,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     const int lane = lane_id();
     const ChainMem cm = carve_chain(chain_mem + (size_t)c * chain_stride, S, n_snaps);
     const uint32_t magic_v = load_magic(magic);
+    const uint32_t n_words = S.n_ops * WAVE;
     for (uint32_t i = lane; i < S.n_ops; i += WAVE) cfg_lds[i] = cm.cfgs[i];
     wave_sync();
     bool poisoned = first_u32(chain_flags[c]) != 0;
@@ -961,7 +994,9 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.n_events_full = first_u64(meta.n_events_full);
     meta.cur_ns = first_u64(meta.cur_ns);
     meta.idle_steps = first_u64(meta.idle_steps);
-    Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
+    meta.loc = first_u32(meta.loc);
+    meta.tag = first_u32(meta.tag);
+    Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1};
     Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
@@ -972,7 +1007,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 
     for (uint32_t s = 0; s < n_steps; s++) {
         Counters cnt = {};
-        bool trial = false, valid = true;
+        bool proposal = false, valid = true;
         uint32_t op = 0;
         uint2 ocfg = make_uint2(0, 0);
         if (search.enabled) {
@@ -987,7 +1022,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     wave_sync();
                     if (lane == 0) cfg_lds[op] = make_uint2(first_u32(deg), first_u32(off) | (1u << 16));   // stride 1
                     wave_sync();
-                    trial = true;
+                    proposal = true;
                 }
             }
         } else if (muts) {
@@ -1009,93 +1044,100 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         StrategyClass cls = STRATEGY_INVALID;
         if (!poisoned) cls = validate_strategy(m);
         valid = cls != STRATEGY_INVALID;
-        if (!poisoned && !valid && !trial) { meta.stale = 1; meta.cur_ns = RESULT_INVALID; }
-        const bool changed = muts != nullptr || trial;
+        if (!poisoned && !valid && !proposal) { meta.stale = 1; meta.cur_ns = RESULT_INVALID; }
+        const bool changed = muts != nullptr || proposal;
         if (changed && !poisoned) meta.n_steps++;
+        bool accepted = false;
 
-        if (search.enabled && !trial && !poisoned && !meta.stale) {
+        if (search.enabled && !proposal && !poisoned && !meta.stale) {
             mk = meta.cur_ns;   // no proposal this step: nothing to simulate
         } else if (!poisoned && valid) {
             // where the simulation may start (0 = time 0)
             uint32_t k = 0, pend_new = 0;
-            if (changed && !meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, rec.end_of, meta, op, ocfg, pend_new);
-            if (!trial && k > 0) {
-                // a forced mutation is committed at once: rewrite the snapshots that stay valid
-                for (uint32_t sn = 1; sn <= k; sn++)
-                    patch_state_for_op(m, cm.snap_words + (size_t)sn * S.n_ops * WAVE, cm.snap_l1 + (size_t)sn * S.n_ops_pad, op, ocfg, pend_new);
-                __threadfence_block();
-                wave_sync();
-            }
+            if (changed && !meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
             const uint32_t capacity = n_snaps;
-            // phase 0: trial of a proposal; phase 1: makespan only (to fix the snapshot spacing);
-            // phase 2: the recorded simulation of the committed strategy
-            int phase = trial ? 0 : ((k == 0 && meta.step == 0) ? 1 : 2);
+            // phase 1: makespan only, to fix the snapshot spacing (no snapshots yet);
+            // phase 2: the recorded simulation
+            int phase = (k == 0 && meta.step == 0) ? 1 : 2;
+            u64 rc = 0;
             while (phase < 3) {
                 const bool record = phase == 2;
                 const u64 before = cnt.n_events;
+                if (record) {
+                    meta.tag = meta.tag >= 0xffffu ? 0u : meta.tag;
+                    if (meta.tag == 0) {
+                        // tags start over: forget what earlier runs wrote
+                        for (uint32_t t = lane; t < n_words; t += WAVE) cm.end_try[t] = 0;
+                        __threadfence_block();
+                        wave_sync();
+                    }
+                    meta.tag++;
+                }
                 rec.step = meta.step;
+                rec.tag = (u64)meta.tag << 48;
+                rec.loc = meta.loc;
                 rec.n_snaps = record ? capacity : 0;
-                rec.end_of = record ? cm.end_of : nullptr;
+                rec.end_try = record ? cm.end_try : nullptr;
                 rec.next = k + 1;
                 if (k == 0) {
                     init_state(m, cnt);
                 } else {
                     load_snapshot(m, rec, k);
-                    // a trial patches its private copy of the state; a committed mutation has
-                    // already rewritten the stored snapshots
-                    if (phase == 0) { patch_state_for_op(m, m.words, L.l1, op, ocfg, pend_new); wave_sync(); }
-                    rebuild_l2(m);
-                    if (record) meta.n_resumed++;
-                }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE>(m, cnt, rec) : run_events<WIDE, true, false, false, TREE>(m, cnt, rec);
-                rec.n_snaps = capacity;
-                rec.end_of = cm.end_of;
-                mk = rc ? rc : makespan(m);
-                if (phase == 0) {
-                    // Metropolis acceptance (Section 6.1) with tabulated probabilities
-                    bool accept = false;
-                    if (mk < RESULT_OVERFLOW) {
-                        if (mk <= meta.cur_ns) {
-                            accept = true;
-                        } else {
-                            u64 b = (mk - meta.cur_ns) / search.bucket_ns;
-                            if (b >= search.n_buckets) b = search.n_buckets - 1;
-                            const uint32_t u = (uint32_t)(draw64(search.seed, 13, c, search.first_step + s) >> 32);
-                            accept = u < search.accept[b];
-                        }
-                    }
-                    if (!accept) {
-                        wave_sync();
-                        if (lane == 0) cfg_lds[op] = ocfg;
-                        wave_sync();
-                        mk = meta.cur_ns;
-                        break;
-                    }
-                    if (lane == 0) cm.cfgs[op] = cfg_lds[op];
-                    // commit: rewrite what the snapshots that stay valid hold about the op
-                    for (uint32_t sn = 1; sn <= k; sn++)
-                        patch_state_for_op(m, cm.snap_words + (size_t)sn * S.n_ops * WAVE, cm.snap_l1 + (size_t)sn * S.n_ops_pad, op, ocfg, pend_new);
-                    __threadfence_block();
+                    // the loaded state still describes the op under its old configuration
+                    patch_state_for_op(m, m.words, L.l1, op, ocfg, pend_new);
                     wave_sync();
-                    phase = (k == 0 && meta.step == 0) ? 1 : 2;
-                    continue;
+                    rebuild_l2(m);
                 }
-                if (rc) { meta.stale = 1; meta.n_valid = 0; break; }
+                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE>(m, cnt, rec)
+                                             : run_events<WIDE, true, false, false, TREE>(m, cnt, rec);
+                mk = rc ? rc : makespan(m);
+                if (rc) break;
                 if (phase == 1) { meta.step = (2 * mk) / capacity + 1; phase = 2; continue; }
-                // phase 2 done
                 if (k == 0) meta.n_events_full = cnt.n_events - before;
-                meta.stale = 0;
-                meta.n_valid = rec.next;
-                meta.cur_ns = mk;
-                // the spacing was fixed by an earlier makespan; if the timeline has become more than
-                // twice shorter or longer, re-space: the snapshots just written are dropped and the
-                // next simulation starts from time 0 with the new spacing
-                const u64 ideal = (2 * mk) / capacity + 1;
-                if (ideal * 2 < meta.step || ideal > meta.step * 2) { meta.step = ideal; meta.n_valid = 1; }
                 break;
             }
             if (changed) meta.n_events += cnt.n_events;
-        } else if (trial && !valid) {
+            // the decision: forced mutations and the starting strategy are always taken; a proposal
+            // by the Metropolis rule (Section 6.1) with tabulated probabilities
+            if (!rc) {
+                accepted = true;
+                if (proposal && mk > meta.cur_ns) {
+                    u64 b = (mk - meta.cur_ns) / search.bucket_ns;
+                    if (b >= search.n_buckets) b = search.n_buckets - 1;
+                    const uint32_t u = (uint32_t)(draw64(search.seed, 13, c, search.first_step + s) >> 32);
+                    accepted = u < search.accept[b];
+                }
+            }
+            if (accepted) {
+                if (proposal && lane == 0) cm.cfgs[op] = cfg_lds[op];
+                if (k > 0) {
+                    meta.n_resumed++;
+                    // what the snapshots that stay hold about the op is rewritten for its new configuration
+                    for (uint32_t sn = 1; sn <= k; sn++) {
+                        const size_t at = (size_t)(((meta.loc >> sn) & 1u) * n_snaps + sn);
+                        patch_state_for_op(m, cm.snap_words + at * n_words, cm.snap_l1 + at * S.n_ops_pad, op, ocfg, pend_new);
+                    }
+                }
+                commit_run(cm, meta, rec, k + 1, n_words);
+                meta.stale = 0;
+                meta.cur_ns = mk;
+                // the spacing was fixed by an earlier makespan; if the timeline has become more than
+                // twice shorter or longer, re-space: the snapshots are dropped and the next simulation
+                // starts from time 0 with the new spacing
+                const u64 ideal = (2 * mk) / capacity + 1;
+                if (ideal * 2 < meta.step || ideal > meta.step * 2) { meta.step = ideal; meta.n_valid = 1; }
+            } else if (proposal) {
+                wave_sync();
+                if (lane == 0) cfg_lds[op] = ocfg;
+                wave_sync();
+                mk = meta.cur_ns;
+            } else {
+                // a forced step whose simulation failed (overflow): no timeline for this strategy
+                meta.stale = 1;
+                meta.n_valid = 0;
+                meta.cur_ns = mk;
+            }
+        } else if (proposal && !valid) {
             // an invalid proposal is rejected
             wave_sync();
             if (lane == 0) cfg_lds[op] = ocfg;
@@ -1161,7 +1203,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
-                Recorder rec{cm.end_of, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, n_snaps, 1};
+                Recorder rec{nullptr, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, first_u32(meta.loc), n_snaps, 1};
                 uint32_t k = 0, pend_new = 0;
                 if (!meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
                 if (k == 0) {
