@@ -142,6 +142,22 @@ typedef struct ff_chains ff_chains_t;
  * return) and uploads them to the current HIP device.  Section 5, inputs G and D. */
 int ff_sim_create(const ff_opgraph_t* graph, const ff_machine_t* machine, const ff_costtable_t* cost,
                   ff_sim_t** out);
+
+/* The same with the cost of an op's tasks given per DEGREE TUPLE instead of per number of parts:
+ * how long a task runs depends on which dims are split, not only on how many parts there are
+ * (Section 5.1 takes exeTime from measurements of the operation at the task's output size).
+ * Op i's entries are tuples[tuple_ptr[i] .. tuple_ptr[i+1]) -- four degrees, one byte each,
+ * deg[0] lowest, strictly ascending as integers -- with exeTime ns[] (>= 1) at the same index.
+ * A configuration whose tuple is not listed has no cost: the strategy is invalid
+ * (FF_INVALID_NS).  HOST pointers, deep-copied. */
+typedef struct {
+    uint32_t n_ops;
+    const uint32_t* tuple_ptr;   /* [n_ops + 1], tuple_ptr[0] = 0 */
+    const uint32_t* tuples;      /* [tuple_ptr[n_ops]] */
+    const uint32_t* ns;          /* [tuple_ptr[n_ops]] */
+} ff_tuplecost_t;
+int ff_sim_create_tuplecost(const ff_opgraph_t* graph, const ff_machine_t* machine, const ff_tuplecost_t* costs,
+                            ff_sim_t** out);
 void ff_sim_destroy(ff_sim_t* sim);
 
 /* Scratch for a batch of B candidates (per-task queue keys and readyTime / pending-input

@@ -32,7 +32,7 @@ def lib():
         L = C.CDLL(build())
         vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
         L.ffo_build.restype = vp
-        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp]
+        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp]
         L.ffo_from_arrays.restype = vp
         L.ffo_from_arrays.argtypes = [u32, vp, vp, u32, u32, vp, vp]
         L.ffo_counts.restype = None
@@ -44,13 +44,24 @@ def lib():
         L.ffo_free.restype = None
         L.ffo_free.argtypes = [vp]
         L.ffo_batch.restype = None
-        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, u32, vp, u32]
+        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32]
         _lib = L
     return _lib
 
 
 def _ptr(a):
     return a.ctypes.data_as(C.c_void_p)
+
+
+def _cost_args(cost):
+    """cost: [n_ops][n_cols] uint32 (exeTime by number of parts), or a triple
+    (tuple_ptr [n_ops+1], tuples, ns): exeTime keyed by the packed degree tuple.
+    Returns (keep-alive arrays, the five C arguments)."""
+    if isinstance(cost, (tuple, list)):
+        ptr, tup, ns = (np.ascontiguousarray(a, "<u4") for a in cost)
+        return (ptr, tup, ns), (None, 0, _ptr(ptr), _ptr(tup), _ptr(ns))
+    cost = np.ascontiguousarray(cost, "<u4")
+    return (cost,), (_ptr(cost), cost.shape[1], None, None, None)
 
 
 def _machine(m):
@@ -88,10 +99,10 @@ class TaskGraph:
 
 def build_task_graph(ops, edges, machine, cost, cfg):
     """Section 5.1 for one strategy (cfg: [n_ops] configs). None if the strategy is invalid."""
-    ops, edges, cost, cfg = map(np.ascontiguousarray, (ops, edges, cost, cfg))
+    ops, edges, cfg = map(np.ascontiguousarray, (ops, edges, cfg))
     m = _machine(machine)
-    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), _ptr(cost),
-                        cost.shape[1], _ptr(cfg))
+    keep, cargs = _cost_args(cost)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg))
     return TaskGraph(h) if h else None
 
 
@@ -105,11 +116,12 @@ def task_graph_from_arrays(exe, dev, n_rows, dep_src, dep_dst):
 
 def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1):
     """makespan (ns) of every strategy in cfgs [B][n_ops]; 2^64-1 for an invalid one."""
-    ops, edges, cost, cfgs = map(np.ascontiguousarray, (ops, edges, cost, cfgs))
+    ops, edges, cfgs = map(np.ascontiguousarray, (ops, edges, cfgs))
     assert cfgs.ndim == 2 and cfgs.shape[1] == len(ops)
     m = _machine(machine)
     out = np.zeros(cfgs.shape[0], "<u8")
-    lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), _ptr(cost), cost.shape[1],
+    keep, cargs = _cost_args(cost)
+    lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs,
                     _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads)
     return out
 

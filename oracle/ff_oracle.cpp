@@ -118,20 +118,38 @@ uint32_t link_row(const Machine& m, uint32_t from, uint32_t to) {
     return D + N * G * G + na * N + nb;
 }
 
+// Where the exeTime of a compute task comes from (Section 5.1 step 1): a table indexed by the
+// op's number of parts, or a list per op keyed by the whole degree tuple (how long a task runs
+// depends on which dims are split).
+struct CostModel {
+    const uint32_t* table; uint32_t n_cols;                           // [n_ops][n_cols], column parts-1
+    const uint32_t* tuple_ptr; const uint32_t* tuples; const uint32_t* tuple_ns;   // or: op i's entries tuple_ptr[i]..tuple_ptr[i+1]
+};
+
+// false: the model has no time for this configuration
+bool exe_time(const CostModel& cm, uint32_t i, const Cfg& c, uint32_t parts, uint64_t* out) {
+    if (cm.table) { *out = cm.table[(size_t)i * cm.n_cols + (parts - 1)]; return true; }
+    const uint32_t key = (uint32_t)c.deg[0] | ((uint32_t)c.deg[1] << 8) | ((uint32_t)c.deg[2] << 16) | ((uint32_t)c.deg[3] << 24);
+    for (uint32_t t = cm.tuple_ptr[i]; t < cm.tuple_ptr[i + 1]; t++)
+        if (cm.tuples[t] == key) { *out = cm.tuple_ns[t]; return true; }
+    return false;
+}
+
 bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, const Machine& m,
-           const uint32_t* cost, uint32_t n_cols, const Cfg* cfg, TaskGraph& tg) {
+           const CostModel& cm, const Cfg* cfg, TaskGraph& tg) {
     const uint32_t G = m.gpus_per_node, N = m.n_nodes, D = N * G;
-    const uint32_t max_parts = std::min(MAX_PARTS, n_cols);
+    const uint32_t max_parts = cm.table ? std::min(MAX_PARTS, cm.n_cols) : MAX_PARTS;
     tg.n_rows = D + N * G * G + N * N;
     std::vector<uint32_t> first(n_ops), np(n_ops);
     // step 1: compute tasks t_{i:1..|c_i|}
     for (uint32_t i = 0; i < n_ops; i++) {
         if (!cfg_valid(ops[i], cfg[i], D, max_parts)) return false;
         np[i] = parts_of(cfg[i]);
+        uint64_t exe = 0;
+        if (!exe_time(cm, i, cfg[i], np[i], &exe)) return false;
         first[i] = (uint32_t)tg.exe.size();
         for (uint32_t k = 0; k < np[i]; k++)
-            tg.add_task(cost[(size_t)i * n_cols + (np[i] - 1)],
-                        (uint32_t)((cfg[i].dev_offset + (uint64_t)k * cfg[i].dev_stride) % D));
+            tg.add_task(exe, (uint32_t)((cfg[i].dev_offset + (uint64_t)k * cfg[i].dev_stride) % D));
     }
     tg.n_compute = (uint32_t)tg.exe.size();
     // step 2: per tensor edge, per pair of tasks with a shared sub-tensor
@@ -193,10 +211,13 @@ extern "C" {
 
 // Build the task graph of one strategy.  Returns an opaque handle or null if the strategy
 // is invalid.
+// cost / n_cols: the table by number of parts; or cost = null and the three tuple arrays.
 void* ffo_build(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
-                const uint32_t* cost, uint32_t n_cols, const void* cfg) {
+                const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
+                const uint32_t* tuple_ns, const void* cfg) {
     TaskGraph* tg = new TaskGraph;
-    if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cost, n_cols,
+    const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
+    if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                (const Cfg*)cfg, *tg)) { delete tg; return nullptr; }
     return tg;
 }
@@ -237,13 +258,14 @@ void ffo_free(void* h) { delete (TaskGraph*)h; }
 // build + simulate for B strategies ([B][n_ops] configs); invalid strategy -> all-ones.
 // n_threads > 1 splits the candidates statically over threads (one independent oracle run each).
 void ffo_batch(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
-               const uint32_t* cost, uint32_t n_cols, const void* cfgs, uint32_t B, uint64_t* out_ns,
-               uint32_t n_threads) {
+               const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
+               const uint32_t* tuple_ns, const void* cfgs, uint32_t B, uint64_t* out_ns, uint32_t n_threads) {
+    const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
     auto work = [&](uint32_t b0, uint32_t b1) {
         for (uint32_t b = b0; b < b1; b++) {
             TaskGraph tg;
-            bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cost,
-                            n_cols, (const Cfg*)cfgs + (size_t)b * n_ops, tg);
+            bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
+                            (const Cfg*)cfgs + (size_t)b * n_ops, tg);
             out_ns[b] = ok ? simulate(tg, nullptr, nullptr, nullptr) : INVALID;
         }
     };

@@ -32,13 +32,17 @@ class ff_costtable_t(C.Structure):
     _fields_ = [("n_ops", C.c_uint32), ("n_cols", C.c_uint32), ("ns", C.c_void_p)]
 
 
-EXPORTS = ["ff_sim_create", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
+EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
            "ff_sim_neighbour_count", "ff_sim_neighbours",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8")])
 
+
+
+class ff_tuplecost_t(C.Structure):
+    _fields_ = [("n_ops", C.c_uint32), ("tuple_ptr", C.c_void_p), ("tuples", C.c_void_p), ("ns", C.c_void_p)]
 
 
 class ff_search_t(C.Structure):
@@ -68,6 +72,9 @@ def lib():
         L.ff_sim_create.restype = C.c_int
         L.ff_sim_create.argtypes = [C.POINTER(ff_opgraph_t), C.POINTER(ff_machine_t), C.POINTER(ff_costtable_t),
                                     C.POINTER(vp)]
+        L.ff_sim_create_tuplecost.restype = C.c_int
+        L.ff_sim_create_tuplecost.argtypes = [C.POINTER(ff_opgraph_t), C.POINTER(ff_machine_t), C.POINTER(ff_tuplecost_t),
+                                              C.POINTER(vp)]
         L.ff_sim_destroy.restype = None
         L.ff_sim_destroy.argtypes = [vp]
         L.ff_sim_workspace_bytes.restype = C.c_size_t
@@ -124,6 +131,20 @@ def ff_sim_create(ops, edges, machine, cost):
     ct = ff_costtable_t(cost.shape[0], cost.shape[1], cost.ctypes.data)
     h = C.c_void_p()
     _check(lib().ff_sim_create(C.byref(g), C.byref(m), C.byref(ct), C.byref(h)), "ff_sim_create")
+    return h.value
+
+
+def ff_sim_create_tuplecost(ops, edges, machine, tuple_ptr, tuples, ns):
+    """costs keyed by the degree tuple: op i's entries tuples[tuple_ptr[i]:tuple_ptr[i+1]] (packed,
+    ascending) with exeTimes ns[] at the same index."""
+    ops = np.ascontiguousarray(ops, W.OP_DT)
+    edges = np.ascontiguousarray(edges, W.EDGE_DT)
+    tuple_ptr, tuples, ns = (np.ascontiguousarray(a, "<u4") for a in (tuple_ptr, tuples, ns))
+    g = ff_opgraph_t(len(ops), len(edges), ops.ctypes.data, edges.ctypes.data)
+    m = ff_machine_t(*(machine.as_tuple() if hasattr(machine, "as_tuple") else tuple(machine)))
+    tc = ff_tuplecost_t(len(ops), tuple_ptr.ctypes.data, tuples.ctypes.data, ns.ctypes.data)
+    h = C.c_void_p()
+    _check(lib().ff_sim_create_tuplecost(C.byref(g), C.byref(m), C.byref(tc), C.byref(h)), "ff_sim_create_tuplecost")
     return h.value
 
 
@@ -218,9 +239,14 @@ class Simulator:
     """owns a handle, its workspace and result buffers (all torch-allocated)."""
 
     def __init__(self, ops, edges, machine, cost):
+        """cost: [n_ops][n_cols] table by number of parts, or a triple (tuple_ptr, tuples, ns)
+        keyed by the degree tuple."""
         _torch()
         self.n_ops = len(ops)
-        self.handle = ff_sim_create(ops, edges, machine, cost)
+        if isinstance(cost, (tuple, list)):
+            self.handle = ff_sim_create_tuplecost(ops, edges, machine, *cost)
+        else:
+            self.handle = ff_sim_create(ops, edges, machine, cost)
         self._ws = None
         self._stats = None
 

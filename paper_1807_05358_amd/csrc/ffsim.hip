@@ -111,11 +111,12 @@ const char* ff_sim_strerror(int code) {
     }
 }
 
-int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtable_t* ct, ff_sim_t** out) {
-    if (!out) return FF_EINVAL;
-    *out = nullptr;
-    if (!g || !m || !ct || !g->ops || (g->n_edges && !g->edges) || !ct->ns) return FF_EINVAL;
-    if (g->n_ops < 1 || ct->n_ops != g->n_ops || ct->n_cols < 1) return FF_EINVAL;
+}  // extern "C"
+
+// cost: the device image of the cost model.  n_cols >= 1: the table [n_ops][n_cols] indexed by the
+// number of parts.  n_cols == 0: costs keyed by the degree tuple, packed as ptr[n_ops+1], then the
+// tuples of all ops, then their exeTimes.
+static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector<uint32_t>& cost, uint32_t n_cols, ff_sim_t** out) {
     if (g->n_ops > FF_MAX_OPS) return FF_ERANGE;
     if (m->n_nodes < 1 || m->gpus_per_node < 1 || m->intra_Bpns < 1 || m->inter_Bpns < 1 || m->elem_bytes < 1) return FF_EINVAL;
     const uint64_t D = (uint64_t)m->n_nodes * m->gpus_per_node;
@@ -191,11 +192,6 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
         }
         for (uint32_t k = 0; k < g->n_edges; k++) in_edges[ops[edges[k].dst].in_end++] = edges[k];
     }
-    std::vector<uint32_t> cost((size_t)g->n_ops * ct->n_cols);
-    for (size_t k = 0; k < cost.size(); k++) {
-        if (ct->ns[k] < 1) return FF_EINVAL;   // every exeTime >= 1
-        cost[k] = ct->ns[k];
-    }
     std::vector<uint32_t> magic(65, 0);
     for (uint32_t d = 2; d <= 64; d++) magic[d] = magic_plus1(d);
 
@@ -206,8 +202,8 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
         (rc = upload(cost, &s->d_cost)) || (rc = upload(magic, &s->d_magic))) { release(s); return rc; }
 
     SimDev& S = s->dev;
-    S.n_ops = g->n_ops; S.n_edges = g->n_edges; S.n_cols = ct->n_cols;
-    S.max_parts = std::min<uint32_t>(FF_MAX_PARTS, ct->n_cols);
+    S.n_ops = g->n_ops; S.n_edges = g->n_edges; S.n_cols = n_cols;
+    S.max_parts = n_cols ? std::min<uint32_t>(FF_MAX_PARTS, n_cols) : FF_MAX_PARTS;
     S.n_nodes = m->n_nodes; S.gpus_per_node = m->gpus_per_node; S.n_dev = (uint32_t)D; S.n_rows = (uint32_t)n_rows;
     S.bw_intra = m->intra_Bpns; S.bw_inter = m->inter_Bpns; S.lat_intra = m->intra_lat_ns; S.lat_inter = m->inter_lat_ns;
     S.elem_bytes = m->elem_bytes;
@@ -247,6 +243,43 @@ int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtab
     s->max_try_slots = (uint32_t)cus * (uint32_t)per_cu;
     *out = s;
     return FF_OK;
+}
+
+extern "C" {
+
+int ff_sim_create(const ff_opgraph_t* g, const ff_machine_t* m, const ff_costtable_t* ct, ff_sim_t** out) {
+    if (!out) return FF_EINVAL;
+    *out = nullptr;
+    if (!g || !m || !ct || !g->ops || (g->n_edges && !g->edges) || !ct->ns) return FF_EINVAL;
+    if (g->n_ops < 1 || ct->n_ops != g->n_ops || ct->n_cols < 1) return FF_EINVAL;
+    std::vector<uint32_t> cost((size_t)g->n_ops * ct->n_cols);
+    for (size_t k = 0; k < cost.size(); k++) {
+        if (ct->ns[k] < 1) return FF_EINVAL;   // every exeTime >= 1
+        cost[k] = ct->ns[k];
+    }
+    return create_impl(g, m, cost, ct->n_cols, out);
+}
+
+int ff_sim_create_tuplecost(const ff_opgraph_t* g, const ff_machine_t* m, const ff_tuplecost_t* tc, ff_sim_t** out) {
+    if (!out) return FF_EINVAL;
+    *out = nullptr;
+    if (!g || !m || !tc || !g->ops || (g->n_edges && !g->edges) || !tc->tuple_ptr || !tc->tuples || !tc->ns) return FF_EINVAL;
+    if (g->n_ops < 1 || tc->n_ops != g->n_ops || tc->tuple_ptr[0] != 0) return FF_EINVAL;
+    const uint32_t E = tc->tuple_ptr[g->n_ops];
+    if (E < 1 || E > (1u << 30)) return FF_ERANGE;
+    for (uint32_t i = 0; i < g->n_ops; i++) {
+        if (tc->tuple_ptr[i] > tc->tuple_ptr[i + 1] || tc->tuple_ptr[i + 1] > E) return FF_EINVAL;
+        for (uint32_t t = tc->tuple_ptr[i]; t < tc->tuple_ptr[i + 1]; t++) {
+            if (tc->ns[t] < 1) return FF_EINVAL;                                              // every exeTime >= 1
+            if (t > tc->tuple_ptr[i] && tc->tuples[t - 1] >= tc->tuples[t]) return FF_EINVAL;   // ascending, no duplicates
+        }
+    }
+    std::vector<uint32_t> cost;
+    cost.reserve((size_t)g->n_ops + 1 + 2 * (size_t)E);
+    cost.insert(cost.end(), tc->tuple_ptr, tc->tuple_ptr + g->n_ops + 1);
+    cost.insert(cost.end(), tc->tuples, tc->tuples + E);
+    cost.insert(cost.end(), tc->ns, tc->ns + E);
+    return create_impl(g, m, cost, 0, out);
 }
 
 void ff_sim_destroy(ff_sim_t* s) { release(s); }

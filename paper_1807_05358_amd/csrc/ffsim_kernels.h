@@ -357,8 +357,24 @@ __device__ __forceinline__ StrategyClass validate_strategy(const SimX& m) {
     bool bad = false, irregular = false;
     for (uint32_t i = lane_id(); i < m.S.n_ops; i += WAVE) {
         OpCfg c = unpack_cfg_lane(m.cfg_raw(i));
-        if (!cfg_ok(m.T.ops[i], c, m.S)) bad = true;
-        else m.exe_of[i] = m.T.cost[(size_t)i * m.S.n_cols + (c.parts - 1)];
+        if (!cfg_ok(m.T.ops[i], c, m.S)) {
+            bad = true;
+        } else if (m.S.n_cols) {
+            m.exe_of[i] = m.T.cost[(size_t)i * m.S.n_cols + (c.parts - 1)];
+        } else {
+            // costs keyed by the whole degree tuple: ptr[n_ops+1], tuples (ascending per op), times;
+            // a tuple that is not listed has no cost: invalid
+            const uint32_t* ptr = m.T.cost;
+            const uint32_t* tuples = ptr + m.S.n_ops + 1;
+            const uint32_t* ns = tuples + ptr[m.S.n_ops];
+            uint32_t lo = ptr[i], hi = ptr[i + 1];
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) / 2;
+                if (tuples[mid] < c.x) lo = mid + 1; else hi = mid;
+            }
+            if (lo < ptr[i + 1] && tuples[lo] == c.x) m.exe_of[i] = ns[lo];
+            else bad = true;
+        }
         irregular = irregular || c.stride != 1 || c.parts > m.S.n_dev;
     }
     if (ballot(bad)) return STRATEGY_INVALID;

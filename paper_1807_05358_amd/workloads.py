@@ -503,6 +503,30 @@ def search_space(ops, max_parts, choices):
     return ptr, np.concatenate(chunks).astype(np.uint32)
 
 
+def tuple_cost_table(ops, cost, max_parts, choices, seed):
+    """costs keyed by the whole degree tuple, derived from a table by number of parts: the
+    entry for `parts` plus, per split dim other than the sample dim, a seeded surcharge of
+    0-25 % (splitting channels or pixels makes tasks less efficient than splitting samples).
+    Returns (tuple_ptr, tuples ascending per op, ns)."""
+    ptr = np.zeros(len(ops) + 1, np.uint32)
+    tup_all, ns_all = [], []
+    for i, o in enumerate(ops):
+        t = valid_degree_tuples(o, max_parts, choices).astype(np.uint64)
+        packed = (t[:, 0] | (t[:, 1] << np.uint64(8)) | (t[:, 2] << np.uint64(16)) | (t[:, 3] << np.uint64(24)))
+        parts = t[:, 0] * t[:, 1] * t[:, 2] * t[:, 3]
+        base = cost[i, parts.astype(np.int64) - 1].astype(np.uint64)
+        extra = np.zeros(len(t), np.uint64)
+        for d in (1, 2, 3):
+            pct = _draw(seed, 7, i, d) % np.uint64(26)
+            extra += np.where(t[:, d] > 1, base * pct // np.uint64(100), np.uint64(0))
+        ns = np.minimum(base + extra, np.uint64(2 ** 32 - 1))
+        order = np.argsort(packed, kind="stable")
+        tup_all.append(packed[order].astype(np.uint32))
+        ns_all.append(ns[order].astype(np.uint32))
+        ptr[i + 1] = ptr[i] + len(t)
+    return ptr, np.concatenate(tup_all), np.concatenate(ns_all)
+
+
 def data_parallel_strategy(ops, n_dev, max_parts=MAX_PARTS):
     """every op split in the sample dim only, as far as the device count allows."""
     cfg = np.zeros(len(ops), CFG_DT)
@@ -548,6 +572,10 @@ class Workload:
     def mutations(self, n_steps, n_chains=1):
         return mutation_chains(self.ops, n_steps, n_chains, self.seed, self.machine.n_devices,
                                self.max_parts, self.choices)
+
+    def tuple_costs(self):
+        """the same costs keyed by degree tuple (see tuple_cost_table)"""
+        return tuple_cost_table(self.ops, self.cost, self.max_parts, self.choices, self.seed)
 
     def search_space(self):
         return search_space(self.ops, self.max_parts, self.choices)

@@ -551,3 +551,55 @@ def test_random_graphs_with_regular_strategies(B, seed, n_nodes, gpn):
         assert np.array_equal(d[:, c], ref), f"chain {c}: steps {np.nonzero(d[:, c] != ref)[0][:5]}"
     ch.close()
     sim.close()
+
+
+@pytest.mark.parametrize("config_id,n", [(0, 64), (1, 256), (2, 48)])
+def test_costs_keyed_by_degree_tuple(B, config_id, n):
+    """the second cost model (ff_sim_create_tuplecost): batch, invalid because a tuple is not
+    listed, delta chain, trial proposals and search, all against the oracle with the same lists"""
+    from oracle import search as S
+    w = W.workload(config_id)
+    tc = w.tuple_costs()
+    sim = B.Simulator(w.ops, w.edges, w.machine, tc)
+    cfgs = w.strategies(n).copy()
+    cfgs[3, 0]["deg"] = (3, 1, 1, 1)       # a valid configuration of op 0 (extent >= 3) that the list does not hold
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, tc, cfgs, n_threads=8)
+    assert want[3] == oracle.INVALID and (want != oracle.INVALID).sum() == n - 1
+    got = sim.simulate(cfgs)
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+    assert (got != oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=8)).any()   # the surcharges matter
+    C = 2
+    muts = w.mutations(12, C)
+    ch = B.Chains(sim, cfgs[:C])
+    d = ch.delta(ch.upload_mutations(muts), 12).cpu().numpy().view("<u8")
+    cur = cfgs[:C].copy()
+    for c in range(C):
+        assert np.array_equal(d[:, c], oracle.simulate_delta_chain(w.ops, w.edges, w.machine, tc, cfgs[c], muts[:, c]))
+        for s in range(12):
+            cur[c, int(muts[s, c]["op"])] = muts[s, c]["cfg"]
+    tp, tu = w.search_space()
+    t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, tc, cur[:1])[0])
+    table = S.metropolis_table(30.0 / t0, max(1, t0 // 256), 64)
+    ch.search_setup(tp, tu, table, max(1, t0 // 256), 5)
+    tr = ch.search(20).cpu().numpy().view("<u8")
+    for c in range(C):
+        ref = S.metropolis_chain(w.ops, w.edges, w.machine, tc, cur[c], tp, tu, table, max(1, t0 // 256), 5, c, 0, 20)[0]
+        assert np.array_equal(tr[:, c], ref)
+    ch.close()
+    sim.close()
+
+
+def test_tuple_cost_argument_errors(B):
+    w = W.workload(0)
+    ptr, tup, ns = w.tuple_costs()
+    with pytest.raises(B.FFSimError):                 # not ascending
+        B.ff_sim_create_tuplecost(w.ops, w.edges, w.machine, ptr, tup[::-1].copy(), ns)
+    z = ns.copy(); z[1] = 0
+    with pytest.raises(B.FFSimError):                 # a zero exeTime
+        B.ff_sim_create_tuplecost(w.ops, w.edges, w.machine, ptr, tup, z)
+    p2 = ptr.copy(); p2[0] = 1
+    with pytest.raises(B.FFSimError):
+        B.ff_sim_create_tuplecost(w.ops, w.edges, w.machine, p2, tup, ns)
+    h = B.ff_sim_create_tuplecost(w.ops, w.edges, w.machine, ptr, tup, ns)
+    B.ff_sim_destroy(h)
