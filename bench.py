@@ -57,6 +57,93 @@ def time_batches(sim, d_strat, B, steps, warmup):
     return sum(kern_ms) / len(kern_ms), wall_ms, out
 
 
+def copy_bandwidth_gbps():
+    """what a plain device-to-device copy of 256 MiB reaches on this machine (read + write bytes per
+    second): the achievable figure to hold beside the published HBM peak."""
+    import torch
+    n = 256 * 2 ** 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    return 5 * 2 * n / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def oracle_build_share(w, cfgs):
+    """seconds the oracle spends building task graphs vs. building + simulating, one thread."""
+    import oracle
+    t0 = time.perf_counter()
+    for c in cfgs:
+        oracle.lib().ffo_free(oracle.lib().ffo_build(len(w.ops), oracle._ptr(w.ops), len(w.edges), oracle._ptr(w.edges),
+                                                     oracle._ptr(oracle._machine(w.machine)), oracle._ptr(w.cost),
+                                                     w.cost.shape[1], None, None, None, oracle._ptr(np_c(c))))
+    t_build = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=1)
+    t_both = time.perf_counter() - t0
+    return t_build, t_both
+
+
+def np_c(a):
+    import numpy as np
+    return np.ascontiguousarray(a)
+
+
+def timeline_items(w, cfg):
+    """the oracle's timeline of one strategy as {task key: (ready, start, end)}; a compute task's
+    key is (op, part), a transfer's is (key of its producer task, key of its consumer task)."""
+    import numpy as np
+    import oracle
+    tg = oracle.build_task_graph(w.ops, w.edges, w.machine, w.cost, cfg)
+    _, r, s_, e = tg.simulate()
+    parts = cfg["deg"].astype(np.int64).prod(axis=1)
+    op_of = np.repeat(np.arange(len(parts)), parts)
+    part_of = np.concatenate([np.arange(p) for p in parts])
+    ckey = op_of * 64 + part_of                                   # compute tasks, in id order
+    pred = np.full(tg.n_tasks, -1, np.int64)
+    succ = np.full(tg.n_tasks, -1, np.int64)
+    comm_dst = tg.dep_dst >= tg.n_compute
+    pred[tg.dep_dst[comm_dst]] = tg.dep_src[comm_dst]
+    comm_src = tg.dep_src >= tg.n_compute
+    succ[tg.dep_src[comm_src]] = tg.dep_dst[comm_src]
+    keys = np.empty(tg.n_tasks, np.int64)
+    keys[:tg.n_compute] = ckey
+    c = np.arange(tg.n_compute, tg.n_tasks)
+    keys[c] = (1 << 40) + ckey[pred[c]] * (1 << 19) + ckey[succ[c]]
+    return keys, np.stack([r, s_, e], axis=1)
+
+
+def changed_items(w, cfg_a, cfg_b):
+    """Section 5.3's work: tasks removed + tasks inserted + tasks whose ready/start/end differ
+    between the timelines of two strategies (counted by the oracle, nothing from the GPU)."""
+    import numpy as np
+    ka, ta = timeline_items(w, cfg_a)
+    kb, tb = timeline_items(w, cfg_b)
+    oa, ob = np.argsort(ka), np.argsort(kb)
+    ka, ta, kb, tb = ka[oa], ta[oa], kb[ob], tb[ob]
+    common, ia, ib = np.intersect1d(ka, kb, assume_unique=True, return_indices=True)
+    moved = int((ta[ia] != tb[ib]).any(axis=1).sum())
+    return {"removed": int(len(ka) - len(common)), "inserted": int(len(kb) - len(common)), "moved": moved,
+            "tasks_after": int(len(kb))}
+
+
 def oracle_rate(w, cfgs, threads):
     import oracle
     t0 = time.perf_counter()
@@ -121,6 +208,9 @@ def main():
             "achieved_GBps": ab * B / (kern_ms * 1e-3) / 1e9,
             "hbm_roofline_frac": ab * B / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
             "hbm_traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get(c),
+            "hbm_traffic_GBps": (MEASURED_TRAFFIC_BYTES[c] / (kern_ms * 1e-3) / 1e9 if c in MEASURED_TRAFFIC_BYTES else None),
+            "irreducible_io_bytes_per_strategy": 8 * w.n_ops + 8,
+            "wavefronts_per_simd": min(B, 1024 * 8) / 1024.0,
             "valu_issue_frac": (MEASURED_VALU_PER_STRATEGY[c] * B / (kern_ms * 1e-3) / 1e9 / VALU_PEAK_G_PER_S
                                 if c in MEASURED_VALU_PER_STRATEGY else None),
             "input_sha256": w.sha256(B),
@@ -144,6 +234,7 @@ def main():
         results[c] = (r, sim, w, cfgs)
 
     head, sim, w, cfgs = results[HEADLINE]
+    copy_gbps = copy_bandwidth_gbps()
     line = {
         "metric": "simulated strategies/sec (build + full simulation)",
         "value": head["strategies_per_s"],
@@ -159,7 +250,10 @@ def main():
                      "frac": head["hbm_roofline_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE),
                      "kernel": "k_sim_batch<WIDE=false, LDSW=true, STATS=false, TREE=false>",
                      "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
-                     "kernel_ms": head["kernel_ms"]},
+                     "kernel_ms": head["kernel_ms"],
+                     "achievable_copy_GBps": copy_gbps, "frac_of_copy": head["achieved_GBps"] / copy_gbps,
+                     "traffic_GBps": head["hbm_traffic_GBps"],
+                     "irreducible_io_bytes_per_launch": head["irreducible_io_bytes_per_strategy"] * head["B"]},
         # the same launch against the vector-issue peak (64-lane integer instructions per second)
         "roofline_alu": {"bound": "alu", "achieved": MEASURED_VALU_PER_STRATEGY[HEADLINE] * head["B"] / (head["kernel_ms"] * 1e-3) / 1e9,
                          "peak": VALU_PEAK_G_PER_S, "unit": "G wavefront-instructions/s", "frac": head["valu_issue_frac"],
@@ -177,7 +271,10 @@ def main():
         line["cpu_baseline"] = {"value": multi, "unit": "strategies/s", "cores": threads, "kind": "oracle",
                                 "sample": f"all {len(cfgs)} candidates of configs[1], {reps} repetitions, "
                                           f"{threads} threads (static split); single thread: {one:.1f} strategies/s",
-                                "single_thread_value": one}
+                                "single_thread_value": one, "cpu_model": cpu_model()}
+        tb, tt = oracle_build_share(w, cfgs[:256])
+        line["cpu_baseline"]["one_thread_build_seconds_per_strategy"] = tb / 256
+        line["cpu_baseline"]["one_thread_build_plus_simulate_seconds_per_strategy"] = tt / 256
     if not args.only_headline and not args.no_delta and 4 in results:
         # delta simulation on configs[4]: one chain, and 256 independent chains
         r4, sim4, w4, cfgs4 = results[4]
@@ -204,6 +301,20 @@ def main():
                 sel = [0, n_steps // 2, n_steps - 1]
                 ref = oracle.simulate_delta_chain(w4.ops, w4.edges, w4.machine, w4.cost, cfgs4[0], muts[:, 0], steps=sel)
                 d["bit_exact_on_sampled_steps"] = bool(np.array_equal(out.cpu().numpy().view("<u8")[sel, 0], ref))
+                # what Algorithm 2 would have to touch, counted by diffing the oracle's timelines of
+                # consecutive strategies (two sampled steps): removed + inserted + moved tasks
+                cur = cfgs4[0].copy()
+                work = []
+                for s_ in range(n_steps):
+                    nxt = cur.copy()
+                    nxt[int(muts[s_, 0]["op"])] = muts[s_, 0]["cfg"]
+                    if s_ in (1, n_steps // 2):
+                        work.append(changed_items(w4, cur, nxt))
+                    cur = nxt
+                d["oracle_changed_tasks_on_sampled_steps"] = work
+                items = float(np.mean([x["removed"] + x["inserted"] + x["moved"] for x in work]))
+                d["algorithmic_bytes_per_step"] = items * 34.0   # 20 B per task written + read, 14 B per record, as in the byte model
+                d["algorithmic_GBps"] = items * 34.0 * n_steps / (ms * 1e-3) / 1e9
             delta.append(d)
             if C == 1:
                 # proposals evaluated side by side against the chain's stored timeline (not committed)
