@@ -260,10 +260,12 @@ int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_ste
 
 /* Telemetry of the chains (HOST array of C records; synchronises the device): how many
  * mutations were applied, how many of them resumed from a stored snapshot of the timeline
- * instead of simulating from time 0, how many queue pops they took in total, and how many
- * pops the last simulation from time 0 took. */
+ * instead of simulating from time 0, how many queue pops they took in total, how many
+ * pops the last simulation from time 0 took, and how many committed steps stopped early
+ * because their timeline had re-joined the previous one (Section 5.3: most of the timeline
+ * does not change). */
 typedef struct {
-    uint64_t n_steps, n_resumed, n_events, n_events_full;
+    uint64_t n_steps, n_resumed, n_events, n_events_full, n_converged;
 } ff_chain_stats_t;
 int ff_sim_chains_get_stats(ff_chains_t* chains, ff_chain_stats_t* h_out);
 

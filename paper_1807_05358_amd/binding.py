@@ -37,7 +37,8 @@ EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
            "ff_sim_neighbour_count", "ff_sim_neighbours",
            "ff_sim_strerror"]
-CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8")])
+CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8"),
+                           ("n_converged", "<u8")])
 
 
 

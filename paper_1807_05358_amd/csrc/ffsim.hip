@@ -475,6 +475,7 @@ int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
         h_out[k].n_resumed = meta.n_resumed;
         h_out[k].n_events = meta.n_events;
         h_out[k].n_events_full = meta.n_events_full;
+        h_out[k].n_converged = meta.n_converged;
     }
     return FF_OK;
 }

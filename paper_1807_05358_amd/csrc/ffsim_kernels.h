@@ -310,8 +310,15 @@ struct Recorder {
     uint32_t loc;            // see above
     uint32_t n_snaps;        // capacity (snapshot 0 is the initial state and is never stored)
     uint32_t next;           // next snapshot index to write
+    // Re-convergence: a run that resumed after a change of op check_op compares every state it
+    // snapshots (index < check_below) with the accepted timeline's snapshot of the same index.
+    // Once they agree (and check_op has no task left), the rest of the two timelines is the same
+    // and the run stops.  check_below = 0: no comparison.
+    uint32_t check_below;
+    uint32_t check_op;
 };
 constexpr uint32_t MAX_SNAPSHOTS = 32;   // bits of loc
+constexpr u64 RUN_CONVERGED = 1;         // run_events: stopped because the timeline re-joined the accepted one
 
 // how many parts of the producer (configuration cp) a consumer part reads through edge e:
 // the product over the producer's dims of the number of producer parts its range touches
@@ -432,16 +439,65 @@ __device__ __forceinline__ void copy_words(u64* __restrict__ dst, const u64* __r
     for (; t < n4; t += WAVE) d4[t] = s4[t];
 }
 
+// the same copy, and: does src differ from old anywhere?  (per lane; combine with a ballot)
+__device__ __forceinline__ bool copy_words_compare(u64* __restrict__ dst, const u64* __restrict__ src, const u64* __restrict__ old,
+                                                   uint32_t n) {
+    const uint4* __restrict__ s4 = (const uint4*)src;
+    const uint4* __restrict__ o4 = (const uint4*)old;
+    uint4* __restrict__ d4 = (uint4*)dst;
+    const uint32_t n4 = n / 2;
+    uint32_t diff = 0;
+    uint32_t t = lane_id();
+    for (; t + 3 * WAVE < n4; t += 4 * WAVE) {
+        uint4 v[4], o[4];
+#pragma unroll
+        for (int u = 0; u < 4; u++) { v[u] = s4[t + u * WAVE]; o[u] = o4[t + u * WAVE]; }
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            d4[t + u * WAVE] = v[u];
+            diff |= (v[u].x ^ o[u].x) | (v[u].y ^ o[u].y) | (v[u].z ^ o[u].z) | (v[u].w ^ o[u].w);
+        }
+    }
+    for (; t < n4; t += WAVE) {
+        const uint4 v = s4[t], o = o4[t];
+        d4[t] = v;
+        diff |= (v.x ^ o.x) | (v.y ^ o.y) | (v.z ^ o.z) | (v.w ^ o.w);
+    }
+    return diff != 0;
+}
+
+// Writes the next snapshot.  Returns true if the comparison is on and the state equals the
+// accepted timeline's snapshot of the same index for everything that can still matter: all task
+// words, and the free time of every device row, where rows that are idle at the snapshot's
+// time count as equal (any later task is ready at or after that time).
 template <class SimX>
-__device__ __forceinline__ void save_snapshot(const SimX& m, Recorder& rec) {
+__device__ __forceinline__ bool save_snapshot(const SimX& m, Recorder& rec) {
     const int lane = lane_id();
-    const size_t k = (size_t)((((rec.loc >> rec.next) & 1u) ^ 1u) * rec.n_snaps + rec.next);   // the place the accepted timeline does not use
-    copy_words(rec.snap_words + k * (size_t)m.S.n_ops * WAVE, m.words, m.S.n_ops * WAVE);
+    const uint32_t idx = rec.next;
+    const size_t k = (size_t)((((rec.loc >> idx) & 1u) ^ 1u) * rec.n_snaps + idx);   // the place the accepted timeline does not use
+    const bool check = idx < rec.check_below;
+    bool differs = false;
+    const size_t nw = (size_t)m.S.n_ops * WAVE;
+    if (check) {
+        const size_t old = (size_t)(((rec.loc >> idx) & 1u) * rec.n_snaps + idx);
+        differs = copy_words_compare(rec.snap_words + k * nw, m.words, rec.snap_words + old * nw, m.S.n_ops * WAVE);
+        const u64 t_snap = ((u64)idx * rec.step) >> 1;
+        const u64* ofr = rec.snap_free + old * (size_t)m.S.n_rows;
+        for (uint32_t t = lane; t < m.S.n_rows; t += WAVE) {
+            const u64 a = m.L.free_at[t], b = ofr[t];
+            differs = differs || (a > t_snap ? a : t_snap) != (b > t_snap ? b : t_snap);
+        }
+        // a task of the changed op still pending would make equal words mean different things
+        differs = differs || m.words[(size_t)rec.check_op * WAVE + lane] != W_NONE;
+    } else {
+        copy_words(rec.snap_words + k * nw, m.words, m.S.n_ops * WAVE);
+    }
     u64* l1 = rec.snap_l1 + k * (size_t)m.S.n_ops_pad;
     for (uint32_t t = lane; t < m.S.n_ops_pad; t += WAVE) l1[t] = m.L.l1[t];
     u64* fr = rec.snap_free + k * (size_t)m.S.n_rows;
     for (uint32_t t = lane; t < m.S.n_rows; t += WAVE) fr[t] = m.L.free_at[t];
     rec.next++;
+    return check && !ballot(differs);
 }
 
 // snapshot k of the accepted timeline
@@ -517,7 +573,9 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         }
         if (RECORD) {
             // the state before the first event at or after a multiple of `step` is a snapshot
-            while (rec.next < rec.n_snaps && kmin >= (u64)rec.next * rec.step) save_snapshot(m, rec);
+            while (rec.next < rec.n_snaps && kmin >= (u64)rec.next * rec.step) {
+                if (save_snapshot(m, rec)) { m.last_key = last_key; return RUN_CONVERGED; }
+            }
         }
         last_key = kmin;
         PROF_MARK(1)
@@ -806,6 +864,7 @@ struct ChainMeta {
     u64 n_events_full;  // queue pops of the last simulation from time 0 (one full simulation)
     u64 cur_ns;         // simulated time of the chain's current strategy (result code if it has none)
     u64 idle_steps;     // search steps since the chain's best time last improved
+    u64 n_converged;    // committed steps whose run stopped early because it re-joined the accepted timeline
     uint32_t loc;       // bit k: which of its two places holds snapshot k of the accepted timeline
     uint32_t tag;       // tag of the last recorded run (1..0xffff; 0 marks entries never written)
 };
@@ -953,10 +1012,13 @@ struct SearchDev {
 
 // Makes a recorded run the chain's accepted timeline: the snapshots it wrote (first..next-1)
 // take the place of the old ones, the endTimes it wrote are copied over the old ones.
-__device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, const Recorder& rec, uint32_t first, uint32_t n_words) {
+// converged: the run stopped where it re-joined the accepted timeline, whose later snapshots and
+// endTimes stay.
+__device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, const Recorder& rec, uint32_t first, uint32_t n_words,
+                                           bool converged) {
     const uint32_t written = rec.next > first ? (uint32_t)(((1ull << rec.next) - 1) & ~((1ull << first) - 1)) : 0u;
     meta.loc ^= written;
-    meta.n_valid = rec.next;
+    if (!converged) meta.n_valid = rec.next;
     const u64 tag = rec.tag;
     for (uint32_t t = lane_id(); t < n_words; t += WAVE) {
         const u64 v = cm.end_try[t];
@@ -1010,9 +1072,10 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.n_events_full = first_u64(meta.n_events_full);
     meta.cur_ns = first_u64(meta.cur_ns);
     meta.idle_steps = first_u64(meta.idle_steps);
+    meta.n_converged = first_u64(meta.n_converged);
     meta.loc = first_u32(meta.loc);
     meta.tag = first_u32(meta.tag);
-    Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1};
+    Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
     Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
@@ -1076,6 +1139,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
             // phase 2: the recorded simulation
             int phase = (k == 0 && meta.step == 0) ? 1 : 2;
             u64 rc = 0;
+            bool converged = false;
             while (phase < 3) {
                 const bool record = phase == 2;
                 const u64 before = cnt.n_events;
@@ -1095,6 +1159,9 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                 rec.n_snaps = record ? capacity : 0;
                 rec.end_try = record ? cm.end_try : nullptr;
                 rec.next = k + 1;
+                // a resumed run of a changed strategy may re-join the accepted timeline
+                rec.check_below = (record && k > 0 && changed) ? meta.n_valid : 0u;
+                rec.check_op = op;
                 if (k == 0) {
                     init_state(m, cnt);
                 } else {
@@ -1106,6 +1173,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                 }
                 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE>(m, cnt, rec)
                                              : run_events<WIDE, true, false, false, TREE>(m, cnt, rec);
+                if (rc == RUN_CONVERGED) { converged = true; rc = 0; mk = meta.cur_ns; break; }
                 mk = rc ? rc : makespan(m);
                 if (rc) break;
                 if (phase == 1) { meta.step = (2 * mk) / capacity + 1; phase = 2; continue; }
@@ -1134,7 +1202,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                         patch_state_for_op(m, cm.snap_words + at * n_words, cm.snap_l1 + at * S.n_ops_pad, op, ocfg, pend_new);
                     }
                 }
-                commit_run(cm, meta, rec, k + 1, n_words);
+                commit_run(cm, meta, rec, k + 1, n_words, converged);
+                if (converged) meta.n_converged++;
                 meta.stale = 0;
                 meta.cur_ns = mk;
                 // the spacing was fixed by an earlier makespan; if the timeline has become more than
@@ -1219,7 +1288,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
-                Recorder rec{nullptr, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, first_u32(meta.loc), n_snaps, 1};
+                Recorder rec{nullptr, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, first_u32(meta.loc), n_snaps, 1, 0, 0};
                 uint32_t k = 0, pend_new = 0;
                 if (!meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
                 if (k == 0) {

@@ -188,6 +188,11 @@ def test_delta_chain_matches_resimulation(B, config_id, C, steps):
         want = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], muts[:, c])
         bad = np.nonzero(got[:, c] != want)[0]
         assert len(bad) == 0, f"chain {c}: first differing step {bad[0]} (op {int(muts[bad[0], c]['op'])}): gpu {got[bad[0], c]} oracle {want[bad[0]]}"
+    st = ch.stats()
+    print(f"resumed {int(st['n_resumed'].sum())} of {int(st['n_steps'].sum())} steps, {int(st['n_converged'].sum())} re-joined the previous timeline", flush=True)
+    if config_id == 2:
+        # this case is known to contain steps whose timeline re-joins the previous one: the early stop is exercised
+        assert st["n_converged"].sum() > 0
     ch.close()
 
 
