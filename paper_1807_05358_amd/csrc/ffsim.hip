@@ -39,6 +39,12 @@ struct ff_sim {
     bool wide = false;            // some tensor has 2^32 bytes or more
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
+    // the batch kernel may keep the per-edge set-up of a candidate (all extents must fit 16 bits):
+    // behind the task words, in the HBM slot, or in LDS for graphs whose words live there
+    bool cache_ok = false;
+    size_t batch_slot_bytes = 0;  // slot_bytes, plus the kept set-up where it lives in HBM
+    size_t lds_cached = 0;        // dynamic LDS of the caching variant (= lds if the set-up lives in HBM)
+    uint32_t max_slots_cached = 0;
     size_t lds = 0;               // dynamic LDS per wavefront, batch kernel
     size_t lds_common = 0;        // device rows + queue levels 1 and 2
     size_t lds_chain = 0;         // dynamic LDS per wavefront, chain kernel (adds the strategy; words in HBM)
@@ -67,17 +73,20 @@ typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, c
 typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
                                uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
 
-// three layouts: task words in LDS (small graphs; never a level 2), in HBM without, and with level 2
-template <bool WIDE, bool STATS>
+// three layouts: task words in LDS (small graphs; never a level 2), in HBM without, and with level 2;
+// each with or without the kept per-edge set-up
+template <bool WIDE, bool STATS, bool CACHE>
 static batch_kernel_t batch_kernel_of(const ff_sim* s) {
-    if (s->lds_words) return k_sim_batch<WIDE, true, STATS, false>;
-    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, true> : k_sim_batch<WIDE, false, STATS, false>;
+    if (s->lds_words) return k_sim_batch<WIDE, true, STATS, false, CACHE>;
+    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, true, CACHE> : k_sim_batch<WIDE, false, STATS, false, CACHE>;
 }
 // the variant that also fills the per-candidate counters is only launched when they are asked for
-static batch_kernel_t batch_kernel(const ff_sim* s) {
-    if (s->wide) return s->d_stats ? batch_kernel_of<true, true>(s) : batch_kernel_of<true, false>(s);
-    return s->d_stats ? batch_kernel_of<false, true>(s) : batch_kernel_of<false, false>(s);
+template <bool CACHE>
+static batch_kernel_t batch_kernel_c(const ff_sim* s) {
+    if (s->wide) return s->d_stats ? batch_kernel_of<true, true, CACHE>(s) : batch_kernel_of<true, false, CACHE>(s);
+    return s->d_stats ? batch_kernel_of<false, true, CACHE>(s) : batch_kernel_of<false, false, CACHE>(s);
 }
+static batch_kernel_t batch_kernel(const ff_sim* s, bool cached) { return cached ? batch_kernel_c<true>(s) : batch_kernel_c<false>(s); }
 static chain_kernel_t chain_kernel(const ff_sim* s) {
     const bool tree = s->dev.n_groups > FLAT_GROUPS;
     if (s->wide) return tree ? k_sim_chain_steps<true, true> : k_sim_chain_steps<true, false>;
@@ -125,6 +134,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
 
     std::vector<DOp> ops(g->n_ops);
     unsigned __int128 max_bytes = 0;
+    uint32_t max_extent = 1;
     for (uint32_t i = 0; i < g->n_ops; i++) {
         const ff_op_t& o = g->ops[i];
         if (o.ndim < 1 || o.ndim > FF_MAX_DIMS) return FF_EINVAL;
@@ -134,6 +144,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
             if (e < 1) return FF_EINVAL;
             if (e > FF_MAX_EXTENT) return FF_ERANGE;
             ops[i].extent[d] = e;
+            max_extent = std::max(max_extent, e);
             elems *= e;
         }
         max_bytes = std::max(max_bytes, elems * m->elem_bytes);
@@ -156,7 +167,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         de.src = e.src_op;
         de.dst = e.dst_op;
         de.src_ndim = ops[e.src_op].ndim;
-        de.dst_ndim = ops[e.dst_op].ndim;
+        de.eid = k;
         for (int d = 0; d < 4; d++) {
             de.src_extent[d] = ops[e.src_op].extent[d];
             de.dst_extent[d] = ops[e.dst_op].extent[d];
@@ -230,13 +241,30 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_common;
     s->lds_words = lds_with_words <= 40 * 1024;
     s->lds = s->lds_words ? lds_with_words : s->lds_common;
+    s->cache_ok = max_extent <= ECACHE_MAX_EXTENT && g->n_edges > 0;
+    s->batch_slot_bytes = s->slot_bytes;
+    s->lds_cached = s->lds;
+    if (s->cache_ok) {
+        if (s->lds_words) {
+            s->lds_cached = lds_with_words + ecache_bytes(S.n_edges);
+            if (s->lds_cached > 40 * 1024) s->cache_ok = false;
+        } else {
+            s->batch_slot_bytes = (((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + ecache_bytes(S.n_edges) + 255) & ~(size_t)255;
+        }
+    }
 
     int dev_id = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev_id) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev_id) != hipSuccess) { release(s); return FF_EHIP; }
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, batch_kernel(s), WAVE, s->lds);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, batch_kernel(s, false), WAVE, s->lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_slots = (uint32_t)cus * (uint32_t)per_cu;
+    per_cu = 0;
+    if (s->cache_ok) {
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, batch_kernel(s, true), WAVE, s->lds_cached);
+        if (e != hipSuccess || per_cu < 1) per_cu = 1;
+        s->max_slots_cached = (uint32_t)cus * (uint32_t)per_cu;
+    }
     per_cu = 0;
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, try_kernel(s), WAVE, s->lds_common);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
@@ -287,7 +315,7 @@ void ff_sim_destroy(ff_sim_t* s) { release(s); }
 size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {
     if (!s) return 0;
     if (s->lds_words) return 0;   // the whole per-candidate state lives in LDS
-    return (size_t)std::max<uint32_t>(1, std::min(B, s->max_slots)) * s->slot_bytes;
+    return (size_t)std::max<uint32_t>(1, std::min(B, s->max_slots)) * s->batch_slot_bytes;
 }
 
 int ff_sim_set_workspace(ff_sim_t* s, void* d_ws, size_t bytes) {
@@ -306,13 +334,16 @@ int ff_sim_set_stats(ff_sim_t* s, ff_stats_t* d_stats) {
 int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns, void* hip_stream) {
     if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
     if (B == 0) return FF_OK;
-    const uint32_t slots = std::min(B, s->max_slots);
-    if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes)) return FF_EWORKSPACE;
+    // Keeping the per-edge set-up costs LDS for graphs whose words live there; it is used unless it
+    // would leave part of the batch waiting for a free compute unit that the plain variant has room for.
+    const bool cached = s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
+    const uint32_t slots = std::min(B, cached ? s->max_slots_cached : s->max_slots);
+    if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     static_assert(sizeof(Counters) == sizeof(ff_stats_t), "stats layout");
-    hipLaunchKernelGGL(batch_kernel(s), dim3(slots), dim3(WAVE), s->lds, st, s->dev, s->d_ops, s->d_edges, s->d_in_edges,
-                       s->d_cost, s->d_magic, (const uint2*)d_strategies, B, (u64*)d_out_ns, (Counters*)s->d_stats,
-                       (unsigned char*)s->ws, s->slot_bytes);
+    hipLaunchKernelGGL(batch_kernel(s, cached), dim3(slots), dim3(WAVE), cached ? s->lds_cached : s->lds, st, s->dev, s->d_ops,
+                       s->d_edges, s->d_in_edges, s->d_cost, s->d_magic, (const uint2*)d_strategies, B, (u64*)d_out_ns,
+                       (Counters*)s->d_stats, (unsigned char*)s->ws, s->batch_slot_bytes);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 

@@ -35,7 +35,7 @@ struct DMap { int32_t src_dim; uint32_t stride; int32_t a, b; uint32_t cext; };
 // a tensor edge with the shapes of both ends inlined, so that releasing the successors of
 // a finished producer needs no second table lookup
 struct DEdge {
-    uint32_t src, dst, src_ndim, dst_ndim;
+    uint32_t src, dst, src_ndim, eid;   // eid: index of the record in the producer-sorted array
     uint32_t src_extent[4];
     uint32_t dst_extent[4];
     DMap map[4];                 // indexed by producer dim

@@ -63,6 +63,7 @@ __host__ __device__ inline size_t lds_common_bytes(uint32_t n_rows, uint32_t n_o
     return (size_t)n_rows * 8 + (size_t)n_ops_pad * 8 + 64 * 8 + ((n_rows + 15) & ~15u);
 }
 // per-candidate task words + per-op exeTime: in LDS for small graphs, else in an HBM slot
+__host__ __device__ inline size_t ecache_bytes(uint32_t n_edges) { return (size_t)n_edges * 5 * WAVE * 4; }
 __host__ __device__ inline size_t slot_bytes(uint32_t n_ops, uint32_t n_ops_pad) {
     return (size_t)n_ops * WAVE * 8 + (size_t)n_ops_pad * 4;
 }
@@ -281,6 +282,7 @@ struct SimT {
     // a trial mutation: op ov_op is simulated with configuration ov_cfg instead of cfgs[ov_op]
     uint32_t ov_op;          // 0xffffffff = none
     uint2 ov_cfg;
+    uint32_t* ecache;        // per (edge, consumer part) values kept from the set-up (see EdgeLane), or null
     __device__ __forceinline__ uint2 cfg_raw(uint32_t j) const {
         uint2 c = cfgs[j];
         if (OVR && j == ov_op) c = ov_cfg;
@@ -319,6 +321,78 @@ struct Recorder {
 };
 constexpr uint32_t MAX_SNAPSHOTS = 32;   // bits of loc
 constexpr u64 RUN_CONVERGED = 1;         // run_events: stopped because the timeline re-joined the accepted one
+
+// What the release of an edge needs to know about each consumer part (one per lane).  It
+// depends only on the edge and on the consumer's configuration, not on which producer part
+// finished or when, and an edge is visited once per group of producer parts that finish
+// together: the batch kernels compute it once per candidate and keep it (ECACHE_WORDS words per
+// lane and edge, in LDS or in the candidate's HBM slot) when all extents fit 16 bits.
+struct EdgeLane {
+    int32_t nlo[4], nhi[4];     // range of every producer dim the part reads ([0,1) beyond the producer's dims)
+    uint32_t dev_c, node_c;     // the part's device and node
+    bool mine;                  // the lane is a part of the consumer
+    // regular strategies: position inside the run of lanes that share a remote link row (see run_events)
+    uint32_t pos, last_run_mask, first_len;
+    bool run_end, wrapped;
+};
+constexpr uint32_t ECACHE_WORDS = 5;
+constexpr uint32_t ECACHE_MAX_EXTENT = 0xffff;
+
+template <bool REG, class SimX>
+__device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, const OpCfg& cj) {
+    const int lane = lane_id();
+    const SimDev& S = m.S;
+    EdgeLane el;
+    el.mine = (uint32_t)lane < cj.parts;
+    const uint32_t digits = part_digits(cj, lane, m.magic_v);
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+        el.nlo[d] = 0; el.nhi[d] = 1;
+        if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, m.magic_v, el.nlo[d], el.nhi[d]);
+    }
+    el.dev_c = part_device<REG>(cj, lane, S);
+    el.node_c = div_magic(el.dev_c, S.magic_gpn, S.pass_gpn);
+    el.pos = 0; el.first_len = 0; el.last_run_mask = 0; el.run_end = false; el.wrapped = false;
+    if (REG) {
+        const uint32_t G = S.gpus_per_node;
+        const uint32_t node0 = div_magic(cj.off, S.magic_gpn, S.pass_gpn);
+        const uint32_t room = G - (cj.off - node0 * G);              // lanes of the first run
+        el.first_len = cj.parts < room ? cj.parts : room;
+        const uint32_t local_c = el.dev_c - el.node_c * G;
+        el.pos = (uint32_t)lane < el.first_len ? (uint32_t)lane : local_c;    // index inside the run
+        const uint32_t last = cj.off + cj.parts - 1;
+        el.wrapped = last >= S.n_dev && div_magic(last - S.n_dev, S.magic_gpn, S.pass_gpn) == node0;
+        el.last_run_mask = (el.wrapped && (uint32_t)lane >= el.first_len && el.node_c == node0) ? 0xffffffffu : 0u;
+        el.run_end = el.mine && ((uint32_t)lane == cj.parts - 1 || local_c == G - 1) &&
+                     !(el.wrapped && (uint32_t)lane == el.first_len - 1);
+    }
+    return el;
+}
+
+// ranges as lo | hi << 16; one word of small fields: device 10 bits, node 10, pos 3, run_end,
+// last run, mine, first_len 4, wrapped
+__device__ __forceinline__ void ecache_store(uint32_t* ecache, uint32_t eid, const EdgeLane& el) {
+    uint32_t* p = ecache + (size_t)eid * (ECACHE_WORDS * WAVE) + lane_id();
+#pragma unroll
+    for (int d = 0; d < 4; d++) p[d * WAVE] = (uint32_t)el.nlo[d] | ((uint32_t)el.nhi[d] << 16);
+    p[4 * WAVE] = el.dev_c | (el.node_c << 10) | (el.pos << 20) | ((uint32_t)el.run_end << 23) | ((el.last_run_mask & 1u) << 24) |
+                  ((uint32_t)el.mine << 25) | (el.first_len << 26) | ((uint32_t)el.wrapped << 30);
+}
+__device__ __forceinline__ EdgeLane ecache_load(const uint32_t* ecache, uint32_t eid) {
+    const uint32_t* p = ecache + (size_t)eid * (ECACHE_WORDS * WAVE) + lane_id();
+    uint32_t v[ECACHE_WORDS];
+#pragma unroll
+    for (int k = 0; k < (int)ECACHE_WORDS; k++) v[k] = p[k * WAVE];
+    EdgeLane el;
+#pragma unroll
+    for (int d = 0; d < 4; d++) { el.nlo[d] = (int32_t)(v[d] & 0xffffu); el.nhi[d] = (int32_t)(v[d] >> 16); }
+    const uint32_t f = v[4];
+    el.dev_c = f & 1023u; el.node_c = (f >> 10) & 1023u; el.pos = (f >> 20) & 7u;
+    el.run_end = (f >> 23) & 1u; el.last_run_mask = 0u - ((f >> 24) & 1u); el.mine = (f >> 25) & 1u;
+    const uint32_t u = first_u32(f);                 // the last two fields are the same in every lane
+    el.first_len = (u >> 26) & 15u; el.wrapped = (u >> 30) & 1u;
+    return el;
+}
 
 // how many parts of the producer (configuration cp) a consumer part reads through edge e:
 // the product over the producer's dims of the number of producer parts its range touches
@@ -401,13 +475,41 @@ __device__ __forceinline__ void rebuild_l2(const SimX& m) {
 
 // Section 5.1 step 1 and the start of Algorithm 1: the tasks, how many inputs each waits
 // for, the initial READY set, idle devices.
+// the same count from ranges that are already known
+__device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg& cp, const EdgeLane& el) {
+    uint32_t n = 1;
+#pragma unroll
+    for (int d = 0; d < 4; d++) {
+        if ((uint32_t)d < e.src_ndim) {
+            uint32_t c = 0;
+            if (el.nhi[d] > el.nlo[d])
+                c = owner_part((uint32_t)el.nhi[d] - 1, e.src_extent[d], cp.deg[d]) - owner_part((uint32_t)el.nlo[d], e.src_extent[d], cp.deg[d]) + 1;
+            n *= c;
+        }
+    }
+    return n;
+}
+
+// regular: only read when the edge cache is filled (m.ecache != null)
 template <class SimX>
-__device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
+__device__ __forceinline__ void init_state(SimX& m, Counters& cnt, bool regular = false) {
     const int lane = lane_id();
     for (uint32_t r = lane; r < m.S.n_rows; r += WAVE) m.L.free_at[r] = 0;
     for (uint32_t j = 0; j < m.S.n_ops; j++) {
         const OpCfg cj = m.cfg(j);
-        const uint32_t pending = count_pending(m, j, cj);
+        uint32_t pending = 0;
+        if (m.ecache) {
+            // what every later release of an in-edge needs about this op's parts is computed here, once
+            const uint32_t in_begin = m.T.ops[j].in_begin, in_end = m.T.ops[j].in_end;
+            for (uint32_t q = in_begin; q < in_end; q++) {
+                const DEdge e = m.T.in_edges[q];
+                const EdgeLane el = regular ? edge_lane<true>(m, e, cj) : edge_lane<false>(m, e, cj);
+                ecache_store(m.ecache, e.eid, el);
+                pending += count_inputs_of(e, m.cfg(e.src), el);
+            }
+        } else {
+            pending = count_pending(m, j, cj);
+        }
         // pending < PENDING_LIMIT is guaranteed by ff_sim_create (at most 511 in-edges per op)
         const u64 w = (uint32_t)lane >= cj.parts ? W_NONE : (pending == 0 ? 1ull : (W_WAIT | ((u64)pending << 48)));
         m.words[j * WAVE + lane] = w;
@@ -520,7 +622,8 @@ __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint
 // REG: the strategy is STRATEGY_REGULAR.  STATS: also count pairs and transfers (the optional
 // per-candidate record); a compile-time switch so that the counters cost the timed path nothing.
 // TREE: more than FLAT_GROUPS groups of 64 ops, the queue has its level 2.
-template <bool WIDE, bool RECORD, bool REG, bool STATS, bool TREE, class SimX>
+// CACHE: the per-edge set-up was stored by init_state (m.ecache).
+template <bool WIDE, bool RECORD, bool REG, bool STATS, bool TREE, bool CACHE, class SimX>
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const int lane = lane_id();
     PROF_DECL
@@ -609,38 +712,21 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 if (ei != out_begin) e = edges[ei];
                 const uint32_t j = e.dst;
                 u64 w = words[j * WAVE + lane];
-                const OpCfg cj = m.cfg(j);
-                const bool mine = (uint32_t)lane < cj.parts;
-                const uint32_t digits = part_digits(cj, lane, magic_v);
-                int32_t nlo[4], nhi[4];
-#pragma unroll
-                for (int d = 0; d < 4; d++) {
-                    nlo[d] = 0; nhi[d] = 1;
-                    if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, magic_v, nlo[d], nhi[d]);
-                }
-                const uint32_t dev_c = part_device<REG>(cj, lane, S);
-                const uint32_t node_c = div_magic(dev_c, S.magic_gpn, S.pass_gpn);
                 // REG: consumer parts sit on consecutive, distinct devices, so the transfers from
                 // one producer part can share a link row only when their consumers sit on the
                 // same remote node, and those consumers are a run of consecutive lanes (the node
                 // of lane 0 may come back once more at the end, after the device numbers wrapped
                 // around).  The FIFO order on every shared row is then a running sum along the
                 // run, and no search for lanes with equal rows is needed.
+                const EdgeLane el = CACHE ? ecache_load(m.ecache, ei) : edge_lane<REG>(m, e, m.cfg(j));
+                const bool mine = el.mine;
+                int32_t nlo[4], nhi[4];
+#pragma unroll
+                for (int d = 0; d < 4; d++) { nlo[d] = el.nlo[d]; nhi[d] = el.nhi[d]; }
+                const uint32_t dev_c = el.dev_c, node_c = el.node_c;
                 const uint32_t G = S.gpus_per_node;
-                uint32_t pos = 0, first_len = 0, last_run_mask = 0;
-                bool run_end = false, wrapped = false;
-                if (REG) {
-                    const uint32_t node0 = div_magic(cj.off, S.magic_gpn, S.pass_gpn);
-                    const uint32_t room = G - (cj.off - node0 * G);              // lanes of the first run
-                    first_len = cj.parts < room ? cj.parts : room;
-                    const uint32_t local_c = dev_c - node_c * G;
-                    pos = (uint32_t)lane < first_len ? (uint32_t)lane : local_c;    // index inside the run
-                    const uint32_t last = cj.off + cj.parts - 1;
-                    wrapped = last >= S.n_dev && div_magic(last - S.n_dev, S.magic_gpn, S.pass_gpn) == node0;
-                    last_run_mask = (wrapped && (uint32_t)lane >= first_len && node_c == node0) ? 0xffffffffu : 0u;
-                    run_end = mine && ((uint32_t)lane == cj.parts - 1 || local_c == G - 1) &&
-                              !(wrapped && (uint32_t)lane == first_len - 1);
-                }
+                const uint32_t pos = el.pos, first_len = el.first_len, last_run_mask = el.last_run_mask;
+                const bool run_end = el.run_end, wrapped = el.wrapped;
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
                 bool touched = false;
@@ -782,13 +868,13 @@ __device__ __forceinline__ u64 makespan(const SimX& m) {
 
 // One candidate: build + simulate.  Returns the makespan or one of the RESULT_* codes.
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
-template <bool WIDE, bool RECORD, bool STATS, bool TREE>
+template <bool WIDE, bool RECORD, bool STATS, bool TREE, bool CACHE>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
-    init_state(m, cnt);
-    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, TREE>(m, cnt, rec)
-                                            : run_events<WIDE, RECORD, false, STATS, TREE>(m, cnt, rec);
+    init_state(m, cnt, cls == STRATEGY_REGULAR);
+    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, TREE, CACHE>(m, cnt, rec)
+                                            : run_events<WIDE, RECORD, false, STATS, TREE, CACHE>(m, cnt, rec);
     if (rc) return rc;
     if (STATS) {   // diagnostics: tasks that never ran (0 in a correct run)
         for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));
@@ -808,7 +894,8 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 __device__ __forceinline__ uint32_t load_magic(const uint32_t* __restrict__ magic) { return magic[lane_id() + 1]; }
 
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
-template <bool WIDE, bool LDSW, bool STATS, bool TREE>
+// CACHE: the per-edge set-up is kept (after the task words: in LDS if LDSW, else in the slot).
+template <bool WIDE, bool LDSW, bool STATS, bool TREE, bool CACHE>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -818,23 +905,27 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     const Tables T{ops, edges, in_edges, cost};
     u64* words;
     uint32_t* exe_of;
+    uint32_t* ecache = nullptr;
     unsigned char* lds_rest = lds_raw;
+    const size_t state_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15;
     if (LDSW) {
         words = (u64*)lds_raw;
         exe_of = (uint32_t*)(lds_raw + (size_t)S.n_ops * WAVE * 8);
-        lds_rest = lds_raw + ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15);
+        lds_rest = lds_raw + state_bytes;
+        if (CACHE) { ecache = (uint32_t*)lds_rest; lds_rest += ecache_bytes(S.n_edges); }
     } else {
         unsigned char* slot = ws + (size_t)blockIdx.x * slot_stride;
         words = (u64*)slot;
         exe_of = (uint32_t*)(slot + (size_t)S.n_ops * WAVE * 8);
+        if (CACHE) ecache = (uint32_t*)(slot + state_bytes);
     }
     const WaveLds L = carve_lds(lds_rest, S);
     const uint32_t magic_v = load_magic(magic);
     Recorder none = {};
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
-        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
-        const u64 mk = simulate_candidate<WIDE, false, STATS, TREE>(m, cnt, none);
+        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache};
+        const u64 mk = simulate_candidate<WIDE, false, STATS, TREE, CACHE>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (STATS) store_counters(cnt, stats + b);
         wave_sync();
@@ -1076,7 +1167,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.loc = first_u32(meta.loc);
     meta.tag = first_u32(meta.tag);
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
-    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0)};
+    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), nullptr};
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
         // the strategy the search starts from counts as seen
@@ -1171,8 +1262,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     wave_sync();
                     rebuild_l2(m);
                 }
-                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE>(m, cnt, rec)
-                                             : run_events<WIDE, true, false, false, TREE>(m, cnt, rec);
+                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE, false>(m, cnt, rec)
+                                             : run_events<WIDE, true, false, false, TREE, false>(m, cnt, rec);
                 if (rc == RUN_CONVERGED) { converged = true; rc = 0; mk = meta.cur_ns; break; }
                 mk = rc ? rc : makespan(m);
                 if (rc) break;
@@ -1284,7 +1375,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         u64 mk = RESULT_INVALID;
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
             const uint2 ocfg = cm.cfgs[op];
-            SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2]))};
+            SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])), nullptr};
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
@@ -1299,7 +1390,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE, false>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE, false>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
