@@ -42,6 +42,7 @@ struct ff_sim {
     // the batch kernel may keep the per-edge set-up of a candidate (all extents must fit 16 bits):
     // behind the task words, in the HBM slot, or in LDS for graphs whose words live there
     bool cache_ok = false;
+    bool chain_cache = false;     // the same for chains: only the extents matter, the set-up lives in the chain's memory
     size_t batch_slot_bytes = 0;  // slot_bytes, plus the kept set-up where it lives in HBM
     size_t lds_cached = 0;        // dynamic LDS of the caching variant (= lds if the set-up lives in HBM)
     uint32_t max_slots_cached = 0;
@@ -87,18 +88,23 @@ static batch_kernel_t batch_kernel_c(const ff_sim* s) {
     return s->d_stats ? batch_kernel_of<false, true, CACHE>(s) : batch_kernel_of<false, false, CACHE>(s);
 }
 static batch_kernel_t batch_kernel(const ff_sim* s, bool cached) { return cached ? batch_kernel_c<true>(s) : batch_kernel_c<false>(s); }
-static chain_kernel_t chain_kernel(const ff_sim* s) {
+template <bool CACHE>
+static chain_kernel_t chain_kernel_c(const ff_sim* s) {
     const bool tree = s->dev.n_groups > FLAT_GROUPS;
-    if (s->wide) return tree ? k_sim_chain_steps<true, true> : k_sim_chain_steps<true, false>;
-    return tree ? k_sim_chain_steps<false, true> : k_sim_chain_steps<false, false>;
+    if (s->wide) return tree ? k_sim_chain_steps<true, true, CACHE> : k_sim_chain_steps<true, false, CACHE>;
+    return tree ? k_sim_chain_steps<false, true, CACHE> : k_sim_chain_steps<false, false, CACHE>;
 }
+// chains keep the per-edge set-up in their own memory whenever the extents allow it
+static chain_kernel_t chain_kernel(const ff_sim* s) { return s->chain_cache ? chain_kernel_c<true>(s) : chain_kernel_c<false>(s); }
 typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
                              uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);
-static try_kernel_t try_kernel(const ff_sim* s) {
+template <bool CACHE>
+static try_kernel_t try_kernel_c(const ff_sim* s) {
     const bool tree = s->dev.n_groups > FLAT_GROUPS;
-    if (s->wide) return tree ? k_sim_chain_try<true, true> : k_sim_chain_try<true, false>;
-    return tree ? k_sim_chain_try<false, true> : k_sim_chain_try<false, false>;
+    if (s->wide) return tree ? k_sim_chain_try<true, true, CACHE> : k_sim_chain_try<true, false, CACHE>;
+    return tree ? k_sim_chain_try<false, true, CACHE> : k_sim_chain_try<false, false, CACHE>;
 }
+static try_kernel_t try_kernel(const ff_sim* s) { return s->chain_cache ? try_kernel_c<true>(s) : try_kernel_c<false>(s); }
 
 static void release(ff_sim* s) {
     if (!s) return;
@@ -242,6 +248,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     s->lds_words = lds_with_words <= 40 * 1024;
     s->lds = s->lds_words ? lds_with_words : s->lds_common;
     s->cache_ok = max_extent <= ECACHE_MAX_EXTENT && g->n_edges > 0;
+    s->chain_cache = s->cache_ok;
     s->batch_slot_bytes = s->slot_bytes;
     s->lds_cached = s->lds;
     if (s->cache_ok) {
@@ -367,7 +374,7 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
     c->sim = s;
     c->C = C;
     c->n_snaps = CHAIN_SNAPSHOTS;
-    c->stride = chain_bytes(s->dev.n_ops, s->dev.n_ops_pad, s->dev.n_rows, c->n_snaps);
+    c->stride = chain_bytes(s->dev.n_ops, s->dev.n_ops_pad, s->dev.n_rows, c->n_snaps, s->dev.n_edges);
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t row_bytes = (size_t)s->dev.n_ops * sizeof(uint2);
     if (hipMalloc((void**)&c->d_mem, (size_t)C * c->stride) != hipSuccess ||
@@ -500,7 +507,7 @@ int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
     if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;
     for (uint32_t k = 0; k < c->C; k++) {
         ChainMeta meta;
-        const unsigned char* p = c->d_mem + (size_t)k * c->stride + chain_meta_offset(c->sim->dev.n_ops, c->sim->dev.n_ops_pad, c->sim->dev.n_rows, c->n_snaps);
+        const unsigned char* p = c->d_mem + (size_t)k * c->stride + chain_meta_offset(c->sim->dev.n_ops, c->sim->dev.n_ops_pad, c->sim->dev.n_rows, c->n_snaps, c->sim->dev.n_edges);
         if (hipMemcpy(&meta, p, sizeof(meta), hipMemcpyDeviceToHost) != hipSuccess) return FF_EHIP;
         h_out[k].n_steps = meta.n_steps;
         h_out[k].n_resumed = meta.n_resumed;

@@ -283,6 +283,8 @@ struct SimT {
     uint32_t ov_op;          // 0xffffffff = none
     uint2 ov_cfg;
     uint32_t* ecache;        // per (edge, consumer part) values kept from the set-up (see EdgeLane), or null
+    bool ecache_fill;        // init_state writes them (false: ecache is someone else's and only read)
+    static constexpr bool kOvr = OVR;
     __device__ __forceinline__ uint2 cfg_raw(uint32_t j) const {
         uint2 c = cfgs[j];
         if (OVR && j == ov_op) c = ov_cfg;
@@ -338,7 +340,7 @@ struct EdgeLane {
 constexpr uint32_t ECACHE_WORDS = 5;
 constexpr uint32_t ECACHE_MAX_EXTENT = 0xffff;
 
-template <bool REG, class SimX>
+template <class SimX>
 __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, const OpCfg& cj) {
     const int lane = lane_id();
     const SimDev& S = m.S;
@@ -350,11 +352,14 @@ __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, con
         el.nlo[d] = 0; el.nhi[d] = 1;
         if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, m.magic_v, el.nlo[d], el.nhi[d]);
     }
-    el.dev_c = part_device<REG>(cj, lane, S);
+    const uint32_t G = S.gpus_per_node;
+    // the run fields only depend on the consumer's own configuration: filled whenever it puts its
+    // parts on consecutive, distinct devices, whatever the other ops do
+    const bool consecutive = cj.stride == 1 && cj.parts <= S.n_dev && G <= MAX_RUN;
+    el.dev_c = consecutive ? part_device<true>(cj, lane, S) : part_device<false>(cj, lane, S);
     el.node_c = div_magic(el.dev_c, S.magic_gpn, S.pass_gpn);
     el.pos = 0; el.first_len = 0; el.last_run_mask = 0; el.run_end = false; el.wrapped = false;
-    if (REG) {
-        const uint32_t G = S.gpus_per_node;
+    if (consecutive) {
         const uint32_t node0 = div_magic(cj.off, S.magic_gpn, S.pass_gpn);
         const uint32_t room = G - (cj.off - node0 * G);              // lanes of the first run
         el.first_len = cj.parts < room ? cj.parts : room;
@@ -490,20 +495,19 @@ __device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg&
     return n;
 }
 
-// regular: only read when the edge cache is filled (m.ecache != null)
 template <class SimX>
-__device__ __forceinline__ void init_state(SimX& m, Counters& cnt, bool regular = false) {
+__device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
     const int lane = lane_id();
     for (uint32_t r = lane; r < m.S.n_rows; r += WAVE) m.L.free_at[r] = 0;
     for (uint32_t j = 0; j < m.S.n_ops; j++) {
         const OpCfg cj = m.cfg(j);
         uint32_t pending = 0;
-        if (m.ecache) {
+        if (m.ecache && m.ecache_fill) {
             // what every later release of an in-edge needs about this op's parts is computed here, once
             const uint32_t in_begin = m.T.ops[j].in_begin, in_end = m.T.ops[j].in_end;
             for (uint32_t q = in_begin; q < in_end; q++) {
                 const DEdge e = m.T.in_edges[q];
-                const EdgeLane el = regular ? edge_lane<true>(m, e, cj) : edge_lane<false>(m, e, cj);
+                const EdgeLane el = edge_lane(m, e, cj);
                 ecache_store(m.ecache, e.eid, el);
                 pending += count_inputs_of(e, m.cfg(e.src), el);
             }
@@ -718,7 +722,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 // of lane 0 may come back once more at the end, after the device numbers wrapped
                 // around).  The FIFO order on every shared row is then a running sum along the
                 // run, and no search for lanes with equal rows is needed.
-                const EdgeLane el = CACHE ? ecache_load(m.ecache, ei) : edge_lane<REG>(m, e, m.cfg(j));
+                // (the op of a trial mutation differs from what the chain's kept set-up describes)
+                const EdgeLane el = (CACHE && !(SimX::kOvr && j == m.ov_op)) ? ecache_load(m.ecache, ei) : edge_lane(m, e, m.cfg(j));
                 const bool mine = el.mine;
                 int32_t nlo[4], nhi[4];
 #pragma unroll
@@ -872,7 +877,7 @@ template <bool WIDE, bool RECORD, bool STATS, bool TREE, bool CACHE>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
-    init_state(m, cnt, cls == STRATEGY_REGULAR);
+    init_state(m, cnt);
     const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, TREE, CACHE>(m, cnt, rec)
                                             : run_events<WIDE, RECORD, false, STATS, TREE, CACHE>(m, cnt, rec);
     if (rc) return rc;
@@ -924,7 +929,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     Recorder none = {};
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
-        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache};
+        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
         const u64 mk = simulate_candidate<WIDE, false, STATS, TREE, CACHE>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (STATS) store_counters(cnt, stats + b);
@@ -969,25 +974,29 @@ struct ChainMem {       // all pointers are per chain
     u64* snap_words;    // [2][n_snaps][n_ops*64]
     u64* snap_l1;       // [2][n_snaps][n_ops_pad]
     u64* snap_free;     // [2][n_snaps][n_rows, padded to even]
+    uint32_t* ecache;   // kept per-edge set-up of the chain's current strategy (see EdgeLane)
     ChainMeta* meta;
 };
 
 // byte offset of the ChainMeta record inside a chain block (it comes last)
-__host__ __device__ inline size_t chain_meta_offset(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps) {
+__host__ __device__ inline size_t chain_meta_offset(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps,
+                                                    uint32_t n_edges) {
     size_t b = (size_t)n_ops_pad * 8;                       // cfgs
+    b += ecache_bytes(n_edges);
     b += (size_t)n_ops * WAVE * 8 * 3;                      // words, end_of, end_try
     b += 2 * (size_t)n_snaps * ((size_t)n_ops * WAVE * 8 + (size_t)n_ops_pad * 8 + (size_t)((n_rows + 1) & ~1u) * 8);
     b += (size_t)n_ops_pad * 4;                             // exe_of
     return b;
 }
-__host__ __device__ inline size_t chain_bytes(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps) {
-    return (chain_meta_offset(n_ops, n_ops_pad, n_rows, n_snaps) + sizeof(ChainMeta) + 255) & ~(size_t)255;
+__host__ __device__ inline size_t chain_bytes(uint32_t n_ops, uint32_t n_ops_pad, uint32_t n_rows, uint32_t n_snaps, uint32_t n_edges) {
+    return (chain_meta_offset(n_ops, n_ops_pad, n_rows, n_snaps, n_edges) + sizeof(ChainMeta) + 255) & ~(size_t)255;
 }
 
 __device__ __forceinline__ ChainMem carve_chain(unsigned char* base, const SimDev& S, uint32_t n_snaps) {
     ChainMem c;
     const size_t nw = (size_t)S.n_ops * WAVE;
     c.cfgs = (uint2*)base; base += (size_t)S.n_ops_pad * 8;
+    c.ecache = (uint32_t*)base; base += ecache_bytes(S.n_edges);
     c.words = (u64*)base; base += nw * 8;
     c.end_of = (u64*)base; base += nw * 8;
     c.end_try = (u64*)base; base += nw * 8;
@@ -1101,6 +1110,19 @@ struct SearchDev {
     uint2* best_cfgs;            // [C][n_ops] the strategy that achieved it (in/out)
 };
 
+// the kept set-up of op j's in-edges follows its configuration
+template <class SimX>
+__device__ __forceinline__ void refresh_ecache_for_op(const SimX& m, uint32_t j) {
+    const OpCfg cj = m.cfg(j);
+    const uint32_t in_begin = m.T.ops[j].in_begin, in_end = m.T.ops[j].in_end;
+    for (uint32_t q = in_begin; q < in_end; q++) {
+        const DEdge e = m.T.in_edges[q];
+        ecache_store(m.ecache, e.eid, edge_lane(m, e, cj));
+    }
+    __threadfence_block();
+    wave_sync();
+}
+
 // Makes a recorded run the chain's accepted timeline: the snapshots it wrote (first..next-1)
 // take the place of the old ones, the endTimes it wrote are copied over the old ones.
 // converged: the run stopped where it re-joined the accepted timeline, whose later snapshots and
@@ -1131,7 +1153,8 @@ __device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, 
 // A forced mutation that names an op outside the graph poisons the chain: this and all
 // later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
 // step s.
-template <bool WIDE, bool TREE>
+// CACHE: the chain keeps the per-edge set-up of its current strategy (all extents fit 16 bits).
+template <bool WIDE, bool TREE, bool CACHE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                           const uint32_t* __restrict__ magic, unsigned char* chain_mem,
@@ -1167,7 +1190,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.loc = first_u32(meta.loc);
     meta.tag = first_u32(meta.tag);
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
-    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), nullptr};
+    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
         // the strategy the search starts from counts as seen
@@ -1256,14 +1279,15 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                 if (k == 0) {
                     init_state(m, cnt);
                 } else {
+                    if (CACHE && record) refresh_ecache_for_op(m, op);
                     load_snapshot(m, rec, k);
                     // the loaded state still describes the op under its old configuration
                     patch_state_for_op(m, m.words, L.l1, op, ocfg, pend_new);
                     wave_sync();
                     rebuild_l2(m);
                 }
-                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE, false>(m, cnt, rec)
-                                             : run_events<WIDE, true, false, false, TREE, false>(m, cnt, rec);
+                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE, CACHE>(m, cnt, rec)
+                                             : run_events<WIDE, true, false, false, TREE, CACHE>(m, cnt, rec);
                 if (rc == RUN_CONVERGED) { converged = true; rc = 0; mk = meta.cur_ns; break; }
                 mk = rc ? rc : makespan(m);
                 if (rc) break;
@@ -1306,6 +1330,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                 wave_sync();
                 if (lane == 0) cfg_lds[op] = ocfg;
                 wave_sync();
+                if (CACHE) refresh_ecache_for_op(m, op);
                 mk = meta.cur_ns;
             } else {
                 // a forced step whose simulation failed (overflow): no timeline for this strategy
@@ -1340,7 +1365,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 // single-op mutations per chain, each against the chain's current strategy and stored
 // timeline, without changing the chain.  One wavefront per (proposal, chain); its task words
 // live in a private workspace slot, the chain's snapshots are only read.
-template <bool WIDE, bool TREE>
+template <bool WIDE, bool TREE, bool CACHE>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                         const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                         const uint32_t* __restrict__ magic, const unsigned char* __restrict__ chain_mem,
@@ -1375,7 +1400,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         u64 mk = RESULT_INVALID;
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
             const uint2 ocfg = cm.cfgs[op];
-            SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])), nullptr};
+            SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
+                       CACHE ? cm.ecache : nullptr, false};
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
@@ -1390,7 +1416,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE, false>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE, false>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE, CACHE>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE, CACHE>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
