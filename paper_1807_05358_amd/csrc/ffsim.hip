@@ -74,12 +74,13 @@ typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, c
 typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
                                uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
 
-// three layouts: task words in LDS (small graphs; never a level 2), in HBM without, and with level 2;
+// four layouts: task words in LDS (small graphs; never a level 2; up to 64 ops the whole queue in a register),
+// in HBM without, and with level 2;
 // each with or without the kept per-edge set-up
 template <bool WIDE, bool STATS, bool CACHE>
 static batch_kernel_t batch_kernel_of(const ff_sim* s) {
-    if (s->lds_words) return k_sim_batch<WIDE, true, STATS, false, CACHE>;
-    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, true, CACHE> : k_sim_batch<WIDE, false, STATS, false, CACHE>;
+    if (s->lds_words) return s->dev.n_ops <= 64 ? k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE> : k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE>;
+    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE>;
 }
 // the variant that also fills the per-candidate counters is only launched when they are asked for
 template <bool CACHE>

@@ -625,10 +625,16 @@ __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint
 // snapshots for delta simulation.  Returns 0 or a RESULT_* code.
 // REG: the strategy is STRATEGY_REGULAR.  STATS: also count pairs and transfers (the optional
 // per-candidate record); a compile-time switch so that the counters cost the timed path nothing.
-// TREE: more than FLAT_GROUPS groups of 64 ops, the queue has its level 2.
 // CACHE: the per-edge set-up was stored by init_state (m.ecache).
-template <bool WIDE, bool RECORD, bool REG, bool STATS, bool TREE, bool CACHE, class SimX>
+// Q: shape of the queue above the task words.
+//   Q_ONE   at most 64 ops: level 1 (one minimum per op) sits in a register, lane = op; nothing of
+//           the queue is in LDS while the loop runs (batch kernels only: level 1 is not written back);
+//   Q_FLAT  up to FLAT_GROUPS groups of 64 ops: level 1 in LDS, every lane scans its column;
+//   Q_TREE  more groups: level 1 in LDS, level 2 (one minimum per group) in a register, lane = group.
+enum QueueShape : int { Q_ONE = 0, Q_FLAT = 1, Q_TREE = 2 };
+template <bool WIDE, bool RECORD, bool REG, bool STATS, int Q, bool CACHE, class SimX>
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
+    constexpr bool TREE = Q == Q_TREE;
     const int lane = lane_id();
     PROF_DECL
     const SimDev& S = m.S;
@@ -639,6 +645,10 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     const uint32_t magic_v = m.magic_v;
     u64 last_key = m.last_key;
     bool overflow = m.overflow;
+    // the register-resident level of the queue (see QueueShape)
+    u64 qreg = W_NONE;
+    if (Q == Q_ONE) qreg = L.l1[lane];
+    if (Q == Q_TREE) qreg = (uint32_t)lane < S.n_groups ? L.l2[lane] : W_NONE;
     // Values chosen per lane between two of these (same node or not) must sit in registers: a
     // select between two fields of the argument block is otherwise turned into a per-lane load
     // from that block, a vector memory round trip for every producer part.
@@ -649,8 +659,14 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
         uint32_t i;
-        if (TREE) {
-            const u64 k2 = (uint32_t)lane < S.n_groups ? L.l2[lane] : W_NONE;
+        if (Q == Q_ONE) {
+            kmin = wave_min_from(qreg, last_key);
+            if (kmin >> 63) break;
+            const u64 m1 = ballot(qreg == kmin);
+            if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }
+            i = __builtin_ctzll(m1);                 // lowest op index among equal keys
+        } else if (TREE) {
+            const u64 k2 = qreg;
             kmin = wave_min_from(k2, last_key);
             if (kmin >> 63) break;
             const uint32_t g = __builtin_ctzll(ballot(k2 == kmin));
@@ -678,6 +694,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const int col = __builtin_ctzll(m1);
             i = readlane_u32(gbest, col) * WAVE + col;
         }
+        static_assert(!(RECORD && Q == Q_ONE), "snapshots read level 1 from LDS");
         if (RECORD) {
             // the state before the first event at or after a multiple of `step` is a snapshot
             while (rec.next < rec.n_snaps && kmin >= (u64)rec.next * rec.step) {
@@ -834,9 +851,11 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 }
                 if (ballot(now_ready)) {
                     const u64 nmin = wave_min_from(now_ready ? w : W_NONE, last_key);
-                    if (lane == 0) {
-                        if (nmin < L.l1[j]) L.l1[j] = nmin;
-                        if (TREE && nmin < L.l2[j >> 6]) L.l2[j >> 6] = nmin;
+                    if (Q == Q_ONE) {
+                        if ((uint32_t)lane == j && nmin < qreg) qreg = nmin;
+                    } else {
+                        if (lane == 0 && nmin < L.l1[j]) L.l1[j] = nmin;
+                        if (TREE && (uint32_t)lane == (j >> 6) && nmin < qreg) qreg = nmin;
                     }
                 }
                 PROF_MARK(5)
@@ -845,14 +864,18 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         }
         if (in_mask) words[i * WAVE + lane] = k0;
         const u64 new_l1 = wave_min_from(k0, last_key);
-        wave_sync();
-        if (lane == 0) L.l1[i] = new_l1;
-        wave_sync();
+        if (Q == Q_ONE) {
+            if ((uint32_t)lane == i) qreg = new_l1;
+            wave_sync();
+        } else {
+            wave_sync();
+            if (lane == 0) L.l1[i] = new_l1;
+            wave_sync();
+        }
         if (TREE) {
             const uint32_t g = i >> 6;
             const u64 new_l2 = wave_min_from(L.l1[g * WAVE + lane], last_key);
-            if (lane == 0) L.l2[g] = new_l2;
-            wave_sync();
+            if ((uint32_t)lane == g) qreg = new_l2;
         }
         PROF_MARK(6)
     }
@@ -873,13 +896,13 @@ __device__ __forceinline__ u64 makespan(const SimX& m) {
 
 // One candidate: build + simulate.  Returns the makespan or one of the RESULT_* codes.
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
-template <bool WIDE, bool RECORD, bool STATS, bool TREE, bool CACHE>
+template <bool WIDE, bool RECORD, bool STATS, int Q, bool CACHE>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
     init_state(m, cnt);
-    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, TREE, CACHE>(m, cnt, rec)
-                                            : run_events<WIDE, RECORD, false, STATS, TREE, CACHE>(m, cnt, rec);
+    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, Q, CACHE>(m, cnt, rec)
+                                            : run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
     if (rc) return rc;
     if (STATS) {   // diagnostics: tasks that never ran (0 in a correct run)
         for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));
@@ -900,7 +923,7 @@ __device__ __forceinline__ uint32_t load_magic(const uint32_t* __restrict__ magi
 
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
 // CACHE: the per-edge set-up is kept (after the task words: in LDS if LDSW, else in the slot).
-template <bool WIDE, bool LDSW, bool STATS, bool TREE, bool CACHE>
+template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -930,7 +953,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
         Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
-        const u64 mk = simulate_candidate<WIDE, false, STATS, TREE, CACHE>(m, cnt, none);
+        const u64 mk = simulate_candidate<WIDE, false, STATS, Q, CACHE>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (STATS) store_counters(cnt, stats + b);
         wave_sync();
@@ -1286,8 +1309,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     wave_sync();
                     rebuild_l2(m);
                 }
-                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE, CACHE>(m, cnt, rec)
-                                             : run_events<WIDE, true, false, false, TREE, CACHE>(m, cnt, rec);
+                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
+                                             : run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
                 if (rc == RUN_CONVERGED) { converged = true; rc = 0; mk = meta.cur_ns; break; }
                 mk = rc ? rc : makespan(m);
                 if (rc) break;
@@ -1416,7 +1439,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE, CACHE>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE, CACHE>(m, cnt, rec);
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
