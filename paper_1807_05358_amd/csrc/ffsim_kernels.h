@@ -746,6 +746,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
 #pragma unroll
                 for (int d = 0; d < 4; d++) { nlo[d] = el.nlo[d]; nhi[d] = el.nhi[d]; }
                 const uint32_t dev_c = el.dev_c, node_c = el.node_c;
+                const uint32_t local_c = dev_c - node_c * S.gpus_per_node;
                 const uint32_t G = S.gpus_per_node;
                 const uint32_t pos = el.pos, first_len = el.first_len, last_run_mask = el.last_run_mask;
                 const bool run_end = el.run_end, wrapped = el.wrapped;
@@ -779,10 +780,12 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     u64 arrive = now;
                     if (comm_mask) {
                         const bool same_node = node_c == node_a;
-                        // Section 5.1: the link device between the two devices
-                        const uint32_t row = same_node
-                            ? S.n_dev + node_a * G * G + (dev_a - node_a * G) * G + (dev_c - node_c * G)
-                            : S.n_dev + S.n_nodes * G * G + node_a * S.n_nodes + node_c;
+                        // Section 5.1: the link device between the two devices.  The producer's share of
+                        // the row index is scalar; per lane one select between two sums.
+                        const uint32_t row_intra = S.n_dev + node_a * G * G + (dev_a - node_a * G) * G;
+                        const uint32_t row_inter = S.n_dev + S.n_nodes * G * G + node_a * S.n_nodes;
+                        const uint32_t to_intra = row_intra + local_c, to_inter = row_inter + node_c;
+                        const uint32_t row = same_node ? to_intra : to_inter;
                         // assumption A2: transfer time = size / bandwidth (rounded up) + latency
                         const uint32_t bw = same_node ? bw_intra : bw_inter;
                         u64 ns;
