@@ -30,7 +30,7 @@ constexpr uint32_t MAX_RUN = 8;
 // accumulated in a register array and reported through the stats record instead of the
 // usual counters.  Compiled out otherwise.
 #ifdef FFSIM_PROFILE
-#define PROF_DECL u64 prof_t[8] = {0, 0, 0, 0, 0, 0, 0, 0}; u64 prof_last = __builtin_readcyclecounter();
+#define PROF_DECL u64 prof_t[8] = {cnt.exit_code, 0, 0, 0, 0, 0, 0, 0}; u64 prof_last = __builtin_readcyclecounter();
 #define PROF_MARK(k) { const u64 prof_now = __builtin_readcyclecounter(); prof_t[k] += prof_now - prof_last; prof_last = prof_now; }
 #define PROF_STORE(c) { c.n_compute = prof_t[0]; c.n_pairs = prof_t[1]; c.n_comm = prof_t[2]; c.sum_comm_ns = lane_id() == 0 ? prof_t[3] : 0; \
                         c.exit_code = prof_t[4]; c.n_stuck = prof_t[5]; c.want_check = prof_t[6]; }
@@ -486,9 +486,16 @@ __device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg&
 #pragma unroll
     for (int d = 0; d < 4; d++) {
         if ((uint32_t)d < e.src_ndim) {
-            uint32_t c = 0;
-            if (el.nhi[d] > el.nlo[d])
-                c = owner_part((uint32_t)el.nhi[d] - 1, e.src_extent[d], cp.deg[d]) - owner_part((uint32_t)el.nlo[d], e.src_extent[d], cp.deg[d]) + 1;
+            uint32_t c;
+            if (cp.deg[d] == 1) {
+                c = el.nhi[d] > el.nlo[d] ? 1u : 0u;           // the producer does not split this dim (uniform)
+            } else if (e.map[d].src_dim < 0) {
+                c = cp.deg[d];                                   // the whole extent is read: every part (uniform)
+            } else {
+                c = 0;
+                if (el.nhi[d] > el.nlo[d])
+                    c = owner_part((uint32_t)el.nhi[d] - 1, e.src_extent[d], cp.deg[d]) - owner_part((uint32_t)el.nlo[d], e.src_extent[d], cp.deg[d]) + 1;
+            }
             n *= c;
         }
     }
@@ -517,8 +524,9 @@ __device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
         // pending < PENDING_LIMIT is guaranteed by ff_sim_create (at most 511 in-edges per op)
         const u64 w = (uint32_t)lane >= cj.parts ? W_NONE : (pending == 0 ? 1ull : (W_WAIT | ((u64)pending << 48)));
         m.words[j * WAVE + lane] = w;
-        const u64 wmin = wave_min_u64(w);
-        if (lane == 0) m.L.l1[j] = wmin;
+        // level 1 only has to order pending events: at the start an op has one (READY at time 0) or none
+        const u64 any_ready = ballot(w == 1ull);
+        if (lane == 0) m.L.l1[j] = any_ready ? 1ull : W_NONE;
         cnt.n_compute += cj.parts;
     }
     for (uint32_t j = m.S.n_ops + lane; j < m.S.n_ops_pad; j += WAVE) m.L.l1[j] = W_NONE;
@@ -901,9 +909,15 @@ __device__ __forceinline__ u64 makespan(const SimX& m) {
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
 template <bool WIDE, bool RECORD, bool STATS, int Q, bool CACHE>
 __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
+#ifdef FFSIM_PROFILE
+    const u64 prof_t0 = __builtin_readcyclecounter();
+#endif
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
     init_state(m, cnt);
+#ifdef FFSIM_PROFILE
+    cnt.exit_code = __builtin_readcyclecounter() - prof_t0;   // reported as section 0
+#endif
     const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, Q, CACHE>(m, cnt, rec)
                                             : run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
     if (rc) return rc;
