@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "csrc", "ffsim.hip")
 LIB = os.path.join(HERE, "libffsim.so")
-DEPS = [SRC, os.path.join(HERE, "csrc", "ffsim_kernels.h"), os.path.join(HERE, "csrc", "ffsim_device.h"),
+DEPS = [SRC] + [os.path.join(HERE, "csrc", h) for h in ("ffsim_kernels.h", "ffsim_chain.h", "ffsim_events.h", "ffsim_strategy.h",
+                                                        "ffsim_device.h")] + [
         os.path.join(os.path.dirname(HERE), "include", "ff_sim.h")]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
