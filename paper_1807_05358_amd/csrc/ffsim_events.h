@@ -95,9 +95,7 @@ __device__ __forceinline__ void rebuild_l2(const SimX& m) {
     }
 }
 
-// Section 5.1 step 1 and the start of Algorithm 1: the tasks, how many inputs each waits
-// for, the initial READY set, idle devices.
-// the same count from ranges that are already known
+// count_inputs (ffsim_strategy.h) from ranges that are already known
 __device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg& cp, const EdgeLane& el) {
     uint32_t n = 1;
 #pragma unroll
@@ -119,6 +117,8 @@ __device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg&
     return n;
 }
 
+// Section 5.1 step 1 and the start of Algorithm 1: the tasks, how many inputs each waits
+// for, the initial READY set, idle devices.
 template <class SimX>
 __device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
     const int lane = lane_id();
