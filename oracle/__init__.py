@@ -32,7 +32,7 @@ def lib():
         L = C.CDLL(build())
         vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
         L.ffo_build.restype = vp
-        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp]
+        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp]
         L.ffo_from_arrays.restype = vp
         L.ffo_from_arrays.argtypes = [u32, vp, vp, u32, u32, vp, vp]
         L.ffo_counts.restype = None
@@ -44,7 +44,7 @@ def lib():
         L.ffo_free.restype = None
         L.ffo_free.argtypes = [vp]
         L.ffo_batch.restype = None
-        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32]
+        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -66,6 +66,21 @@ def _cost_args(cost):
 
 def _machine(m):
     return np.array(m.as_tuple() if hasattr(m, "as_tuple") else tuple(m), dtype="<u4")
+
+
+def _link_args(m):
+    """optional per-pair links inside a node: attributes link_Bpns / link_lat_ns of the machine,
+    [gpus_per_node][gpus_per_node] (from local GPU, to local GPU); latency defaults to the
+    machine's intra-node latency.  Returns (keep-alive arrays, the two C arguments)."""
+    bw = getattr(m, "link_Bpns", None)
+    if bw is None:
+        return (), (None, None)
+    G = int(m.gpus_per_node)
+    bw = np.ascontiguousarray(bw, "<u4")
+    lat = getattr(m, "link_lat_ns", None)
+    lat = np.full((G, G), m.intra_lat_ns, "<u4") if lat is None else np.ascontiguousarray(lat, "<u4")
+    assert bw.shape == (G, G) and lat.shape == (G, G)
+    return (bw, lat), (_ptr(bw), _ptr(lat))
 
 
 class TaskGraph:
@@ -97,12 +112,19 @@ class TaskGraph:
             self._h = None
 
 
-def build_task_graph(ops, edges, machine, cost, cfg):
-    """Section 5.1 for one strategy (cfg: [n_ops] configs). None if the strategy is invalid."""
+def build_task_graph(ops, edges, machine, cost, cfg, devmap=None):
+    """Section 5.1 for one strategy (cfg: [n_ops] configs). None if the strategy is invalid.
+    devmap [n_ops][64] uint16: the device of every part given explicitly (the configs' offset
+    and stride are then not used)."""
     ops, edges, cfg = map(np.ascontiguousarray, (ops, edges, cfg))
     m = _machine(machine)
     keep, cargs = _cost_args(cost)
-    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg))
+    keep_l, largs = _link_args(machine)
+    if devmap is not None:
+        devmap = np.ascontiguousarray(devmap, "<u2")
+        assert devmap.shape == (len(ops), 64)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs,
+                        None if devmap is None else _ptr(devmap))
     return TaskGraph(h) if h else None
 
 
@@ -114,15 +136,21 @@ def task_graph_from_arrays(exe, dev, n_rows, dep_src, dep_dst):
     return TaskGraph(lib().ffo_from_arrays(len(exe), _ptr(exe), _ptr(dev), n_rows, len(ds), _ptr(ds), _ptr(dd)))
 
 
-def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1):
-    """makespan (ns) of every strategy in cfgs [B][n_ops]; 2^64-1 for an invalid one."""
+def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None):
+    """makespan (ns) of every strategy in cfgs [B][n_ops]; 2^64-1 for an invalid one.
+    devmaps [B][n_ops][64] uint16: explicit devices of all parts (see build_task_graph)."""
     ops, edges, cfgs = map(np.ascontiguousarray, (ops, edges, cfgs))
     assert cfgs.ndim == 2 and cfgs.shape[1] == len(ops)
     m = _machine(machine)
     out = np.zeros(cfgs.shape[0], "<u8")
     keep, cargs = _cost_args(cost)
+    keep_l, largs = _link_args(machine)
+    if devmaps is not None:
+        devmaps = np.ascontiguousarray(devmaps, "<u2")
+        assert devmaps.shape == (cfgs.shape[0], len(ops), 64)
     lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs,
-                    _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads)
+                    _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads, *largs,
+                    None if devmaps is None else _ptr(devmaps))
     return out
 
 

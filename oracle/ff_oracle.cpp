@@ -135,21 +135,37 @@ bool exe_time(const CostModel& cm, uint32_t i, const Cfg& c, uint32_t parts, uin
     return false;
 }
 
+// Optional refinements of the inputs (all null = the plain forms):
+// link_bw / link_lat [G][G]: bandwidth and latency of the link from local GPU a to local GPU b
+// of one node (the same in every node; the diagonal is not used) instead of the machine's
+// single intra-node figures -- the device topology's connections need not be alike.
+// devmap [n_ops][64]: the device of every task given one by one (Section 4: a configuration
+// assigns each task its device), instead of offset + k * stride.
+struct Extras { const uint32_t* link_bw; const uint32_t* link_lat; const uint16_t* devmap; };
+
 bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, const Machine& m,
-           const CostModel& cm, const Cfg* cfg, TaskGraph& tg) {
+           const CostModel& cm, const Cfg* cfg, const Extras& x, TaskGraph& tg) {
     const uint32_t G = m.gpus_per_node, N = m.n_nodes, D = N * G;
     const uint32_t max_parts = cm.table ? std::min(MAX_PARTS, cm.n_cols) : MAX_PARTS;
     tg.n_rows = D + N * G * G + N * N;
     std::vector<uint32_t> first(n_ops), np(n_ops);
     // step 1: compute tasks t_{i:1..|c_i|}
     for (uint32_t i = 0; i < n_ops; i++) {
-        if (!cfg_valid(ops[i], cfg[i], D, max_parts)) return false;
+        Cfg c = cfg[i];
+        if (x.devmap) { c.dev_offset = 0; c.dev_stride = 1; }     // not used with explicit devices
+        if (!cfg_valid(ops[i], c, D, max_parts)) return false;
         np[i] = parts_of(cfg[i]);
         uint64_t exe = 0;
         if (!exe_time(cm, i, cfg[i], np[i], &exe)) return false;
         first[i] = (uint32_t)tg.exe.size();
-        for (uint32_t k = 0; k < np[i]; k++)
-            tg.add_task(exe, (uint32_t)((cfg[i].dev_offset + (uint64_t)k * cfg[i].dev_stride) % D));
+        for (uint32_t k = 0; k < np[i]; k++) {
+            uint32_t dev = (uint32_t)((cfg[i].dev_offset + (uint64_t)k * cfg[i].dev_stride) % D);
+            if (x.devmap) {
+                dev = x.devmap[(size_t)i * MAX_PARTS + k];
+                if (dev >= D) return false;
+            }
+            tg.add_task(exe, dev);
+        }
     }
     tg.n_compute = (uint32_t)tg.exe.size();
     // step 2: per tensor edge, per pair of tasks with a shared sub-tensor
@@ -166,6 +182,11 @@ bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, c
                 bool same_node = tg.dev[tp] / G == tg.dev[tc] / G;
                 uint64_t bw = same_node ? m.intra_Bpns : m.inter_Bpns;
                 uint64_t lat = same_node ? m.intra_lat_ns : m.inter_lat_ns;
+                if (same_node && x.link_bw) {
+                    const size_t pair = (size_t)(tg.dev[tp] % G) * G + tg.dev[tc] % G;
+                    bw = x.link_bw[pair];
+                    lat = x.link_lat[pair];
+                }
                 uint64_t bytes = elems * m.elem_bytes;
                 uint32_t c = tg.add_task((bytes + bw - 1) / bw + lat, link_row(m, tg.dev[tp], tg.dev[tc]));
                 tg.add_dep(tp, c);
@@ -214,11 +235,13 @@ extern "C" {
 // cost / n_cols: the table by number of parts; or cost = null and the three tuple arrays.
 void* ffo_build(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
                 const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
-                const uint32_t* tuple_ns, const void* cfg) {
+                const uint32_t* tuple_ns, const void* cfg, const uint32_t* link_bw, const uint32_t* link_lat,
+                const uint16_t* devmap) {
     TaskGraph* tg = new TaskGraph;
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
+    const Extras x{link_bw, link_lat, devmap};
     if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
-               (const Cfg*)cfg, *tg)) { delete tg; return nullptr; }
+               (const Cfg*)cfg, x, *tg)) { delete tg; return nullptr; }
     return tg;
 }
 
@@ -259,13 +282,15 @@ void ffo_free(void* h) { delete (TaskGraph*)h; }
 // n_threads > 1 splits the candidates statically over threads (one independent oracle run each).
 void ffo_batch(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
                const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
-               const uint32_t* tuple_ns, const void* cfgs, uint32_t B, uint64_t* out_ns, uint32_t n_threads) {
+               const uint32_t* tuple_ns, const void* cfgs, uint32_t B, uint64_t* out_ns, uint32_t n_threads,
+               const uint32_t* link_bw, const uint32_t* link_lat, const uint16_t* devmaps) {
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
     auto work = [&](uint32_t b0, uint32_t b1) {
         for (uint32_t b = b0; b < b1; b++) {
             TaskGraph tg;
+            const Extras x{link_bw, link_lat, devmaps ? devmaps + (size_t)b * n_ops * MAX_PARTS : nullptr};
             bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
-                            (const Cfg*)cfgs + (size_t)b * n_ops, tg);
+                            (const Cfg*)cfgs + (size_t)b * n_ops, x, tg);
             out_ns[b] = ok ? simulate(tg, nullptr, nullptr, nullptr) : INVALID;
         }
     };

@@ -68,6 +68,10 @@ class Machine:
     intra_lat_ns: int = 0
     inter_lat_ns: int = 0
     elem_bytes: int = 4
+    # optional [gpus_per_node][gpus_per_node] tables (from local GPU, to local GPU): links inside
+    # a node that are not all alike; None = intra_Bpns / intra_lat_ns for every pair
+    link_Bpns: object = None
+    link_lat_ns: object = None
 
     @property
     def n_devices(self) -> int:
@@ -525,6 +529,30 @@ def tuple_cost_table(ops, cost, max_parts, choices, seed):
         ns_all.append(ns[order].astype(np.uint32))
         ptr[i + 1] = ptr[i] + len(t)
     return ptr, np.concatenate(tup_all), np.concatenate(ns_all)
+
+
+def paired_links(gpus_per_node, fast_Bpns, slow_Bpns, fast_lat_ns=0, slow_lat_ns=0):
+    """link tables [G][G] of a node whose GPUs sit in pairs (2k, 2k+1) behind a common switch:
+    the two GPUs of a pair talk over the fast link, any other two over the slow one (the shape
+    of the dual-GPU boards of the paper's older cluster, Section 8.1)."""
+    G = gpus_per_node
+    a = np.arange(G)
+    same = (a[:, None] // 2) == (a[None, :] // 2)
+    return (np.where(same, fast_Bpns, slow_Bpns).astype("<u4"),
+            np.where(same, fast_lat_ns, slow_lat_ns).astype("<u4"))
+
+
+def device_maps(cfgs, n_dev, seed, spread=None):
+    """a seeded explicit device for every part of every op of cfgs [B][n_ops]: [B][n_ops][64]
+    uint16; entries beyond an op's parts hold 0xffff (they must be ignored).  spread: devices are
+    drawn from the first `spread` devices only (more sharing)."""
+    B, n_ops = cfgs.shape
+    hi = n_dev if spread is None else min(n_dev, spread)
+    rng = np.random.Generator(np.random.PCG64(seed))
+    maps = rng.integers(0, hi, size=(B, n_ops, MAX_PARTS), dtype=np.uint16)
+    parts = cfgs["deg"].astype(np.uint32).prod(axis=2)
+    maps[np.arange(MAX_PARTS)[None, None, :] >= parts[:, :, None]] = 0xFFFF
+    return maps
 
 
 def data_parallel_strategy(ops, n_dev, max_parts=MAX_PARTS):
