@@ -160,6 +160,23 @@ int ff_sim_create_tuplecost(const ff_opgraph_t* graph, const ff_machine_t* machi
                             ff_sim_t** out);
 void ff_sim_destroy(ff_sim_t* sim);
 
+/* Links inside a node that are not all alike (Section 3: the device topology's connections each
+ * carry their own bandwidth and latency; Section 8.1's older cluster pairs GPUs on boards behind
+ * a shared switch).  Bpns[a * gpus_per_node + b] / lat_ns[...] describe the link from local
+ * GPU a to local GPU b, the same in every node; entries with a == b are not used; lat_ns may be
+ * null (0 ns).  They replace machine.intra_Bpns / intra_lat_ns for every later call; links
+ * between nodes keep the machine's figures.  links == NULL returns to the machine's single
+ * figures.  HOST pointers, deep-copied.  Waits for the device to be idle.  Chain sets created
+ * before the call hold timelines simulated with the old links: every later ff_sim_delta,
+ * ff_sim_delta_try, ff_sim_search and ff_sim_neighbours on them returns FF_EINVAL (destroy them).
+ * FF_EINVAL if gpus_per_node differs from the machine's or if a bandwidth is 0. */
+typedef struct {
+    uint32_t gpus_per_node;
+    const uint32_t* Bpns;
+    const uint32_t* lat_ns;
+} ff_linktable_t;
+int ff_sim_set_links(ff_sim_t* sim, const ff_linktable_t* links);
+
 /* Scratch for a batch of B candidates (per-task queue keys and readyTime / pending-input
  * counters of the resident candidates).  The workspace is caller-allocated device memory,
  * 256-byte aligned, and may be shared by successive calls on the same stream.  Small
@@ -175,6 +192,15 @@ int ff_sim_set_stats(ff_sim_t* sim, ff_stats_t* d_stats);
  * its strategy is invalid.  Asynchronous on hip_stream (a hipStream_t, null = default). */
 int ff_sim_batch(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns,
                  void* hip_stream);
+
+/* The same with the device of every task given one by one (Section 4: a configuration assigns
+ * each of its tasks a device) instead of dev_offset + k * dev_stride: d_devmaps is
+ * [B][n_ops][FF_MAX_PARTS], entry k of an op = device of its part k (< n_devices, else the
+ * strategy is invalid); entries beyond the op's number of parts and the configurations'
+ * dev_offset / dev_stride are not read.  Device memory, read only.  Workspace, stats and
+ * results as for ff_sim_batch. */
+int ff_sim_batch_devmaps(ff_sim_t* sim, const ff_opcfg_t* d_strategies, const uint16_t* d_devmaps, uint32_t B,
+                         uint64_t* d_out_ns, void* hip_stream);
 
 /* Delta simulation (Section 5.3, Algorithm 2's contract: same timeline as a full simulation
  * of the changed strategy).  A chain set holds C current strategies on the device;

@@ -32,14 +32,19 @@ class ff_costtable_t(C.Structure):
     _fields_ = [("n_ops", C.c_uint32), ("n_cols", C.c_uint32), ("ns", C.c_void_p)]
 
 
-EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
-           "ff_sim_batch", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
+EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links",
+           "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
+           "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
            "ff_sim_neighbour_count", "ff_sim_neighbours",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8"),
                            ("n_converged", "<u8")])
 
+
+
+class ff_linktable_t(C.Structure):
+    _fields_ = [("gpus_per_node", C.c_uint32), ("Bpns", C.c_void_p), ("lat_ns", C.c_void_p)]
 
 
 class ff_tuplecost_t(C.Structure):
@@ -86,6 +91,10 @@ def lib():
         L.ff_sim_set_stats.argtypes = [vp, vp]
         L.ff_sim_batch.restype = C.c_int
         L.ff_sim_batch.argtypes = [vp, vp, u32, vp, vp]
+        L.ff_sim_batch_devmaps.restype = C.c_int
+        L.ff_sim_batch_devmaps.argtypes = [vp, vp, vp, u32, vp, vp]
+        L.ff_sim_set_links.restype = C.c_int
+        L.ff_sim_set_links.argtypes = [vp, vp]
         L.ff_sim_chains_create.restype = C.c_int
         L.ff_sim_chains_create.argtypes = [vp, vp, u32, vp, vp, C.POINTER(vp)]
         L.ff_sim_delta.restype = C.c_int
@@ -153,6 +162,20 @@ def ff_sim_destroy(sim):
     lib().ff_sim_destroy(sim)
 
 
+def ff_sim_set_links(sim, gpus_per_node=0, Bpns=None, lat_ns=None):
+    """Bpns / lat_ns: [gpus_per_node][gpus_per_node] (from local GPU, to local GPU); Bpns None:
+    back to the machine's single intra-node figures."""
+    if Bpns is None:
+        _check(lib().ff_sim_set_links(sim, None), "ff_sim_set_links")
+        return
+    Bpns = np.ascontiguousarray(Bpns, "<u4")
+    lat = None if lat_ns is None else np.ascontiguousarray(lat_ns, "<u4")
+    if Bpns.size != gpus_per_node * gpus_per_node or (lat is not None and lat.size != Bpns.size):
+        raise ValueError("link tables must be [gpus_per_node][gpus_per_node]")
+    lt = ff_linktable_t(gpus_per_node, Bpns.ctypes.data, None if lat is None else lat.ctypes.data)
+    _check(lib().ff_sim_set_links(sim, C.byref(lt)), "ff_sim_set_links")
+
+
 def ff_sim_workspace_bytes(sim, B):
     return lib().ff_sim_workspace_bytes(sim, B)
 
@@ -167,6 +190,10 @@ def ff_sim_set_stats(sim, d_stats):
 
 def ff_sim_batch(sim, d_strategies, B, d_out_ns, stream=None):
     _check(lib().ff_sim_batch(sim, d_strategies, B, d_out_ns, stream), "ff_sim_batch")
+
+
+def ff_sim_batch_devmaps(sim, d_strategies, d_devmaps, B, d_out_ns, stream=None):
+    _check(lib().ff_sim_batch_devmaps(sim, d_strategies, d_devmaps, B, d_out_ns, stream), "ff_sim_batch_devmaps")
 
 
 def ff_sim_chains_create(sim, d_strategies, C_, d_out_ns0, stream=None):
@@ -248,6 +275,11 @@ class Simulator:
             self.handle = ff_sim_create_tuplecost(ops, edges, machine, *cost)
         else:
             self.handle = ff_sim_create(ops, edges, machine, cost)
+        if getattr(machine, "link_Bpns", None) is not None:
+            lat = machine.link_lat_ns
+            if lat is None:
+                lat = np.full((machine.gpus_per_node,) * 2, machine.intra_lat_ns, "<u4")
+            ff_sim_set_links(self.handle, machine.gpus_per_node, machine.link_Bpns, lat)
         self._ws = None
         self._stats = None
 
@@ -275,9 +307,10 @@ class Simulator:
         assert cfgs.ndim == 2 and cfgs.shape[1] == self.n_ops
         return to_device(cfgs)
 
-    def batch(self, d_strategies, B, d_out=None, stats=False):
+    def batch(self, d_strategies, B, d_out=None, stats=False, d_devmaps=None):
         """d_strategies: device tensor from upload_strategies.  Returns the device tensor of
-        B int64 (bit pattern of uint64 ns); asynchronous on the current stream."""
+        B int64 (bit pattern of uint64 ns); asynchronous on the current stream.
+        d_devmaps: device tensor of [B][n_ops][64] uint16, the device of every part given explicitly."""
         torch = _torch()
         self._ensure_workspace(B)
         if d_out is None:
@@ -287,14 +320,24 @@ class Simulator:
             ff_sim_set_stats(self.handle, self._stats.data_ptr())
         else:
             ff_sim_set_stats(self.handle, None)
-        ff_sim_batch(self.handle, d_strategies.data_ptr(), B, d_out.data_ptr(),
-                     torch.cuda.current_stream().cuda_stream)
+        if d_devmaps is not None:
+            ff_sim_batch_devmaps(self.handle, d_strategies.data_ptr(), d_devmaps.data_ptr(), B, d_out.data_ptr(),
+                                 torch.cuda.current_stream().cuda_stream)
+        else:
+            ff_sim_batch(self.handle, d_strategies.data_ptr(), B, d_out.data_ptr(),
+                         torch.cuda.current_stream().cuda_stream)
         return d_out
 
-    def simulate(self, cfgs, stats=False):
-        """host convenience: numpy configs [B][n_ops] -> numpy uint64 [B] (and stats)."""
+    def simulate(self, cfgs, stats=False, devmaps=None):
+        """host convenience: numpy configs [B][n_ops] -> numpy uint64 [B] (and stats).
+        devmaps: numpy [B][n_ops][64] uint16 (optional explicit devices)."""
         d = self.upload_strategies(cfgs)
-        out = self.batch(d, len(cfgs), stats=stats)
+        dm = None
+        if devmaps is not None:
+            devmaps = np.ascontiguousarray(devmaps, "<u2")
+            assert devmaps.shape == (len(cfgs), self.n_ops, 64)
+            dm = to_device(devmaps)
+        out = self.batch(d, len(cfgs), stats=stats, d_devmaps=dm)
         res = out.cpu().numpy().view("<u8")
         if stats:
             return res, self._stats.cpu().numpy().view(STATS_DT)

@@ -36,7 +36,10 @@ struct ff_sim {
     DEdge* d_in_edges = nullptr;
     uint32_t* d_cost = nullptr;
     uint32_t* d_magic = nullptr;
-    bool wide = false;            // some tensor has 2^32 bytes or more
+    bool wide = false;            // some tensor has 2^32 bytes or more, or a link row's running sum may pass 2^32 ns
+    bool big_tensors = false;     // some tensor has 2^32 bytes or more
+    ff_machine_t mach{};
+    uint32_t links_gen = 0;       // counts ff_sim_set_links calls (a chain set's stored timelines depend on the links)
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
     // the batch kernel may keep the per-edge set-up of a candidate (all extents must fit 16 bits):
@@ -64,48 +67,60 @@ struct ff_chains {
     unsigned char* d_mem = nullptr; // [C] chain blocks: strategy, task words, endTimes, snapshots
     uint32_t* d_flags = nullptr;   // [C] nonzero once a chain saw an out-of-range mutation
     uint32_t* d_counter = nullptr; // work counter of the trial-mutation kernel
+    uint32_t links_gen = 0;        // sim->links_gen when the chains were created
 };
 
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMeta::loc");
 
 typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const uint2*,
-                               uint32_t, u64*, Counters*, unsigned char*, size_t);
+                               uint32_t, u64*, Counters*, unsigned char*, size_t, const uint16_t*);
 typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
                                uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
 
 // four layouts: task words in LDS (small graphs; never a level 2; up to 64 ops the whole queue in a register),
 // in HBM without, and with level 2;
 // each with or without the kept per-edge set-up
-template <bool WIDE, bool STATS, bool CACHE>
+template <bool WIDE, bool STATS, bool CACHE, bool EXT>
 static batch_kernel_t batch_kernel_of(const ff_sim* s) {
-    if (s->lds_words) return s->dev.n_ops <= 64 ? k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE> : k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE>;
-    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE>;
+    if (s->lds_words) return s->dev.n_ops <= 64 ? k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE, EXT> : k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE, EXT>;
+    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE, EXT> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE, EXT>;
 }
 // the variant that also fills the per-candidate counters is only launched when they are asked for
-template <bool CACHE>
+template <bool CACHE, bool EXT>
 static batch_kernel_t batch_kernel_c(const ff_sim* s) {
-    if (s->wide) return s->d_stats ? batch_kernel_of<true, true, CACHE>(s) : batch_kernel_of<true, false, CACHE>(s);
-    return s->d_stats ? batch_kernel_of<false, true, CACHE>(s) : batch_kernel_of<false, false, CACHE>(s);
+    if (s->wide) return s->d_stats ? batch_kernel_of<true, true, CACHE, EXT>(s) : batch_kernel_of<true, false, CACHE, EXT>(s);
+    return s->d_stats ? batch_kernel_of<false, true, CACHE, EXT>(s) : batch_kernel_of<false, false, CACHE, EXT>(s);
 }
-static batch_kernel_t batch_kernel(const ff_sim* s, bool cached) { return cached ? batch_kernel_c<true>(s) : batch_kernel_c<false>(s); }
-template <bool CACHE>
+// ext: the launch uses the link table or explicit devices (kernels of their own, which do not keep
+// the per-edge set-up in the batch form)
+static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = false) {
+    if (ext) return batch_kernel_c<false, true>(s);
+    return cached ? batch_kernel_c<true, false>(s) : batch_kernel_c<false, false>(s);
+}
+template <bool CACHE, bool EXT>
 static chain_kernel_t chain_kernel_c(const ff_sim* s) {
     const bool tree = s->dev.n_groups > FLAT_GROUPS;
-    if (s->wide) return tree ? k_sim_chain_steps<true, true, CACHE> : k_sim_chain_steps<true, false, CACHE>;
-    return tree ? k_sim_chain_steps<false, true, CACHE> : k_sim_chain_steps<false, false, CACHE>;
+    if (s->wide) return tree ? k_sim_chain_steps<true, true, CACHE, EXT> : k_sim_chain_steps<true, false, CACHE, EXT>;
+    return tree ? k_sim_chain_steps<false, true, CACHE, EXT> : k_sim_chain_steps<false, false, CACHE, EXT>;
 }
 // chains keep the per-edge set-up in their own memory whenever the extents allow it
-static chain_kernel_t chain_kernel(const ff_sim* s) { return s->chain_cache ? chain_kernel_c<true>(s) : chain_kernel_c<false>(s); }
+static chain_kernel_t chain_kernel(const ff_sim* s) {
+    if (s->dev.link_table) return s->chain_cache ? chain_kernel_c<true, true>(s) : chain_kernel_c<false, true>(s);
+    return s->chain_cache ? chain_kernel_c<true, false>(s) : chain_kernel_c<false, false>(s);
+}
 typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
                              uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);
-template <bool CACHE>
+template <bool CACHE, bool EXT>
 static try_kernel_t try_kernel_c(const ff_sim* s) {
     const bool tree = s->dev.n_groups > FLAT_GROUPS;
-    if (s->wide) return tree ? k_sim_chain_try<true, true, CACHE> : k_sim_chain_try<true, false, CACHE>;
-    return tree ? k_sim_chain_try<false, true, CACHE> : k_sim_chain_try<false, false, CACHE>;
+    if (s->wide) return tree ? k_sim_chain_try<true, true, CACHE, EXT> : k_sim_chain_try<true, false, CACHE, EXT>;
+    return tree ? k_sim_chain_try<false, true, CACHE, EXT> : k_sim_chain_try<false, false, CACHE, EXT>;
 }
-static try_kernel_t try_kernel(const ff_sim* s) { return s->chain_cache ? try_kernel_c<true>(s) : try_kernel_c<false>(s); }
+static try_kernel_t try_kernel(const ff_sim* s) {
+    if (s->dev.link_table) return s->chain_cache ? try_kernel_c<true, true>(s) : try_kernel_c<false, true>(s);
+    return s->chain_cache ? try_kernel_c<true, false>(s) : try_kernel_c<false, false>(s);
+}
 
 static void release(ff_sim* s) {
     if (!s) return;
@@ -132,6 +147,28 @@ const char* ff_sim_strerror(int code) {
 // cost: the device image of the cost model.  n_cols >= 1: the table [n_ops][n_cols] indexed by the
 // number of parts.  n_cols == 0: costs keyed by the degree tuple, packed as ptr[n_ops+1], then the
 // tuples of all ops, then their exeTimes.
+// the constants buffer of the kernels (layout: LINK_TABLE_AT in ffsim_device.h)
+static std::vector<uint32_t> constants_image(const ff_linktable_t* links, uint32_t G) {
+    std::vector<uint32_t> c(LINK_TABLE_AT + 4 * (links ? (size_t)G * G : 1), 0);
+    for (uint32_t d = 2; d <= 64; d++) c[d] = magic_plus1(d);
+    if (links)
+        for (uint32_t p = 0; p < G * G; p++) {
+            c[LINK_TABLE_AT + 4 * p + 0] = links->Bpns[p];
+            c[LINK_TABLE_AT + 4 * p + 1] = magic_floor(links->Bpns[p]);
+            c[LINK_TABLE_AT + 4 * p + 2] = links->lat_ns ? links->lat_ns[p] : 0;
+        }
+    return c;
+}
+
+// The narrow kernels count elements, bytes and a link row's running sum of transfer times in
+// 32 bits: every tensor must stay below 2^32 bytes, and gpus_per_node of the longest possible
+// transfers (the most one producer part can queue on one row) below 2^32 ns.  Everything else
+// runs in the 64-bit (WIDE) kernels.
+static bool needs_wide(bool big_tensors, uint32_t bw_min, uint32_t lat_max, uint32_t gpus_per_node) {
+    const uint64_t ns_max = (0xffffffffull + bw_min - 1) / bw_min + lat_max;
+    return big_tensors || ns_max * gpus_per_node >= (1ull << 32);
+}
+
 static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector<uint32_t>& cost, uint32_t n_cols, ff_sim_t** out) {
     if (g->n_ops > FF_MAX_OPS) return FF_ERANGE;
     if (m->n_nodes < 1 || m->gpus_per_node < 1 || m->intra_Bpns < 1 || m->inter_Bpns < 1 || m->elem_bytes < 1) return FF_EINVAL;
@@ -210,8 +247,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         }
         for (uint32_t k = 0; k < g->n_edges; k++) in_edges[ops[edges[k].dst].in_end++] = edges[k];
     }
-    std::vector<uint32_t> magic(65, 0);
-    for (uint32_t d = 2; d <= 64; d++) magic[d] = magic_plus1(d);
+    std::vector<uint32_t> magic = constants_image(nullptr, 0);
 
     ff_sim* s = new (std::nothrow) ff_sim;
     if (!s) return FF_ENOMEM;
@@ -230,15 +266,10 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     S.pass_dev = D == 1 ? 0xffffffffu : 0u; S.pass_gpn = m->gpus_per_node == 1 ? 0xffffffffu : 0u;
     S.n_ops_pad = (g->n_ops + 63) & ~63u;
     S.n_groups = S.n_ops_pad / 64;
-    {
-        // The narrow kernels count elements, bytes and a link row's running sum of transfer
-        // times in 32 bits: every tensor must stay below 2^32 bytes, and gpus_per_node of the
-        // longest possible transfers (the most one producer part can queue on one row) below
-        // 2^32 ns.  Everything else runs in the 64-bit (WIDE) kernels.
-        const uint64_t bw_min = std::min(m->intra_Bpns, m->inter_Bpns);
-        const uint64_t ns_max = (0xffffffffull + bw_min - 1) / bw_min + std::max(m->intra_lat_ns, m->inter_lat_ns);
-        s->wide = max_bytes >= ((unsigned __int128)1 << 32) || ns_max * m->gpus_per_node >= (1ull << 32);
-    }
+    s->mach = *m;
+    s->big_tensors = max_bytes >= ((unsigned __int128)1 << 32);
+    s->wide = needs_wide(s->big_tensors, std::min(m->intra_Bpns, m->inter_Bpns), std::max(m->intra_lat_ns, m->inter_lat_ns),
+                         m->gpus_per_node);
     s->slot_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 255) & ~(size_t)255;
     s->lds_common = lds_common_bytes(S.n_rows, S.n_ops_pad);
     s->lds_chain = s->lds_common + (size_t)S.n_ops_pad * 8;
@@ -320,6 +351,35 @@ int ff_sim_create_tuplecost(const ff_opgraph_t* g, const ff_machine_t* m, const 
 
 void ff_sim_destroy(ff_sim_t* s) { release(s); }
 
+int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
+    if (!s) return FF_EINVAL;
+    const ff_machine_t& m = s->mach;
+    const uint32_t G = m.gpus_per_node;
+    uint32_t bw_min = std::min(m.intra_Bpns, m.inter_Bpns), lat_max = std::max(m.intra_lat_ns, m.inter_lat_ns);
+    if (links) {
+        if (!links->Bpns || links->gpus_per_node != G) return FF_EINVAL;
+        bw_min = m.inter_Bpns; lat_max = m.inter_lat_ns;
+        for (uint32_t a = 0; a < G; a++)
+            for (uint32_t b = 0; b < G; b++) {
+                if (a == b) continue;                                  // a device needs no link to itself
+                if (links->Bpns[a * G + b] < 1) return FF_EINVAL;
+                bw_min = std::min(bw_min, links->Bpns[a * G + b]);
+                lat_max = std::max(lat_max, links->lat_ns ? links->lat_ns[a * G + b] : 0u);
+            }
+    }
+    std::vector<uint32_t> image = constants_image(links, G);
+    uint32_t* d_new = nullptr;
+    int rc = upload(image, &d_new);
+    if (rc) return rc;
+    if (hipDeviceSynchronize() != hipSuccess) { hipFree(d_new); return FF_EHIP; }   // no launch may still read the old table
+    hipFree(s->d_magic);
+    s->d_magic = d_new;
+    s->dev.link_table = links ? 1u : 0u;
+    s->links_gen++;
+    s->wide = needs_wide(s->big_tensors, bw_min, lat_max, G);
+    return FF_OK;
+}
+
 size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {
     if (!s) return 0;
     if (s->lds_words) return 0;   // the whole per-candidate state lives in LDS
@@ -339,20 +399,32 @@ int ff_sim_set_stats(ff_sim_t* s, ff_stats_t* d_stats) {
     return FF_OK;
 }
 
-int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns, void* hip_stream) {
+static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_t* d_devmaps, uint32_t B, uint64_t* d_out_ns,
+                      void* hip_stream) {
     if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
     if (B == 0) return FF_OK;
     // Keeping the per-edge set-up costs LDS for graphs whose words live there; it is used unless it
     // would leave part of the batch waiting for a free compute unit that the plain variant has room for.
-    const bool cached = s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
+    const bool ext = s->dev.link_table || d_devmaps;
+    const bool cached = !ext && s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
     const uint32_t slots = std::min(B, cached ? s->max_slots_cached : s->max_slots);
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     static_assert(sizeof(Counters) == sizeof(ff_stats_t), "stats layout");
-    hipLaunchKernelGGL(batch_kernel(s, cached), dim3(slots), dim3(WAVE), cached ? s->lds_cached : s->lds, st, s->dev, s->d_ops,
+    hipLaunchKernelGGL(batch_kernel(s, cached, ext), dim3(slots), dim3(WAVE), cached ? s->lds_cached : s->lds, st, s->dev, s->d_ops,
                        s->d_edges, s->d_in_edges, s->d_cost, s->d_magic, (const uint2*)d_strategies, B, (u64*)d_out_ns,
-                       (Counters*)s->d_stats, (unsigned char*)s->ws, s->batch_slot_bytes);
+                       (Counters*)s->d_stats, (unsigned char*)s->ws, s->batch_slot_bytes, d_devmaps);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
+}
+
+int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns, void* hip_stream) {
+    return batch_impl(s, d_strategies, nullptr, B, d_out_ns, hip_stream);
+}
+
+int ff_sim_batch_devmaps(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_t* d_devmaps, uint32_t B, uint64_t* d_out_ns,
+                         void* hip_stream) {
+    if (B && !d_devmaps) return FF_EINVAL;
+    return batch_impl(s, d_strategies, d_devmaps, B, d_out_ns, hip_stream);
 }
 
 static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out, hipStream_t st,
@@ -391,18 +463,21 @@ int ff_sim_chains_create(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t C
     }
     int rc = launch_chain_steps(c, nullptr, 1, d_out_ns0, st, SearchDev{});
     if (rc) { ff_sim_chains_destroy(c); return rc; }
+    c->links_gen = s->links_gen;
     *out = c;
     return FF_OK;
 }
 
 int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, uint64_t* d_out_ns, void* hip_stream) {
     if (!c || (n_steps && (!d_muts || !d_out_ns))) return FF_EINVAL;
+    if (c->links_gen != c->sim->links_gen) return FF_EINVAL;
     if (n_steps == 0) return FF_OK;
     return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream, SearchDev{});
 }
 
 int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64_t* d_trace_ns, void* hip_stream) {
     if (!c || !p || (n_steps && !d_trace_ns)) return FF_EINVAL;
+    if (c->links_gen != c->sim->links_gen) return FF_EINVAL;
     if (!p->d_accept || !p->d_tuple_ptr || !p->d_tuples || !p->d_best_ns || !p->d_best || p->n_buckets < 1 || p->bucket_ns < 1 ||
         p->n_tuples < 1) return FF_EINVAL;
     if (n_steps == 0) return FF_OK;
@@ -456,6 +531,7 @@ int ff_sim_neighbours(ff_chains_t* c, const uint32_t* d_tuple_ptr, const uint32_
                       uint32_t op_end, ff_mutation_t* d_muts, uint64_t* d_out_ns, uint64_t* d_best_ns, uint32_t* d_best_index,
                       void* hip_stream) {
     if (!c || !d_tuple_ptr || !d_tuples || !d_muts || !d_out_ns || !d_best_ns || !d_best_index) return FF_EINVAL;
+    if (c->links_gen != c->sim->links_gen) return FF_EINVAL;
     std::vector<uint32_t> first;
     uint64_t total = 0;
     int rc = neighbour_ranges(c, d_tuple_ptr, n_tuples, op_begin, op_end, &first, &total);
@@ -490,6 +566,7 @@ size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* c, uint32_t M) {
 
 int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, uint64_t* d_out_ns, void* hip_stream) {
     if (!c || (M && (!d_muts || !d_out_ns))) return FF_EINVAL;
+    if (c->links_gen != c->sim->links_gen) return FF_EINVAL;
     if (M == 0) return FF_OK;
     if ((uint64_t)M * c->C > 0xffffffffull) return FF_ERANGE;
     ff_sim* s = c->sim;

@@ -222,7 +222,8 @@ __device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, 
 // later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
 // step s.
 // CACHE: the chain keeps the per-edge set-up of its current strategy (all extents fit 16 bits).
-template <bool WIDE, bool TREE, bool CACHE>
+// EXT: with the table of links inside a node.
+template <bool WIDE, bool TREE, bool CACHE, bool EXT>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                           const uint32_t* __restrict__ magic, unsigned char* chain_mem,
@@ -258,7 +259,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.loc = first_u32(meta.loc);
     meta.tag = first_u32(meta.tag);
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
-    Sim m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
+    SimT<false, EXT> m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
+    if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
         // the strategy the search starts from counts as seen
@@ -354,8 +356,12 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     wave_sync();
                     rebuild_l2(m);
                 }
-                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
-                                             : run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
+                if constexpr (EXT) {
+                    rc = run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
+                } else {
+                    rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
+                                                 : run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
+                }
                 if (rc == RUN_CONVERGED) { converged = true; rc = 0; mk = meta.cur_ns; break; }
                 mk = rc ? rc : makespan(m);
                 if (rc) break;
@@ -433,7 +439,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 // single-op mutations per chain, each against the chain's current strategy and stored
 // timeline, without changing the chain.  One wavefront per (proposal, chain); its task words
 // live in a private workspace slot, the chain's snapshots are only read.
-template <bool WIDE, bool TREE, bool CACHE>
+template <bool WIDE, bool TREE, bool CACHE, bool EXT>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                         const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                         const uint32_t* __restrict__ magic, const unsigned char* __restrict__ chain_mem,
@@ -468,8 +474,9 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         u64 mk = RESULT_INVALID;
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
             const uint2 ocfg = cm.cfgs[op];
-            SimTrial m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
-                       CACHE ? cm.ecache : nullptr, false};
+            SimT<true, EXT> m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
+                              CACHE ? cm.ecache : nullptr, false};
+            if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
@@ -484,7 +491,13 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec) : run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
+                u64 rc;
+                if constexpr (EXT) {
+                    rc = run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
+                } else {
+                    rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
+                                                 : run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
+                }
                 mk = rc ? rc : makespan(m);
             }
         }

@@ -60,7 +60,13 @@ struct SimDev {
     uint32_t pass_dev, pass_gpn;       // all ones iff the divisor is 1
     uint32_t n_ops_pad;                // n_ops rounded up to a multiple of 64
     uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
+    uint32_t link_table;               // 1: links inside a node differ per ordered GPU pair (see LINK_TABLE_AT)
 };
+// The constants buffer every kernel receives: words 0..64 are division constants
+// (floor(2^32/d)+1 for d = 2..64); if SimDev::link_table is set, four words per ordered pair of
+// local GPUs (from * gpus_per_node + to) follow at word LINK_TABLE_AT: bandwidth (B/ns),
+// floor(2^32 / bandwidth), latency (ns), 0.
+constexpr uint32_t LINK_TABLE_AT = 128;
 
 __device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }
 

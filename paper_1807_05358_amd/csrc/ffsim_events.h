@@ -339,11 +339,11 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         cnt.n_events++;
         const u64 now = kmin >> 1;
         const bool in_mask = (mask >> lane) & 1;
-        const uint32_t dev_p = part_device<REG>(ci, lane, S);
+        const uint32_t dev_p = m.template device_of<REG>(i, ci);
 
         if (kmin & 1) {
             // dequeue READY compute tasks: start = max(readyTime, device free), end = start + exeTime
-            const bool may_share = REG ? false : !(ci.stride == 1 && ci.parts <= S.n_dev);
+            const bool may_share = REG ? false : ((SimX::kExt && m.devmap != nullptr) || !(ci.stride == 1 && ci.parts <= S.n_dev));
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
             if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
@@ -412,16 +412,25 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         const uint32_t to_intra = row_intra + local_c, to_inter = row_inter + node_c;
                         const uint32_t row = same_node ? to_intra : to_inter;
                         // assumption A2: transfer time = size / bandwidth (rounded up) + latency
-                        const uint32_t bw = same_node ? bw_intra : bw_inter;
+                        uint32_t bw = same_node ? bw_intra : bw_inter;
+                        uint32_t m_bw = same_node ? m_bw_intra : m_bw_inter;
+                        uint32_t lat = same_node ? lat_intra : lat_inter;
+                        if (!REG && SimX::kExt && S.link_table) {
+                            // links inside a node that are not all alike: the pair's own figures
+                            if (comm && same_node) {
+                                const uint4 t = m.links[(dev_a - node_a * G) * G + local_c];
+                                bw = t.x; m_bw = t.y; lat = t.z;
+                            }
+                        }
                         u64 ns;
                         if (WIDE) {
                             const u64 bytes = elems * S.elem_bytes;
                             ns = (bytes + bw - 1) / bw;
                         } else {
                             const uint32_t bytes = (uint32_t)elems * S.elem_bytes;
-                            ns = ceil_div_u32(comm ? bytes : 1u, bw, same_node ? m_bw_intra : m_bw_inter);
+                            ns = ceil_div_u32(comm ? bytes : 1u, bw, m_bw);
                         }
-                        ns += same_node ? lat_intra : lat_inter;
+                        ns += lat;
                         u64 end;
                         if (REG) {
                             const u64 f = L.free_at[row];                  // in range for every lane

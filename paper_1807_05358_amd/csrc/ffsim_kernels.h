@@ -27,8 +27,8 @@ namespace ffsim {
 
 // One candidate: build + simulate.  Returns the makespan or one of the RESULT_* codes.
 // WIDE selects 64-bit element counts (tensors of 2^32 bytes or more).
-template <bool WIDE, bool RECORD, bool STATS, int Q, bool CACHE>
-__device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
+template <bool WIDE, bool RECORD, bool STATS, int Q, bool CACHE, class SimX>
+__device__ u64 simulate_candidate(SimX& m, Counters& cnt, Recorder& rec) {
 #ifdef FFSIM_PROFILE
     const u64 prof_t0 = __builtin_readcyclecounter();
 #endif
@@ -38,8 +38,13 @@ __device__ u64 simulate_candidate(Sim& m, Counters& cnt, Recorder& rec) {
 #ifdef FFSIM_PROFILE
     cnt.exit_code = __builtin_readcyclecounter() - prof_t0;   // reported as section 0
 #endif
-    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, Q, CACHE>(m, cnt, rec)
-                                            : run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
+    u64 rc;
+    if constexpr (SimX::kExt) {
+        rc = run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
+    } else {
+        rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, Q, CACHE>(m, cnt, rec)
+                                     : run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
+    }
     if (rc) return rc;
     if (STATS) {   // diagnostics: tasks that never ran (0 in a correct run)
         for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));
@@ -57,12 +62,14 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
 // CACHE: the per-edge set-up is kept (after the task words: in LDS if LDSW, else in the slot).
-template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE>
+// EXT: with the link table and / or explicit devices (devmaps, else null and never read).
+template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE, bool EXT>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
                                                     uint32_t B, u64* __restrict__ out_ns, Counters* __restrict__ stats,
-                                                    unsigned char* __restrict__ ws, size_t slot_stride) {
+                                                    unsigned char* __restrict__ ws, size_t slot_stride,
+                                                    const uint16_t* __restrict__ devmaps) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const Tables T{ops, edges, in_edges, cost};
     u64* words;
@@ -86,7 +93,11 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     Recorder none = {};
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
-        Sim m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
+        SimT<false, EXT> m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
+        if (EXT) {
+            m.links = (const uint4*)(magic + LINK_TABLE_AT);
+            if (devmaps) m.devmap = devmaps + (size_t)b * S.n_ops * WAVE;
+        }
         const u64 mk = simulate_candidate<WIDE, false, STATS, Q, CACHE>(m, cnt, none);
         if (lane_id() == 0) out_ns[b] = mk;
         if (STATS) store_counters(cnt, stats + b);

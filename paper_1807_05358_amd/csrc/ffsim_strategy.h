@@ -205,7 +205,10 @@ __device__ __forceinline__ uint32_t owner_part(uint32_t x, uint32_t E, uint32_t 
 // from it must not be treated as invariant.
 // OVR: one op's configuration may be overridden (trial mutations); the plain form does not
 // pay for the comparison.
-template <bool OVR>
+// EXT: the refinements of the inputs that only some callers use -- links inside a node that
+// differ per pair, explicit devices per task -- are compiled into kernels of their own, which
+// always run the general event loop; the plain kernels carry none of it.
+template <bool OVR, bool EXT = false>
 struct SimT {
     const SimDev& S;
     const Tables& T;
@@ -221,13 +224,22 @@ struct SimT {
     uint2 ov_cfg;
     uint32_t* ecache;        // per (edge, consumer part) values kept from the set-up (see EdgeLane), or null
     bool ecache_fill;        // init_state writes them (false: ecache is someone else's and only read)
+    const uint4* links = nullptr;        // per ordered pair of local GPUs: bandwidth, its magic, latency (S.link_table)
+    const uint16_t* devmap = nullptr;    // [n_ops][64] device of every part given explicitly, or null
     static constexpr bool kOvr = OVR;
+    static constexpr bool kExt = EXT;
     __device__ __forceinline__ uint2 cfg_raw(uint32_t j) const {
         uint2 c = cfgs[j];
         if (OVR && j == ov_op) c = ov_cfg;
         return c;
     }
     __device__ __forceinline__ OpCfg cfg(uint32_t j) const { return unpack_cfg(cfg_raw(j)); }
+    // Section 4: the device of this lane's part of op j (lanes beyond the parts get some device in range)
+    template <bool REG>
+    __device__ __forceinline__ uint32_t device_of(uint32_t j, const OpCfg& c) const {
+        if (EXT && !REG && devmap) return (uint32_t)lane_id() < c.parts ? devmap[(size_t)j * WAVE + lane_id()] : 0u;
+        return part_device<REG>(c, lane_id(), S);
+    }
 };
 constexpr uint32_t NO_OVERRIDE = 0xffffffffu;
 typedef SimT<false> Sim;
@@ -264,8 +276,8 @@ __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, con
     const uint32_t G = S.gpus_per_node;
     // the run fields only depend on the consumer's own configuration: filled whenever it puts its
     // parts on consecutive, distinct devices, whatever the other ops do
-    const bool consecutive = cj.stride == 1 && cj.parts <= S.n_dev && G <= MAX_RUN;
-    el.dev_c = consecutive ? part_device<true>(cj, lane, S) : part_device<false>(cj, lane, S);
+    const bool consecutive = cj.stride == 1 && cj.parts <= S.n_dev && G <= MAX_RUN && !(SimX::kExt && m.devmap);
+    el.dev_c = consecutive ? part_device<true>(cj, lane, S) : m.template device_of<false>(e.dst, cj);
     el.node_c = div_magic(el.dev_c, S.magic_gpn, S.pass_gpn);
     el.pos = 0; el.first_len = 0; el.last_run_mask = 0; el.run_end = false; el.wrapped = false;
     if (consecutive) {
@@ -352,6 +364,7 @@ __device__ __forceinline__ StrategyClass validate_strategy(const SimX& m) {
     bool bad = false, irregular = false;
     for (uint32_t i = lane_id(); i < m.S.n_ops; i += WAVE) {
         OpCfg c = unpack_cfg_lane(m.cfg_raw(i));
+        if (SimX::kExt && m.devmap) c.off = 0;             // offset and stride are not used with explicit devices
         if (!cfg_ok(m.T.ops[i], c, m.S)) {
             bad = true;
         } else if (m.S.n_cols) {
@@ -371,8 +384,11 @@ __device__ __forceinline__ StrategyClass validate_strategy(const SimX& m) {
             else bad = true;
         }
         irregular = irregular || c.stride != 1 || c.parts > m.S.n_dev;
+        if (SimX::kExt && m.devmap && !bad)
+            for (uint32_t k = 0; k < c.parts; k++) bad = bad || m.devmap[(size_t)i * WAVE + k] >= m.S.n_dev;
     }
     if (ballot(bad)) return STRATEGY_INVALID;
+    if (SimX::kExt) return STRATEGY_GENERAL;
     return (ballot(irregular) || m.S.gpus_per_node > MAX_RUN) ? STRATEGY_GENERAL : STRATEGY_REGULAR;
 }
 

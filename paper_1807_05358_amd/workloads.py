@@ -595,7 +595,7 @@ class Workload:
         if self._strategies is None or len(self._strategies) < n:
             self._strategies = strategies(self.ops, n, self.seed, self.machine.n_devices,
                                           self.max_parts, self.choices)
-        return np.ascontiguousarray(self._strategies[:n])
+        return self._strategies[:n].copy()      # callers may edit their batch
 
     def mutations(self, n_steps, n_chains=1):
         return mutation_chains(self.ops, n_steps, n_chains, self.seed, self.machine.n_devices,
