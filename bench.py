@@ -91,19 +91,12 @@ def oracle_build_share(w, cfgs):
     import oracle
     t0 = time.perf_counter()
     for c in cfgs:
-        oracle.lib().ffo_free(oracle.lib().ffo_build(len(w.ops), oracle._ptr(w.ops), len(w.edges), oracle._ptr(w.edges),
-                                                     oracle._ptr(oracle._machine(w.machine)), oracle._ptr(w.cost),
-                                                     w.cost.shape[1], None, None, None, oracle._ptr(np_c(c))))
+        oracle.build_and_discard(w.ops, w.edges, w.machine, w.cost, c)
     t_build = time.perf_counter() - t0
     t0 = time.perf_counter()
     oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=1)
     t_both = time.perf_counter() - t0
     return t_build, t_both
-
-
-def np_c(a):
-    import numpy as np
-    return np.ascontiguousarray(a)
 
 
 def timeline_items(w, cfg):

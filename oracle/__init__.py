@@ -128,6 +128,19 @@ def build_task_graph(ops, edges, machine, cost, cfg, devmap=None):
     return TaskGraph(h) if h else None
 
 
+def build_and_discard(ops, edges, machine, cost, cfg):
+    """Section 5.1 for one strategy, the task graph dropped at once (for timing the construction
+    alone).  False if the strategy is invalid."""
+    ops, edges, cfg = map(np.ascontiguousarray, (ops, edges, cfg))
+    m = _machine(machine)
+    keep, cargs = _cost_args(cost)
+    keep_l, largs = _link_args(machine)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None)
+    if h:
+        lib().ffo_free(h)
+    return bool(h)
+
+
 def task_graph_from_arrays(exe, dev, n_rows, dep_src, dep_dst):
     exe = np.ascontiguousarray(exe, "<u8")
     dev = np.ascontiguousarray(dev, "<u4")
