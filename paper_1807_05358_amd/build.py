@@ -1,17 +1,20 @@
-"""Builds the HIP library (csrc/ffsim.hip) for gfx950 with hipcc, in-tree."""
+"""Builds the HIP library for gfx950 with hipcc, in-tree: the host file and the kernel files of
+csrc/ are compiled side by side (the kernels are many template instantiations), then linked."""
 from __future__ import annotations
 
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "ffsim.hip")
+CSRC = os.path.join(HERE, "csrc")
+UNITS = ["ffsim.hip", "ffsim_k_batch.hip", "ffsim_k_batch_ext.hip", "ffsim_k_chain.hip", "ffsim_k_try.hip"]
+HEADERS = ["ffsim_select.h", "ffsim_sweep.h", "ffsim_kernels.h", "ffsim_chain.h", "ffsim_events.h", "ffsim_strategy.h",
+           "ffsim_device.h"]
+OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libffsim.so")
-DEPS = [SRC] + [os.path.join(HERE, "csrc", h) for h in ("ffsim_kernels.h", "ffsim_chain.h", "ffsim_events.h", "ffsim_strategy.h",
-                                                        "ffsim_device.h")] + [
-        os.path.join(os.path.dirname(HERE), "include", "ff_sim.h")]
+DEPS = [os.path.join(CSRC, f) for f in UNITS + HEADERS] + [os.path.join(os.path.dirname(HERE), "include", "ff_sim.h")]
 
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                # keep the compiler from forming packed-fp32 instructions
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-value"]
@@ -22,7 +25,16 @@ def build_library(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS):
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    subprocess.check_call([hipcc, *HIPCC_FLAGS, "-o", LIB, SRC])
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs, procs = [], []
+    for u in UNITS:
+        obj = os.path.join(OBJ_DIR, os.path.splitext(u)[0] + ".o")
+        objs.append(obj)
+        procs.append((u, subprocess.Popen([hipcc, *HIPCC_FLAGS, "-c", "-o", obj, os.path.join(CSRC, u)])))
+    failed = [u for u, p in procs if p.wait() != 0]
+    if failed:
+        raise RuntimeError("hipcc failed on " + ", ".join(failed))
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
     return LIB
 
 

@@ -9,7 +9,8 @@
 #include <new>
 #include <vector>
 
-#include "ffsim_kernels.h"
+#include "ffsim_select.h"
+#include "ffsim_sweep.h"
 
 using namespace ffsim;
 
@@ -73,54 +74,14 @@ struct ff_chains {
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMeta::loc");
 
-typedef void (*batch_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const uint2*,
-                               uint32_t, u64*, Counters*, unsigned char*, size_t, const uint16_t*);
-typedef void (*chain_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, unsigned char*, size_t,
-                               uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, uint32_t*, SearchDev);
-
-// four layouts: task words in LDS (small graphs; never a level 2; up to 64 ops the whole queue in a register),
-// in HBM without, and with level 2;
-// each with or without the kept per-edge set-up
-template <bool WIDE, bool STATS, bool CACHE, bool EXT>
-static batch_kernel_t batch_kernel_of(const ff_sim* s) {
-    if (s->lds_words) return s->dev.n_ops <= 64 ? k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE, EXT> : k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE, EXT>;
-    return s->dev.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE, EXT> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE, EXT>;
+// ext: the launch uses the link table or explicit devices
+static KernelChoice choice(const ff_sim* s, bool cache, bool ext) {
+    return KernelChoice{s->wide, s->lds_words, s->d_stats != nullptr, cache, ext, s->dev.n_ops, s->dev.n_groups};
 }
-// the variant that also fills the per-candidate counters is only launched when they are asked for
-template <bool CACHE, bool EXT>
-static batch_kernel_t batch_kernel_c(const ff_sim* s) {
-    if (s->wide) return s->d_stats ? batch_kernel_of<true, true, CACHE, EXT>(s) : batch_kernel_of<true, false, CACHE, EXT>(s);
-    return s->d_stats ? batch_kernel_of<false, true, CACHE, EXT>(s) : batch_kernel_of<false, false, CACHE, EXT>(s);
-}
-// ext: the launch uses the link table or explicit devices (kernels of their own, which do not keep
-// the per-edge set-up in the batch form)
-static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = false) {
-    if (ext) return batch_kernel_c<false, true>(s);
-    return cached ? batch_kernel_c<true, false>(s) : batch_kernel_c<false, false>(s);
-}
-template <bool CACHE, bool EXT>
-static chain_kernel_t chain_kernel_c(const ff_sim* s) {
-    const bool tree = s->dev.n_groups > FLAT_GROUPS;
-    if (s->wide) return tree ? k_sim_chain_steps<true, true, CACHE, EXT> : k_sim_chain_steps<true, false, CACHE, EXT>;
-    return tree ? k_sim_chain_steps<false, true, CACHE, EXT> : k_sim_chain_steps<false, false, CACHE, EXT>;
-}
+static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = false) { return select_batch_kernel(choice(s, cached, ext)); }
 // chains keep the per-edge set-up in their own memory whenever the extents allow it
-static chain_kernel_t chain_kernel(const ff_sim* s) {
-    if (s->dev.link_table) return s->chain_cache ? chain_kernel_c<true, true>(s) : chain_kernel_c<false, true>(s);
-    return s->chain_cache ? chain_kernel_c<true, false>(s) : chain_kernel_c<false, false>(s);
-}
-typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, const uint32_t*, const uint32_t*, const unsigned char*, size_t,
-                             uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);
-template <bool CACHE, bool EXT>
-static try_kernel_t try_kernel_c(const ff_sim* s) {
-    const bool tree = s->dev.n_groups > FLAT_GROUPS;
-    if (s->wide) return tree ? k_sim_chain_try<true, true, CACHE, EXT> : k_sim_chain_try<true, false, CACHE, EXT>;
-    return tree ? k_sim_chain_try<false, true, CACHE, EXT> : k_sim_chain_try<false, false, CACHE, EXT>;
-}
-static try_kernel_t try_kernel(const ff_sim* s) {
-    if (s->dev.link_table) return s->chain_cache ? try_kernel_c<true, true>(s) : try_kernel_c<false, true>(s);
-    return s->chain_cache ? try_kernel_c<true, false>(s) : try_kernel_c<false, false>(s);
-}
+static chain_kernel_t chain_kernel(const ff_sim* s) { return select_chain_kernel(choice(s, s->chain_cache, s->dev.link_table != 0)); }
+static try_kernel_t try_kernel(const ff_sim* s) { return select_try_kernel(choice(s, s->chain_cache, s->dev.link_table != 0)); }
 
 static void release(ff_sim* s) {
     if (!s) return;
@@ -406,7 +367,7 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
     // Keeping the per-edge set-up costs LDS for graphs whose words live there; it is used unless it
     // would leave part of the batch waiting for a free compute unit that the plain variant has room for.
     const bool ext = s->dev.link_table || d_devmaps;
-    const bool cached = !ext && s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
+    const bool cached = s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
     const uint32_t slots = std::min(B, cached ? s->max_slots_cached : s->max_slots);
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;

@@ -356,12 +356,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                     wave_sync();
                     rebuild_l2(m);
                 }
-                if constexpr (EXT) {
-                    rc = run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
-                } else {
-                    rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
-                                                 : run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
-                }
+                rc = cls == STRATEGY_REGULAR ? run_events<WIDE, true, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
+                                             : run_events<WIDE, true, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
                 if (rc == RUN_CONVERGED) { converged = true; rc = 0; mk = meta.cur_ns; break; }
                 mk = rc ? rc : makespan(m);
                 if (rc) break;
@@ -491,13 +487,8 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
                     wave_sync();
                     rebuild_l2(m);
                 }
-                u64 rc;
-                if constexpr (EXT) {
-                    rc = run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
-                } else {
-                    rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
-                                                 : run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
-                }
+                const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, false, true, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec)
+                                                       : run_events<WIDE, false, false, false, TREE ? Q_TREE : Q_FLAT, CACHE>(m, cnt, rec);
                 mk = rc ? rc : makespan(m);
             }
         }
@@ -505,52 +496,5 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         wave_sync();
     }
 }
-
-// clears the work counter of k_sim_chain_try (a kernel, so that a captured stream sees a node)
-// ---- neighbour sweep (Section 8: is a strategy locally optimal?) --------------------------
-//
-// The neighbours of a strategy differ from it in the configuration of one op.  Neighbour k of
-// the enumeration: ops op_begin..op_end-1 in order; per op every degree tuple of its list, in
-// list order; per tuple every device offset 0..n_dev-1; stride 1.  first[o - op_begin] is the
-// index of the first neighbour of op o.  Writes the same mutation for every chain ([M][C]).
-__global__ __launch_bounds__(WAVE) void k_neighbour_list(const uint32_t* __restrict__ tuple_ptr, const uint32_t* __restrict__ tuples,
-                                                         const uint32_t* __restrict__ first, uint32_t op_begin, uint32_t op_end,
-                                                         uint32_t n_dev, uint32_t M, uint32_t C, uint32_t* __restrict__ muts) {
-    const uint32_t k = blockIdx.x * WAVE + threadIdx.x;
-    if (k >= M) return;
-    // binary search for the op whose range holds k
-    uint32_t lo = 0, hi = op_end - op_begin;       // first[lo] <= k < first[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) / 2;
-        if (first[mid] <= k) lo = mid; else hi = mid;
-    }
-    const uint32_t op = op_begin + lo;
-    const uint32_t r = k - first[lo];
-    const uint32_t deg = tuples[tuple_ptr[op] + r / n_dev];
-    const uint32_t off = r % n_dev;
-    for (uint32_t c = 0; c < C; c++) {
-        uint32_t* mu = muts + ((size_t)k * C + c) * 3;
-        mu[0] = op; mu[1] = deg; mu[2] = off | (1u << 16);
-    }
-}
-
-// per chain: the smallest time among its M results ([M][C]) and the lowest index that has it;
-// one wavefront per chain
-__global__ __launch_bounds__(WAVE) void k_best_of(const u64* __restrict__ ns, uint32_t M, uint32_t C, u64* __restrict__ best_ns,
-                                                  uint32_t* __restrict__ best_idx) {
-    const uint32_t c = blockIdx.x;
-    if (c >= C) return;
-    u64 b = ~0ull;
-    uint32_t bi = 0xffffffffu;
-    for (uint32_t k = lane_id(); k < M; k += WAVE) {
-        const u64 v = ns[(size_t)k * C + c];
-        if (v < b) { b = v; bi = k; }        // ascending k: the first index wins inside a lane
-    }
-    const u64 m = wave_min_u64(b);
-    const uint32_t mi = wave_min_u32(b == m ? bi : 0xffffffffu);
-    if (lane_id() == 0) { best_ns[c] = m; best_idx[c] = mi; }
-}
-
-__global__ void k_zero_u32(uint32_t* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
 
 }  // namespace ffsim

@@ -415,7 +415,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         uint32_t bw = same_node ? bw_intra : bw_inter;
                         uint32_t m_bw = same_node ? m_bw_intra : m_bw_inter;
                         uint32_t lat = same_node ? lat_intra : lat_inter;
-                        if (!REG && SimX::kExt && S.link_table) {
+                        if (SimX::kExt && S.link_table) {
                             // links inside a node that are not all alike: the pair's own figures
                             if (comm && same_node) {
                                 const uint4 t = m.links[(dev_a - node_a * G) * G + local_c];

@@ -19,7 +19,9 @@
 //
 // Files: ffsim_device.h (word encoding, wavefront primitives), ffsim_strategy.h (configurations,
 // geometry, kept per-edge set-up, validity), ffsim_events.h (FIFO, recording, initial state, event
-// loop), this file (the batch kernel), ffsim_chain.h (delta simulation, search, neighbour sweep).
+// loop), this file (the batch kernel), ffsim_chain.h (delta simulation, search), ffsim_sweep.h
+// (neighbour list and reduction), ffsim_select.h + ffsim_k_*.hip (the instantiations, compiled
+// side by side), ffsim.hip (host side of the C boundary).
 #pragma once
 #include "ffsim_events.h"
 
@@ -38,13 +40,8 @@ __device__ u64 simulate_candidate(SimX& m, Counters& cnt, Recorder& rec) {
 #ifdef FFSIM_PROFILE
     cnt.exit_code = __builtin_readcyclecounter() - prof_t0;   // reported as section 0
 #endif
-    u64 rc;
-    if constexpr (SimX::kExt) {
-        rc = run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
-    } else {
-        rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, Q, CACHE>(m, cnt, rec)
-                                     : run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
-    }
+    const u64 rc = cls == STRATEGY_REGULAR ? run_events<WIDE, RECORD, true, STATS, Q, CACHE>(m, cnt, rec)
+                                            : run_events<WIDE, RECORD, false, STATS, Q, CACHE>(m, cnt, rec);
     if (rc) return rc;
     if (STATS) {   // diagnostics: tasks that never ran (0 in a correct run)
         for (uint32_t j = 0; j < m.S.n_ops; j++) cnt.n_stuck += __popcll(ballot(m.words[j * WAVE + lane_id()] != W_NONE));

@@ -206,8 +206,8 @@ __device__ __forceinline__ uint32_t owner_part(uint32_t x, uint32_t E, uint32_t 
 // OVR: one op's configuration may be overridden (trial mutations); the plain form does not
 // pay for the comparison.
 // EXT: the refinements of the inputs that only some callers use -- links inside a node that
-// differ per pair, explicit devices per task -- are compiled into kernels of their own, which
-// always run the general event loop; the plain kernels carry none of it.
+// differ per pair, explicit devices per task -- are compiled into kernels of their own; the
+// plain kernels carry none of it.
 template <bool OVR, bool EXT = false>
 struct SimT {
     const SimDev& S;
@@ -388,7 +388,7 @@ __device__ __forceinline__ StrategyClass validate_strategy(const SimX& m) {
             for (uint32_t k = 0; k < c.parts; k++) bad = bad || m.devmap[(size_t)i * WAVE + k] >= m.S.n_dev;
     }
     if (ballot(bad)) return STRATEGY_INVALID;
-    if (SimX::kExt) return STRATEGY_GENERAL;
+    if (SimX::kExt && m.devmap) return STRATEGY_GENERAL;      // the regular form assumes consecutive devices
     return (ballot(irregular) || m.S.gpus_per_node > MAX_RUN) ? STRATEGY_GENERAL : STRATEGY_REGULAR;
 }
 

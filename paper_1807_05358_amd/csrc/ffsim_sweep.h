@@ -1,0 +1,56 @@
+// Small kernels around the trial-mutation kernel: the list of a strategy's neighbours, the
+// reduction over their times, and a counter reset.  Included by the host file only (the
+// kernels here are not templates: one definition in the library).
+#pragma once
+#include "ffsim_device.h"
+
+namespace ffsim {
+
+// ---- neighbour sweep (Section 8: is a strategy locally optimal?) --------------------------
+//
+// The neighbours of a strategy differ from it in the configuration of one op.  Neighbour k of
+// the enumeration: ops op_begin..op_end-1 in order; per op every degree tuple of its list, in
+// list order; per tuple every device offset 0..n_dev-1; stride 1.  first[o - op_begin] is the
+// index of the first neighbour of op o.  Writes the same mutation for every chain ([M][C]).
+__global__ __launch_bounds__(WAVE) void k_neighbour_list(const uint32_t* __restrict__ tuple_ptr, const uint32_t* __restrict__ tuples,
+                                                         const uint32_t* __restrict__ first, uint32_t op_begin, uint32_t op_end,
+                                                         uint32_t n_dev, uint32_t M, uint32_t C, uint32_t* __restrict__ muts) {
+    const uint32_t k = blockIdx.x * WAVE + threadIdx.x;
+    if (k >= M) return;
+    // binary search for the op whose range holds k
+    uint32_t lo = 0, hi = op_end - op_begin;       // first[lo] <= k < first[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) / 2;
+        if (first[mid] <= k) lo = mid; else hi = mid;
+    }
+    const uint32_t op = op_begin + lo;
+    const uint32_t r = k - first[lo];
+    const uint32_t deg = tuples[tuple_ptr[op] + r / n_dev];
+    const uint32_t off = r % n_dev;
+    for (uint32_t c = 0; c < C; c++) {
+        uint32_t* mu = muts + ((size_t)k * C + c) * 3;
+        mu[0] = op; mu[1] = deg; mu[2] = off | (1u << 16);
+    }
+}
+
+// per chain: the smallest time among its M results ([M][C]) and the lowest index that has it;
+// one wavefront per chain
+__global__ __launch_bounds__(WAVE) void k_best_of(const u64* __restrict__ ns, uint32_t M, uint32_t C, u64* __restrict__ best_ns,
+                                                  uint32_t* __restrict__ best_idx) {
+    const uint32_t c = blockIdx.x;
+    if (c >= C) return;
+    u64 b = ~0ull;
+    uint32_t bi = 0xffffffffu;
+    for (uint32_t k = lane_id(); k < M; k += WAVE) {
+        const u64 v = ns[(size_t)k * C + c];
+        if (v < b) { b = v; bi = k; }        // ascending k: the first index wins inside a lane
+    }
+    const u64 m = wave_min_u64(b);
+    const uint32_t mi = wave_min_u32(b == m ? bi : 0xffffffffu);
+    if (lane_id() == 0) { best_ns[c] = m; best_idx[c] = mi; }
+}
+
+// clears the work counter of k_sim_chain_try (a kernel, so that a captured stream sees a node)
+__global__ void k_zero_u32(uint32_t* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
+
+}  // namespace ffsim
