@@ -7,7 +7,10 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-UNITS = ["ffsim.hip", "ffsim_k_batch.hip", "ffsim_k_batch_ext.hip", "ffsim_k_chain.hip", "ffsim_k_try.hip"]
+HOST_UNIT = "ffsim.hip"
+KERNEL_UNITS = ["ffsim_k_batch.hip", "ffsim_k_chain.hip", "ffsim_k_try.hip"]   # each compiled per (EXT, GPN)
+VARIANTS = [(0, 4), (0, 0), (1, 4), (1, 0)]
+UNITS = [HOST_UNIT] + KERNEL_UNITS
 HEADERS = ["ffsim_select.h", "ffsim_sweep.h", "ffsim_kernels.h", "ffsim_chain.h", "ffsim_events.h", "ffsim_strategy.h",
            "ffsim_device.h"]
 OBJ_DIR = os.path.join(HERE, "_build")
@@ -26,12 +29,20 @@ def build_library(force: bool = True) -> str:
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ_DIR, exist_ok=True)
-    objs, procs = [], []
-    for u in UNITS:
-        obj = os.path.join(OBJ_DIR, os.path.splitext(u)[0] + ".o")
-        objs.append(obj)
-        procs.append((u, subprocess.Popen([hipcc, *HIPCC_FLAGS, "-c", "-o", obj, os.path.join(CSRC, u)])))
-    failed = [u for u, p in procs if p.wait() != 0]
+    jobs = [(HOST_UNIT, [], "ffsim.o")]
+    for ext, gpn in VARIANTS:
+        for u in KERNEL_UNITS:
+            jobs.append((u, [f"-DFFSIM_EXT={ext}", f"-DFFSIM_GPN={gpn}"], f"{os.path.splitext(u)[0]}_e{ext}_g{gpn}.o"))
+    objs = [os.path.join(OBJ_DIR, o) for _, _, o in jobs]
+    workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1))))
+    running, failed, todo = [], [], list(zip(jobs, objs))
+    while todo or running:
+        while todo and len(running) < workers:
+            (u, defs, _), obj = todo.pop(0)
+            running.append((u + " " + " ".join(defs), subprocess.Popen([hipcc, *HIPCC_FLAGS, *defs, "-c", "-o", obj, os.path.join(CSRC, u)])))
+        name, p = running.pop(0)
+        if p.wait() != 0:
+            failed.append(name)
     if failed:
         raise RuntimeError("hipcc failed on " + ", ".join(failed))
     subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])

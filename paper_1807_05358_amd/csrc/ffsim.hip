@@ -74,14 +74,29 @@ struct ff_chains {
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMeta::loc");
 
-// ext: the launch uses the link table or explicit devices
-static KernelChoice choice(const ff_sim* s, bool cache, bool ext) {
-    return KernelChoice{s->wide, s->lds_words, s->d_stats != nullptr, cache, ext, s->dev.n_ops, s->dev.n_groups};
+static KernelChoice choice(const ff_sim* s, bool cache) {
+    return KernelChoice{s->wide, s->lds_words, s->d_stats != nullptr, cache, s->dev.n_ops, s->dev.n_groups};
 }
-static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = false) { return select_batch_kernel(choice(s, cached, ext)); }
+// ext: the launch uses the link table or explicit devices.  Machines with four GPUs per node (all
+// benchmark configurations) have kernels compiled for that node size.
+static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = false) {
+    const KernelChoice k = choice(s, cached);
+    if (s->dev.gpus_per_node == 4) return ext ? batch_kernels<true, 4>(k) : batch_kernels<false, 4>(k);
+    return ext ? batch_kernels<true, 0>(k) : batch_kernels<false, 0>(k);
+}
 // chains keep the per-edge set-up in their own memory whenever the extents allow it
-static chain_kernel_t chain_kernel(const ff_sim* s) { return select_chain_kernel(choice(s, s->chain_cache, s->dev.link_table != 0)); }
-static try_kernel_t try_kernel(const ff_sim* s) { return select_try_kernel(choice(s, s->chain_cache, s->dev.link_table != 0)); }
+static chain_kernel_t chain_kernel(const ff_sim* s) {
+    const KernelChoice k = choice(s, s->chain_cache);
+    const bool ext = s->dev.link_table != 0;
+    if (s->dev.gpus_per_node == 4) return ext ? chain_kernels<true, 4>(k) : chain_kernels<false, 4>(k);
+    return ext ? chain_kernels<true, 0>(k) : chain_kernels<false, 0>(k);
+}
+static try_kernel_t try_kernel(const ff_sim* s) {
+    const KernelChoice k = choice(s, s->chain_cache);
+    const bool ext = s->dev.link_table != 0;
+    if (s->dev.gpus_per_node == 4) return ext ? try_kernels<true, 4>(k) : try_kernels<false, 4>(k);
+    return ext ? try_kernels<true, 0>(k) : try_kernels<false, 0>(k);
+}
 
 static void release(ff_sim* s) {
     if (!s) return;

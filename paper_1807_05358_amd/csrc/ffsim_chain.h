@@ -222,8 +222,8 @@ __device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, 
 // later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
 // step s.
 // CACHE: the chain keeps the per-edge set-up of its current strategy (all extents fit 16 bits).
-// EXT: with the table of links inside a node.
-template <bool WIDE, bool TREE, bool CACHE, bool EXT>
+// EXT: with the table of links inside a node.  GPN: compiled for this many GPUs per node (0 = any).
+template <bool WIDE, bool TREE, bool CACHE, bool EXT, int GPN>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                           const uint32_t* __restrict__ magic, unsigned char* chain_mem,
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.loc = first_u32(meta.loc);
     meta.tag = first_u32(meta.tag);
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
-    SimT<false, EXT> m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
+    SimT<false, EXT, GPN> m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
     if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
@@ -435,7 +435,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 // single-op mutations per chain, each against the chain's current strategy and stored
 // timeline, without changing the chain.  One wavefront per (proposal, chain); its task words
 // live in a private workspace slot, the chain's snapshots are only read.
-template <bool WIDE, bool TREE, bool CACHE, bool EXT>
+template <bool WIDE, bool TREE, bool CACHE, bool EXT, int GPN>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                         const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                         const uint32_t* __restrict__ magic, const unsigned char* __restrict__ chain_mem,
@@ -470,7 +470,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
         u64 mk = RESULT_INVALID;
         if (op < S.n_ops && first_u32(chain_flags[c]) == 0) {
             const uint2 ocfg = cm.cfgs[op];
-            SimT<true, EXT> m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
+            SimT<true, EXT, GPN> m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
                               CACHE ? cm.ecache : nullptr, false};
             if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
             const StrategyClass cls = validate_strategy(m);

@@ -353,7 +353,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             // the parts in `mask` finished at `now`: release their successors edge by edge
             DEdge e = opi_p->first;
             const Box pb = part_box(e.src_extent, ci, lane, magic_v);
-            const uint32_t node_p = div_magic(dev_p, S.magic_gpn, S.pass_gpn);
+            const uint32_t node_p = m.node_of(dev_p);
             for (uint32_t ei = out_begin; ei < out_end; ei++) {
                 if (ei != out_begin) e = edges[ei];
                 const uint32_t j = e.dst;
@@ -371,8 +371,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
 #pragma unroll
                 for (int d = 0; d < 4; d++) { nlo[d] = el.nlo[d]; nhi[d] = el.nhi[d]; }
                 const uint32_t dev_c = el.dev_c, node_c = el.node_c;
-                const uint32_t local_c = dev_c - node_c * S.gpus_per_node;
-                const uint32_t G = S.gpus_per_node;
+                const uint32_t local_c = m.local_of(dev_c, node_c);
+                const uint32_t G = m.gpn();
                 const uint32_t pos = el.pos, first_len = el.first_len, last_run_mask = el.last_run_mask;
                 const bool run_end = el.run_end, wrapped = el.wrapped;
                 u64 ready = w & (TIME_LIMIT - 1);
@@ -407,7 +407,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         const bool same_node = node_c == node_a;
                         // Section 5.1: the link device between the two devices.  The producer's share of
                         // the row index is scalar; per lane one select between two sums.
-                        const uint32_t row_intra = S.n_dev + node_a * G * G + (dev_a - node_a * G) * G;
+                        // (node * G * G + local * G = device * G)
+                        const uint32_t row_intra = S.n_dev + dev_a * G;
                         const uint32_t row_inter = S.n_dev + S.n_nodes * G * G + node_a * S.n_nodes;
                         const uint32_t to_intra = row_intra + local_c, to_inter = row_inter + node_c;
                         const uint32_t row = same_node ? to_intra : to_inter;
@@ -418,7 +419,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         if (SimX::kExt && S.link_table) {
                             // links inside a node that are not all alike: the pair's own figures
                             if (comm && same_node) {
-                                const uint4 t = m.links[(dev_a - node_a * G) * G + local_c];
+                                const uint4 t = m.links[m.local_of(dev_a, node_a) * G + local_c];
                                 bw = t.x; m_bw = t.y; lat = t.z;
                             }
                         }

@@ -1,7 +1,28 @@
-// Batch kernels without the refinements of the inputs (the ones the benchmark configurations run).
+// Batch kernels; compiled once per (FFSIM_EXT, FFSIM_GPN).
 #include "ffsim_select.h"
 
+#if !defined(FFSIM_EXT) || !defined(FFSIM_GPN)
+#error "define FFSIM_EXT (0/1) and FFSIM_GPN (0/4)"
+#endif
+
 namespace ffsim {
-batch_kernel_t select_batch_kernel_plain(const KernelChoice& k) { return batch_kernel_any<false>(k); }
-batch_kernel_t select_batch_kernel(const KernelChoice& k) { return k.ext ? select_batch_kernel_ext(k) : select_batch_kernel_plain(k); }
+
+template <bool WIDE, bool STATS, bool CACHE>
+static batch_kernel_t batch_kernel_of(const KernelChoice& k) {
+    constexpr bool EXT = FFSIM_EXT;
+    constexpr int GPN = FFSIM_GPN;
+    if (k.lds_words) return k.n_ops <= 64 ? k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE, EXT, GPN> : k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE, EXT, GPN>;
+    return k.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE, EXT, GPN> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE, EXT, GPN>;
+}
+
+template <>
+batch_kernel_t batch_kernels<FFSIM_EXT, FFSIM_GPN>(const KernelChoice& k) {
+    if (k.cache) {
+        if (k.wide) return k.stats ? batch_kernel_of<true, true, true>(k) : batch_kernel_of<true, false, true>(k);
+        return k.stats ? batch_kernel_of<false, true, true>(k) : batch_kernel_of<false, false, true>(k);
+    }
+    if (k.wide) return k.stats ? batch_kernel_of<true, true, false>(k) : batch_kernel_of<true, false, false>(k);
+    return k.stats ? batch_kernel_of<false, true, false>(k) : batch_kernel_of<false, false, false>(k);
+}
+
 }  // namespace ffsim

@@ -60,7 +60,8 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 // LDSW: the task words and per-op exeTimes of the candidate live in LDS (small graphs).
 // CACHE: the per-edge set-up is kept (after the task words: in LDS if LDSW, else in the slot).
 // EXT: with the link table and / or explicit devices (devmaps, else null and never read).
-template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE, bool EXT>
+// GPN: compiled for machines with this many GPUs per node (0 = any).
+template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE, bool EXT, int GPN>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
     Recorder none = {};
     for (uint32_t b = blockIdx.x; b < B; b += gridDim.x) {
         Counters cnt = {};
-        SimT<false, EXT> m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
+        SimT<false, EXT, GPN> m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
         if (EXT) {
             m.links = (const uint4*)(magic + LINK_TABLE_AT);
             if (devmaps) m.devmap = devmaps + (size_t)b * S.n_ops * WAVE;

@@ -208,7 +208,10 @@ __device__ __forceinline__ uint32_t owner_part(uint32_t x, uint32_t E, uint32_t 
 // EXT: the refinements of the inputs that only some callers use -- links inside a node that
 // differ per pair, explicit devices per task -- are compiled into kernels of their own; the
 // plain kernels carry none of it.
-template <bool OVR, bool EXT = false>
+// GPN: the machine's number of GPUs per node when the kernel is compiled for one (4: node and
+// local index of a device are a shift and a mask, and three scalars fewer stay alive in the
+// event loop), 0 = any.
+template <bool OVR, bool EXT = false, int GPN = 0>
 struct SimT {
     const SimDev& S;
     const Tables& T;
@@ -228,6 +231,14 @@ struct SimT {
     const uint16_t* devmap = nullptr;    // [n_ops][64] device of every part given explicitly, or null
     static constexpr bool kOvr = OVR;
     static constexpr bool kExt = EXT;
+    static_assert(GPN == 0 || GPN == 4, "compiled node sizes");
+    __device__ __forceinline__ uint32_t gpn() const { return GPN ? (uint32_t)GPN : S.gpus_per_node; }
+    __device__ __forceinline__ uint32_t node_of(uint32_t dev) const {
+        return GPN == 4 ? dev >> 2 : div_magic(dev, S.magic_gpn, S.pass_gpn);
+    }
+    __device__ __forceinline__ uint32_t local_of(uint32_t dev, uint32_t node) const {
+        return GPN == 4 ? (dev & 3u) : dev - node * S.gpus_per_node;
+    }
     __device__ __forceinline__ uint2 cfg_raw(uint32_t j) const {
         uint2 c = cfgs[j];
         if (OVR && j == ov_op) c = ov_cfg;
@@ -273,21 +284,21 @@ __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, con
         el.nlo[d] = 0; el.nhi[d] = 1;
         if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, m.magic_v, el.nlo[d], el.nhi[d]);
     }
-    const uint32_t G = S.gpus_per_node;
+    const uint32_t G = m.gpn();
     // the run fields only depend on the consumer's own configuration: filled whenever it puts its
     // parts on consecutive, distinct devices, whatever the other ops do
     const bool consecutive = cj.stride == 1 && cj.parts <= S.n_dev && G <= MAX_RUN && !(SimX::kExt && m.devmap);
     el.dev_c = consecutive ? part_device<true>(cj, lane, S) : m.template device_of<false>(e.dst, cj);
-    el.node_c = div_magic(el.dev_c, S.magic_gpn, S.pass_gpn);
+    el.node_c = m.node_of(el.dev_c);
     el.pos = 0; el.first_len = 0; el.last_run_mask = 0; el.run_end = false; el.wrapped = false;
     if (consecutive) {
-        const uint32_t node0 = div_magic(cj.off, S.magic_gpn, S.pass_gpn);
+        const uint32_t node0 = m.node_of(cj.off);
         const uint32_t room = G - (cj.off - node0 * G);              // lanes of the first run
         el.first_len = cj.parts < room ? cj.parts : room;
-        const uint32_t local_c = el.dev_c - el.node_c * G;
+        const uint32_t local_c = m.local_of(el.dev_c, el.node_c);
         el.pos = (uint32_t)lane < el.first_len ? (uint32_t)lane : local_c;    // index inside the run
         const uint32_t last = cj.off + cj.parts - 1;
-        el.wrapped = last >= S.n_dev && div_magic(last - S.n_dev, S.magic_gpn, S.pass_gpn) == node0;
+        el.wrapped = last >= S.n_dev && m.node_of(last - S.n_dev) == node0;
         el.last_run_mask = (el.wrapped && (uint32_t)lane >= el.first_len && el.node_c == node0) ? 0xffffffffu : 0u;
         el.run_end = el.mine && ((uint32_t)lane == cj.parts - 1 || local_c == G - 1) &&
                      !(el.wrapped && (uint32_t)lane == el.first_len - 1);
@@ -389,7 +400,7 @@ __device__ __forceinline__ StrategyClass validate_strategy(const SimX& m) {
     }
     if (ballot(bad)) return STRATEGY_INVALID;
     if (SimX::kExt && m.devmap) return STRATEGY_GENERAL;      // the regular form assumes consecutive devices
-    return (ballot(irregular) || m.S.gpus_per_node > MAX_RUN) ? STRATEGY_GENERAL : STRATEGY_REGULAR;
+    return (ballot(irregular) || m.gpn() > MAX_RUN) ? STRATEGY_GENERAL : STRATEGY_REGULAR;
 }
 
 }  // namespace ffsim
