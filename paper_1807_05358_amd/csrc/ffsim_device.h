@@ -68,6 +68,17 @@ struct SimDev {
 // floor(2^32 / bandwidth), latency (ns), 0.
 constexpr uint32_t LINK_TABLE_AT = 128;
 
+// the per-lane condition "my bit of this lane mask is set" (the mask is used as it is)
+__device__ __forceinline__ bool lanes_of(u64 mask) { return __builtin_amdgcn_inverse_ballot_w64(mask); }
+
+// a uniform value placed in a vector register, opaque to the compiler (which would otherwise copy
+// it from its scalar register again at every use)
+__device__ __forceinline__ uint32_t vector_copy(uint32_t uniform) {
+    uint32_t v;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(v) : "s"(uniform));
+    return v;
+}
+
 __device__ __forceinline__ int lane_id() { return (int)threadIdx.x & (WAVE - 1); }
 
 // Orders LDS traffic between the lanes of the (single-wavefront) workgroup.  LDS operations

@@ -277,9 +277,11 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     // Values chosen per lane between two of these (same node or not) must sit in registers: a
     // select between two fields of the argument block is otherwise turned into a per-lane load
     // from that block, a vector memory round trip for every producer part.
-    const uint32_t bw_intra = first_u32(S.bw_intra), bw_inter = first_u32(S.bw_inter);
-    const uint32_t m_bw_intra = first_u32(S.m_bw_intra), m_bw_inter = first_u32(S.m_bw_inter);
-    const uint32_t lat_intra = first_u32(S.lat_intra), lat_inter = first_u32(S.lat_inter);
+    // They are kept in vector registers for the whole loop: a select then is one instruction (it can
+    // read only one scalar operand, the lane mask), and six scalar registers stay free.
+    const uint32_t bw_intra = vector_copy(S.bw_intra), bw_inter = vector_copy(S.bw_inter);
+    const uint32_t m_bw_intra = vector_copy(S.m_bw_intra), m_bw_inter = vector_copy(S.m_bw_inter);
+    const uint32_t lat_intra = vector_copy(S.lat_intra), lat_inter = vector_copy(S.lat_inter);
     const u64 max_events = 2ull * S.n_ops * WAVE + 8;   // every task is popped at most twice
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
@@ -374,16 +376,20 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 const uint32_t local_c = m.local_of(dev_c, node_c);
                 const uint32_t G = m.gpn();
                 const uint32_t pos = el.pos, first_len = el.first_len, last_run_mask = el.last_run_mask;
-                const bool run_end = el.run_end, wrapped = el.wrapped;
+                const bool wrapped = el.wrapped;
+                const u64 run_end_m = REG ? ballot(el.run_end) : 0;
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
-                bool touched = false;
+                // Which lanes take part is kept as 64-bit lane masks and combined with scalar
+                // instructions; a per-lane condition is made from a mask only where a lane acts on it.
+                const u64 mine_m = ballot(mine);
+                u64 touched_m = 0;
                 u64 todo = mask;
                 PROF_MARK(3)
                 while (todo) {
                     const int kp = __builtin_ctzll(todo);
                     todo &= todo - 1;
-                    bool hit = mine;
+                    u64 hit_m = mine_m;
                     u64 elems = 1;
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
@@ -391,20 +397,20 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             const int32_t plo = (int32_t)readlane_u32(pb.lo[d], kp), phi = (int32_t)readlane_u32(pb.hi[d], kp);
                             const int32_t lo = nlo[d] > plo ? nlo[d] : plo;
                             const int32_t hi = nhi[d] < phi ? nhi[d] : phi;
-                            hit = hit && hi > lo;
+                            hit_m &= ballot(hi > lo);
                             if (WIDE) elems *= (u64)(uint32_t)(hi > lo ? hi - lo : 0);
                             else elems = (uint32_t)elems * (uint32_t)(hi > lo ? hi - lo : 0);
                         }
                     }
-                    const u64 hit_mask = ballot(hit);
-                    if (!hit_mask) continue;
+                    if (!hit_m) continue;
                     const uint32_t dev_a = readlane_u32(dev_p, kp);
                     const uint32_t node_a = readlane_u32(node_p, kp);
-                    const bool comm = hit && dev_c != dev_a;
-                    const u64 comm_mask = ballot(comm);
+                    const u64 comm_mask = hit_m & ballot(dev_c != dev_a);
+                    const bool comm = lanes_of(comm_mask);
                     u64 arrive = now;
                     if (comm_mask) {
-                        const bool same_node = node_c == node_a;
+                        const u64 same_m = ballot(node_c == node_a);
+                        const bool same_node = lanes_of(same_m);
                         // Section 5.1: the link device between the two devices.  The producer's share of
                         // the row index is scalar; per lane one select between two sums.
                         // (node * G * G + local * G = device * G)
@@ -436,7 +442,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         if (REG) {
                             const u64 f = L.free_at[row];                  // in range for every lane
                             const u64 base = f > now ? f : now;            // the same for all lanes of a row
-                            const bool chained = comm && !same_node;       // rows between GPUs of one node are private
+                            const bool chained = lanes_of(comm_mask & ~same_m);   // rows between GPUs of one node are private
                             u64 incl;
                             if (!WIDE) {
                                 // a row's running sum of transfer times cannot reach 2^32 (the host
@@ -462,7 +468,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                                 }
                             }
                             end = base + (same_node ? ns : incl);
-                            if (same_node ? comm : (run_end && incl != 0)) L.free_at[row] = end;
+                            const u64 write_m = (comm_mask & same_m) | (run_end_m & ~same_m & ballot(incl != 0));
+                            if (lanes_of(write_m)) L.free_at[row] = end;
                             wave_sync();
                         } else {
                             end = fifo_commit(comm, row, ns, now, true, L);
@@ -473,14 +480,15 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             if (comm) cnt.sum_comm_ns += ns;   // per-lane partial sums, reduced by the caller
                         }
                     }
-                    if (hit) {
+                    if (lanes_of(hit_m)) {
                         ready = arrive > ready ? arrive : ready;
                         pending -= 1;
-                        touched = true;
                     }
-                    if (STATS) cnt.n_pairs += __popcll(hit_mask);
+                    touched_m |= hit_m;
+                    if (STATS) cnt.n_pairs += __popcll(hit_m);
                 }
                 PROF_MARK(4)
+                const bool touched = lanes_of(touched_m);
                 overflow = overflow || (touched && ready >= TIME_LIMIT);
                 const bool now_ready = touched && pending == 0;
                 if (touched) {
