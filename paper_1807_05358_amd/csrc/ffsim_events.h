@@ -340,7 +340,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         if (!mask) { cnt.exit_code = 2; return RESULT_INTERNAL; }
         cnt.n_events++;
         const u64 now = kmin >> 1;
-        const bool in_mask = (mask >> lane) & 1;
+        const bool in_mask = lanes_of(mask);
         const uint32_t dev_p = m.template device_of<REG>(i, ci);
 
         if (kmin & 1) {
