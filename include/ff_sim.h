@@ -41,6 +41,11 @@ enum {
 #define FF_MAX_OPS 4096
 #define FF_MAX_EXTENT (1u << 20)
 #define FF_MAX_DEVICES 1024
+/* Graph and machine together must also fit one workgroup's LDS (160 KB on gfx950), else
+ * ff_sim_create returns FF_ERANGE: 16 * ceil(n_ops / 64) * 64 + 9 * R + 1040 bytes, where
+ * R = n_devices + n_nodes * gpus_per_node^2 + n_nodes^2 is the number of device rows (compute
+ * devices, links inside nodes, links between nodes).  Examples that fit: 4096 ops on 16 x 4
+ * devices; any graph of up to 1024 ops on 64 x 4 or 120 x 1 devices. */
 #define FF_MAX_MAP_STRIDE 1024       /* ff_dimmap_t.stride */
 #define FF_MAX_MAP_OFFSET (1 << 29)  /* |ff_dimmap_t.a|, |ff_dimmap_t.b| */
 #define FF_MAX_IN_EDGES 511          /* tensor edges into one op */

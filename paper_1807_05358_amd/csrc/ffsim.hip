@@ -98,6 +98,13 @@ static try_kernel_t try_kernel(const ff_sim* s) {
     return ext ? try_kernels<true, 0>(k) : try_kernels<false, 0>(k);
 }
 
+// A launch with more than 64 KB of dynamic LDS (gfx950 allows a workgroup up to 160 KB) has to be
+// announced for the kernel first.
+static bool allow_lds(const void* kernel, size_t bytes) {
+    if (bytes <= 64 * 1024) return true;
+    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) == hipSuccess;
+}
+
 static void release(ff_sim* s) {
     if (!s) return;
     hipFree(s->d_ops); hipFree(s->d_edges); hipFree(s->d_in_edges); hipFree(s->d_cost); hipFree(s->d_magic);
@@ -249,7 +256,12 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     s->slot_bytes = (slot_bytes(S.n_ops, S.n_ops_pad) + 255) & ~(size_t)255;
     s->lds_common = lds_common_bytes(S.n_rows, S.n_ops_pad);
     s->lds_chain = s->lds_common + (size_t)S.n_ops_pad * 8;
-    if (s->lds_chain > 64 * 1024) { release(s); return FF_ERANGE; }
+    int dev_id = 0, cus = 0, per_cu = 0, lds_limit = 0;
+    if (hipGetDevice(&dev_id) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev_id) != hipSuccess ||
+        hipDeviceGetAttribute(&lds_limit, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id) != hipSuccess) { release(s); return FF_EHIP; }
+    // device rows, queue levels and (chains) the strategy of one candidate must fit a workgroup's LDS
+    if (s->lds_chain > (size_t)lds_limit) { release(s); return FF_ERANGE; }
     // small graphs keep a candidate's task words in LDS, as long as four wavefronts (one per
     // SIMD) still fit in a CU's 160 KB
     const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_common;
@@ -268,9 +280,8 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         }
     }
 
-    int dev_id = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev_id) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev_id) != hipSuccess) { release(s); return FF_EHIP; }
+    if (!allow_lds((const void*)batch_kernel(s, false), s->lds) || !allow_lds((const void*)try_kernel(s), s->lds_common) ||
+        (s->cache_ok && !allow_lds((const void*)batch_kernel(s, true), s->lds_cached))) { release(s); return FF_EHIP; }
     hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, batch_kernel(s, false), WAVE, s->lds);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_slots = (uint32_t)cus * (uint32_t)per_cu;
@@ -387,6 +398,7 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     static_assert(sizeof(Counters) == sizeof(ff_stats_t), "stats layout");
+    if (!allow_lds((const void*)batch_kernel(s, cached, ext), cached ? s->lds_cached : s->lds)) return FF_EHIP;
     hipLaunchKernelGGL(batch_kernel(s, cached, ext), dim3(slots), dim3(WAVE), cached ? s->lds_cached : s->lds, st, s->dev, s->d_ops,
                        s->d_edges, s->d_in_edges, s->d_cost, s->d_magic, (const uint2*)d_strategies, B, (u64*)d_out_ns,
                        (Counters*)s->d_stats, (unsigned char*)s->ws, s->batch_slot_bytes, d_devmaps);
@@ -407,6 +419,7 @@ static int launch_chain_steps(ff_chains* c, const ff_mutation_t* d_muts, uint32_
                               const SearchDev& search) {
     ff_sim* s = c->sim;
     static_assert(sizeof(ff_mutation_t) == 12, "mutation layout");
+    if (!allow_lds((const void*)chain_kernel(s), s->lds_chain)) return FF_EHIP;
     hipLaunchKernelGGL(chain_kernel(s), dim3(c->C), dim3(WAVE), s->lds_chain, st, s->dev, s->d_ops, s->d_edges, s->d_in_edges,
                        s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, n_steps,
                        (u64*)d_out, c->d_flags, search);
@@ -550,6 +563,7 @@ int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, ui
     const uint32_t slots = std::min(total, s->max_try_slots);
     if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
     hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(WAVE), 0, (hipStream_t)hip_stream, c->d_counter);
+    if (!allow_lds((const void*)try_kernel(s), s->lds_common)) return FF_EHIP;
     hipLaunchKernelGGL(try_kernel(s), dim3(slots), dim3(WAVE), s->lds_common, (hipStream_t)hip_stream, s->dev, s->d_ops, s->d_edges,
                        s->d_in_edges, s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, M,
                        (u64*)d_out_ns, c->d_flags, c->d_counter, (unsigned char*)s->ws, s->slot_bytes);

@@ -608,3 +608,65 @@ def test_tuple_cost_argument_errors(B):
         B.ff_sim_create_tuplecost(w.ops, w.edges, w.machine, p2, tup, ns)
     h = B.ff_sim_create_tuplecost(w.ops, w.edges, w.machine, ptr, tup, ns)
     B.ff_sim_destroy(h)
+
+
+def test_largest_graph_and_largest_machines(B):
+    """the limits of the boundary: FF_MAX_OPS ops (64 groups in the queue's upper level), extents of
+    FF_MAX_EXTENT (too large for the kept per-edge set-up), a machine whose device rows nearly
+    fill a workgroup's 160 KB of LDS, a node with more GPUs than the regular event loop handles;
+    and machines beyond the limit are refused."""
+    rng = np.random.default_rng(77)
+    ops, edges, _ = random_graph(rng, 4096)
+    assert len(ops) == 4096
+    mach = W.Machine(16, 4, 7, 3, 11, 29, 2)
+    cost = rng.integers(1, 3000, size=(4096, 64)).astype("<u4")
+    n = 6
+    cfgs = np.zeros((n, 4096), W.CFG_DT)
+    for i in range(4096):
+        t = W.valid_degree_tuples(ops[i], 64, (1, 2, 3, 4, 8, 16, 64))
+        cfgs["deg"][:, i] = t[rng.integers(len(t), size=n)]
+    cfgs["dev_offset"] = rng.integers(0, mach.n_devices, size=(n, 4096))
+    cfgs["dev_stride"] = 1
+    cfgs["dev_stride"][n // 2:] = rng.integers(0, 4, size=(n - n // 2, 4096))
+    sim = B.Simulator(ops, edges, mach, cost)
+    got, st = sim.simulate(cfgs, stats=True)
+    assert not st["exit_code"].any() and not st["n_stuck"].any()
+    assert np.array_equal(got, oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8))
+    muts = np.zeros((4, 1), W.MUT_DT)
+    muts["op"][:, 0] = [4095, 0, 2048, 4095]
+    for s in range(4):
+        i = int(muts[s, 0]["op"])
+        t = W.valid_degree_tuples(ops[i], 64, (1, 2, 4, 8))
+        muts[s, 0]["cfg"]["deg"] = t[rng.integers(len(t))]
+        muts[s, 0]["cfg"]["dev_offset"] = rng.integers(0, mach.n_devices)
+        muts[s, 0]["cfg"]["dev_stride"] = 1
+    ch = B.Chains(sim, cfgs[:1])
+    d = ch.delta(ch.upload_mutations(muts), 4).cpu().numpy().view("<u8")
+    assert np.array_equal(d[:, 0], oracle.simulate_delta_chain(ops, edges, mach, cost, cfgs[0], muts[:, 0]))
+    ch.close()
+    sim.close()
+
+    # extents at the limit on a 64 x 4 machine (5376 device rows), on 2 x 32 (general loop only)
+    # and on 120 x 1 (14640 device rows: 130 KB of LDS per candidate)
+    g = W.GraphBuilder()
+    a = g.op(W.T_ELEM, (1 << 20, 64), (0, 1), 1)
+    b = g.elementwise([a])
+    c = g.op(W.T_ELEM, (64, 1 << 20), (0, 1), 1)
+    g.edge(b, c, [W.ALL, W.ident(0)])
+    g.elementwise([c])
+    ops, edges, _ = g.finish()
+    cost = rng.integers(1, 100000, size=(len(ops), 64)).astype("<u4")
+    for mach in (W.Machine(64, 4, 20, 12, 0, 5, 4), W.Machine(2, 32, 3, 1, 2, 0, 8), W.Machine(120, 1)):
+        cfgs = W.strategies(ops, 64, 5, mach.n_devices, 64, (1, 2, 4, 8, 16, 32, 64))
+        sim = B.Simulator(ops, edges, mach, cost)
+        got = sim.simulate(cfgs)
+        want = oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8)
+        assert np.array_equal(got, want), f"machine {mach.as_tuple()}: {np.nonzero(got != want)[0][:5]}"
+        sim.close()
+    for mach in (W.Machine(256, 4), W.Machine(1, 1024), W.Machine(1024, 1)):
+        with pytest.raises(B.FFSimError) as e:
+            B.ff_sim_create(ops, edges, mach, cost)
+        assert e.value.code == B.FF_ERANGE
+    with pytest.raises(B.FFSimError) as e:
+        B.ff_sim_create(ops, edges, W.Machine(1025, 1), cost)
+    assert e.value.code == B.FF_ERANGE
