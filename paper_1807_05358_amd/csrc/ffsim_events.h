@@ -398,8 +398,10 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             const int32_t lo = nlo[d] > plo ? nlo[d] : plo;
                             const int32_t hi = nhi[d] < phi ? nhi[d] : phi;
                             hit_m &= ballot(hi > lo);
-                            if (WIDE) elems *= (u64)(uint32_t)(hi > lo ? hi - lo : 0);
-                            else elems = (uint32_t)elems * (uint32_t)(hi > lo ? hi - lo : 0);
+                            // (a lane that misses in some dim carries a meaningless product: it is
+                            // only used by lanes that hit in all dims)
+                            if (WIDE) elems *= (u64)(uint32_t)(hi - lo);
+                            else elems = (uint32_t)elems * (uint32_t)(hi - lo);
                         }
                     }
                     if (!hit_m) continue;
