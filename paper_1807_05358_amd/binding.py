@@ -15,6 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libffsim.so")
 
 FF_OK, FF_EINVAL, FF_ENOMEM, FF_EWORKSPACE, FF_ERANGE, FF_EHIP = 0, -1, -2, -3, -4, -5
 FF_INVALID_NS = 2 ** 64 - 1
+FF_INTERNAL_NS = 2 ** 64 - 2
+FF_OVERFLOW_NS = 2 ** 64 - 3
 STATS_DT = np.dtype([("n_compute", "<u8"), ("n_pairs", "<u8"), ("n_comm", "<u8"), ("sum_comm_ns", "<u8"),
                      ("n_events", "<u8"), ("exit_code", "<u8"), ("n_stuck", "<u8"), ("reserved", "<u8")])
 

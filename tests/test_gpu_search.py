@@ -242,3 +242,32 @@ def test_search_stopping_rule(B):
     assert np.array_equal(best_ns, got.min(axis=0).clip(max=ch.start_ns()))
     ch.close()
     sim.close()
+
+
+def test_search_driver_matches_the_oracle_chain_by_chain(B):
+    """paper_1807_05358_amd.search.find_strategy: starting points, table and budget rule are its own;
+    every chain it runs must be the oracle's chain for the same inputs, and the result the best of them"""
+    from paper_1807_05358_amd import search as driver
+    w = W.workload(1)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    C, steps, seed = 6, 24, 5
+    res = driver.find_strategy(sim, w.ops, w.machine, w.max_parts, w.choices, n_chains=C, steps=steps, steps_per_call=10, seed=seed)
+    cfg0 = driver.starting_strategies(w.ops, w.machine, w.max_parts, w.choices, C, seed)
+    assert np.array_equal(cfg0[0], W.data_parallel_strategy(w.ops, w.machine.n_devices, w.max_parts))
+    start = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0)
+    assert np.array_equal(res.start_ns, start)
+    ref = float(np.median(start))
+    bucket = max(1, int(ref * 0.02 * 8 / 256))
+    table = S.metropolis_table(1.0 / (ref * 0.02), bucket, 256)
+    assert np.array_equal(table, B.metropolis_table(1.0 / (ref * 0.02), bucket, 256))
+    tp, tu = w.search_space()
+    best = []
+    for c in range(C):
+        trace, _, best_ns, best_cfg, _ = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], tp, tu, table, bucket,
+                                                                  seed, c, 0, steps, patience=steps // 2)
+        assert np.array_equal(res.trace_ns[:, c], trace), f"chain {c}"
+        assert int(res.chain_best_ns[c]) == best_ns
+        best.append(best_ns)
+    assert res.best_ns == min(best) <= int(start.min())
+    assert int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, res.best[None])[0]) == res.best_ns
+    sim.close()
