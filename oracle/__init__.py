@@ -32,7 +32,7 @@ def lib():
         L = C.CDLL(build())
         vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
         L.ffo_build.restype = vp
-        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp]
+        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ffo_from_arrays.restype = vp
         L.ffo_from_arrays.argtypes = [u32, vp, vp, u32, u32, vp, vp]
         L.ffo_counts.restype = None
@@ -44,7 +44,7 @@ def lib():
         L.ffo_free.restype = None
         L.ffo_free.argtypes = [vp]
         L.ffo_batch.restype = None
-        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp]
+        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -83,6 +83,18 @@ def _link_args(m):
     return (bw, lat), (_ptr(bw), _ptr(lat))
 
 
+def _param_args(params, n_ops):
+    """params: None, or (param_bytes [n_ops] uint32, param_dims [n_ops] uint8): bytes of parameters
+    of every op (0 = none) and the output dims that index them (bit d).  Returns (keep-alive
+    arrays, the two C arguments)."""
+    if params is None:
+        return (), (None, None)
+    pb = np.ascontiguousarray(params[0], "<u4")
+    pd = np.ascontiguousarray(params[1], np.uint8)
+    assert pb.shape == (n_ops,) and pd.shape == (n_ops,)
+    return (pb, pd), (_ptr(pb), _ptr(pd))
+
+
 class TaskGraph:
     """a built task graph: exe[t], dev[t], deps (src, dst); the first n_compute tasks are
     compute tasks in (op, part) order, the rest communication tasks in creation order."""
@@ -112,7 +124,7 @@ class TaskGraph:
             self._h = None
 
 
-def build_task_graph(ops, edges, machine, cost, cfg, devmap=None):
+def build_task_graph(ops, edges, machine, cost, cfg, devmap=None, params=None):
     """Section 5.1 for one strategy (cfg: [n_ops] configs). None if the strategy is invalid.
     devmap [n_ops][64] uint16: the device of every part given explicitly (the configs' offset
     and stride are then not used)."""
@@ -123,8 +135,9 @@ def build_task_graph(ops, edges, machine, cost, cfg, devmap=None):
     if devmap is not None:
         devmap = np.ascontiguousarray(devmap, "<u2")
         assert devmap.shape == (len(ops), 64)
+    keep_p, pargs = _param_args(params, len(ops))
     h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs,
-                        None if devmap is None else _ptr(devmap))
+                        None if devmap is None else _ptr(devmap), *pargs)
     return TaskGraph(h) if h else None
 
 
@@ -135,7 +148,7 @@ def build_and_discard(ops, edges, machine, cost, cfg):
     m = _machine(machine)
     keep, cargs = _cost_args(cost)
     keep_l, largs = _link_args(machine)
-    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None, None, None)
     if h:
         lib().ffo_free(h)
     return bool(h)
@@ -149,7 +162,7 @@ def task_graph_from_arrays(exe, dev, n_rows, dep_src, dep_dst):
     return TaskGraph(lib().ffo_from_arrays(len(exe), _ptr(exe), _ptr(dev), n_rows, len(ds), _ptr(ds), _ptr(dd)))
 
 
-def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None):
+def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None, params=None):
     """makespan (ns) of every strategy in cfgs [B][n_ops]; 2^64-1 for an invalid one.
     devmaps [B][n_ops][64] uint16: explicit devices of all parts (see build_task_graph)."""
     ops, edges, cfgs = map(np.ascontiguousarray, (ops, edges, cfgs))
@@ -161,13 +174,14 @@ def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None):
     if devmaps is not None:
         devmaps = np.ascontiguousarray(devmaps, "<u2")
         assert devmaps.shape == (cfgs.shape[0], len(ops), 64)
+    keep_p, pargs = _param_args(params, len(ops))
     lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs,
                     _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads, *largs,
-                    None if devmaps is None else _ptr(devmaps))
+                    None if devmaps is None else _ptr(devmaps), *pargs)
     return out
 
 
-def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None):
+def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None, params=None):
     """oracle for delta simulation: apply the single-op mutations cumulatively and fully
     re-simulate (the definition of the delta result, Section 5.3).  mutations: [n_steps]
     records (op, cfg).  `steps` selects which steps (0-based) to evaluate; returns their
@@ -182,4 +196,4 @@ def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None)
             snaps.append(cur.copy())
     if not snaps:
         return np.zeros(0, "<u8")
-    return simulate_batch(ops, edges, machine, cost, np.stack(snaps))
+    return simulate_batch(ops, edges, machine, cost, np.stack(snaps), params=params)

@@ -141,7 +141,34 @@ bool exe_time(const CostModel& cm, uint32_t i, const Cfg& c, uint32_t parts, uin
 // single intra-node figures -- the device topology's connections need not be alike.
 // devmap [n_ops][64]: the device of every task given one by one (Section 4: a configuration
 // assigns each task its device), instead of offset + k * stride.
-struct Extras { const uint32_t* link_bw; const uint32_t* link_lat; const uint16_t* devmap; };
+// param_bytes / param_dims [n_ops]: parameter synchronisation.  Section 8 discusses how strategies
+// differ in the data they move to synchronise parameters among replicas; Section 5.1 gives no
+// construction for it.  Reading taken here: op i holds param_bytes[i] bytes of parameters, indexed by
+// the output dims in param_dims[i] (bit d); its configuration cuts them into one shard per index
+// along those dims, and the parts that differ only in the other dims are replicas of a shard.  The
+// replica with index 0 in all other dims owns the shard; every other replica, when its task has
+// finished, sends its gradient of the shard (ceil(param_bytes / shards) bytes) to the owner's
+// device: one communication task per replica on another device than the owner, with the
+// replica's compute task as its only predecessor and no successor.  The update itself and the
+// way back are not modelled.  These tasks are created right after the communication tasks of
+// the op's out-edges (so ids go op by op).
+struct Extras {
+    const uint32_t* link_bw; const uint32_t* link_lat; const uint16_t* devmap;
+    const uint32_t* param_bytes; const uint8_t* param_dims;
+};
+
+uint64_t transfer_ns(const Machine& m, const Extras& x, uint32_t from, uint32_t to, uint64_t bytes) {
+    const uint32_t G = m.gpus_per_node;
+    const bool same_node = from / G == to / G;
+    uint64_t bw = same_node ? m.intra_Bpns : m.inter_Bpns;
+    uint64_t lat = same_node ? m.intra_lat_ns : m.inter_lat_ns;
+    if (same_node && x.link_bw) {
+        const size_t pair = (size_t)(from % G) * G + to % G;
+        bw = x.link_bw[pair];
+        lat = x.link_lat[pair];
+    }
+    return (bytes + bw - 1) / bw + lat;       // assumption A2, rounded up, plus the link's latency
+}
 
 bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, const Machine& m,
            const CostModel& cm, const Cfg* cfg, const Extras& x, TaskGraph& tg) {
@@ -168,29 +195,44 @@ bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, c
         }
     }
     tg.n_compute = (uint32_t)tg.exe.size();
-    // step 2: per tensor edge, per pair of tasks with a shared sub-tensor
-    for (uint32_t e = 0; e < n_edges; e++) {
-        uint32_t i = edges[e].src_op, j = edges[e].dst_op;
-        for (uint32_t kp = 0; kp < np[i]; kp++) {
-            Box pb = part_box(ops[i], cfg[i], kp);
-            for (uint32_t kc = 0; kc < np[j]; kc++) {
-                Box cb = part_box(ops[j], cfg[j], kc);
-                uint64_t elems = shared_elems(ops[i], edges[e], pb, cb);
-                if (!elems) continue;
-                uint32_t tp = first[i] + kp, tc = first[j] + kc;
-                if (tg.dev[tp] == tg.dev[tc]) { tg.add_dep(tp, tc); continue; }
-                bool same_node = tg.dev[tp] / G == tg.dev[tc] / G;
-                uint64_t bw = same_node ? m.intra_Bpns : m.inter_Bpns;
-                uint64_t lat = same_node ? m.intra_lat_ns : m.inter_lat_ns;
-                if (same_node && x.link_bw) {
-                    const size_t pair = (size_t)(tg.dev[tp] % G) * G + tg.dev[tc] % G;
-                    bw = x.link_bw[pair];
-                    lat = x.link_lat[pair];
+    // step 2, op by op: per tensor edge out of the op, per pair of tasks with a shared sub-tensor
+    std::vector<std::vector<uint32_t>> out_edges(n_ops);      // per producer, in the given order
+    for (uint32_t e = 0; e < n_edges; e++) out_edges[edges[e].src_op].push_back(e);
+    for (uint32_t i = 0; i < n_ops; i++) {
+        for (uint32_t e : out_edges[i]) {
+            const uint32_t j = edges[e].dst_op;
+            for (uint32_t kp = 0; kp < np[i]; kp++) {
+                Box pb = part_box(ops[i], cfg[i], kp);
+                for (uint32_t kc = 0; kc < np[j]; kc++) {
+                    Box cb = part_box(ops[j], cfg[j], kc);
+                    uint64_t elems = shared_elems(ops[i], edges[e], pb, cb);
+                    if (!elems) continue;
+                    uint32_t tp = first[i] + kp, tc = first[j] + kc;
+                    if (tg.dev[tp] == tg.dev[tc]) { tg.add_dep(tp, tc); continue; }
+                    uint32_t c = tg.add_task(transfer_ns(m, x, tg.dev[tp], tg.dev[tc], elems * m.elem_bytes),
+                                             link_row(m, tg.dev[tp], tg.dev[tc]));
+                    tg.add_dep(tp, c);
+                    tg.add_dep(c, tc);
                 }
-                uint64_t bytes = elems * m.elem_bytes;
-                uint32_t c = tg.add_task((bytes + bw - 1) / bw + lat, link_row(m, tg.dev[tp], tg.dev[tc]));
-                tg.add_dep(tp, c);
-                tg.add_dep(c, tc);
+            }
+        }
+        // parameter synchronisation of the op (see Extras)
+        if (x.param_bytes && x.param_bytes[i]) {
+            const Cfg& c = cfg[i];
+            uint32_t shards = 1;
+            for (int d = 0; d < 4; d++) if ((x.param_dims[i] >> d) & 1) shards *= c.deg[d];
+            const uint64_t shard_bytes = ((uint64_t)x.param_bytes[i] + shards - 1) / shards;
+            for (uint32_t k = 0; k < np[i]; k++) {
+                // index of part k along each dim (dim 0 slowest), and the owner: the same index
+                // along the parameter dims, 0 along the others
+                uint32_t idx[4], rem = k;
+                for (int d = 3; d >= 0; d--) { idx[d] = rem % c.deg[d]; rem /= c.deg[d]; }
+                uint32_t owner = 0;
+                for (int d = 0; d < 4; d++) owner = owner * c.deg[d] + (((x.param_dims[i] >> d) & 1) ? idx[d] : 0);
+                const uint32_t tk = first[i] + k, to = first[i] + owner;
+                if (owner == k || tg.dev[tk] == tg.dev[to]) continue;
+                uint32_t t = tg.add_task(transfer_ns(m, x, tg.dev[tk], tg.dev[to], shard_bytes), link_row(m, tg.dev[tk], tg.dev[to]));
+                tg.add_dep(tk, t);
             }
         }
     }
@@ -236,10 +278,10 @@ extern "C" {
 void* ffo_build(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
                 const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
                 const uint32_t* tuple_ns, const void* cfg, const uint32_t* link_bw, const uint32_t* link_lat,
-                const uint16_t* devmap) {
+                const uint16_t* devmap, const uint32_t* param_bytes, const uint8_t* param_dims) {
     TaskGraph* tg = new TaskGraph;
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
-    const Extras x{link_bw, link_lat, devmap};
+    const Extras x{link_bw, link_lat, devmap, param_bytes, param_dims};
     if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                (const Cfg*)cfg, x, *tg)) { delete tg; return nullptr; }
     return tg;
@@ -283,12 +325,13 @@ void ffo_free(void* h) { delete (TaskGraph*)h; }
 void ffo_batch(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
                const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
                const uint32_t* tuple_ns, const void* cfgs, uint32_t B, uint64_t* out_ns, uint32_t n_threads,
-               const uint32_t* link_bw, const uint32_t* link_lat, const uint16_t* devmaps) {
+               const uint32_t* link_bw, const uint32_t* link_lat, const uint16_t* devmaps, const uint32_t* param_bytes,
+               const uint8_t* param_dims) {
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
     auto work = [&](uint32_t b0, uint32_t b1) {
         for (uint32_t b = b0; b < b1; b++) {
             TaskGraph tg;
-            const Extras x{link_bw, link_lat, devmaps ? devmaps + (size_t)b * n_ops * MAX_PARTS : nullptr};
+            const Extras x{link_bw, link_lat, devmaps ? devmaps + (size_t)b * n_ops * MAX_PARTS : nullptr, param_bytes, param_dims};
             bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                             (const Cfg*)cfgs + (size_t)b * n_ops, x, tg);
             out_ns[b] = ok ? simulate(tg, nullptr, nullptr, nullptr) : INVALID;

@@ -50,7 +50,7 @@ def metropolis_table(beta_per_ns: float, bucket_ns: int, n_buckets: int) -> np.n
 
 
 def metropolis_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept, bucket_ns, seed,
-                     chain, first_step, n_steps, patience=0, idle_steps=0, best_so_far=None):
+                     chain, first_step, n_steps, patience=0, idle_steps=0, best_so_far=None, params=None):
     """runs n_steps of one chain starting from the valid strategy cfg0.  patience > 0: the
     stopping rule of Section 6.2 -- after `patience` steps without a new best the chain makes
     no further proposals (idle_steps / best_so_far carry the state of an earlier call over).
@@ -59,7 +59,7 @@ def metropolis_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept,
     n_ops = len(ops)
     n_dev = int(machine.n_devices)
     cur = np.array(cfg0, copy=True)
-    cur_ns = int(simulate_batch(ops, edges, machine, cost, cur[None])[0])
+    cur_ns = int(simulate_batch(ops, edges, machine, cost, cur[None], params=params)[0])
     assert cur_ns != INVALID, "the chain must start from a valid strategy"
     best_ns, best = cur_ns, cur.copy()
     if best_so_far is not None and best_so_far < best_ns:
@@ -77,7 +77,7 @@ def metropolis_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept,
             prop[op]["deg"] = [(word >> (8 * d)) & 0xFF for d in range(4)]
             prop[op]["dev_offset"] = draw(seed, OFFSET, chain, st) % n_dev
             prop[op]["dev_stride"] = 1
-            new_ns = int(simulate_batch(ops, edges, machine, cost, prop[None])[0])
+            new_ns = int(simulate_batch(ops, edges, machine, cost, prop[None], params=params)[0])
             ok = False
             if new_ns < INVALID - 2:            # a time, not a result code
                 if new_ns <= cur_ns:

@@ -555,6 +555,24 @@ def device_maps(cfgs, n_dev, seed, spread=None):
     return maps
 
 
+def param_table(ops, flops, bytes_per_param=4):
+    """parameters of every op for the parameter-synchronisation refinement: (param_bytes [n_ops]
+    uint32, param_dims [n_ops] uint8).  Convolutions and matrix products hold
+    out_channels x (inputs per output element) parameters, recovered from the op's FLOPs
+    (2 x outputs x inputs per output element) and indexed by the output's channel dim (bit 1); all
+    other ops hold none.  Every op owns its parameters (unrolled steps of a recurrent layer are not
+    tied together)."""
+    pb = np.zeros(len(ops), "<u4")
+    pd = np.zeros(len(ops), np.uint8)
+    for i, o in enumerate(ops):
+        if o["type"] in (T_CONV, T_FC):
+            e = [int(x) for x in o["extent"]]
+            n_params = int(flops[i]) // (2 * e[0] * e[2] * e[3])
+            pb[i] = min(n_params * bytes_per_param, 2 ** 32 - 1)
+            pd[i] = 2
+    return pb, pd
+
+
 def data_parallel_strategy(ops, n_dev, max_parts=MAX_PARTS):
     """every op split in the sample dim only, as far as the device count allows."""
     cfg = np.zeros(len(ops), CFG_DT)
@@ -607,6 +625,9 @@ class Workload:
 
     def search_space(self):
         return search_space(self.ops, self.max_parts, self.choices)
+
+    def param_table(self):
+        return param_table(self.ops, self.flops)
 
     def sha256(self, n=None):
         h = hashlib.sha256()
