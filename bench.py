@@ -366,6 +366,33 @@ def main():
                            "median_start_ns": float(np.median(start)), "median_best_ns": float(np.median(best_ns))})
             ch.close()
         line["search"] = search
+        # the whole search with parameter-synchronisation traffic simulated (ff_sim_set_params): can it
+        # beat data parallelism, as Section 8 reports?  (a simulator of its own, the timed kernels above
+        # never see the refinement)
+        if 1 in results:
+            from paper_1807_05358_amd import search as driver
+            w_p = results[1][2]
+            sim_p = binding.Simulator(w_p.ops, w_p.edges, w_p.machine, w_p.cost, params=w_p.param_table())
+            C, n_steps = 256, 1024
+            cfg0 = driver.starting_strategies(w_p.ops, w_p.machine, w_p.max_parts, w_p.choices, C, 1807)
+            cfg0[:C // 2] = W.data_parallel_strategy(w_p.ops, w_p.machine.n_devices, w_p.max_parts)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            res = driver.find_strategy(sim_p, w_p.ops, w_p.machine, w_p.max_parts, w_p.choices, steps=n_steps, accept_scale=0.005,
+                                       seed=1807, start=cfg0)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            line["search_with_parameter_traffic"] = {
+                "workload": f"configs[1] {w_p.name}, parameters of conv / fc ops synchronised among replicas",
+                "chains": C, "steps": n_steps, "wall_s": dt, "proposals_per_s": C * n_steps / dt,
+                "data_parallel_ns": int(res.start_ns[0]), "best_found_ns": res.best_ns,
+                "speedup_over_data_parallel": int(res.start_ns[0]) / res.best_ns,
+                "best_degrees_per_op": res.best["deg"].tolist()}
+            if not args.no_cpu:
+                import oracle
+                line["search_with_parameter_traffic"]["best_confirmed_by_oracle"] = bool(int(oracle.simulate_batch(
+                    w_p.ops, w_p.edges, w_p.machine, w_p.cost, res.best[None], params=w_p.param_table())[0]) == res.best_ns)
+            sim_p.close()
         # neighbour sweep (local-optimality check): all single-op neighbours of one strategy
         if 1 in results:
             _, sim_n, w_n, cfgs_n = results[1]

@@ -182,6 +182,22 @@ typedef struct {
 } ff_linktable_t;
 int ff_sim_set_links(ff_sim_t* sim, const ff_linktable_t* links);
 
+/* Parameter synchronisation (Section 8 compares strategies by the data they move to keep the
+ * replicas of an op's parameters in step; Section 5.1 has no construction for it).  Reading
+ * taken: op i holds param_bytes[i] bytes of parameters (0: none), indexed by the output dims in
+ * param_dims[i] (bit d = dim d).  A configuration cuts them into one shard per index along those
+ * dims (shards = product of their degrees, ceil(param_bytes / shards) bytes each); the parts that
+ * differ only in the other dims are replicas of a shard, and the replica with index 0 in all
+ * other dims owns it.  When a replica's task has finished it sends its gradient of the shard to
+ * the owner's device: one communication task per replica that sits on another device than the
+ * owner, with the replica's task as its only predecessor and no successor, created right after
+ * the communication tasks of the op's out-edges (ids go op by op).  The simulated time is then
+ * the largest endTime over compute and communication tasks.  The update and the way back are
+ * not modelled.
+ * HOST pointers [n_ops], deep-copied; param_bytes == NULL switches it off.  Waits for the
+ * device to be idle; chain sets created before the call are invalidated as by ff_sim_set_links. */
+int ff_sim_set_params(ff_sim_t* sim, const uint32_t* param_bytes, const uint8_t* param_dims);
+
 /* Scratch for a batch of B candidates (per-task queue keys and readyTime / pending-input
  * counters of the resident candidates).  The workspace is caller-allocated device memory,
  * 256-byte aligned, and may be shared by successive calls on the same stream.  Small

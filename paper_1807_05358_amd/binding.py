@@ -34,7 +34,7 @@ class ff_costtable_t(C.Structure):
     _fields_ = [("n_ops", C.c_uint32), ("n_cols", C.c_uint32), ("ns", C.c_void_p)]
 
 
-EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links",
+EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_params",
            "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
@@ -97,6 +97,8 @@ def lib():
         L.ff_sim_batch_devmaps.argtypes = [vp, vp, vp, u32, vp, vp]
         L.ff_sim_set_links.restype = C.c_int
         L.ff_sim_set_links.argtypes = [vp, vp]
+        L.ff_sim_set_params.restype = C.c_int
+        L.ff_sim_set_params.argtypes = [vp, vp, vp]
         L.ff_sim_chains_create.restype = C.c_int
         L.ff_sim_chains_create.argtypes = [vp, vp, u32, vp, vp, C.POINTER(vp)]
         L.ff_sim_delta.restype = C.c_int
@@ -176,6 +178,19 @@ def ff_sim_set_links(sim, gpus_per_node=0, Bpns=None, lat_ns=None):
         raise ValueError("link tables must be [gpus_per_node][gpus_per_node]")
     lt = ff_linktable_t(gpus_per_node, Bpns.ctypes.data, None if lat is None else lat.ctypes.data)
     _check(lib().ff_sim_set_links(sim, C.byref(lt)), "ff_sim_set_links")
+
+
+def ff_sim_set_params(sim, n_ops, param_bytes=None, param_dims=None):
+    """param_bytes [n_ops] uint32 / param_dims [n_ops] uint8 (bit d: output dim d indexes the
+    parameters); param_bytes None switches parameter synchronisation off."""
+    if param_bytes is None:
+        _check(lib().ff_sim_set_params(sim, None, None), "ff_sim_set_params")
+        return
+    pb = np.ascontiguousarray(param_bytes, "<u4")
+    pd = np.ascontiguousarray(param_dims, np.uint8)
+    if pb.shape != (n_ops,) or pd.shape != (n_ops,):
+        raise ValueError("parameter tables must have one entry per op")
+    _check(lib().ff_sim_set_params(sim, pb.ctypes.data, pd.ctypes.data), "ff_sim_set_params")
 
 
 def ff_sim_workspace_bytes(sim, B):
@@ -268,9 +283,10 @@ def metropolis_table(beta_per_ns, bucket_ns, n_buckets):
 class Simulator:
     """owns a handle, its workspace and result buffers (all torch-allocated)."""
 
-    def __init__(self, ops, edges, machine, cost):
+    def __init__(self, ops, edges, machine, cost, params=None):
         """cost: [n_ops][n_cols] table by number of parts, or a triple (tuple_ptr, tuples, ns)
-        keyed by the degree tuple."""
+        keyed by the degree tuple.  params: (param_bytes, param_dims) per op, to simulate the
+        parameter-synchronisation transfers as well."""
         _torch()
         self.n_ops = len(ops)
         if isinstance(cost, (tuple, list)):
@@ -282,6 +298,8 @@ class Simulator:
             if lat is None:
                 lat = np.full((machine.gpus_per_node,) * 2, machine.intra_lat_ns, "<u4")
             ff_sim_set_links(self.handle, machine.gpus_per_node, machine.link_Bpns, lat)
+        if params is not None:
+            ff_sim_set_params(self.handle, self.n_ops, params[0], params[1])
         self._ws = None
         self._stats = None
 

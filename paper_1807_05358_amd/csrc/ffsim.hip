@@ -40,7 +40,8 @@ struct ff_sim {
     bool wide = false;            // some tensor has 2^32 bytes or more, or a link row's running sum may pass 2^32 ns
     bool big_tensors = false;     // some tensor has 2^32 bytes or more
     ff_machine_t mach{};
-    uint32_t links_gen = 0;       // counts ff_sim_set_links calls (a chain set's stored timelines depend on the links)
+    uint32_t links_gen = 0;       // counts ff_sim_set_links / ff_sim_set_params calls (a chain set's stored timelines depend on both)
+    std::vector<DOp> h_ops;       // host copy of the op records (ff_sim_set_params rewrites two fields)
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
     // the batch kernel may keep the per-edge set-up of a candidate (all extents must fit 16 bits):
@@ -87,13 +88,13 @@ static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = fals
 // chains keep the per-edge set-up in their own memory whenever the extents allow it
 static chain_kernel_t chain_kernel(const ff_sim* s) {
     const KernelChoice k = choice(s, s->chain_cache);
-    const bool ext = s->dev.link_table != 0;
+    const bool ext = s->dev.link_table || s->dev.sync;
     if (s->dev.gpus_per_node == 4) return ext ? chain_kernels<true, 4>(k) : chain_kernels<false, 4>(k);
     return ext ? chain_kernels<true, 0>(k) : chain_kernels<false, 0>(k);
 }
 static try_kernel_t try_kernel(const ff_sim* s) {
     const KernelChoice k = choice(s, s->chain_cache);
-    const bool ext = s->dev.link_table != 0;
+    const bool ext = s->dev.link_table || s->dev.sync;
     if (s->dev.gpus_per_node == 4) return ext ? try_kernels<true, 4>(k) : try_kernels<false, 4>(k);
     return ext ? try_kernels<true, 0>(k) : try_kernels<false, 0>(k);
 }
@@ -216,7 +217,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
             ops[i].out_begin = k;
             while (k < g->n_edges && edges[k].src == i) k++;
             ops[i].out_end = k;
-            ops[i].pad0 = ops[i].pad1 = 0;
+            ops[i].param_bytes = ops[i].param_dims = 0;
             if (ops[i].out_end > ops[i].out_begin) ops[i].first = edges[ops[i].out_begin];
             else std::memset(&ops[i].first, 0, sizeof(DEdge));
         }
@@ -238,6 +239,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     if ((rc = upload(ops, &s->d_ops)) || (rc = upload(edges, &s->d_edges)) || (rc = upload(in_edges, &s->d_in_edges)) ||
         (rc = upload(cost, &s->d_cost)) || (rc = upload(magic, &s->d_magic))) { release(s); return rc; }
 
+    s->h_ops = ops;
     SimDev& S = s->dev;
     S.n_ops = g->n_ops; S.n_edges = g->n_edges; S.n_cols = n_cols;
     S.max_parts = n_cols ? std::min<uint32_t>(FF_MAX_PARTS, n_cols) : FF_MAX_PARTS;
@@ -338,6 +340,22 @@ int ff_sim_create_tuplecost(const ff_opgraph_t* g, const ff_machine_t* m, const 
 
 void ff_sim_destroy(ff_sim_t* s) { release(s); }
 
+int ff_sim_set_params(ff_sim_t* s, const uint32_t* param_bytes, const uint8_t* param_dims) {
+    if (!s || (param_bytes && !param_dims)) return FF_EINVAL;
+    bool any = false;
+    for (uint32_t i = 0; i < s->dev.n_ops; i++) {
+        DOp& o = s->h_ops[i];
+        o.param_bytes = param_bytes ? param_bytes[i] : 0;
+        o.param_dims = param_bytes ? (param_dims[i] & ((1u << o.ndim) - 1)) : 0;
+        any = any || o.param_bytes;
+    }
+    if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;       // no launch may still read the old records
+    if (hipMemcpy(s->d_ops, s->h_ops.data(), s->h_ops.size() * sizeof(DOp), hipMemcpyHostToDevice) != hipSuccess) return FF_EHIP;
+    s->dev.sync = any ? 1u : 0u;
+    s->links_gen++;
+    return FF_OK;
+}
+
 int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
     if (!s) return FF_EINVAL;
     const ff_machine_t& m = s->mach;
@@ -392,7 +410,7 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
     if (B == 0) return FF_OK;
     // Keeping the per-edge set-up costs LDS for graphs whose words live there; it is used unless it
     // would leave part of the batch waiting for a free compute unit that the plain variant has room for.
-    const bool ext = s->dev.link_table || d_devmaps;
+    const bool ext = s->dev.link_table || s->dev.sync || d_devmaps;
     const bool cached = s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
     const uint32_t slots = std::min(B, cached ? s->max_slots_cached : s->max_slots);
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;

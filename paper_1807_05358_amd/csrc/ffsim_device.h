@@ -45,7 +45,8 @@ struct DOp {
     uint32_t ndim, par_mask;
     uint32_t out_begin, out_end; // range in edges[] (edges are sorted by producer)
     uint32_t in_begin, in_end;   // range in in_list[]
-    uint32_t pad0, pad1;
+    uint32_t param_bytes;        // parameters the op holds (0: none) and the output dims that index them (bit d);
+    uint32_t param_dims;         // used when SimDev::sync is set
     DEdge first;                 // copy of edges[out_begin] (most ops have one consumer): one
                                  // scalar burst brings the op and its first out-edge
 };
@@ -61,6 +62,7 @@ struct SimDev {
     uint32_t n_ops_pad;                // n_ops rounded up to a multiple of 64
     uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
     uint32_t link_table;               // 1: links inside a node differ per ordered GPU pair (see LINK_TABLE_AT)
+    uint32_t sync;                     // 1: parameter synchronisation transfers are simulated (DOp::param_bytes)
 };
 // The constants buffer every kernel receives: words 0..64 are division constants
 // (floor(2^32/d)+1 for d = 2..64); if SimDev::link_table is set, four words per ordered pair of

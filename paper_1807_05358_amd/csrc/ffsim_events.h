@@ -348,7 +348,9 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const bool may_share = REG ? false : ((SimX::kExt && m.devmap != nullptr) || !(ci.stride == 1 && ci.parts <= S.n_dev));
             const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
             overflow = overflow || end >= TIME_LIMIT;
-            if (in_mask) k0 = out_end > out_begin ? end << 1 : W_NONE;
+            // a finished task is looked at again only if it has something to release
+            const bool releases = out_end > out_begin || (SimX::kExt && S.sync && opi_p->param_bytes != 0);
+            if (in_mask) k0 = releases ? end << 1 : W_NONE;
             if (RECORD) { if (in_mask && rec.end_try) rec.end_try[i * WAVE + lane] = rec.tag | end; }
             PROF_MARK(2)
         } else {
@@ -508,6 +510,53 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 }
                 PROF_MARK(5)
             }
+            if (SimX::kExt && S.sync) {
+                // Parameter synchronisation (a refinement of the inputs; Section 8 discusses the traffic,
+                // Section 5.1 has no construction for it).  The op's parameters are cut into one shard per
+                // index along the dims that index them; parts that differ only in the other dims are
+                // replicas of a shard, and the replica with index 0 in those dims owns it.  A replica
+                // that has finished sends its gradient of the shard to the owner's device: a transfer
+                // with no successor, queued on its link row after the op's transfers to consumers.
+                const uint32_t pbytes = opi_p->param_bytes;
+                if (pbytes) {
+                    const uint32_t pdims = opi_p->param_dims;
+                    const uint32_t digits = part_digits(ci, lane, magic_v);
+                    uint32_t owner = 0, shards = 1;
+#pragma unroll
+                    for (int d = 0; d < 4; d++) {
+                        const bool indexes = (pdims >> d) & 1u;         // uniform
+                        owner = owner * ci.deg[d] + (indexes ? (digits >> (8 * d)) & 0xffu : 0u);
+                        if (indexes) shards *= ci.deg[d];
+                    }
+                    const uint32_t shard_bytes = (pbytes - 1) / shards + 1;       // ceil, pbytes >= 1
+                    const uint32_t dev_o = m.template device_of_part<REG>(i, ci, in_mask ? owner : 0u);
+                    const bool act = in_mask && owner != (uint32_t)lane && dev_o != dev_p;
+                    if (ballot(act)) {
+                        const uint32_t G = m.gpn();
+                        const uint32_t node_o = m.node_of(dev_o);
+                        const uint32_t local_o = m.local_of(dev_o, node_o);
+                        const bool same_node = node_o == node_p;
+                        const uint32_t row = same_node ? S.n_dev + dev_p * G + local_o
+                                                       : S.n_dev + S.n_nodes * G * G + node_p * S.n_nodes + node_o;
+                        uint32_t bw = same_node ? bw_intra : bw_inter;
+                        uint32_t m_bw = same_node ? m_bw_intra : m_bw_inter;
+                        uint32_t lat = same_node ? lat_intra : lat_inter;
+                        if (S.link_table) {
+                            if (act && same_node) {
+                                const uint4 t = m.links[m.local_of(dev_p, node_p) * G + local_o];
+                                bw = t.x; m_bw = t.y; lat = t.z;
+                            }
+                        }
+                        const u64 ns = (WIDE ? ((u64)shard_bytes + bw - 1) / bw : (u64)ceil_div_u32(shard_bytes, bw, m_bw)) + lat;
+                        const u64 end = fifo_commit(act, act ? row : 0u, ns, now, true, L);
+                        overflow = overflow || (act && end >= TIME_LIMIT);
+                        if (STATS) {
+                            cnt.n_comm += __popcll(ballot(act));
+                            if (act) cnt.sum_comm_ns += ns;
+                        }
+                    }
+                }
+            }
             if (in_mask) k0 = W_NONE;
         }
         if (in_mask) words[i * WAVE + lane] = k0;
@@ -537,8 +586,10 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
 // later, so the makespan is the largest free time over the compute device rows.
 template <class SimX>
 __device__ __forceinline__ u64 makespan(const SimX& m) {
+    // (parameter-synchronisation transfers feed nothing: with them the link rows count as well)
+    const uint32_t n = (SimX::kExt && m.S.sync) ? m.S.n_rows : m.S.n_dev;
     u64 mk = 0;
-    for (uint32_t d = lane_id(); d < m.S.n_dev; d += WAVE) mk = m.L.free_at[d] > mk ? m.L.free_at[d] : mk;
+    for (uint32_t d = lane_id(); d < n; d += WAVE) mk = m.L.free_at[d] > mk ? m.L.free_at[d] : mk;
     return wave_max_u64(mk);
 }
 

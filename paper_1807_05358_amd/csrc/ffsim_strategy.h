@@ -247,9 +247,12 @@ struct SimT {
     __device__ __forceinline__ OpCfg cfg(uint32_t j) const { return unpack_cfg(cfg_raw(j)); }
     // Section 4: the device of this lane's part of op j (lanes beyond the parts get some device in range)
     template <bool REG>
-    __device__ __forceinline__ uint32_t device_of(uint32_t j, const OpCfg& c) const {
-        if (EXT && !REG && devmap) return (uint32_t)lane_id() < c.parts ? devmap[(size_t)j * WAVE + lane_id()] : 0u;
-        return part_device<REG>(c, lane_id(), S);
+    __device__ __forceinline__ uint32_t device_of(uint32_t j, const OpCfg& c) const { return device_of_part<REG>(j, c, lane_id()); }
+    // the same for part k of op j (k may differ per lane)
+    template <bool REG>
+    __device__ __forceinline__ uint32_t device_of_part(uint32_t j, const OpCfg& c, uint32_t k) const {
+        if (EXT && !REG && devmap) return k < c.parts ? devmap[(size_t)j * WAVE + k] : 0u;
+        return part_device<REG>(c, k, S);
     }
 };
 constexpr uint32_t NO_OVERRIDE = 0xffffffffu;
