@@ -39,20 +39,25 @@ def alg_bytes(n_ops, tc, npairs):
 
 
 def time_batches(sim, d_strat, B, steps, warmup):
-    """per-launch durations (ms) from HIP events on the launch stream + wall ms per step."""
+    """wall ms per step over exactly `steps` launches back to back (the timed region of the
+    contract), then, in a second pass of as many launches, the per-launch duration (ms) from HIP
+    events on the launch stream."""
     import torch
     for _ in range(warmup):
         sim.batch(d_strat, B)
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     out = torch.empty(B, dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for _ in range(steps):
+        sim.batch(d_strat, B, d_out=out)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     for a, b in ev:
         a.record()
         sim.batch(d_strat, B, d_out=out)
         b.record()
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     kern_ms = [a.elapsed_time(b) for a, b in ev]
     return sum(kern_ms) / len(kern_ms), wall_ms, out
 
