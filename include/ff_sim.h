@@ -215,8 +215,9 @@ int ff_sim_batch(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t B, uint
                  void* hip_stream);
 /* ff_sim_batch, ff_sim_batch_devmaps, ff_sim_delta and ff_sim_delta_try put nothing but kernel
  * launches on the stream (no allocation, no memset, no copy): they may be recorded into a HIP
- * graph.  ff_sim_search reads its proposal ranges back once per call and ff_sim_neighbours
- * allocates and waits: those two are not for capture. */
+ * graph.  So may ff_sim_search from the second call with the same d_tuple_ptr / n_tuples on (the
+ * first one reads the ranges back to check them; they must not change afterwards).
+ * ff_sim_neighbours allocates and waits: not for capture. */
 
 /* The same with the device of every task given one by one (Section 4: a configuration assigns
  * each of its tasks a device) instead of dev_offset + k * dev_stride: d_devmaps is

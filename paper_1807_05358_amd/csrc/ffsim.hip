@@ -70,6 +70,8 @@ struct ff_chains {
     uint32_t* d_flags = nullptr;   // [C] nonzero once a chain saw an out-of-range mutation
     uint32_t* d_counter = nullptr; // work counter of the trial-mutation kernel
     uint32_t links_gen = 0;        // sim->links_gen when the chains were created
+    const uint32_t* checked_ptr = nullptr;   // the proposal ranges ff_sim_search has checked last
+    uint32_t checked_n = 0;
 };
 
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
@@ -488,16 +490,21 @@ int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64
     if (!p->d_accept || !p->d_tuple_ptr || !p->d_tuples || !p->d_best_ns || !p->d_best || p->n_buckets < 1 || p->bucket_ns < 1 ||
         p->n_tuples < 1) return FF_EINVAL;
     if (n_steps == 0) return FF_OK;
-    // the per-op ranges index the tuple list on the device: check them here, once per call
-    const uint32_t n_ops = c->sim->dev.n_ops;
-    std::vector<uint32_t> ptr(n_ops + 1);
-    if (hipMemcpy(ptr.data(), p->d_tuple_ptr, ptr.size() * 4, hipMemcpyDeviceToHost) != hipSuccess) return FF_EHIP;
-    for (uint32_t i = 0; i < n_ops; i++)
-        if (ptr[i] > ptr[i + 1] || ptr[i + 1] > p->n_tuples) return FF_EINVAL;
+    // the per-op ranges index the tuple list on the device: they are read back and checked when a
+    // chain set sees a list for the first time; later calls with the same list only launch
+    if (c->checked_ptr != p->d_tuple_ptr || c->checked_n != p->n_tuples) {
+        const uint32_t n_ops = c->sim->dev.n_ops;
+        std::vector<uint32_t> ptr(n_ops + 1);
+        if (hipMemcpy(ptr.data(), p->d_tuple_ptr, ptr.size() * 4, hipMemcpyDeviceToHost) != hipSuccess) return FF_EHIP;
+        for (uint32_t i = 0; i < n_ops; i++)
+            if (ptr[i] > ptr[i + 1] || ptr[i + 1] > p->n_tuples) return FF_EINVAL;
+        c->checked_ptr = p->d_tuple_ptr;
+        c->checked_n = p->n_tuples;
+    }
     SearchDev sd{};
     sd.seed = p->seed; sd.first_step = p->first_step; sd.bucket_ns = p->bucket_ns;
     sd.accept = p->d_accept; sd.tuple_ptr = p->d_tuple_ptr; sd.tuples = p->d_tuples;
-    sd.n_buckets = p->n_buckets; sd.enabled = 1; sd.patience = p->patience;
+    sd.n_buckets = p->n_buckets; sd.enabled = 1; sd.patience = p->patience; sd.n_tuples = p->n_tuples;
     sd.best_ns = (u64*)p->d_best_ns; sd.best_cfgs = (uint2*)p->d_best;
     return launch_chain_steps(c, nullptr, n_steps, d_trace_ns, (hipStream_t)hip_stream, sd);
 }

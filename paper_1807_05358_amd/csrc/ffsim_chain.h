@@ -173,6 +173,7 @@ struct SearchDev {
     const uint32_t* tuples;      // degree tuples (four bytes each) a proposal may pick for each op
     uint32_t n_buckets;
     uint32_t enabled;
+    uint32_t n_tuples;           // entries of tuples[]
     u64 patience;                // a chain stops proposing after this many steps without a new best (0 = never)
     u64* best_ns;                // [C] best simulated time seen (in/out)
     uint2* best_cfgs;            // [C][n_ops] the strategy that achieved it (in/out)
@@ -277,7 +278,11 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
             if (!poisoned && !meta.stale && !(search.patience && meta.idle_steps >= search.patience)) {
                 const u64 st = search.first_step + s;
                 op = first_u32((uint32_t)(draw64(search.seed, 10, c, st) % S.n_ops));
-                const uint32_t t0 = first_u32(search.tuple_ptr[op]), t1 = first_u32(search.tuple_ptr[op + 1]);
+                // (the host has checked the ranges; the clamp keeps the read inside the list even if the
+                // caller changed them afterwards)
+                const uint32_t t0 = first_u32(search.tuple_ptr[op]);
+                const uint32_t t1r = first_u32(search.tuple_ptr[op + 1]);
+                const uint32_t t1 = t1r < search.n_tuples ? t1r : search.n_tuples;
                 if (t1 > t0) {   // an op without a list gets no proposals
                     const uint32_t deg = search.tuples[t0 + (uint32_t)(draw64(search.seed, 11, c, st) % (t1 - t0))];
                     const uint32_t off = (uint32_t)(draw64(search.seed, 12, c, st) % S.n_dev);

@@ -76,3 +76,43 @@ def test_delta_and_trial_mutations_in_a_graph(B):
     ch.close()
     eager.close()
     sim.close()
+
+
+def test_search_steps_in_a_graph(B):
+    """after one eager call (which checks the proposal lists) ff_sim_search only launches: a graph of
+    search steps, replayed, continues the chains exactly as eager calls do"""
+    import torch
+    from oracle import search as S
+    w = W.workload(1)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    C, n = 3, 5
+    cfg0 = w.strategies(C)
+    tp, tu = w.search_space()
+    t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[:1])[0])
+    bucket = max(1, t0 // 256)
+    table = B.metropolis_table(20.0 / t0, bucket, 64)
+    ch = B.Chains(sim, cfg0)
+    ch.search_setup(tp, tu, table, bucket, seed=4)
+    trace = torch.zeros((n, C), dtype=torch.int64, device="cuda")
+    got = [ch.search(n, d_trace=trace).cpu().numpy().view("<u8").copy()]      # eager: steps 0..n-1
+    sp = ch._sp
+    # the graph holds the call for steps n..2n-1; step numbers are an argument, so each replay repeats those draws:
+    # the second replay proposes the same ops again from where the first one left the chains
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ch.search(n, d_trace=trace)
+    for replay in range(2):
+        g.replay()
+        torch.cuda.synchronize()
+        got.append(trace.cpu().numpy().view("<u8").copy())
+    for c in range(C):
+        a = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, cfg0[c], tp, tu, table, bucket, 4, c, 0, n)
+        assert np.array_equal(got[0][:, c], a[0])
+        b1 = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, a[1], tp, tu, table, bucket, 4, c, n, n, best_so_far=a[2])
+        assert np.array_equal(got[1][:, c], b1[0]), f"chain {c}, first replay"
+        b2 = S.metropolis_chain(w.ops, w.edges, w.machine, w.cost, b1[1], tp, tu, table, bucket, 4, c, n, n,
+                                best_so_far=min(a[2], b1[2]))
+        assert np.array_equal(got[2][:, c], b2[0]), f"chain {c}, second replay"
+    assert sp["step"] == 2 * n
+    ch.close()
+    sim.close()
