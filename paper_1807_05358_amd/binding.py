@@ -394,8 +394,8 @@ class Chains:
                      torch.cuda.current_stream().cuda_stream)
         return d_out
 
-    def try_mutations(self, d_muts, M, d_out=None):
-        """evaluate M proposals per chain ([M][C] mutations) without changing the chains."""
+    def _ensure_try_workspace(self, M):
+        """the trial kernel's slots live in the simulator's workspace"""
         torch = _torch()
         need = ff_sim_delta_try_workspace_bytes(self.handle, M)
         sim = self.sim
@@ -403,6 +403,11 @@ class Chains:
             sim._ws = None
             sim._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
             ff_sim_set_workspace(sim.handle, sim._ws.data_ptr(), sim._ws.numel())
+
+    def try_mutations(self, d_muts, M, d_out=None):
+        """evaluate M proposals per chain ([M][C] mutations) without changing the chains."""
+        torch = _torch()
+        self._ensure_try_workspace(M)
         if d_out is None:
             d_out = torch.empty((M, self.C), dtype=torch.int64, device="cuda")
         ff_sim_delta_try(self.handle, d_muts.data_ptr(), M, d_out.data_ptr(), torch.cuda.current_stream().cuda_stream)
@@ -450,12 +455,7 @@ class Chains:
         d_ptr = to_device(np.ascontiguousarray(tuple_ptr, "<u4"))
         d_tup = to_device(np.ascontiguousarray(tuples, "<u4"))
         M = ff_sim_neighbour_count(self.handle, d_ptr.data_ptr(), len(tuples), op_begin, op_end)
-        need = ff_sim_delta_try_workspace_bytes(self.handle, M)
-        sim = self.sim
-        if sim._ws is None or sim._ws.numel() < need:
-            sim._ws = None
-            sim._ws = torch.empty(need, dtype=torch.uint8, device="cuda")
-            ff_sim_set_workspace(sim.handle, sim._ws.data_ptr(), sim._ws.numel())
+        self._ensure_try_workspace(M)
         d_muts = torch.empty(M * self.C * W.MUT_DT.itemsize, dtype=torch.uint8, device="cuda")
         d_out = torch.empty((M, self.C), dtype=torch.int64, device="cuda")
         d_best = torch.empty(self.C, dtype=torch.int64, device="cuda")

@@ -77,3 +77,29 @@ def critical_path(exe, dep_src, dep_dst):
             if indeg[s] == 0:
                 stack.append(s)
     return int(dist.max())
+
+
+def random_graph(rng, n_ops):
+    """random DAG with random shapes and random affine input maps (not a DNN: it only has to
+    be a valid input of the boundary)."""
+    g = W.GraphBuilder()
+    for i in range(n_ops):
+        ndim = int(rng.integers(1, 5))
+        ext = [int(rng.choice([1, 2, 3, 5, 8, 12, 17, 32, 64, 100])) for _ in range(ndim)]
+        par = [d for d in range(ndim) if rng.random() < 0.8] or [0]
+        g.op(W.T_ELEM, ext, par, 1)
+        n_in = 0 if i == 0 else int(rng.integers(0, min(i, 3) + 1))
+        for src in sorted(rng.choice(i, size=n_in, replace=False).tolist()) if n_in else []:
+            sext = g.extent(src)
+            maps = []
+            for d in range(len(sext)):
+                if rng.random() < 0.3:
+                    maps.append(W.ALL)
+                else:
+                    c = int(rng.integers(0, ndim))
+                    stride = int(rng.choice([1, 1, 1, 2, 3]))
+                    a = int(rng.integers(-3, 4))
+                    b = a + int(rng.integers(0, 4))
+                    maps.append((c, stride, a, b))
+            g.edge(src, i, maps)
+    return g.finish()

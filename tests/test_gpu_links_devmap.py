@@ -174,7 +174,7 @@ def test_explicit_devices_invalid_entries_and_arguments(B):
 
 
 def test_explicit_devices_with_unequal_links_on_random_graphs(B):
-    from test_gpu_parity import random_graph
+    from helpers import random_graph
     for seed in range(4):
         rng = np.random.default_rng(7000 + seed)
         n_ops = int(rng.integers(3, 80))

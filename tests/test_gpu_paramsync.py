@@ -52,7 +52,7 @@ def test_parameter_traffic_matches_the_oracle(B, config_id, n):
 
 
 def test_parameter_dims_and_sizes_of_all_kinds_on_random_graphs(B):
-    from test_gpu_parity import random_graph
+    from helpers import random_graph
     for seed in range(5):
         rng = np.random.default_rng(9100 + seed)
         n_ops = int(rng.integers(3, 80))

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import graph_from_golden, load_golden
+from helpers import graph_from_golden, load_golden, random_graph
 from paper_1807_05358_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -354,32 +354,6 @@ def test_workspace_errors_and_other_stream(B):
     with pytest.raises(B.FFSimError) as e:
         B.ff_sim_create(big, w.edges, w.machine, w.cost)
     assert e.value.code == B.FF_ERANGE
-
-
-def random_graph(rng, n_ops):
-    """random DAG with random shapes and random affine input maps (not a DNN: it only has to
-    be a valid input of the boundary)."""
-    g = W.GraphBuilder()
-    for i in range(n_ops):
-        ndim = int(rng.integers(1, 5))
-        ext = [int(rng.choice([1, 2, 3, 5, 8, 12, 17, 32, 64, 100])) for _ in range(ndim)]
-        par = [d for d in range(ndim) if rng.random() < 0.8] or [0]
-        g.op(W.T_ELEM, ext, par, 1)
-        n_in = 0 if i == 0 else int(rng.integers(0, min(i, 3) + 1))
-        for src in sorted(rng.choice(i, size=n_in, replace=False).tolist()) if n_in else []:
-            sext = g.extent(src)
-            maps = []
-            for d in range(len(sext)):
-                if rng.random() < 0.3:
-                    maps.append(W.ALL)
-                else:
-                    c = int(rng.integers(0, ndim))
-                    stride = int(rng.choice([1, 1, 1, 2, 3]))
-                    a = int(rng.integers(-3, 4))
-                    b = a + int(rng.integers(0, 4))
-                    maps.append((c, stride, a, b))
-            g.edge(src, i, maps)
-    return g.finish()
 
 
 @pytest.mark.parametrize("seed", range(6))
