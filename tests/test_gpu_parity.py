@@ -68,10 +68,11 @@ def test_batch_matches_oracle(B, config_id, n, n_stats):
 
 
 def test_full_size_batches_run_in_bench_configuration(B):
-    """configs 2 and 3 at their full B (4096), launch shape as in the bench; a strided
-    sample is compared with the oracle, and all results must respect the bounds that hold
-    for any strategy (at least the largest single task, at most the unsplit serial time...)."""
-    for config_id, n, every in ((2, 4096, 128), (3, 4096, 256)):
+    """every configuration at its full B, launch shape and kernel variant as in the bench (no
+    per-candidate counters); all of configs[1], a strided sample of the others is compared with
+    the oracle, and all results must respect the bounds that hold for any strategy (at least the
+    largest single task...)."""
+    for config_id, n, every in ((1, 1024, 1), (2, 4096, 128), (3, 4096, 256), (4, 1024, 128)):
         w = W.workload(config_id)
         cfgs = w.strategies(n)
         got = sim_for(B, config_id).simulate(cfgs)
