@@ -72,7 +72,7 @@ def test_full_size_batches_run_in_bench_configuration(B):
     per-candidate counters); all of configs[1], a strided sample of the others is compared with
     the oracle, and all results must respect the bounds that hold for any strategy (at least the
     largest single task...)."""
-    for config_id, n, every in ((1, 1024, 1), (2, 4096, 128), (3, 4096, 256), (4, 1024, 128)):
+    for config_id, n, every in ((0, 64, 1), (1, 1024, 1), (2, 4096, 128), (3, 4096, 256), (4, 1024, 128)):
         w = W.workload(config_id)
         cfgs = w.strategies(n)
         got = sim_for(B, config_id).simulate(cfgs)
