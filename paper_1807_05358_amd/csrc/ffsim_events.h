@@ -393,9 +393,13 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     todo &= todo - 1;
                     u64 hit_m = mine_m;
                     u64 elems = 1;
+                    // (the number of dims stays one scalar that is compared here: taken out of the loop, the
+                    // four comparisons would each occupy a pair of scalar registers as a lane mask)
+                    uint32_t n_dims = first_u32(e.src_ndim);
+                    asm volatile("" : "+s"(n_dims));
 #pragma unroll
                     for (int d = 0; d < 4; d++) {
-                        if ((uint32_t)d < e.src_ndim) {
+                        if ((uint32_t)d < n_dims) {
                             const int32_t plo = (int32_t)readlane_u32(pb.lo[d], kp), phi = (int32_t)readlane_u32(pb.hi[d], kp);
                             const int32_t lo = nlo[d] > plo ? nlo[d] : plo;
                             const int32_t hi = nhi[d] < phi ? nhi[d] : phi;
