@@ -398,6 +398,39 @@ def main():
                 line["search_with_parameter_traffic"]["best_confirmed_by_oracle"] = bool(int(oracle.simulate_batch(
                     w_p.ops, w_p.edges, w_p.machine, w_p.cost, res.best[None], params=w_p.param_table())[0]) == res.best_ns)
             sim_p.close()
+        # the refinements of the inputs on the headline workload: what each costs per launch
+        if 1 in results:
+            import dataclasses
+            w_r = results[1][2]
+            cfgs_r = w_r.strategies(1024)
+            lbw, llat = W.paired_links(w_r.machine.gpus_per_node, 20, 6, 100, 900)
+            variants = {
+                "unequal_links": (dataclasses.replace(w_r.machine, link_Bpns=lbw, link_lat_ns=llat), None, None),
+                "parameter_traffic": (w_r.machine, w_r.param_table(), None),
+                "explicit_devices": (w_r.machine, None, W.device_maps(cfgs_r, w_r.machine.n_devices, 1807)),
+            }
+            ref = {}
+            for name, (mach_r, params_r, maps_r) in variants.items():
+                sim_r = binding.Simulator(w_r.ops, w_r.edges, mach_r, w_r.cost, params=params_r)
+                d_r = sim_r.upload_strategies(cfgs_r)
+                dm_r = None if maps_r is None else binding.to_device(maps_r)
+                out_r = sim_r.batch(d_r, 1024, d_devmaps=dm_r)
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(5):
+                    sim_r.batch(d_r, 1024, d_out=out_r, d_devmaps=dm_r)
+                b.record()
+                torch.cuda.synchronize()
+                ms = a.elapsed_time(b) / 5
+                ref[name] = {"kernel_ms": ms, "strategies_per_s": 1024 / (ms * 1e-3)}
+                if not args.no_cpu:
+                    import oracle
+                    want = oracle.simulate_batch(w_r.ops, w_r.edges, mach_r, w_r.cost, cfgs_r[:64], params=params_r,
+                                                 devmaps=None if maps_r is None else maps_r[:64])
+                    ref[name]["bit_exact_on_sample"] = bool(np.array_equal(out_r.cpu().numpy().view("<u8")[:64], want))
+                sim_r.close()
+            line["refinements_on_configs1"] = ref
         # neighbour sweep (local-optimality check): all single-op neighbours of one strategy
         if 1 in results:
             _, sim_n, w_n, cfgs_n = results[1]
