@@ -163,8 +163,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (candidates are independent; see DESIGN.md for how the "
-              "batch would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (candidates are independent: several GPUs would each take a "
+              "contiguous share of the batch). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -1,8 +1,8 @@
 /* ff_sim.h -- C boundary of the batched execution simulator for gfx950 (MI355X).
  *
  * The library predicts the per-iteration execution time of an operator graph G on a
- * simulated device topology D under a parallelization strategy S (FlexFlow, Section 5:
- * "takes G, D and S as inputs and predicts the execution time").  It does so for many
+ * simulated device topology D under a parallelization strategy S (FlexFlow, Section 5: the
+ * simulator's inputs are G, D and S, its output is the predicted time).  It does so for many
  * candidate strategies at once, one candidate per wavefront.
  *
  * All times are unsigned 64-bit integer nanoseconds.  Results are bit-exact: the value
@@ -55,8 +55,8 @@ enum {
 #define FF_OVERFLOW_NS (UINT64_MAX - 2) /* result if a simulated time reached FF_TIME_LIMIT_NS */
 
 /* How a consumer part's output range along one dim selects the range it reads along one
- * PRODUCER dim ("given the output tensor of a task and its operation type, we can infer
- * the necessary input tensors", Section 4).  src_dim = consumer output dim driving this
+ * PRODUCER dim (Section 4: the input tensors a task needs follow from its output tensor and
+ * the type of the operation).  src_dim = consumer output dim driving this
  * producer dim, or -1 if every consumer part reads the producer's whole extent.  For a
  * consumer part covering [lo, hi) along src_dim the range read is
  * [lo*stride + a, (hi-1)*stride + b + 1), clamped to [0, extent).  stride >= 1. */

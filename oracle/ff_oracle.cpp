@@ -110,7 +110,8 @@ uint64_t shared_elems(const Op& prod, const Edge& e, const Box& pb, const Box& c
     return elems;
 }
 
-// Section 5.1: "the communication device between the devices"
+// Section 5.1: the communication device that connects the two devices (see the readings: one link per
+// ordered GPU pair inside a node, one per ordered node pair between nodes)
 uint32_t link_row(const Machine& m, uint32_t from, uint32_t to) {
     uint32_t G = m.gpus_per_node, N = m.n_nodes, D = N * G;
     uint32_t na = from / G, nb = to / G;
