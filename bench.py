@@ -23,12 +23,12 @@ HEADLINE = 1
 # HBM bytes per launch of the batch kernel (fetch + write), from rocprofv3 --pmc FETCH_SIZE and
 # --pmc WRITE_SIZE runs of this script, scaled by what the same counters read for a 256 MiB
 # device-to-device copy (profiles/k_sim_batch_hbm_traffic.txt).  Not measured live.
-MEASURED_TRAFFIC_BYTES = {1: 491520, 2: 4188.1e6, 3: 6380.1e6, 4: 18026.1e6}
+MEASURED_TRAFFIC_BYTES = {1: 483328, 2: 4147.4e6, 3: 6382.8e6, 4: 18033.9e6}
 # Vector instructions per candidate (SQ_INSTS_VALU / B, profiles/k_sim_batch_sq_counters.txt) and the
 # chip's vector issue peak: 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per 64-lane instruction.  The
 # kernel is bound by instruction issue and latency, not by HBM; this second view says how busy the
 # vector units are.  Not measured live.
-MEASURED_VALU_PER_STRATEGY = {1: 24510.0, 2: 919919.0, 4: 12460557.0}
+MEASURED_VALU_PER_STRATEGY = {1: 22157.0, 2: 919919.0, 4: 12460557.0}
 VALU_PEAK_G_PER_S = 256 * 4 * 2.4e9 / 4 / 1e9
 
 
@@ -246,7 +246,7 @@ def main():
                    "candidates_per_step": head["B"]},
         "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": head["hbm_roofline_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE),
-                     "kernel": "k_sim_batch<WIDE=false, LDSW=true, STATS=false, Q=0, CACHE=true, EXT=false, GPN=4>",
+                     "kernel": "k_sim_batch<WIDE=false, LDSW=true, STATS=false, Q=3, CACHE=true, EXT=false, GPN=4>",
                      "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
                      "kernel_ms": head["kernel_ms"],
                      "achievable_copy_GBps": copy_gbps, "frac_of_copy": head["achieved_GBps"] / copy_gbps,

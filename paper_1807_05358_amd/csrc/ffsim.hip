@@ -78,7 +78,7 @@ constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMeta::loc");
 
 static KernelChoice choice(const ff_sim* s, bool cache) {
-    return KernelChoice{s->wide, s->lds_words, s->d_stats != nullptr, cache, s->dev.n_ops, s->dev.n_groups};
+    return KernelChoice{s->wide, s->lds_words, s->d_stats != nullptr, cache, s->dev.n_ops, s->dev.n_groups, s->dev.max_parts};
 }
 // ext: the launch uses the link table or explicit devices.  Machines with four GPUs per node (all
 // benchmark configurations) have kernels compiled for that node size.

@@ -158,10 +158,21 @@ __device__ __forceinline__ u64 wave_max_u64(u64 v) { return ~wave_min_u64(~v); }
 // Same minimum for words that are all >= base (pending events never lie before the event
 // popped last): one 32-bit reduction over the saturated distance to base; the 64-bit
 // reduction only runs if every distance is 2^32-1 or more (no event, or a far one).
+// ROW0: the caller knows at compile time that lanes 16..63 hold words with bit 63 set (no event
+// there): the butterfly inside the first row of 16 lanes is then the whole reduction.
+__device__ __forceinline__ uint32_t row0_min_u32(uint32_t v) {
+    uint32_t t;
+    t = dpp_u32<0xB1>(v); v = t < v ? t : v;
+    t = dpp_u32<0x4E>(v); v = t < v ? t : v;
+    t = dpp_u32<0x141>(v); v = t < v ? t : v;
+    t = dpp_u32<0x140>(v); v = t < v ? t : v;
+    return readlane_u32(v, 0);
+}
+template <bool ROW0 = false>
 __device__ __forceinline__ u64 wave_min_from(u64 v, u64 base) {
     const u64 d = v - base;
     const uint32_t sat = (uint32_t)(d >> 32) ? 0xffffffffu : (uint32_t)d;
-    const uint32_t m = wave_min_u32(sat);
+    const uint32_t m = ROW0 ? row0_min_u32(sat) : wave_min_u32(sat);
     if (m != 0xffffffffu) return base + m;
     return wave_min_u64(v);
 }

@@ -254,12 +254,15 @@ __device__ __forceinline__ void load_snapshot(SimX& m, const Recorder& rec, uint
 // Q: shape of the queue above the task words.
 //   Q_ONE   at most 64 ops: level 1 (one minimum per op) sits in a register, lane = op; nothing of
 //           the queue is in LDS while the loop runs (batch kernels only: level 1 is not written back);
+//   Q_ONE16 the same for at most 16 ops of at most 16 parts each (16 columns in the cost table): every
+//           reduction over ops or over parts ends in the first row of 16 lanes;
 //   Q_FLAT  up to FLAT_GROUPS groups of 64 ops: level 1 in LDS, every lane scans its column;
 //   Q_TREE  more groups: level 1 in LDS, level 2 (one minimum per group) in a register, lane = group.
-enum QueueShape : int { Q_ONE = 0, Q_FLAT = 1, Q_TREE = 2 };
+enum QueueShape : int { Q_ONE = 0, Q_FLAT = 1, Q_TREE = 2, Q_ONE16 = 3 };
 template <bool WIDE, bool RECORD, bool REG, bool STATS, int Q, bool CACHE, class SimX>
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     constexpr bool TREE = Q == Q_TREE;
+    constexpr bool ONE = Q == Q_ONE || Q == Q_ONE16, ROW0 = Q == Q_ONE16;
     const int lane = lane_id();
     PROF_DECL
     const SimDev& S = m.S;
@@ -272,7 +275,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     bool overflow = m.overflow;
     // the register-resident level of the queue (see QueueShape)
     u64 qreg = W_NONE;
-    if (Q == Q_ONE) qreg = L.l1[lane];
+    if (ONE) qreg = L.l1[lane];
     if (Q == Q_TREE) qreg = (uint32_t)lane < S.n_groups ? L.l2[lane] : W_NONE;
     // Values chosen per lane between two of these (same node or not) must sit in registers: a
     // select between two fields of the argument block is otherwise turned into a per-lane load
@@ -286,8 +289,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
         uint32_t i;
-        if (Q == Q_ONE) {
-            kmin = wave_min_from(qreg, last_key);
+        if (ONE) {
+            kmin = wave_min_from<ROW0>(qreg, last_key);
             if (kmin >> 63) break;
             const u64 m1 = ballot(qreg == kmin);
             if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }
@@ -321,7 +324,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const int col = __builtin_ctzll(m1);
             i = readlane_u32(gbest, col) * WAVE + col;
         }
-        static_assert(!(RECORD && Q == Q_ONE), "snapshots read level 1 from LDS");
+        static_assert(!(RECORD && ONE), "snapshots read level 1 from LDS");
         if (RECORD) {
             // the state before the first event at or after a multiple of `step` is a snapshot
             while (rec.next < rec.n_snaps && kmin >= (u64)rec.next * rec.step) {
@@ -504,8 +507,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     words[j * WAVE + lane] = w;
                 }
                 if (ballot(now_ready)) {
-                    const u64 nmin = wave_min_from(now_ready ? w : W_NONE, last_key);
-                    if (Q == Q_ONE) {
+                    const u64 nmin = wave_min_from<ROW0>(now_ready ? w : W_NONE, last_key);
+                    if (ONE) {
                         if ((uint32_t)lane == j && nmin < qreg) qreg = nmin;
                     } else {
                         if (lane == 0 && nmin < L.l1[j]) L.l1[j] = nmin;
@@ -564,8 +567,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             if (in_mask) k0 = W_NONE;
         }
         if (in_mask) words[i * WAVE + lane] = k0;
-        const u64 new_l1 = wave_min_from(k0, last_key);
-        if (Q == Q_ONE) {
+        const u64 new_l1 = wave_min_from<ROW0>(k0, last_key);
+        if (ONE) {
             if ((uint32_t)lane == i) qreg = new_l1;
             wave_sync();
         } else {

@@ -14,12 +14,13 @@ typedef void (*try_kernel_t)(SimDev, const DOp*, const DEdge*, const DEdge*, con
                              uint32_t, uint32_t, const uint32_t*, uint32_t, u64*, const uint32_t*, uint32_t*, unsigned char*, size_t);
 
 // What fixes the instantiation inside one object.  Batch kernels: four layouts -- task words in
-// LDS (small graphs; never a queue level 2; up to 64 ops the whole queue in a register), in HBM
+// LDS (small graphs; never a queue level 2; up to 64 ops the whole queue in a register, with a
+// shorter form for 16 ops of 16 parts), in HBM
 // without and with level 2 -- each with or without the kept per-edge set-up, the per-candidate
 // counters and 64-bit sums.
 struct KernelChoice {
     bool wide, lds_words, stats, cache;
-    uint32_t n_ops, n_groups;
+    uint32_t n_ops, n_groups, max_parts;
 };
 // EXT: the refinements of the inputs (link table, explicit devices); GPN: GPUs per node the
 // kernels are compiled for (4, or 0 = any).  One explicit specialisation per object.

@@ -597,7 +597,7 @@ class Workload:
     edges: np.ndarray
     flops: np.ndarray
     machine: Machine
-    cost: np.ndarray            # [n_ops][MAX_PARTS] uint32 ns
+    cost: np.ndarray            # [n_ops][max_parts] uint32 ns
     n_candidates: int
     max_parts: int
     choices: tuple
@@ -654,7 +654,8 @@ def workload(config_id: int) -> Workload:
         name, fn, mach, n_cand, max_parts, choices = _SPECS[config_id]
         ops, edges, flops = fn()
         seed = BASE_SEED + config_id
-        _cache[config_id] = Workload(config_id, name, ops, edges, flops, mach,
-                                     cost_table(config_id, flops, seed), n_cand, max_parts,
+        # one column per possible number of parts of the configuration (configs[0]: 4, [1]: 16, others 64)
+        cost = np.ascontiguousarray(cost_table(config_id, flops, seed)[:, :max_parts])
+        _cache[config_id] = Workload(config_id, name, ops, edges, flops, mach, cost, n_cand, max_parts,
                                      choices, seed)
     return _cache[config_id]
