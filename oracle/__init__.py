@@ -13,17 +13,23 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ff_oracle.cpp")
-_LIB = os.path.join(_HERE, "libff_oracle.so")
+# FF_ORACLE_LIB: tests that plant a mistake in a copy of the source point the pins at the copy's library
+_LIB = os.environ.get("FF_ORACLE_LIB") or os.path.join(_HERE, "libff_oracle.so")
 INVALID = 2 ** 64 - 1
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """compile the oracle with g++ (plain -O2, no vector tricks)."""
+    if os.environ.get("FF_ORACLE_LIB"):
+        return _LIB                       # someone else's build
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-pthread",
-                               "-Wall", "-o", _LIB, _SRC])
+        compile_oracle(_SRC, _LIB)
     return _LIB
+
+
+def compile_oracle(src: str, lib_path: str) -> None:
+    subprocess.check_call(["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-pthread", "-Wall", "-o", lib_path, src])
 
 
 def lib():
@@ -33,6 +39,8 @@ def lib():
         vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
         L.ffo_build.restype = vp
         L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ffo_graph_ok.restype = C.c_int
+        L.ffo_graph_ok.argtypes = [u32, u32, vp]
         L.ffo_from_arrays.restype = vp
         L.ffo_from_arrays.argtypes = [u32, vp, vp, u32, u32, vp, vp]
         L.ffo_counts.restype = None
@@ -51,6 +59,12 @@ def lib():
 
 def _ptr(a):
     return a.ctypes.data_as(C.c_void_p)
+
+
+def _check_graph(ops, edges):
+    """the oracle's readings of task ids need the tensor edges listed producer by producer"""
+    if not lib().ffo_graph_ok(len(ops), len(edges), _ptr(edges)):
+        raise ValueError("oracle: edges must go from a lower to a higher op index and be listed producer by producer")
 
 
 def _cost_args(cost):
@@ -129,6 +143,7 @@ def build_task_graph(ops, edges, machine, cost, cfg, devmap=None, params=None):
     devmap [n_ops][64] uint16: the device of every part given explicitly (the configs' offset
     and stride are then not used)."""
     ops, edges, cfg = map(np.ascontiguousarray, (ops, edges, cfg))
+    _check_graph(ops, edges)
     m = _machine(machine)
     keep, cargs = _cost_args(cost)
     keep_l, largs = _link_args(machine)
@@ -167,6 +182,7 @@ def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None, p
     devmaps [B][n_ops][64] uint16: explicit devices of all parts (see build_task_graph)."""
     ops, edges, cfgs = map(np.ascontiguousarray, (ops, edges, cfgs))
     assert cfgs.ndim == 2 and cfgs.shape[1] == len(ops)
+    _check_graph(ops, edges)
     m = _machine(machine)
     out = np.zeros(cfgs.shape[0], "<u8")
     keep, cargs = _cost_args(cost)

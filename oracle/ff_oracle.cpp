@@ -11,8 +11,9 @@
 //             producer-part / consumer-part pair that shares a sub-tensor: a dependency
 //             if both parts sit on the same device, otherwise a communication task on the
 //             link device between them, assumption A2 for its time).
-//   simulate: Algorithm 1 (full simulation) literally, with a binary-heap priority queue
-//             ordered by (readyTime, task id).
+//   simulate: the full simulation of Section 5.2 (Algorithm 1): READY tasks leave one global
+//             queue in (readyTime, task id) order; a dequeued task starts once its device has
+//             finished the task dequeued for it before (assumptions A3, A4).
 // Delta simulation (Algorithm 2) is defined by the paper to produce the same timeline as a
 // full simulation of the changed strategy (Section 5.3), so the oracle for it is: change the
 // strategy, build, simulate.
@@ -24,7 +25,10 @@
 //   [floor(p*E/deg), floor((p+1)*E/deg)); device of part k = (offset + k*stride) mod D;
 //   link device rows: D + node*G*G + ls*G + lt inside a node (one per ordered GPU pair),
 //   D + N*G*G + a*N + b between nodes a != b (one per ordered node pair);
-//   transfer time = ceil(bytes / bandwidth) + latency.
+//   transfer time = ceil(bytes / bandwidth) + latency;
+//   tensor edges are listed producer by producer (src_op never decreases along the list), so that
+//   "communication tasks in edge order" and "op by op" are the same order; other lists are refused
+//   (ffo_graph_ok).
 //
 // Pins: tests/test_oracle_*.py (closed forms, bounds, brute force over task orders, a
 // timeline verifier, hand-computed cases under tests/golden/).
@@ -32,7 +36,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
-#include <queue>
+#include <set>
 #include <thread>
 #include <utility>
 #include <vector>
@@ -171,8 +175,18 @@ uint64_t transfer_ns(const Machine& m, const Extras& x, uint32_t from, uint32_t 
     return (bytes + bw - 1) / bw + lat;       // assumption A2, rounded up, plus the link's latency
 }
 
+// The readings above need the edge list producer by producer; ops in topological order.
+bool graph_ok(uint32_t n_ops, uint32_t n_edges, const Edge* edges) {
+    for (uint32_t e = 0; e < n_edges; e++) {
+        if (edges[e].src_op >= n_ops || edges[e].dst_op >= n_ops || edges[e].src_op >= edges[e].dst_op) return false;
+        if (e > 0 && edges[e - 1].src_op > edges[e].src_op) return false;
+    }
+    return true;
+}
+
 bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, const Machine& m,
            const CostModel& cm, const Cfg* cfg, const Extras& x, TaskGraph& tg) {
+    if (!graph_ok(n_ops, n_edges, edges)) return false;
     const uint32_t G = m.gpus_per_node, N = m.n_nodes, D = N * G;
     const uint32_t max_parts = cm.table ? std::min(MAX_PARTS, cm.n_cols) : MAX_PARTS;
     tg.n_rows = D + N * G * G + N * N;
@@ -240,38 +254,56 @@ bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, c
     return true;
 }
 
-// Algorithm 1.  ready/start/end may be null.
+// Section 5.2, full simulation.  Every task is NOTREADY until its last predecessor is COMPLETE; then it
+// is READY, and its readyTime is the largest endTime among its predecessors (0 for a task without
+// any).  READY tasks wait in one global queue ordered by (readyTime, task id).  The task at the head
+// of the queue is assigned to its device: the device runs one task at a time, in the order the
+// tasks are handed to it, so the task starts when both its inputs and the device are available
+// (assumptions A3, A4) and ends exeTime later.  The result is the largest endTime.
+// ready_o / start_o / end_o (may be null) receive the timeline.
+enum TaskState : uint8_t { NOTREADY, READY, COMPLETE };
+
 uint64_t simulate(const TaskGraph& tg, uint64_t* ready_o, uint64_t* start_o, uint64_t* end_o) {
     const size_t n = tg.exe.size();
-    std::vector<uint64_t> ready(n, 0), start(n, 0), end(n, 0), last_end(tg.n_rows, 0);
-    std::vector<uint32_t> waiting(tg.n_in);   // predecessors not yet COMPLETE
-    typedef std::pair<uint64_t, uint32_t> Key;  // (readyTime, id)
-    std::priority_queue<Key, std::vector<Key>, std::greater<Key>> ready_queue;
+    std::vector<uint64_t> ready_time(n, 0), start_time(n, 0), end_time(n, 0);
+    std::vector<TaskState> state(n, NOTREADY);
+    std::vector<uint32_t> complete_preds(n, 0);          // predecessors of the task that are COMPLETE
+    std::vector<uint64_t> device_busy_until(tg.n_rows, 0);
+    std::set<std::pair<uint64_t, uint32_t>> ready_queue;   // (readyTime, id) of every READY task, ascending
+
     for (uint32_t t = 0; t < n; t++)
-        if (tg.n_in[t] == 0) ready_queue.push(Key(0, t));
+        if (tg.n_in[t] == 0) { state[t] = READY; ready_queue.emplace(0, t); }
+
     uint64_t makespan = 0;
     while (!ready_queue.empty()) {
-        uint32_t t = ready_queue.top().second;
-        ready_queue.pop();
-        uint32_t d = tg.dev[t];
-        start[t] = std::max(ready[t], last_end[d]);
-        end[t] = start[t] + tg.exe[t];
-        last_end[d] = end[t];
-        makespan = std::max(makespan, end[t]);
-        for (uint32_t s : tg.out[t]) {
-            ready[s] = std::max(ready[s], end[t]);
-            if (--waiting[s] == 0) ready_queue.push(Key(ready[s], s));
+        const uint32_t t = ready_queue.begin()->second;
+        ready_queue.erase(ready_queue.begin());
+        uint64_t& busy_until = device_busy_until[tg.dev[t]];
+        start_time[t] = std::max(ready_time[t], busy_until);
+        end_time[t] = start_time[t] + tg.exe[t];
+        busy_until = end_time[t];
+        state[t] = COMPLETE;
+        makespan = std::max(makespan, end_time[t]);
+        for (uint32_t succ : tg.out[t]) {
+            ready_time[succ] = std::max(ready_time[succ], end_time[t]);
+            if (++complete_preds[succ] == tg.n_in[succ]) {
+                state[succ] = READY;
+                ready_queue.emplace(ready_time[succ], succ);
+            }
         }
     }
-    if (ready_o) std::memcpy(ready_o, ready.data(), n * 8);
-    if (start_o) std::memcpy(start_o, start.data(), n * 8);
-    if (end_o) std::memcpy(end_o, end.data(), n * 8);
+    if (ready_o) std::memcpy(ready_o, ready_time.data(), n * 8);
+    if (start_o) std::memcpy(start_o, start_time.data(), n * 8);
+    if (end_o) std::memcpy(end_o, end_time.data(), n * 8);
     return makespan;
 }
 
 }  // namespace
 
 extern "C" {
+
+// 1 if the edge list is one the oracle accepts (see graph_ok), else 0
+int ffo_graph_ok(uint32_t n_ops, uint32_t n_edges, const void* edges) { return graph_ok(n_ops, n_edges, (const Edge*)edges) ? 1 : 0; }
 
 // Build the task graph of one strategy.  Returns an opaque handle or null if the strategy
 // is invalid.

@@ -19,7 +19,9 @@ def cfgs_all(ops, deg=(1, 1, 1, 1), off=0, stride=1):
 
 @pytest.mark.parametrize("name", ["build_two_ops_two_gpus.json", "build_shared_internode_link.json",
                                   "build_part_order_row_major.json", "build_link_latency.json",
-                                  "build_intranode_latency.json"])
+                                  "build_intranode_latency.json", "build_uneven_split_7_by_3.json",
+                                  "build_uneven_split_35_by_4.json", "build_strided_window_uneven_split.json",
+                                  "build_pair_order_on_shared_link.json"])
 def test_hand_computed_build_and_timeline(golden_dir, name):
     g = load_golden(golden_dir, name)
     tg = oracle.build_task_graph(*graph_from_golden(g))
@@ -30,8 +32,9 @@ def test_hand_computed_build_and_timeline(golden_dir, name):
     assert start.tolist() == g["start"] and end.tolist() == g["end"] and mk == g["makespan"]
 
 
-def test_hand_computed_window_pairs(golden_dir):
-    g = load_golden(golden_dir, "build_conv_window_pairs.json")
+@pytest.mark.parametrize("name", ["build_conv_window_pairs.json", "build_strided_window_uneven_split.json"])
+def test_hand_computed_window_pairs(golden_dir, name):
+    g = load_golden(golden_dir, name)
     tg = oracle.build_task_graph(*graph_from_golden(g))
     comm = []
     for c in range(tg.n_compute, tg.n_tasks):
@@ -244,6 +247,24 @@ def test_delta_oracle_is_resimulation_and_inverse_restores():
     inv[1]["cfg"] = cfg0[int(muts[0]["op"])]
     back = oracle.simulate_delta_chain(w.ops, w.edges, w.machine, w.cost, cfg0, inv)
     assert back[1] == oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[None])[0]
+
+
+def test_edge_lists_not_grouped_by_producer_are_refused():
+    """task ids follow (edge, producer part, consumer part) and, with parameter traffic, op by op: the two
+    agree only for an edge list that is grouped by producer, so the oracle refuses any other"""
+    w = W.workload(2)
+    cfg = w.strategies(1)
+    bad = w.edges.copy()
+    k = int(np.nonzero(np.diff(bad["src_op"]) > 0)[0][0])
+    bad[[k, k + 1]] = bad[[k + 1, k]]
+    with pytest.raises(ValueError):
+        oracle.simulate_batch(w.ops, bad, w.machine, w.cost, cfg)
+    with pytest.raises(ValueError):
+        oracle.build_task_graph(w.ops, bad, w.machine, w.cost, cfg[0])
+    back = bad.copy()
+    back[0]["src_op"], back[0]["dst_op"] = back[0]["dst_op"], back[0]["src_op"]     # an edge from a later to an earlier op
+    with pytest.raises(ValueError):
+        oracle.simulate_batch(w.ops, back, w.machine, w.cost, cfg)
 
 
 def test_batch_threads_agree():
