@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the batched execution simulator on one MI355X.
 
-A step is one pass of the whole hot path (task-graph construction + full simulation,
-one ff_sim_batch call) over one batch of seeded synthetic candidate strategies that is
-already resident in HBM.  The headline workload is configs[1] (AlexNet-shaped graph,
-4x4 simulated devices, 1024 candidates); the other four configurations and the delta
-chain of configs[4] are measured the same way and reported in "workloads".
+A step is one pass of the whole hot path (task-graph construction + full simulation, one
+ff_sim_batch call) over one batch of seeded synthetic candidate strategies that is already
+resident in HBM.  The headline workload is the largest configuration, configs[4] (NMT-shaped
+graph of 2321 ops, 16x4 simulated devices, 1024 candidates per step); the other four
+configurations, the delta chains of configs[4], the search loop and the refinements are
+measured the same way and reported beside it.
 
 Prints ONE JSON line.  python bench.py --gpus 1 --steps K --warmup W
+       python bench.py --long-chain 10000    (the configuration's 10000-step mutation chain alone)
 """
 import argparse
 import json
@@ -19,17 +21,29 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published
-HEADLINE = 1
-# HBM bytes per launch of the batch kernel (fetch + write), from rocprofv3 --pmc FETCH_SIZE and
-# --pmc WRITE_SIZE runs of this script, scaled by what the same counters read for a 256 MiB
-# device-to-device copy (profiles/k_sim_batch_hbm_traffic.txt).  Not measured live.
-MEASURED_TRAFFIC_BYTES = {1: 483328, 2: 4147.4e6, 3: 6382.8e6, 4: 18033.9e6}
-# Vector instructions per candidate (SQ_INSTS_VALU / B, profiles/k_sim_batch_sq_counters.txt) and the
-# chip's vector issue peak: 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per 64-lane instruction.  The
-# kernel is bound by instruction issue and latency, not by HBM; this second view says how busy the
-# vector units are.  Not measured live.
-MEASURED_VALU_PER_STRATEGY = {1: 22157.0, 2: 919919.0, 4: 12460557.0}
+HEADLINE = 4
+# the chip's vector issue peak: 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per 64-lane instruction
 VALU_PEAK_G_PER_S = 256 * 4 * 2.4e9 / 4 / 1e9
+# rocprofv3 counter readings per launch (HBM traffic from FETCH_SIZE / WRITE_SIZE, instruction
+# counts from SQ_INSTS_*), one line per workload with the kernel instantiation they were read for
+COUNTER_FILE = os.path.join(ROOT, "profiles", "k_sim_batch_pmc_counters.txt")
+
+
+def profiled_counters():
+    """{config id: {"kernel": name, "B": .., "traffic_bytes": .., "insts_valu": ..}} from the
+    tracked summary of the counter runs; {} if there is none."""
+    out = {}
+    try:
+        for line in open(COUNTER_FILE):
+            if not line.startswith("counters "):
+                continue
+            f = dict(kv.split("=", 1) for kv in line.split()[1:] if "=" in kv)
+            name = line.split('kernel="', 1)[1].split('"', 1)[0]
+            out[int(f["config"])] = {"kernel": name, "B": int(f["B"]), "traffic_bytes": float(f["traffic_bytes"]),
+                                     "insts_valu": float(f["insts_valu"])}
+    except OSError:
+        pass
+    return out
 
 
 def alg_bytes(n_ops, tc, npairs):
@@ -91,6 +105,17 @@ def cpu_model():
     return "unknown"
 
 
+def host_cores():
+    """(threads the oracle is run on, logical CPUs of the box, CPUs this process may use)"""
+    logical = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = logical
+    # a one-GPU box's CPU share is 16 cores, whatever the host shows
+    return max(1, min(usable, 16)), logical, usable
+
+
 def oracle_build_share(w, cfgs):
     """seconds the oracle spends building task graphs vs. building + simulating, one thread."""
     import oracle
@@ -128,18 +153,34 @@ def timeline_items(w, cfg):
     return keys, np.stack([r, s_, e], axis=1)
 
 
-def changed_items(w, cfg_a, cfg_b):
+def changed_items(items_a, items_b):
     """Section 5.3's work: tasks removed + tasks inserted + tasks whose ready/start/end differ
     between the timelines of two strategies (counted by the oracle, nothing from the GPU)."""
     import numpy as np
-    ka, ta = timeline_items(w, cfg_a)
-    kb, tb = timeline_items(w, cfg_b)
+    ka, ta = items_a
+    kb, tb = items_b
     oa, ob = np.argsort(ka), np.argsort(kb)
     ka, ta, kb, tb = ka[oa], ta[oa], kb[ob], tb[ob]
     common, ia, ib = np.intersect1d(ka, kb, assume_unique=True, return_indices=True)
     moved = int((ta[ia] != tb[ib]).any(axis=1).sum())
     return {"removed": int(len(ka) - len(common)), "inserted": int(len(kb) - len(common)), "moved": moved,
             "tasks_after": int(len(kb))}
+
+
+def delta_work_model(w, cfg0, muts, steps):
+    """what an exact delta algorithm has to touch on the given steps of a chain: per step the
+    oracle's timelines before and after the mutation are diffed."""
+    import numpy as np
+    want = sorted(int(s) for s in steps)
+    cur = np.array(cfg0, copy=True)
+    work = []
+    for s in range(want[-1] + 1):
+        nxt = cur.copy()
+        nxt[int(muts[s]["op"])] = muts[s]["cfg"]
+        if s in want:
+            work.append(changed_items(timeline_items(w, cur), timeline_items(w, nxt)))
+        cur = nxt
+    return work
 
 
 def oracle_rate(w, cfgs, threads):
@@ -149,18 +190,82 @@ def oracle_rate(w, cfgs, threads):
     return len(cfgs) / (time.perf_counter() - t0), res
 
 
+def oracle_chain_steps(w, cfg0, muts, steps, threads):
+    """the oracle's times after the given steps of a mutation chain (full re-simulation of each)"""
+    import numpy as np
+    import oracle
+    want = set(int(s) for s in steps)
+    cur = np.array(cfg0, copy=True)
+    snaps = []
+    for s in range(max(want) + 1):
+        cur[int(muts[s]["op"])] = muts[s]["cfg"]
+        if s in want:
+            snaps.append(cur.copy())
+    return oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, np.stack(snaps), n_threads=threads)
+
+
+def long_chain(n_steps, check, threads):
+    """the mutation chain of configs[4] at its full length: n_steps cumulative single-op mutations on
+    one chain with delta simulation, in calls of 250 steps (a progress line each), `check` steps
+    spread over the chain compared with the oracle."""
+    import numpy as np
+    import torch
+    from paper_1807_05358_amd import binding, workloads as W
+    w = W.workload(4)
+    cfg0 = w.strategies(1)
+    muts = w.mutations(n_steps, 1)
+    sim = binding.Simulator(w.ops, w.edges, w.machine, w.cost)
+    ch = binding.Chains(sim, cfg0)
+    got, gpu_ms = [], 0.0
+    t0 = time.perf_counter()
+    for a in range(0, n_steps, 250):
+        n = min(250, n_steps - a)
+        d_m = ch.upload_mutations(muts[a:a + n])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        out = ch.delta(d_m, n)
+        e1.record()
+        torch.cuda.synchronize()
+        gpu_ms += e0.elapsed_time(e1)
+        got.append(out.cpu().numpy().view("<u8")[:, 0])
+        print(f"long chain: {a + n} of {n_steps} steps, {gpu_ms / (a + n):.2f} ms per step", file=sys.stderr, flush=True)
+    wall = time.perf_counter() - t0
+    got = np.concatenate(got)
+    st = ch.stats()
+    sel = sorted(set(np.linspace(0, n_steps - 1, check).astype(int).tolist()) | {0, n_steps - 1})
+    want = oracle_chain_steps(w, cfg0[0], muts[:, 0], sel, threads)
+    bad = [s for s, v in zip(sel, want) if got[s] != v]
+    full = float(st["n_events_full"][0])
+    line = {"metric": "delta-sims/sec", "workload": "configs[4] nmt: one chain of cumulative single-op mutations (delta simulation)",
+            "steps": n_steps, "gpu_ms": gpu_ms, "ms_per_step": gpu_ms / n_steps, "delta_sims_per_s": n_steps / (gpu_ms * 1e-3),
+            "wall_s_including_uploads": wall,
+            "steps_resumed_from_snapshot": int(st["n_resumed"][0]), "steps_rejoined_previous_timeline": int(st["n_converged"][0]),
+            "mean_events_per_step": float(st["n_events"][0]) / max(1, int(st["n_steps"][0])),
+            "events_of_a_full_simulation": full,
+            "share_of_a_full_simulation_per_step": float(st["n_events"][0]) / max(1, int(st["n_steps"][0])) / max(1.0, full),
+            "oracle_checked_steps": len(sel), "first_mismatching_step": (bad[0] if bad else None), "bit_exact_on_checked_steps": not bad,
+            "min_ns": int(got.min()), "max_ns": int(got[got < 2 ** 63].max()), "input_sha256_first_candidate": w.sha256(1)}
+    ch.close()
+    sim.close()
+    print(json.dumps(line))
+    return 0 if not bad else 1
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--only-headline", action="store_true", help="skip the other workloads and the delta chain")
     ap.add_argument("--workloads", default="", help="comma-separated config ids to run instead of all five (profiling runs)")
-    ap.add_argument("--no-delta", action="store_true", help="skip the delta chains")
+    ap.add_argument("--no-delta", action="store_true", help="skip the delta chains, the search and the refinements")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run three device-to-device copies of 256 MiB (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--long-chain", type=int, default=0, metavar="N",
+                    help="run only the N-step mutation chain of configs[4] (10000 in the configuration list)")
+    ap.add_argument("--check", type=int, default=200, help="with --long-chain: steps compared with the oracle")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (candidates are independent: several GPUs would each take a "
@@ -171,6 +276,10 @@ def main():
     import torch
     from paper_1807_05358_amd import binding, workloads as W
 
+    threads, logical_cpus, usable_cpus = host_cores()
+    if args.long_chain:
+        sys.exit(long_chain(args.long_chain, args.check, threads))
+
     if args.calibration_copy:
         src = torch.empty(256 * 2 ** 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -179,9 +288,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    threads = min(os.cpu_count() or 1, 16)
+    prof = profiled_counters()
     results = {}
-    order = [HEADLINE] if args.only_headline else [HEADLINE, 0, 2, 3, 4]
+    order = [HEADLINE] if args.only_headline else [HEADLINE, 0, 1, 2, 3]
     if args.workloads:
         order = [HEADLINE] + [int(x) for x in args.workloads.split(",") if int(x) != HEADLINE]
     for c in order:
@@ -191,26 +300,39 @@ def main():
         sim = binding.Simulator(w.ops, w.edges, w.machine, w.cost)
         d_strat = sim.upload_strategies(cfgs)
         _, st = sim.simulate(cfgs, stats=True)          # untimed: counters for the byte model
-        steps = args.steps if c != 4 else max(2, min(args.steps, 5))
-        kern_ms, wall_ms, out = time_batches(sim, d_strat, B, steps, args.warmup if c != 4 else 1)
+        sim.batch(d_strat, B)                            # back to the kernel without counters
+        kernel = binding.ff_sim_batch_kernel_name(sim.handle, B)
+        if c == HEADLINE:
+            steps, warmup = args.steps, args.warmup
+        else:
+            steps, warmup = (20, 3) if c < 2 else (5, 1)
+        kern_ms, wall_ms, out = time_batches(sim, d_strat, B, steps, warmup)
         got = out.cpu().numpy().view("<u8")
         tc, npairs = float(st["n_compute"].mean()), float(st["n_pairs"].mean())
         ab = alg_bytes(w.n_ops, tc, npairs)
+        # counter readings only count if they were taken for the instantiation launched here
+        pc = prof.get(c)
+        if pc is not None and (pc["kernel"] != kernel or pc["B"] != B):
+            pc = None
+        traffic = pc["traffic_bytes"] if pc else None
+        valu = pc["insts_valu"] if pc else None
         r = {
             "workload": f"configs[{c}] {w.name}", "B": B, "n_ops": w.n_ops, "n_edges": int(len(w.edges)),
-            "simulated_devices": w.machine.n_devices, "steps": steps,
+            "simulated_devices": w.machine.n_devices, "steps": steps, "warmup": warmup,
             "ms_per_step": wall_ms, "kernel_ms": kern_ms, "strategies_per_s": B / (wall_ms * 1e-3),
             "mean_compute_tasks": tc, "mean_pairs": npairs, "mean_comm_tasks": float(st["n_comm"].mean()),
             "mean_events": float(st["n_events"].mean()),
-            "alg_bytes_per_strategy": ab,
-            "achieved_GBps": ab * B / (kern_ms * 1e-3) / 1e9,
-            "hbm_roofline_frac": ab * B / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-            "hbm_traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get(c),
-            "hbm_traffic_GBps": (MEASURED_TRAFFIC_BYTES[c] / (kern_ms * 1e-3) / 1e9 if c in MEASURED_TRAFFIC_BYTES else None),
-            "irreducible_io_bytes_per_strategy": 8 * w.n_ops + 8,
+            "roofline": {"bound": "hbm", "achieved": ab * B / (kern_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": ab * B / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": traffic,
+                         "kernel": kernel, "alg_bytes_per_strategy": ab, "alg_bytes_per_launch": ab * B, "kernel_ms": kern_ms,
+                         "traffic_GBps": (traffic / (kern_ms * 1e-3) / 1e9 if traffic else None),
+                         "irreducible_io_bytes_per_launch": (8 * w.n_ops + 8) * B},
+            "roofline_alu": ({"bound": "alu", "achieved": valu / (kern_ms * 1e-3) / 1e9, "peak": VALU_PEAK_G_PER_S,
+                              "unit": "G wavefront-instructions/s", "frac": valu / (kern_ms * 1e-3) / 1e9 / VALU_PEAK_G_PER_S,
+                              "insts_valu_per_strategy": valu / B,
+                              "note": "instruction count per launch from rocprofv3 SQ_INSTS_VALU (profiles/), kernel time live"}
+                             if valu else None),
             "wavefronts_per_simd": min(B, 1024 * 8) / 1024.0,
-            "valu_issue_frac": (MEASURED_VALU_PER_STRATEGY[c] * B / (kern_ms * 1e-3) / 1e9 / VALU_PEAK_G_PER_S
-                                if c in MEASURED_VALU_PER_STRATEGY else None),
             "input_sha256": w.sha256(B),
         }
         if not args.workloads and not args.only_headline:
@@ -222,7 +344,7 @@ def main():
             r["saturation_strategies_per_s"] = 4 * B / (w4ms * 1e-3)
             del d4
         if not args.no_cpu:
-            n_s = {0: 64, 1: 1024, 2: 128, 3: 64, 4: 16}[c]
+            n_s = {0: 64, 1: 1024, 2: 128, 3: 64, 4: 128}[c]
             idx = np.linspace(0, B - 1, n_s).astype(np.int64)
             rate_t, ref = oracle_rate(w, cfgs[idx], threads)
             r["oracle_strategies_per_s"] = rate_t
@@ -233,6 +355,9 @@ def main():
 
     head, sim, w, cfgs = results[HEADLINE]
     copy_gbps = copy_bandwidth_gbps()
+    roof = dict(head["roofline"])
+    roof["achievable_copy_GBps"] = copy_gbps
+    roof["frac_of_copy"] = roof["achieved"] / copy_gbps
     line = {
         "metric": "simulated strategies/sec (build + full simulation)",
         "value": head["strategies_per_s"],
@@ -241,43 +366,32 @@ def main():
         "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "configs[1]: AlexNet-shaped 12-op graph, batch 256, 4 nodes x 4 simulated devices, "
-                               "1024 seeded candidate strategies per step", "B": head["B"],
+        "config": {"workload": f"configs[{HEADLINE}]: NMT-shaped graph ({w.n_ops} ops, {len(w.edges)} tensor edges: 2+2 LSTM layers "
+                               "unrolled 40 steps, attention, vocabulary 32768), batch 64, 16 nodes x 4 simulated devices, "
+                               f"{head['B']} seeded candidate strategies per step", "B": head["B"],
                    "candidates_per_step": head["B"]},
-        "roofline": {"bound": "hbm", "achieved": head["achieved_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": head["hbm_roofline_frac"], "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE),
-                     "kernel": "k_sim_batch<WIDE=false, LDSW=true, STATS=false, Q=3, CACHE=true, EXT=false, GPN=4>",
-                     "alg_bytes_per_launch": head["alg_bytes_per_strategy"] * head["B"],
-                     "kernel_ms": head["kernel_ms"],
-                     "achievable_copy_GBps": copy_gbps, "frac_of_copy": head["achieved_GBps"] / copy_gbps,
-                     "traffic_GBps": head["hbm_traffic_GBps"],
-                     "irreducible_io_bytes_per_launch": head["irreducible_io_bytes_per_strategy"] * head["B"]},
-        # the same launch against the vector-issue peak (64-lane integer instructions per second)
-        "roofline_alu": {"bound": "alu", "achieved": MEASURED_VALU_PER_STRATEGY[HEADLINE] * head["B"] / (head["kernel_ms"] * 1e-3) / 1e9,
-                         "peak": VALU_PEAK_G_PER_S, "unit": "G wavefront-instructions/s", "frac": head["valu_issue_frac"],
-                         "note": "instruction count from rocprofv3 SQ_INSTS_VALU (profiles/), kernel time live"},
+        "roofline": roof,
+        "roofline_alu": head["roofline_alu"],
     }
     if not args.no_cpu:
-        # the oracle as it stands on the host cores: the whole 1024-candidate batch, repeated
-        # until about 10 s of CPU work have been spent
-        one, _ = oracle_rate(w, cfgs, 1)
-        reps = max(1, int(10.0 * one / len(cfgs)))
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            oracle_rate(w, cfgs, threads)
-        multi = reps * len(cfgs) / (time.perf_counter() - t0)
+        # the oracle as it stands on the host cores, on a bounded sample of the same batch: every
+        # 8th candidate (about 20 s of CPU time), and its single-thread rate on 8 of them
+        idx = np.arange(0, head["B"], 8)
+        multi, _ = oracle_rate(w, cfgs[idx], threads)
+        one, _ = oracle_rate(w, cfgs[idx[:8]], 1)
         line["cpu_baseline"] = {"value": multi, "unit": "strategies/s", "cores": threads, "kind": "oracle",
-                                "sample": f"all {len(cfgs)} candidates of configs[1], {reps} repetitions, "
-                                          f"{threads} threads (static split); single thread: {one:.1f} strategies/s",
-                                "single_thread_value": one, "cpu_model": cpu_model()}
-        tb, tt = oracle_build_share(w, cfgs[:256])
-        line["cpu_baseline"]["one_thread_build_seconds_per_strategy"] = tb / 256
-        line["cpu_baseline"]["one_thread_build_plus_simulate_seconds_per_strategy"] = tt / 256
-    if not args.only_headline and not args.no_delta and 4 in results:
+                                "sample": f"every 8th of the {head['B']} candidates of configs[{HEADLINE}] ({len(idx)} strategies), "
+                                          f"{threads} threads (static split); single thread on 8 of them: {one:.2f} strategies/s",
+                                "single_thread_value": one, "cpu_model": cpu_model(),
+                                "logical_cpus_of_the_box": logical_cpus, "cpus_usable_by_this_process": usable_cpus}
+        tb, tt = oracle_build_share(w, cfgs[:4])
+        line["cpu_baseline"]["one_thread_build_seconds_per_strategy"] = tb / 4
+        line["cpu_baseline"]["one_thread_build_plus_simulate_seconds_per_strategy"] = tt / 4
+    if not args.only_headline and not args.no_delta:
         # delta simulation on configs[4]: one chain, and 256 independent chains
         r4, sim4, w4, cfgs4 = results[4]
         delta = []
-        for C, n_steps in ((1, 24), (256, 6)):
+        for C, n_steps in ((1, 256), (256, 32)):
             muts = w4.mutations(n_steps, C)
             ch = binding.Chains(sim4, cfgs4[:C])
             d_m = ch.upload_mutations(muts)
@@ -293,26 +407,31 @@ def main():
                  "delta_sims_per_s": C * n_steps / (ms * 1e-3),
                  "steps_resumed_from_snapshot": int(st["n_resumed"].sum()), "steps_total": int(st["n_steps"].sum()),
                  "mean_events_per_step": float(st["n_events"].sum() / max(1, st["n_steps"].sum())),
-                 "events_of_a_full_simulation": float(st["n_events_full"].mean())}
+                 "events_of_a_full_simulation": float(st["n_events_full"].mean()),
+                 "full_chain_length_in_the_configuration_list": 10000,
+                 "note": "python bench.py --long-chain 10000 runs the full chain (profiles/)"}
+            got = out.cpu().numpy().view("<u8")
             if not args.no_cpu and C == 1:
-                import oracle
-                sel = [0, n_steps // 2, n_steps - 1]
-                ref = oracle.simulate_delta_chain(w4.ops, w4.edges, w4.machine, w4.cost, cfgs4[0], muts[:, 0], steps=sel)
-                d["bit_exact_on_sampled_steps"] = bool(np.array_equal(out.cpu().numpy().view("<u8")[sel, 0], ref))
+                sel = sorted(set(np.linspace(0, n_steps - 1, 16).astype(int).tolist()))
+                ref = oracle_chain_steps(w4, cfgs4[0], muts[:, 0], sel, threads)
+                d["oracle_checked_steps"] = len(sel)
+                d["bit_exact_on_checked_steps"] = bool(np.array_equal(got[sel, 0], ref))
                 # what Algorithm 2 would have to touch, counted by diffing the oracle's timelines of
-                # consecutive strategies (two sampled steps): removed + inserted + moved tasks
-                cur = cfgs4[0].copy()
-                work = []
-                for s_ in range(n_steps):
-                    nxt = cur.copy()
-                    nxt[int(muts[s_, 0]["op"])] = muts[s_, 0]["cfg"]
-                    if s_ in (1, n_steps // 2):
-                        work.append(changed_items(w4, cur, nxt))
-                    cur = nxt
+                # consecutive strategies on 16 steps spread over the chain: removed + inserted + moved tasks
+                work = delta_work_model(w4, cfgs4[0], muts[:, 0], sel)
                 d["oracle_changed_tasks_on_sampled_steps"] = work
                 items = float(np.mean([x["removed"] + x["inserted"] + x["moved"] for x in work]))
+                d["mean_changed_share_of_tasks"] = float(np.mean([(x["removed"] + x["inserted"] + x["moved"]) / x["tasks_after"] for x in work]))
                 d["algorithmic_bytes_per_step"] = items * 34.0   # 20 B per task written + read, 14 B per record, as in the byte model
                 d["algorithmic_GBps"] = items * 34.0 * n_steps / (ms * 1e-3) / 1e9
+            if not args.no_cpu and C > 1:
+                chains_checked = [0, 31, 64, 100, 127, 200, 254, 255]
+                ok = True
+                for cc in chains_checked:
+                    ref = oracle_chain_steps(w4, cfgs4[cc], muts[:, cc], [n_steps // 2, n_steps - 1], threads)
+                    ok = ok and bool(np.array_equal(got[[n_steps // 2, n_steps - 1], cc], ref))
+                d["oracle_checked_chains"] = len(chains_checked)
+                d["bit_exact_on_checked_chains"] = ok
             delta.append(d)
             if C == 1:
                 # proposals evaluated side by side against the chain's stored timeline (not committed)
@@ -334,7 +453,7 @@ def main():
                     cur = cfgs4[0].copy()
                     for s_ in range(n_steps):
                         cur[int(muts[s_, 0]["op"])] = muts[s_, 0]["cfg"]
-                    sel = [0, M // 2, M - 1]
+                    sel = [0, M // 4, M // 2, M - 1]
                     cand = np.repeat(cur[None], len(sel), 0)
                     for q, p_ in enumerate(sel):
                         cand[q, int(props[p_, 0]["op"])] = props[p_, 0]["cfg"]
@@ -354,7 +473,7 @@ def main():
             start = ch.start_ns().copy()
             bucket = max(1, int(np.median(start)) // 256)
             tp, tu = w_s.search_space()
-            ch.search_setup(tp, tu, binding.metropolis_table(50.0 / float(np.median(start)), bucket, 256), bucket, 1807)
+            ch.search_setup(tp, tu, binding.ff_sim_accept_table(50.0 / float(np.median(start)), bucket, 256), bucket, 1807)
             ch.search(1)
             torch.cuda.synchronize()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -398,13 +517,14 @@ def main():
                 line["search_with_parameter_traffic"]["best_confirmed_by_oracle"] = bool(int(oracle.simulate_batch(
                     w_p.ops, w_p.edges, w_p.machine, w_p.cost, res.best[None], params=w_p.param_table())[0]) == res.best_ns)
             sim_p.close()
-        # the refinements of the inputs on the headline workload: what each costs per launch
+        # the refinements of the inputs on configs[1]: what each costs per launch
         if 1 in results:
             import dataclasses
             w_r = results[1][2]
             cfgs_r = w_r.strategies(1024)
             lbw, llat = W.paired_links(w_r.machine.gpus_per_node, 20, 6, 100, 900)
             variants = {
+                "plain": (w_r.machine, None, None),
                 "unequal_links": (dataclasses.replace(w_r.machine, link_Bpns=lbw, link_lat_ns=llat), None, None),
                 "parameter_traffic": (w_r.machine, w_r.param_table(), None),
                 "explicit_devices": (w_r.machine, None, W.device_maps(cfgs_r, w_r.machine.n_devices, 1807)),

@@ -219,6 +219,12 @@ int ff_sim_batch(ff_sim_t* sim, const ff_opcfg_t* d_strategies, uint32_t B, uint
  * first one reads the ranges back to check them; they must not change afterwards).
  * ff_sim_neighbours allocates and waits: not for capture. */
 
+/* Which kernel instantiation ff_sim_batch launches for B candidates on this handle (measurement
+ * aid: a profile of the kernel can be matched to the launch it belongs to): writes
+ * "k_sim_batch<WIDE, LDSW, STATS, Q, CACHE, EXT, GPN>" with the template arguments as they appear
+ * in a kernel trace into buf (HOST memory, len bytes; FF_ERANGE if it does not fit). */
+int ff_sim_batch_kernel_name(const ff_sim_t* sim, uint32_t B, char* buf, size_t len);
+
 /* The same with the device of every task given one by one (Section 4: a configuration assigns
  * each of its tasks a device) instead of dev_offset + k * dev_stride: d_devmaps is
  * [B][n_ops][FF_MAX_PARTS], entry k of an op = device of its part k (< n_devices, else the
@@ -286,10 +292,10 @@ int ff_sim_neighbours(ff_chains_t* chains, const uint32_t* d_tuple_ptr, const ui
  * draw(11) mod (number of entries) of the op's list d_tuples[d_tuple_ptr[op] .. d_tuple_ptr[op+1])
  * (four degrees, one byte each, deg[0] lowest), dev_offset = draw(12) mod n_devices,
  * dev_stride = 1; the acceptance draw is draw(13).  An invalid proposal is rejected.
- * Section 6.2 ends the search from one initial strategy when its budget is spent (n_steps, the
- * caller's) or when the best discovered strategy has not improved for half of the search time:
- * a chain that has gone `patience` steps without a new best makes no further proposals (its
- * time repeats in the trace); the count carries over between calls on the same chains.
+ * Stopping (Section 6.2 gives two criteria): the budget is n_steps, the caller's; and a chain that
+ * has gone `patience` steps without finding a new best makes no further proposals (its time
+ * repeats in the trace; a caller who wants the paper's setting passes half of its step budget);
+ * the count carries over between calls on the same chains.
  * d_trace_ns[s][c] receives the time of chain c's strategy after step s; d_best_ns[c] /
  * d_best[c][n_ops] are updated whenever a step ends with a better time than d_best_ns[c]
  * (initialise it to UINT64_MAX).  All d_* are device pointers.  The call copies n_ops+1
@@ -309,6 +315,16 @@ typedef struct {
 } ff_search_t;
 int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_steps, uint64_t* d_trace_ns,
                   void* hip_stream);
+
+/* The acceptance table of ff_sim_search for the Metropolis rule of Section 6.1 with a given beta:
+ * out[b] = floor(2^32 * exp(-beta_per_ns * b * bucket_ns)), capped at 2^32 - 1 -- the probability
+ * of accepting a proposal that is slower by b * bucket_ns, the lower edge of bucket b (so a
+ * proposal slower by delta is accepted with exp(-beta * bucket_ns * floor(delta / bucket_ns)),
+ * at most a factor exp(beta * bucket_ns) above the rule's exp(-beta * delta); beyond the last
+ * bucket the probability stays at that bucket's).  Double-precision arithmetic on the host, in
+ * this order: ((-beta_per_ns) * b) * bucket_ns.  out: HOST array of n_buckets entries (upload it
+ * as ff_search_t.d_accept).  FF_EINVAL for beta < 0 or NaN, bucket_ns = 0, n_buckets = 0. */
+int ff_sim_accept_table(double beta_per_ns, uint64_t bucket_ns, uint32_t n_buckets, uint32_t* out);
 
 /* Telemetry of the chains (HOST array of C records; synchronises the device): how many
  * mutations were applied, how many of them resumed from a stored snapshot of the timeline

@@ -37,7 +37,8 @@ class ff_costtable_t(C.Structure):
 EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_params",
            "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
-           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search",
+           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search", "ff_sim_accept_table",
+           "ff_sim_batch_kernel_name",
            "ff_sim_neighbour_count", "ff_sim_neighbours",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8"),
@@ -111,6 +112,10 @@ def lib():
         L.ff_sim_delta_try_workspace_bytes.argtypes = [vp, u32]
         L.ff_sim_search.restype = C.c_int
         L.ff_sim_search.argtypes = [vp, C.POINTER(ff_search_t), u32, vp, vp]
+        L.ff_sim_accept_table.restype = C.c_int
+        L.ff_sim_accept_table.argtypes = [C.c_double, C.c_uint64, u32, vp]
+        L.ff_sim_batch_kernel_name.restype = C.c_int
+        L.ff_sim_batch_kernel_name.argtypes = [vp, u32, C.c_char_p, C.c_size_t]
         L.ff_sim_neighbour_count.restype = C.c_int
         L.ff_sim_neighbour_count.argtypes = [vp, vp, u32, u32, u32, C.POINTER(u32)]
         L.ff_sim_neighbours.restype = C.c_int
@@ -235,7 +240,7 @@ def ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream=None):
     _check(lib().ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream), "ff_sim_delta_try")
 
 
-def ff_sim_search(chains, params: ff_search_t, n_steps, d_trace_ns, stream=None):
+def ff_sim_search(chains, params, n_steps, d_trace_ns, stream=None):
     _check(lib().ff_sim_search(chains, C.byref(params), n_steps, d_trace_ns, stream), "ff_sim_search")
 
 
@@ -273,11 +278,17 @@ def to_device(arr):
     return torch.from_numpy(a.view(np.uint8).reshape(-1).copy()).cuda()
 
 
-def metropolis_table(beta_per_ns, bucket_ns, n_buckets):
-    """acceptance probabilities of Section 6.1 for ff_sim_search, scaled by 2^32: entry b is
-    exp(-beta * b * bucket_ns), the value at the lower edge of the bucket."""
-    p = np.exp(-float(beta_per_ns) * float(bucket_ns) * np.arange(n_buckets, dtype=np.float64))
-    return np.minimum(np.floor(p * 4294967296.0), 4294967295.0).astype(np.uint32)
+def ff_sim_accept_table(beta_per_ns, bucket_ns, n_buckets):
+    """the acceptance table of ff_sim_search for a given beta (computed by the library)."""
+    out = np.zeros(int(n_buckets), "<u4")
+    _check(lib().ff_sim_accept_table(float(beta_per_ns), int(bucket_ns), int(n_buckets), out.ctypes.data), "ff_sim_accept_table")
+    return out
+
+
+def ff_sim_batch_kernel_name(sim, B):
+    buf = C.create_string_buffer(256)
+    _check(lib().ff_sim_batch_kernel_name(sim, B, buf, len(buf)), "ff_sim_batch_kernel_name")
+    return buf.value.decode()
 
 
 class Simulator:

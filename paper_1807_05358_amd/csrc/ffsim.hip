@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -73,6 +75,9 @@ struct ff_chains {
     const uint32_t* checked_ptr = nullptr;   // the proposal ranges ff_sim_search has checked last
     uint32_t checked_n = 0;
 };
+
+static bool batch_cached(const ff_sim* s, uint32_t B);
+static uint32_t batch_slots(const ff_sim* s, uint32_t B);
 
 constexpr uint32_t CHAIN_SNAPSHOTS = 32;
 static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMeta::loc");
@@ -390,7 +395,7 @@ int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
 size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {
     if (!s) return 0;
     if (s->lds_words) return 0;   // the whole per-candidate state lives in LDS
-    return (size_t)std::max<uint32_t>(1, std::min(B, s->max_slots)) * s->batch_slot_bytes;
+    return (size_t)std::max<uint32_t>(1, batch_slots(s, B)) * s->batch_slot_bytes;
 }
 
 int ff_sim_set_workspace(ff_sim_t* s, void* d_ws, size_t bytes) {
@@ -406,15 +411,23 @@ int ff_sim_set_stats(ff_sim_t* s, ff_stats_t* d_stats) {
     return FF_OK;
 }
 
+// Keeping the per-edge set-up costs LDS for graphs whose words live there; it is used unless it
+// would leave part of the batch waiting for a free compute unit that the plain variant has room for.
+static bool batch_cached(const ff_sim* s, uint32_t B) {
+    return s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
+}
+// wavefronts (= workspace slots) a launch of B candidates uses
+static uint32_t batch_slots(const ff_sim* s, uint32_t B) {
+    return std::min(B, batch_cached(s, B) ? s->max_slots_cached : s->max_slots);
+}
+
 static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_t* d_devmaps, uint32_t B, uint64_t* d_out_ns,
                       void* hip_stream) {
     if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
     if (B == 0) return FF_OK;
-    // Keeping the per-edge set-up costs LDS for graphs whose words live there; it is used unless it
-    // would leave part of the batch waiting for a free compute unit that the plain variant has room for.
     const bool ext = s->dev.link_table || s->dev.sync || d_devmaps;
-    const bool cached = s->cache_ok && (B <= s->max_slots_cached || s->max_slots_cached >= s->max_slots);
-    const uint32_t slots = std::min(B, cached ? s->max_slots_cached : s->max_slots);
+    const bool cached = batch_cached(s, B);
+    const uint32_t slots = batch_slots(s, B);
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
     static_assert(sizeof(Counters) == sizeof(ff_stats_t), "stats layout");
@@ -423,6 +436,26 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
                        s->d_edges, s->d_in_edges, s->d_cost, s->d_magic, (const uint2*)d_strategies, B, (u64*)d_out_ns,
                        (Counters*)s->d_stats, (unsigned char*)s->ws, s->batch_slot_bytes, d_devmaps);
     return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
+}
+
+int ff_sim_batch_kernel_name(const ff_sim_t* s, uint32_t B, char* buf, size_t len) {
+    if (!s || !buf || len < 1) return FF_EINVAL;
+    const bool ext = s->dev.link_table || s->dev.sync;
+    const KernelChoice k = choice(s, batch_cached(s, B));
+    const int n = snprintf(buf, len, "k_sim_batch<%s, %s, %s, %d, %s, %s, %d>", k.wide ? "true" : "false", k.lds_words ? "true" : "false",
+                           k.stats ? "true" : "false", batch_queue_shape(k), k.cache ? "true" : "false", ext ? "true" : "false",
+                           s->dev.gpus_per_node == 4 ? 4 : 0);
+    return (n < 0 || (size_t)n >= len) ? FF_ERANGE : FF_OK;
+}
+
+int ff_sim_accept_table(double beta_per_ns, uint64_t bucket_ns, uint32_t n_buckets, uint32_t* out) {
+    if (!out || n_buckets < 1 || bucket_ns < 1 || !(beta_per_ns >= 0.0)) return FF_EINVAL;
+    for (uint32_t b = 0; b < n_buckets; b++) {
+        // probability of accepting a proposal at the lower edge of bucket b, scaled by 2^32
+        const double p = std::exp(-beta_per_ns * (double)b * (double)bucket_ns) * 4294967296.0;
+        out[b] = p >= 4294967295.0 ? 0xffffffffu : (uint32_t)std::floor(p);
+    }
+    return FF_OK;
 }
 
 int ff_sim_batch(ff_sim_t* s, const ff_opcfg_t* d_strategies, uint32_t B, uint64_t* d_out_ns, void* hip_stream) {

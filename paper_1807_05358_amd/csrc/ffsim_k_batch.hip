@@ -11,9 +11,13 @@ template <bool WIDE, bool STATS, bool CACHE>
 static batch_kernel_t batch_kernel_of(const KernelChoice& k) {
     constexpr bool EXT = FFSIM_EXT;
     constexpr int GPN = FFSIM_GPN;
-    if (k.lds_words && k.n_ops <= 16 && k.max_parts <= 16) return k_sim_batch<WIDE, true, STATS, Q_ONE16, CACHE, EXT, GPN>;
-    if (k.lds_words) return k.n_ops <= 64 ? k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE, EXT, GPN> : k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE, EXT, GPN>;
-    return k.n_groups > FLAT_GROUPS ? k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE, EXT, GPN> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE, EXT, GPN>;
+    switch (batch_queue_shape(k)) {
+        case Q_ONE16: return k_sim_batch<WIDE, true, STATS, Q_ONE16, CACHE, EXT, GPN>;
+        case Q_ONE: return k_sim_batch<WIDE, true, STATS, Q_ONE, CACHE, EXT, GPN>;
+        case Q_TREE: return k_sim_batch<WIDE, false, STATS, Q_TREE, CACHE, EXT, GPN>;
+        default: break;
+    }
+    return k.lds_words ? k_sim_batch<WIDE, true, STATS, Q_FLAT, CACHE, EXT, GPN> : k_sim_batch<WIDE, false, STATS, Q_FLAT, CACHE, EXT, GPN>;
 }
 
 template <>

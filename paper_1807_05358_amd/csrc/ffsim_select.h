@@ -22,6 +22,12 @@ struct KernelChoice {
     bool wide, lds_words, stats, cache;
     uint32_t n_ops, n_groups, max_parts;
 };
+// the queue shape (QueueShape) of the batch kernel that serves a graph
+inline int batch_queue_shape(const KernelChoice& k) {
+    if (k.lds_words && k.n_ops <= 16 && k.max_parts <= 16) return Q_ONE16;
+    if (k.lds_words) return k.n_ops <= 64 ? Q_ONE : Q_FLAT;
+    return k.n_groups > FLAT_GROUPS ? Q_TREE : Q_FLAT;
+}
 // EXT: the refinements of the inputs (link table, explicit devices); GPN: GPUs per node the
 // kernels are compiled for (4, or 0 = any).  One explicit specialisation per object.
 template <bool EXT, int GPN> batch_kernel_t batch_kernels(const KernelChoice& k);

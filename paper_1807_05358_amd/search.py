@@ -56,7 +56,7 @@ def find_strategy(sim: B.Simulator, ops, machine, max_parts, choices, n_chains=6
         bucket = max(1, int(ref * accept_scale * 8 / n_buckets))          # the table spans 8 / beta
         beta = 1.0 / (ref * accept_scale)
         ptr, tuples = W.search_space(ops, max_parts, choices)
-        chains.search_setup(ptr, tuples, B.metropolis_table(beta, bucket, n_buckets), bucket, seed, patience=max(1, steps // 2))
+        chains.search_setup(ptr, tuples, B.ff_sim_accept_table(beta, bucket, n_buckets), bucket, seed, patience=max(1, steps // 2))
         traces = []
         done = 0
         while done < steps:

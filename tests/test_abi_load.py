@@ -65,3 +65,20 @@ def test_exact_division_tricks_used_by_the_kernels():
         for xx in range(E):
             p = ((xx + 1) * deg - 1) // E
             assert bounds[p] <= xx < bounds[p + 1], (E, deg, xx)
+
+
+def test_accept_table_matches_the_search_oracle_entry_by_entry():
+    """ff_sim_accept_table is host arithmetic (Section 6.1's exp(-beta * delta) at the lower edge of every
+    bucket): the oracle's table, written independently, must agree in every entry."""
+    from oracle import search as S
+    for beta, bucket, n in [(1e-3, 100, 64), (0.0, 7, 5), (2.5e-7, 50_000, 256), (3.1e-9, 123_457, 1024), (0.5, 1, 80)]:
+        got = binding.ff_sim_accept_table(beta, bucket, n)
+        want = S.metropolis_table(beta, bucket, n)
+        assert np.array_equal(got, want), (beta, bucket, n, np.nonzero(got != want)[0][:5])
+    L = binding.lib()
+    out = np.zeros(4, "<u4")
+    assert L.ff_sim_accept_table(-1.0, 10, 4, out.ctypes.data) == binding.FF_EINVAL
+    assert L.ff_sim_accept_table(float("nan"), 10, 4, out.ctypes.data) == binding.FF_EINVAL
+    assert L.ff_sim_accept_table(1.0, 0, 4, out.ctypes.data) == binding.FF_EINVAL
+    assert L.ff_sim_accept_table(1.0, 10, 0, out.ctypes.data) == binding.FF_EINVAL
+    assert L.ff_sim_accept_table(1.0, 10, 4, None) == binding.FF_EINVAL

@@ -90,7 +90,7 @@ def test_search_steps_in_a_graph(B):
     tp, tu = w.search_space()
     t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[:1])[0])
     bucket = max(1, t0 // 256)
-    table = B.metropolis_table(20.0 / t0, bucket, 64)
+    table = B.ff_sim_accept_table(20.0 / t0, bucket, 64)
     ch = B.Chains(sim, cfg0)
     ch.search_setup(tp, tu, table, bucket, seed=4)
     trace = torch.zeros((n, C), dtype=torch.int64, device="cuda")

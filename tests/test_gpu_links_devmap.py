@@ -117,7 +117,7 @@ def test_delta_and_search_with_unequal_links(B, config_id, C, steps):
     # the search loop on the same machine
     ptr, tup = w.search_space()
     n_steps = 10 if config_id == 1 else 5
-    accept = B.metropolis_table(2e-7, 50_000, 64)
+    accept = B.ff_sim_accept_table(2e-7, 50_000, 64)
     ch = B.Chains(sim, cfg0)
     ch.search_setup(ptr, tup, accept, 50_000, seed=77)
     trace = ch.search(n_steps).cpu().numpy().view("<u8")

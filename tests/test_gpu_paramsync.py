@@ -120,7 +120,7 @@ def test_delta_and_search_with_parameter_traffic(B, config_id, C, steps):
     n_steps = 10 if config_id == 1 else 5
     t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[:1], params=params)[0])
     bucket = max(1, t0 // 256)
-    accept = B.metropolis_table(20.0 / t0, bucket, 64)
+    accept = B.ff_sim_accept_table(20.0 / t0, bucket, 64)
     ch = B.Chains(sim, cfg0)
     ch.search_setup(ptr, tup, accept, bucket, seed=31)
     trace = ch.search(n_steps).cpu().numpy().view("<u8")

@@ -35,7 +35,9 @@ def oracle_stats(w, cfg):
 
 @pytest.mark.parametrize("name", ["build_two_ops_two_gpus.json", "build_shared_internode_link.json",
                                   "build_part_order_row_major.json", "build_link_latency.json",
-                                  "build_intranode_latency.json"])
+                                  "build_intranode_latency.json", "build_uneven_split_7_by_3.json",
+                                  "build_uneven_split_35_by_4.json", "build_strided_window_uneven_split.json",
+                                  "build_pair_order_on_shared_link.json"])
 def test_hand_computed_fixtures(B, golden_dir, name):
     g = load_golden(golden_dir, name)
     ops, edges, mach, cost, cfg = graph_from_golden(g)
@@ -69,19 +71,19 @@ def test_batch_matches_oracle(B, config_id, n, n_stats):
 
 def test_full_size_batches_run_in_bench_configuration(B):
     """every configuration at its full B, launch shape and kernel variant as in the bench (no
-    per-candidate counters); all of configs[1], a strided sample of the others is compared with
-    the oracle, and all results must respect the bounds that hold for any strategy (at least the
-    largest single task...)."""
-    for config_id, n, every in ((0, 64, 1), (1, 1024, 1), (2, 4096, 128), (3, 4096, 256), (4, 1024, 128)):
+    per-candidate counters): every candidate of every configuration is compared with the oracle, and
+    all results must respect a bound that holds for any strategy (some task runs from start to end)."""
+    for config_id, n in ((0, 64), (1, 1024), (2, 4096), (3, 4096), (4, 1024)):
         w = W.workload(config_id)
         cfgs = w.strategies(n)
+        print(f"config {config_id} ({w.name}): all {n} candidates", flush=True)
         got = sim_for(B, config_id).simulate(cfgs)
-        idx = np.arange(0, n, every)
-        want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs[idx], n_threads=8)
-        assert np.array_equal(got[idx], want)
+        want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=16)
+        bad = np.nonzero(got != want)[0]
+        assert len(bad) == 0, f"config {config_id}: {len(bad)} of {n} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
         parts = cfgs["deg"].astype(np.int64).prod(-1)
         task_ns = np.take_along_axis(np.broadcast_to(w.cost[None], (n,) + w.cost.shape), (parts - 1)[..., None], 2)[..., 0]
-        assert (got >= task_ns.max(1)).all()                      # some task runs start to end
+        assert (got >= task_ns.max(1)).all()
         assert (got < 2 ** 63).all()
 
 
@@ -263,6 +265,32 @@ def test_more_candidates_than_resident_wavefronts(B):
     want = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs[idx], n_threads=8)
     assert B.ff_sim_workspace_bytes(sim.handle, n) < n * B.ff_sim_workspace_bytes(sim.handle, 1)   # fewer slots than candidates
     assert np.array_equal(got[idx], want)
+
+
+def test_advertised_workspace_is_enough_for_any_batch_size(B):
+    """ff_sim_batch must accept exactly ff_sim_workspace_bytes(B) bytes, also for batches larger than
+    the number of wavefronts either kernel variant keeps resident."""
+    import torch
+    w = W.workload(2)
+    h = B.ff_sim_create(w.ops, w.edges, w.machine, w.cost)
+    L = B.lib()
+    for n in (1, 700, 5000, 20000):
+        cfgs = w.strategies(n if n <= 5000 else 5000)
+        if n > 5000:
+            cfgs = np.concatenate([cfgs] * 4)
+        d = B.to_device(cfgs)
+        out = torch.empty(n, dtype=torch.int64, device="cuda")
+        need = B.ff_sim_workspace_bytes(h, n)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        assert L.ff_sim_set_workspace(h, ws.data_ptr(), need) == B.FF_OK
+        assert L.ff_sim_batch(h, d.data_ptr(), n, out.data_ptr(), None) == B.FF_OK
+        torch.cuda.synchronize()
+        if n == 700:
+            assert np.array_equal(out.cpu().numpy().view("<u8")[::100], oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs[::100], n_threads=8))
+        assert L.ff_sim_set_workspace(h, ws.data_ptr(), need - 256) == B.FF_OK
+        assert L.ff_sim_batch(h, d.data_ptr(), n, out.data_ptr(), None) == B.FF_EWORKSPACE
+    torch.cuda.synchronize()
+    B.ff_sim_destroy(h)
 
 
 def test_graphs_without_edges_and_single_op(B):

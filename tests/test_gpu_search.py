@@ -259,7 +259,7 @@ def test_search_driver_matches_the_oracle_chain_by_chain(B):
     ref = float(np.median(start))
     bucket = max(1, int(ref * 0.02 * 8 / 256))
     table = S.metropolis_table(1.0 / (ref * 0.02), bucket, 256)
-    assert np.array_equal(table, B.metropolis_table(1.0 / (ref * 0.02), bucket, 256))
+    assert np.array_equal(table, B.ff_sim_accept_table(1.0 / (ref * 0.02), bucket, 256))
     tp, tu = w.search_space()
     best = []
     for c in range(C):
