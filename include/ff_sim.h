@@ -278,6 +278,24 @@ int ff_sim_neighbours(ff_chains_t* chains, const uint32_t* d_tuple_ptr, const ui
                       uint32_t op_begin, uint32_t op_end, ff_mutation_t* d_muts, uint64_t* d_out_ns,
                       uint64_t* d_best_ns, uint32_t* d_best_index, void* hip_stream);
 
+/* ff_sim_neighbours for callers that cannot allocate or wait: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs and results as
+ * ff_sim_neighbours, but the call only puts kernels on the stream: it allocates nothing (host or
+ * device), copies nothing back and does not synchronise.  The index of every op's first neighbour,
+ * which ff_sim_neighbours builds on the host and keeps in a temporary allocation, is built by a
+ * kernel in a fixed scratch array that lives in the library's device image (16.6 KB per GPU, held
+ * until the process ends).  The caller passes M, the neighbour count it sized d_muts / d_out_ns for
+ * (ff_sim_neighbour_count, called once outside the loop); the ranges of d_tuple_ptr are checked on
+ * the device: if they are malformed or do not add up to M, every result of the call is
+ * FF_INVALID_NS (d_best_ns too) and d_muts names no op.
+ * Limits: op_end - op_begin <= 4096 (FF_ERANGE beyond; the library's own limit on ops), M * C < 2^32.
+ * All calls on one GPU share the one scratch array: calls that overlap in time on the same GPU (other
+ * streams, other chain sets, other threads) race; calls in stream order do not.  Workspace as for
+ * ff_sim_delta_try with the same M. */
+int ff_sim_neighbours_noalloc(ff_chains_t* chains, const uint32_t* d_tuple_ptr, const uint32_t* d_tuples, uint32_t n_tuples,
+                              uint32_t op_begin, uint32_t op_end, uint32_t M, ff_mutation_t* d_muts, uint64_t* d_out_ns,
+                              uint64_t* d_best_ns, uint32_t* d_best_index, void* hip_stream);
+
 /* The search loop of Section 6 on the device, one Markov chain per chain: per step one
  * proposal (Section 6.2: a random op gets a random configuration) is simulated as a trial
  * and accepted by the Metropolis rule of Section 6.1, min(1, exp(beta*(cost - cost*))), which

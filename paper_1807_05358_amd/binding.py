@@ -39,7 +39,7 @@ EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim
            "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search", "ff_sim_accept_table",
            "ff_sim_batch_kernel_name",
-           "ff_sim_neighbour_count", "ff_sim_neighbours",
+           "ff_sim_neighbour_count", "ff_sim_neighbours", "ff_sim_neighbours_noalloc",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8"),
                            ("n_converged", "<u8")])
@@ -120,6 +120,8 @@ def lib():
         L.ff_sim_neighbour_count.argtypes = [vp, vp, u32, u32, u32, C.POINTER(u32)]
         L.ff_sim_neighbours.restype = C.c_int
         L.ff_sim_neighbours.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp, vp, vp]
+        L.ff_sim_neighbours_noalloc.restype = C.c_int
+        L.ff_sim_neighbours_noalloc.argtypes = [vp, vp, vp, u32, u32, u32, u32, vp, vp, vp, vp, vp]
         L.ff_sim_chains_get_stats.restype = C.c_int
         L.ff_sim_chains_get_stats.argtypes = [vp, vp]
         L.ff_sim_strerror.restype = C.c_char_p
@@ -254,6 +256,12 @@ def ff_sim_neighbours(chains, d_tuple_ptr, d_tuples, n_tuples, op_begin, op_end,
                       d_best_index, stream=None):
     _check(lib().ff_sim_neighbours(chains, d_tuple_ptr, d_tuples, n_tuples, op_begin, op_end, d_muts, d_out_ns,
                                    d_best_ns, d_best_index, stream), "ff_sim_neighbours")
+
+
+def ff_sim_neighbours_noalloc(chains, d_tuple_ptr, d_tuples, n_tuples, op_begin, op_end, M, d_muts, d_out_ns, d_best_ns,
+                              d_best_index, stream=None):
+    _check(lib().ff_sim_neighbours_noalloc(chains, d_tuple_ptr, d_tuples, n_tuples, op_begin, op_end, M, d_muts, d_out_ns,
+                                           d_best_ns, d_best_index, stream), "ff_sim_neighbours_noalloc")
 
 
 def ff_sim_chains_get_stats(chains, n_chains):

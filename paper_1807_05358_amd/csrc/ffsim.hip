@@ -76,6 +76,27 @@ struct ff_chains {
     uint32_t checked_n = 0;
 };
 
+// Scratch of ff_sim_neighbours_noalloc: the index of every op's first neighbour (one entry per op of the
+// range plus the total) and a status word, in device memory that exists from the moment the library is
+// loaded, so that the call allocates nothing.  Every GPU holds its own copy at its own address; in host
+// code the array's name is only a handle for hipGetSymbolAddress, never an address to hand to a kernel.
+constexpr uint32_t NEIGHBOUR_SCRATCH_OPS = FF_MAX_OPS;
+static __device__ __align__(256) uint32_t neighbour_scratch[NEIGHBOUR_SCRATCH_OPS + 1 + 63];
+constexpr int SCRATCH_MAX_GPUS = 64;
+static uint32_t* neighbour_scratch_ptr[SCRATCH_MAX_GPUS];      // per device, resolved once
+
+// the current device's copy of the scratch array, or null if it cannot be resolved
+static uint32_t* neighbour_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SCRATCH_MAX_GPUS) return nullptr;
+    if (!neighbour_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(neighbour_scratch)) != hipSuccess) return nullptr;
+        neighbour_scratch_ptr[dev] = (uint32_t*)p;
+    }
+    return neighbour_scratch_ptr[dev];
+}
+
 static bool batch_cached(const ff_sim* s, uint32_t B);
 static uint32_t batch_slots(const ff_sim* s, uint32_t B);
 
@@ -304,6 +325,8 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, try_kernel(s), WAVE, s->lds_common);
     if (e != hipSuccess || per_cu < 1) per_cu = 1;
     s->max_try_slots = (uint32_t)cus * (uint32_t)per_cu;
+    // the address of this device's scratch array (ff_sim_neighbours_noalloc) is looked up here, once per device
+    if (!neighbour_scratch_of_current_device()) { release(s); return FF_EHIP; }
     *out = s;
     return FF_OK;
 }
@@ -593,7 +616,7 @@ int ff_sim_neighbours(ff_chains_t* c, const uint32_t* d_tuple_ptr, const uint32_
     if (hipMemcpyAsync(d_first, first.data(), first.size() * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) { hipFree(d_first); return FF_EHIP; }   // `first` is pageable host memory
     hipLaunchKernelGGL(k_neighbour_list, dim3((M + WAVE - 1) / WAVE), dim3(WAVE), 0, st, d_tuple_ptr, d_tuples, d_first, op_begin,
-                       op_end, c->sim->dev.n_dev, M, c->C, (uint32_t*)d_muts);
+                       op_end, c->sim->dev.n_dev, M, c->C, (uint32_t*)d_muts, (const uint32_t*)nullptr);
     rc = ff_sim_delta_try(c, d_muts, M, d_out_ns, hip_stream);
     if (rc == FF_OK) {
         hipLaunchKernelGGL(k_best_of, dim3(c->C), dim3(WAVE), 0, st, (const u64*)d_out_ns, M, c->C, (u64*)d_best_ns, d_best_index);
@@ -603,6 +626,30 @@ int ff_sim_neighbours(ff_chains_t* c, const uint32_t* d_tuple_ptr, const uint32_
     if (hipStreamSynchronize(st) != hipSuccess && rc == FF_OK) rc = FF_EHIP;
     hipFree(d_first);
     return rc;
+}
+
+int ff_sim_neighbours_noalloc(ff_chains_t* c, const uint32_t* d_tuple_ptr, const uint32_t* d_tuples, uint32_t n_tuples, uint32_t op_begin,
+                              uint32_t op_end, uint32_t M, ff_mutation_t* d_muts, uint64_t* d_out_ns, uint64_t* d_best_ns,
+                              uint32_t* d_best_index, void* hip_stream) {
+    if (!c || !d_tuple_ptr || !d_tuples || !d_muts || !d_out_ns || !d_best_ns || !d_best_index) return FF_EINVAL;
+    if (c->links_gen != c->sim->links_gen) return FF_EINVAL;
+    if (op_begin >= op_end || op_end > c->sim->dev.n_ops || M == 0) return FF_EINVAL;
+    if (op_end - op_begin > NEIGHBOUR_SCRATCH_OPS) return FF_ERANGE;
+    if ((uint64_t)M * c->C > 0xffffffffull) return FF_ERANGE;
+    uint32_t* scratch = neighbour_scratch_of_current_device();
+    if (!scratch) return FF_EHIP;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint32_t* d_first = scratch;
+    uint32_t* d_status = scratch + NEIGHBOUR_SCRATCH_OPS + 1;
+    hipLaunchKernelGGL(k_neighbour_first, dim3(1), dim3(WAVE), 0, st, d_tuple_ptr, n_tuples, op_begin, op_end, c->sim->dev.n_dev, M,
+                       d_first, d_status);
+    hipLaunchKernelGGL(k_neighbour_list, dim3((M + WAVE - 1) / WAVE), dim3(WAVE), 0, st, d_tuple_ptr, d_tuples, (const uint32_t*)d_first,
+                       op_begin, op_end, c->sim->dev.n_dev, M, c->C, (uint32_t*)d_muts, (const uint32_t*)d_status);
+    if (hipGetLastError() != hipSuccess) return FF_EHIP;
+    int rc = ff_sim_delta_try(c, d_muts, M, d_out_ns, hip_stream);
+    if (rc != FF_OK) return rc;
+    hipLaunchKernelGGL(k_best_of, dim3(c->C), dim3(WAVE), 0, st, (const u64*)d_out_ns, M, c->C, (u64*)d_best_ns, d_best_index);
+    return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
 }
 
 size_t ff_sim_delta_try_workspace_bytes(const ff_chains_t* c, uint32_t M) {
