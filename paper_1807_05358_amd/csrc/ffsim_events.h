@@ -263,6 +263,14 @@ template <bool WIDE, bool RECORD, bool REG, bool STATS, int Q, bool CACHE, class
 __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     constexpr bool TREE = Q == Q_TREE;
     constexpr bool ONE = Q == Q_ONE || Q == Q_ONE16, ROW0 = Q == Q_ONE16;
+    // runs of events (below) are formed where looking for them pays: graphs of more than 64 ops
+#if defined(FFSIM_NO_RUNS)
+    constexpr bool RUNS = false;
+#elif defined(FFSIM_RUNS_ALL)
+    constexpr bool RUNS = true;
+#else
+    constexpr bool RUNS = !ONE;
+#endif
     const int lane = lane_id();
     PROF_DECL
     const SimDev& S = m.S;
@@ -289,6 +297,10 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
     for (u64 ev = 0; ev < max_events; ev++) {
         u64 kmin;
         uint32_t i;
+        // what the search for the popped op leaves behind for `others_min` below
+        u64 row_rest = W_NONE;      // TREE: smallest key of the other ops of the popped op's group
+        u64 k1 = W_NONE;            // FLAT: this lane's column minimum of level 1
+        uint32_t gbest = 0, col = 0;
         if (ONE) {
             kmin = wave_min_from<ROW0>(qreg, last_key);
             if (kmin >> 63) break;
@@ -300,14 +312,17 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             kmin = wave_min_from(k2, last_key);
             if (kmin >> 63) break;
             const uint32_t g = __builtin_ctzll(ballot(k2 == kmin));
-            const u64 k1 = L.l1[g * WAVE + lane];
-            const u64 m1 = ballot(k1 == kmin);
+            const u64 row = L.l1[g * WAVE + lane];
+            const u64 m1 = ballot(row == kmin);
             if (!m1) { cnt.exit_code = 1; return RESULT_INTERNAL; }   // tree inconsistent: give up, never spin
-            i = g * WAVE + __builtin_ctzll(m1);
+            col = __builtin_ctzll(m1);
+            i = g * WAVE + col;
+            // the group's minimum once the popped op is set aside: the end of the event needs it for
+            // level 2 (no second pass over the row), and a run of events may extend up to it
+            row_rest = wave_min_from((uint32_t)lane == col ? W_NONE : row, last_key);
         } else {
             // few ops: every lane scans its column of level 1, no level 2
-            u64 k1 = L.l1[lane];
-            uint32_t gbest = 0;
+            k1 = L.l1[lane];
             for (uint32_t g = 1; g < S.n_groups; g++) {
                 const u64 k = L.l1[g * WAVE + lane];
                 if (k < k1) { k1 = k; gbest = g; }
@@ -321,7 +336,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 const uint32_t gmin = wave_min_u32(k1 == kmin ? gbest : 0xffffffffu);
                 m1 = ballot(k1 == kmin && gbest == gmin);
             }
-            const int col = __builtin_ctzll(m1);
+            col = __builtin_ctzll(m1);
             i = readlane_u32(gbest, col) * WAVE + col;
         }
         static_assert(!(RECORD && ONE), "snapshots read level 1 from LDS");
@@ -339,18 +354,76 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         const uint32_t out_begin = opi_p->out_begin, out_end = opi_p->out_end;
         const OpCfg ci = m.cfg(i);
         const u64 exe = m.exe_of[i];
-        const u64 mask = ballot(k0 == kmin);            // parts of op i that hold the minimum
-        if (!mask) { cnt.exit_code = 2; return RESULT_INTERNAL; }
+        const u64 mask_same = ballot(k0 == kmin);       // parts of op i that hold the minimum
+        if (!mask_same) { cnt.exit_code = 2; return RESULT_INTERNAL; }
         cnt.n_events++;
         const u64 now = kmin >> 1;
+        const u64 k_own = k0;                            // the event words of op i as loaded
+        // A RUN of events.  The events of Algorithm 1's queue that follow the popped one in
+        // (time, kind, op, part) order and belong to the same op and kind can be handled in the same step, each
+        // at its own time, as long as no event of another op, no event of the other kind of this op and
+        // (RECORD) no snapshot boundary lies before them: they are consecutive in the order, so handling
+        // them together IS handling them in order.  The events a run creates must not fall inside it:
+        // a dequeued task is released exeTime after its readyTime or later; a release makes consumer
+        // tasks READY, whose dequeuing touches nothing a release touches (compute device rows and their
+        // own words against link rows and waiting words), but whose own releases come exeTime later.
+        // Only in the regular form (the parts of an op sit on distinct devices), for releases only
+        // if the op has one out-edge (transfers of several edges interleave by time on shared links)
+        // and no parameter traffic (queued per replica after the op's transfers).
+        u64 mask = mask_same;
+        bool mixed = false;                              // the step holds events of different times
+        if (REG && RUNS && ((kmin & 1) || (out_end - out_begin == 1 && !(SimX::kExt && S.sync)))) {
+            const bool same_kind = !(k0 >> 63) && (((uint32_t)k0 ^ (uint32_t)kmin) & 1u) == 0;
+            const u64 kind_m = ballot(same_kind);
+            if (kind_m != mask_same) {
+                // smallest key among the other ops
+                u64 bound;
+                if (ONE) {
+                    bound = wave_min_from<ROW0>((uint32_t)lane == i ? W_NONE : qreg, last_key);
+                } else if (TREE) {
+                    bound = wave_min_from((uint32_t)lane == (i >> 6) ? row_rest : qreg, last_key);
+                } else {
+                    // the other columns' minima, and the popped op's column in the other groups
+                    u64 v = (uint32_t)lane == col ? W_NONE : k1;
+                    if ((uint32_t)lane < S.n_groups && (uint32_t)lane != (i >> 6)) {
+                        const u64 c = L.l1[lane * WAVE + col];
+                        v = c < v ? c : v;
+                    }
+                    bound = wave_min_from(v, last_key);
+                }
+                // the op's own events of the other kind end the run as well
+                const bool other_kind = !(k0 >> 63) && (((uint32_t)k0 ^ (uint32_t)kmin) & 1u) != 0;
+                if (ballot(other_kind)) {
+                    const u64 r0 = wave_min_from<ROW0>(other_kind ? k0 : W_NONE, last_key);
+                    bound = r0 < bound ? r0 : bound;
+                }
+                // what the run itself brings about must come after it: the releases of the tasks it
+                // dequeues (a task ends exeTime after its start or later), or the releases of the consumer
+                // tasks it makes READY (dequeued at or after the release that completed their inputs)
+                const u64 next_exe = (kmin & 1) ? exe : (u64)m.exe_of[opi_p->first.dst];
+                const u64 first_new = kmin + 2 * next_exe;
+                bound = first_new < bound ? first_new : bound;
+                if (RECORD) {
+                    if (rec.next < rec.n_snaps) {
+                        const u64 edge = (u64)rec.next * rec.step;
+                        bound = edge < bound ? edge : bound;
+                    }
+                }
+                const u64 far = kmin + 0xfffffff0ull;    // times inside a step are told apart by 32-bit distances
+                bound = far < bound ? far : bound;
+                mask = mask_same | ballot(same_kind && k0 < bound);
+                mixed = mask != mask_same;
+            }
+        }
         const bool in_mask = lanes_of(mask);
         const uint32_t dev_p = m.template device_of<REG>(i, ci);
 
         if (kmin & 1) {
             // dequeue READY compute tasks: start = max(readyTime, device free), end = start + exeTime
             const bool may_share = REG ? false : ((SimX::kExt && m.devmap != nullptr) || !(ci.stride == 1 && ci.parts <= S.n_dev));
-            const u64 end = fifo_commit(in_mask, dev_p, exe, now, may_share, L);
-            overflow = overflow || end >= TIME_LIMIT;
+            // (a run of READY tasks: every task at its own readyTime; their devices are distinct)
+            const u64 end = fifo_commit(in_mask, dev_p, exe, (REG && mixed) ? (k_own >> 1) : now, may_share, L);
+            overflow = overflow || (in_mask && end >= TIME_LIMIT);
             // a finished task is looked at again only if it has something to release
             const bool releases = out_end > out_begin || (SimX::kExt && S.sync && opi_p->param_bytes != 0);
             if (in_mask) k0 = releases ? end << 1 : W_NONE;
@@ -392,8 +465,16 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 u64 todo = mask;
                 PROF_MARK(3)
                 while (todo) {
-                    const int kp = __builtin_ctzll(todo);
-                    todo &= todo - 1;
+                    // next producer part: by part index; in a run of releases by (time, part index)
+                    int kp = __builtin_ctzll(todo);
+                    u64 now_kp = now;
+                    if (REG && mixed) {
+                        const uint32_t dist = lanes_of(todo) ? (uint32_t)(k_own - kmin) : 0xffffffffu;
+                        const uint32_t dmin = wave_min_u32(dist);
+                        kp = __builtin_ctzll(ballot(dist == dmin));
+                        now_kp = (kmin + dmin) >> 1;
+                    }
+                    todo &= ~(1ull << kp);
                     u64 hit_m = mine_m;
                     u64 elems = 1;
                     // (the number of dims stays one scalar that is compared here: taken out of the loop, the
@@ -418,7 +499,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     const uint32_t node_a = readlane_u32(node_p, kp);
                     const u64 comm_mask = hit_m & ballot(dev_c != dev_a);
                     const bool comm = lanes_of(comm_mask);
-                    u64 arrive = now;
+                    u64 arrive = now_kp;
                     if (comm_mask) {
                         const u64 same_m = ballot(node_c == node_a);
                         const bool same_node = lanes_of(same_m);
@@ -452,7 +533,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         u64 end;
                         if (REG) {
                             const u64 f = L.free_at[row];                  // in range for every lane
-                            const u64 base = f > now ? f : now;            // the same for all lanes of a row
+                            const u64 base = f > now_kp ? f : now_kp;            // the same for all lanes of a row
                             const bool chained = lanes_of(comm_mask & ~same_m);   // rows between GPUs of one node are private
                             u64 incl;
                             if (!WIDE) {
@@ -483,7 +564,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             if (lanes_of(write_m)) L.free_at[row] = end;
                             wave_sync();
                         } else {
-                            end = fifo_commit(comm, row, ns, now, true, L);
+                            end = fifo_commit(comm, row, ns, now_kp, true, L);
                         }
                         if (comm) arrive = end;
                         if (STATS) {
@@ -513,6 +594,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     } else {
                         if (lane == 0 && nmin < L.l1[j]) L.l1[j] = nmin;
                         if (TREE && (uint32_t)lane == (j >> 6) && nmin < qreg) qreg = nmin;
+                        if (TREE && (j >> 6) == (i >> 6) && nmin < row_rest) row_rest = nmin;
                     }
                 }
                 PROF_MARK(5)
@@ -577,9 +659,9 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             wave_sync();
         }
         if (TREE) {
-            const uint32_t g = i >> 6;
-            const u64 new_l2 = wave_min_from(L.l1[g * WAVE + lane], last_key);
-            if ((uint32_t)lane == g) qreg = new_l2;
+            // level 2 of the group: the popped op's new minimum against the rest of its row
+            const u64 new_l2 = new_l1 < row_rest ? new_l1 : row_rest;
+            if ((uint32_t)lane == (i >> 6)) qreg = new_l2;
         }
         PROF_MARK(6)
     }
