@@ -186,7 +186,7 @@ __device__ __forceinline__ void refresh_ecache_for_op(const SimX& m, uint32_t j)
     const uint32_t in_begin = m.T.ops[j].in_begin, in_end = m.T.ops[j].in_end;
     for (uint32_t q = in_begin; q < in_end; q++) {
         const DEdge e = m.T.in_edges[q];
-        ecache_store(m.ecache, e.eid, edge_lane(m, e, cj));
+        ecache_store(m.ecache, m.S.n_edges, e.eid, edge_lane(m, e, cj));
     }
     __threadfence_block();
     wave_sync();
@@ -262,6 +262,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
     SimT<false, EXT, GPN> m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
     if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
+    m.want_sort = true;          // a later step may make the strategy a general one: the kept set-up is always complete
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
         // the strategy the search starts from counts as seen
@@ -478,6 +479,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
             SimT<true, EXT, GPN> m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
                               CACHE ? cm.ecache : nullptr, false};
             if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
+            m.want_sort = true;
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};

@@ -131,6 +131,39 @@ __device__ __forceinline__ u64 wave_shr1_u64(u64 v) {
     return ((u64)hi << 32) | lo;
 }
 
+// lane l reads v of lane src (any permutation or gather; through the LDS crossbar, no LDS memory).  Call only
+// with all 64 lanes active.
+__device__ __forceinline__ uint32_t gather_u32(uint32_t v, uint32_t src) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)(src << 2), (int)v);
+}
+// lane l hands v to lane dst (dst must be a permutation of the lanes).  All 64 lanes active.
+__device__ __forceinline__ uint32_t scatter_u32(uint32_t v, uint32_t dst) {
+    return (uint32_t)__builtin_amdgcn_ds_permute((int)(dst << 2), (int)v);
+}
+
+// Segmented inclusive running sum along the 64 lanes: lane l gets the sum of v over the lanes from the
+// last lane <= l whose `head` is set up to l (lane 0 counts as a head).  Six DPP steps on the pair
+// (head seen so far, sum): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of
+// rows 0 / 2 into rows 1 / 3 and lane 31 into rows 2 and 3.  Lanes that a step gives no source keep
+// their value (old = 0 is the identity of both components).  All 64 lanes active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void seg_step(uint32_t& f, uint32_t& v) {
+    const uint32_t tv = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+    const uint32_t tf = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)f, CTRL, ROW_MASK, 0xf, false);
+    v += f ? 0u : tv;
+    f |= tf;
+}
+__device__ __forceinline__ uint32_t seg_running_sum(uint32_t v, bool head) {
+    uint32_t f = head ? 1u : 0u;
+    seg_step<0x111, 0xf>(f, v);      // row_shr:1
+    seg_step<0x112, 0xf>(f, v);      // row_shr:2
+    seg_step<0x114, 0xf>(f, v);      // row_shr:4
+    seg_step<0x118, 0xf>(f, v);      // row_shr:8
+    seg_step<0x142, 0xa>(f, v);      // row_bcast:15 into rows 1 and 3
+    seg_step<0x143, 0xc>(f, v);      // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 // wavefront-wide min of a 32-bit value, uniform result: butterfly inside each row of 16
 // lanes with DPP, then the four row results are combined on the scalar unit
 __device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {

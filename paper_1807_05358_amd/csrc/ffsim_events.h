@@ -132,7 +132,7 @@ __device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
             for (uint32_t q = in_begin; q < in_end; q++) {
                 const DEdge e = m.T.in_edges[q];
                 const EdgeLane el = edge_lane(m, e, cj);
-                ecache_store(m.ecache, e.eid, el);
+                ecache_store(m.ecache, m.S.n_edges, e.eid, el);
                 pending += count_inputs_of(e, m.cfg(e.src), el);
             }
         } else {
@@ -354,6 +354,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         const uint32_t out_begin = opi_p->out_begin, out_end = opi_p->out_end;
         const OpCfg ci = m.cfg(i);
         const u64 exe = m.exe_of[i];
+        const uint32_t dev_p = m.template device_of<REG>(i, ci);   // (with explicit devices a load: requested with the words)
         const u64 mask_same = ballot(k0 == kmin);       // parts of op i that hold the minimum
         if (!mask_same) { cnt.exit_code = 2; return RESULT_INTERNAL; }
         cnt.n_events++;
@@ -367,12 +368,12 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         // a dequeued task is released exeTime after its readyTime or later; a release makes consumer
         // tasks READY, whose dequeuing touches nothing a release touches (compute device rows and their
         // own words against link rows and waiting words), but whose own releases come exeTime later.
-        // Only in the regular form (the parts of an op sit on distinct devices), for releases only
+        // READY tasks only in the regular form (the parts of an op sit on distinct devices); releases only
         // if the op has one out-edge (transfers of several edges interleave by time on shared links)
         // and no parameter traffic (queued per replica after the op's transfers).
         u64 mask = mask_same;
         bool mixed = false;                              // the step holds events of different times
-        if (REG && RUNS && ((kmin & 1) || (out_end - out_begin == 1 && !(SimX::kExt && S.sync)))) {
+        if (RUNS && ((kmin & 1) ? REG : (out_end - out_begin == 1 && !(SimX::kExt && S.sync)))) {
             const bool same_kind = !(k0 >> 63) && (((uint32_t)k0 ^ (uint32_t)kmin) & 1u) == 0;
             const u64 kind_m = ballot(same_kind);
             if (kind_m != mask_same) {
@@ -416,7 +417,6 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             }
         }
         const bool in_mask = lanes_of(mask);
-        const uint32_t dev_p = m.template device_of<REG>(i, ci);
 
         if (kmin & 1) {
             // dequeue READY compute tasks: start = max(readyTime, device free), end = start + exeTime
@@ -456,6 +456,9 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 const uint32_t pos = el.pos, first_len = el.first_len, last_run_mask = el.last_run_mask;
                 const bool wrapped = el.wrapped;
                 const u64 run_end_m = REG ? ballot(el.run_end) : 0;
+                // (general form: the consumer's parts in (node, part) order, and which of them share a GPU)
+                const uint32_t sortw = (REG || WIDE) ? 0u : ((CACHE && !(SimX::kOvr && j == m.ov_op)) ? ecache_sort_word(m.ecache, S.n_edges, ei) : el.sortw);
+                const u64 dup_m = (REG || WIDE) ? 0 : ballot((sortw >> 23) & 1u);
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;
                 // Which lanes take part is kept as 64-bit lane masks and combined with scalar
@@ -468,7 +471,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     // next producer part: by part index; in a run of releases by (time, part index)
                     int kp = __builtin_ctzll(todo);
                     u64 now_kp = now;
-                    if (REG && mixed) {
+                    if (mixed) {
                         const uint32_t dist = lanes_of(todo) ? (uint32_t)(k_own - kmin) : 0xffffffffu;
                         const uint32_t dmin = wave_min_u32(dist);
                         kp = __builtin_ctzll(ballot(dist == dmin));
@@ -563,6 +566,28 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                             const u64 write_m = (comm_mask & same_m) | (run_end_m & ~same_m & ballot(incl != 0));
                             if (lanes_of(write_m)) L.free_at[row] = end;
                             wave_sync();
+                        } else if (!WIDE) {
+                            // General strategies.  Transfers to another node queue on the link row of the node pair
+                            // in consumer-part order: a running sum along the consumer's parts taken in (node, part)
+                            // order (kept with the edge's set-up), cut where the node changes; every lane of a row
+                            // reads the same free time and the row keeps the largest end.
+                            const bool inter = lanes_of(comm_mask & ~same_m);
+                            const uint32_t at_pos = gather_u32(inter ? (uint32_t)ns : 0u, sortw & 63u);
+                            const uint32_t sum_pos = seg_running_sum(at_pos, (sortw >> 22) & 1u);
+                            const uint32_t incl = gather_u32(sum_pos, (sortw >> 6) & 63u);
+                            u64 f = 0;
+                            if (inter) f = L.free_at[row];
+                            end = (f > now_kp ? f : now_kp) + incl;
+                            if (inter) __hip_atomic_fetch_max(&L.free_at[row], end, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            wave_sync();
+                            // Transfers inside the producer's node have a row per GPU pair: they only meet if two
+                            // consumer parts sit on one GPU.
+                            const u64 near_m = comm_mask & same_m;
+                            if (near_m) {
+                                const bool near = lanes_of(near_m);
+                                const u64 end_near = fifo_commit(near, row, ns, now_kp, (near_m & dup_m) != 0, L);
+                                if (near) end = end_near;
+                            }
                         } else {
                             end = fifo_commit(comm, row, ns, now_kp, true, L);
                         }

@@ -36,6 +36,7 @@ __device__ u64 simulate_candidate(SimX& m, Counters& cnt, Recorder& rec) {
 #endif
     const StrategyClass cls = validate_strategy(m);
     if (cls == STRATEGY_INVALID) return RESULT_INVALID;
+    m.want_sort = cls != STRATEGY_REGULAR;
     init_state(m, cnt);
 #ifdef FFSIM_PROFILE
     cnt.exit_code = __builtin_readcyclecounter() - prof_t0;   // reported as section 0

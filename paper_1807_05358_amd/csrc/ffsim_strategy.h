@@ -49,7 +49,9 @@ __host__ __device__ inline size_t lds_common_bytes(uint32_t n_rows, uint32_t n_o
     return (size_t)n_rows * 8 + (size_t)n_ops_pad * 8 + 64 * 8 + ((n_rows + 15) & ~15u);
 }
 // per-candidate task words + per-op exeTime: in LDS for small graphs, else in an HBM slot
-__host__ __device__ inline size_t ecache_bytes(uint32_t n_edges) { return (size_t)n_edges * 5 * WAVE * 4; }
+// (five words per lane and edge, then, behind those of all edges, one more per lane and edge: the
+// consumer's parts in (node, part) order, see EdgeLane::sortw)
+__host__ __device__ inline size_t ecache_bytes(uint32_t n_edges) { return (size_t)n_edges * 6 * WAVE * 4; }
 __host__ __device__ inline size_t slot_bytes(uint32_t n_ops, uint32_t n_ops_pad) {
     return (size_t)n_ops * WAVE * 8 + (size_t)n_ops_pad * 4;
 }
@@ -229,6 +231,7 @@ struct SimT {
     bool ecache_fill;        // init_state writes them (false: ecache is someone else's and only read)
     const uint4* links = nullptr;        // per ordered pair of local GPUs: bandwidth, its magic, latency (S.link_table)
     const uint16_t* devmap = nullptr;    // [n_ops][64] device of every part given explicitly, or null
+    bool want_sort = false;              // the set-up of an edge includes the consumer's parts in (node, part) order (general event loop)
     static constexpr bool kOvr = OVR;
     static constexpr bool kExt = EXT;
     static_assert(GPN == 0 || GPN == 4, "compiled node sizes");
@@ -271,6 +274,12 @@ struct EdgeLane {
     // regular strategies: position inside the run of lanes that share a remote link row (see run_events)
     uint32_t pos, last_run_mask, first_len;
     bool run_end, wrapped;
+    // general strategies: the consumer's parts in (node, part) order, so that the transfers from one producer part
+    // that share a link row between two nodes are neighbours.  Bits 0-5: the part that sorts to this
+    // lane's position; 6-11: this lane's part's position; 12-21: the node of the part at this position; 22: the
+    // position starts a node (or lies beyond the parts); 23: this lane's part shares its device with a
+    // lower part of the consumer.
+    uint32_t sortw;
 };
 constexpr uint32_t ECACHE_WORDS = 5;
 constexpr uint32_t ECACHE_MAX_EXTENT = 0xffff;
@@ -294,6 +303,22 @@ __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, con
     el.dev_c = consecutive ? part_device<true>(cj, lane, S) : m.template device_of<false>(e.dst, cj);
     el.node_c = m.node_of(el.dev_c);
     el.pos = 0; el.first_len = 0; el.last_run_mask = 0; el.run_end = false; el.wrapped = false;
+    el.sortw = 0;
+    if (m.want_sort) {
+        uint32_t rank = 0;
+        bool dup = false;
+        for (uint32_t l2 = 0; l2 < cj.parts; l2++) {
+            const uint32_t n2 = readlane_u32(el.node_c, (int)l2), d2 = readlane_u32(el.dev_c, (int)l2);
+            rank += (n2 < el.node_c || (n2 == el.node_c && l2 < (uint32_t)lane)) ? 1u : 0u;
+            dup = dup || (d2 == el.dev_c && l2 < (uint32_t)lane);
+        }
+        const uint32_t spos = el.mine ? rank : (uint32_t)lane;       // lanes beyond the parts stay where they are
+        const uint32_t part_here = scatter_u32((uint32_t)lane, spos);
+        const uint32_t node_here = scatter_u32(el.node_c, spos);
+        const uint32_t node_before = wave_shr1_u32(node_here);
+        const bool head = lane == 0 || (uint32_t)lane >= cj.parts || node_here != node_before;
+        el.sortw = part_here | (spos << 6) | (node_here << 12) | ((uint32_t)head << 22) | ((uint32_t)(dup && el.mine) << 23);
+    }
     if (consecutive) {
         const uint32_t node0 = m.node_of(cj.off);
         const uint32_t room = G - (cj.off - node0 * G);              // lanes of the first run
@@ -311,7 +336,8 @@ __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, con
 
 // ranges as lo | hi << 16; one word of small fields: device 10 bits, node 10, pos 3, run_end,
 // last run, mine, first_len 4, wrapped
-__device__ __forceinline__ void ecache_store(uint32_t* ecache, uint32_t eid, const EdgeLane& el) {
+__device__ __forceinline__ void ecache_store(uint32_t* ecache, uint32_t n_edges, uint32_t eid, const EdgeLane& el) {
+    ecache[(size_t)n_edges * (ECACHE_WORDS * WAVE) + (size_t)eid * WAVE + lane_id()] = el.sortw;
     uint32_t* p = ecache + (size_t)eid * (ECACHE_WORDS * WAVE) + lane_id();
 #pragma unroll
     for (int d = 0; d < 4; d++) p[d * WAVE] = (uint32_t)el.nlo[d] | ((uint32_t)el.nhi[d] << 16);
@@ -331,7 +357,11 @@ __device__ __forceinline__ EdgeLane ecache_load(const uint32_t* ecache, uint32_t
     el.run_end = (f >> 23) & 1u; el.last_run_mask = 0u - ((f >> 24) & 1u); el.mine = (f >> 25) & 1u;
     const uint32_t u = first_u32(f);                 // the last two fields are the same in every lane
     el.first_len = (u >> 26) & 15u; el.wrapped = (u >> 30) & 1u;
+    el.sortw = 0;
     return el;
+}
+__device__ __forceinline__ uint32_t ecache_sort_word(const uint32_t* ecache, uint32_t n_edges, uint32_t eid) {
+    return ecache[(size_t)n_edges * (ECACHE_WORDS * WAVE) + (size_t)eid * WAVE + lane_id()];
 }
 
 // how many parts of the producer (configuration cp) a consumer part reads through edge e:
