@@ -38,7 +38,7 @@ def lib():
         L = C.CDLL(build())
         vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
         L.ffo_build.restype = vp
-        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ffo_graph_ok.restype = C.c_int
         L.ffo_graph_ok.argtypes = [u32, u32, vp]
         L.ffo_from_arrays.restype = vp
@@ -52,7 +52,7 @@ def lib():
         L.ffo_free.restype = None
         L.ffo_free.argtypes = [vp]
         L.ffo_batch.restype = None
-        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
+        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -94,6 +94,21 @@ def _link_args(m):
     lat = getattr(m, "link_lat_ns", None)
     lat = np.full((G, G), m.intra_lat_ns, "<u4") if lat is None else np.ascontiguousarray(lat, "<u4")
     assert bw.shape == (G, G) and lat.shape == (G, G)
+    return (bw, lat), (_ptr(bw), _ptr(lat))
+
+
+def _node_link_args(m):
+    """optional per-pair links between nodes: attributes node_Bpns / node_lat_ns of the machine,
+    [n_nodes][n_nodes] (from node, to node); latency defaults to the machine's inter-node latency.
+    Returns (keep-alive arrays, the two C arguments)."""
+    bw = getattr(m, "node_Bpns", None)
+    if bw is None:
+        return (), (None, None)
+    N = int(m.n_nodes)
+    bw = np.ascontiguousarray(bw, "<u4")
+    lat = getattr(m, "node_lat_ns", None)
+    lat = np.full((N, N), m.inter_lat_ns, "<u4") if lat is None else np.ascontiguousarray(lat, "<u4")
+    assert bw.shape == (N, N) and lat.shape == (N, N)
     return (bw, lat), (_ptr(bw), _ptr(lat))
 
 
@@ -151,8 +166,9 @@ def build_task_graph(ops, edges, machine, cost, cfg, devmap=None, params=None):
         devmap = np.ascontiguousarray(devmap, "<u2")
         assert devmap.shape == (len(ops), 64)
     keep_p, pargs = _param_args(params, len(ops))
+    keep_n, nargs = _node_link_args(machine)
     h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs,
-                        None if devmap is None else _ptr(devmap), *pargs)
+                        None if devmap is None else _ptr(devmap), *pargs, *nargs)
     return TaskGraph(h) if h else None
 
 
@@ -163,7 +179,8 @@ def build_and_discard(ops, edges, machine, cost, cfg):
     m = _machine(machine)
     keep, cargs = _cost_args(cost)
     keep_l, largs = _link_args(machine)
-    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None, None, None)
+    keep_n, nargs = _node_link_args(machine)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None, None, None, *nargs)
     if h:
         lib().ffo_free(h)
     return bool(h)
@@ -191,9 +208,10 @@ def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None, p
         devmaps = np.ascontiguousarray(devmaps, "<u2")
         assert devmaps.shape == (cfgs.shape[0], len(ops), 64)
     keep_p, pargs = _param_args(params, len(ops))
+    keep_n, nargs = _node_link_args(machine)
     lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs,
                     _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads, *largs,
-                    None if devmaps is None else _ptr(devmaps), *pargs)
+                    None if devmaps is None else _ptr(devmaps), *pargs, *nargs)
     return out
 
 

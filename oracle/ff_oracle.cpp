@@ -144,6 +144,8 @@ bool exe_time(const CostModel& cm, uint32_t i, const Cfg& c, uint32_t parts, uin
 // link_bw / link_lat [G][G]: bandwidth and latency of the link from local GPU a to local GPU b
 // of one node (the same in every node; the diagonal is not used) instead of the machine's
 // single intra-node figures -- the device topology's connections need not be alike.
+// node_bw / node_lat [N][N]: bandwidth and latency of the network link from node a to node b (the
+// diagonal is not used) instead of the machine's single inter-node figures.
 // devmap [n_ops][64]: the device of every task given one by one (Section 4: a configuration
 // assigns each task its device), instead of offset + k * stride.
 // param_bytes / param_dims [n_ops]: parameter synchronisation.  Section 8 discusses how strategies
@@ -160,6 +162,7 @@ bool exe_time(const CostModel& cm, uint32_t i, const Cfg& c, uint32_t parts, uin
 struct Extras {
     const uint32_t* link_bw; const uint32_t* link_lat; const uint16_t* devmap;
     const uint32_t* param_bytes; const uint8_t* param_dims;
+    const uint32_t* node_bw; const uint32_t* node_lat;
 };
 
 uint64_t transfer_ns(const Machine& m, const Extras& x, uint32_t from, uint32_t to, uint64_t bytes) {
@@ -171,6 +174,11 @@ uint64_t transfer_ns(const Machine& m, const Extras& x, uint32_t from, uint32_t 
         const size_t pair = (size_t)(from % G) * G + to % G;
         bw = x.link_bw[pair];
         lat = x.link_lat[pair];
+    }
+    if (!same_node && x.node_bw) {
+        const size_t pair = (size_t)(from / G) * m.n_nodes + to / G;
+        bw = x.node_bw[pair];
+        lat = x.node_lat[pair];
     }
     return (bytes + bw - 1) / bw + lat;       // assumption A2, rounded up, plus the link's latency
 }
@@ -311,10 +319,11 @@ int ffo_graph_ok(uint32_t n_ops, uint32_t n_edges, const void* edges) { return g
 void* ffo_build(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* edges, const void* machine,
                 const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
                 const uint32_t* tuple_ns, const void* cfg, const uint32_t* link_bw, const uint32_t* link_lat,
-                const uint16_t* devmap, const uint32_t* param_bytes, const uint8_t* param_dims) {
+                const uint16_t* devmap, const uint32_t* param_bytes, const uint8_t* param_dims,
+                const uint32_t* node_bw, const uint32_t* node_lat) {
     TaskGraph* tg = new TaskGraph;
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
-    const Extras x{link_bw, link_lat, devmap, param_bytes, param_dims};
+    const Extras x{link_bw, link_lat, devmap, param_bytes, param_dims, node_bw, node_lat};
     if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                (const Cfg*)cfg, x, *tg)) { delete tg; return nullptr; }
     return tg;
@@ -359,12 +368,13 @@ void ffo_batch(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* ed
                const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
                const uint32_t* tuple_ns, const void* cfgs, uint32_t B, uint64_t* out_ns, uint32_t n_threads,
                const uint32_t* link_bw, const uint32_t* link_lat, const uint16_t* devmaps, const uint32_t* param_bytes,
-               const uint8_t* param_dims) {
+               const uint8_t* param_dims, const uint32_t* node_bw, const uint32_t* node_lat) {
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
     auto work = [&](uint32_t b0, uint32_t b1) {
         for (uint32_t b = b0; b < b1; b++) {
             TaskGraph tg;
-            const Extras x{link_bw, link_lat, devmaps ? devmaps + (size_t)b * n_ops * MAX_PARTS : nullptr, param_bytes, param_dims};
+            const Extras x{link_bw, link_lat, devmaps ? devmaps + (size_t)b * n_ops * MAX_PARTS : nullptr, param_bytes, param_dims,
+                           node_bw, node_lat};
             bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                             (const Cfg*)cfgs + (size_t)b * n_ops, x, tg);
             out_ns[b] = ok ? simulate(tg, nullptr, nullptr, nullptr) : INVALID;

@@ -72,6 +72,10 @@ class Machine:
     # a node that are not all alike; None = intra_Bpns / intra_lat_ns for every pair
     link_Bpns: object = None
     link_lat_ns: object = None
+    # optional [n_nodes][n_nodes] tables (from node, to node): network links between nodes that are not
+    # all alike; None = inter_Bpns / inter_lat_ns for every pair
+    node_Bpns: object = None
+    node_lat_ns: object = None
 
     @property
     def n_devices(self) -> int:
@@ -540,6 +544,16 @@ def paired_links(gpus_per_node, fast_Bpns, slow_Bpns, fast_lat_ns=0, slow_lat_ns
     same = (a[:, None] // 2) == (a[None, :] // 2)
     return (np.where(same, fast_Bpns, slow_Bpns).astype("<u4"),
             np.where(same, fast_lat_ns, slow_lat_ns).astype("<u4"))
+
+
+def ring_node_links(n_nodes, near_Bpns, far_Bpns, hop_lat_ns=0):
+    """link tables [N][N] of nodes on a ring: neighbours talk at near_Bpns, any other two nodes at
+    far_Bpns; latency hop_lat_ns per hop of the shorter way round (a network whose connections are not
+    all alike, as the device topology of Section 3 allows)."""
+    a = np.arange(n_nodes)
+    d = np.abs(a[:, None] - a[None, :])
+    hops = np.minimum(d, n_nodes - d)
+    return (np.where(hops <= 1, near_Bpns, far_Bpns).astype("<u4"), (hops * hop_lat_ns).astype("<u4"))
 
 
 def device_maps(cfgs, n_dev, seed, spread=None):

@@ -171,3 +171,91 @@ def test_the_task_graph_takes_devices_from_the_map():
         for s_, d_ in zip(tg.dep_src, tg.dep_dst):
             if s_ < tg.n_compute and d_ < tg.n_compute:
                 assert tg.dev[s_] == tg.dev[d_]
+
+
+# ---- links between nodes that are not all alike ---------------------------------------------------
+
+def test_a_table_of_equal_node_links_is_the_plain_machine():
+    w = W.workload(1)
+    N = w.machine.n_nodes
+    m2 = dataclasses.replace(w.machine, node_Bpns=np.full((N, N), w.machine.inter_Bpns), node_lat_ns=None)
+    cfgs = w.strategies(48)
+    assert np.array_equal(oracle.simulate_batch(w.ops, w.edges, m2, w.cost, cfgs),
+                          oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs))
+
+
+def test_every_ordered_node_pair_uses_its_own_bandwidth_and_latency():
+    ops, edges = _two_op_chain()
+    cost = np.array([[1000], [700]], np.uint32)
+    N, G = 3, 2
+    primes = np.array([3, 5, 7, 11, 13, 17, 19, 23, 29], np.uint32).reshape(N, N)
+    lats = (np.arange(9, dtype=np.uint32) * 10 + 1).reshape(N, N)
+    mach = W.Machine(N, G, intra_Bpns=1000, inter_Bpns=9, intra_lat_ns=5, inter_lat_ns=2, elem_bytes=4,
+                     node_Bpns=primes, node_lat_ns=lats)
+    n_bytes = 8 * 6 * 4
+    for a in range(N):
+        for b in range(N):
+            for ga in range(G):
+                for gb in range(G):
+                    got = int(oracle.simulate_batch(ops, edges, mach, cost, _unsplit(2, [a * G + ga, b * G + gb]))[0])
+                    if a == b:        # inside a node the table plays no part
+                        assert got == (1700 if ga == gb else 1000 + (n_bytes + 999) // 1000 + 5 + 700)
+                    else:
+                        bw, lat = int(primes[a, b]), int(lats[a, b])
+                        assert got == 1000 + (n_bytes + bw - 1) // bw + lat + 700
+    assert primes[0, 2] != primes[2, 0]               # the direction matters
+
+
+def test_node_latency_table_defaults_to_the_machines_latency():
+    ops, edges = _two_op_chain()
+    cost = np.array([[1000], [700]], np.uint32)
+    mach = W.Machine(2, 1, inter_Bpns=1000, inter_lat_ns=77, node_Bpns=np.array([[1, 4], [8, 1]]))
+    assert int(oracle.simulate_batch(ops, edges, mach, cost, _unsplit(2, [0, 1]))[0]) == 1000 + 192 // 4 + 77 + 700
+    assert int(oracle.simulate_batch(ops, edges, mach, cost, _unsplit(2, [1, 0]))[0]) == 1000 + 192 // 8 + 77 + 700
+
+
+def test_the_task_graph_prices_each_transfer_between_nodes_by_its_node_pair():
+    """config 1's graph on its 4 x 4 machine with ring links between the nodes: every communication task
+    on a network row must take the shared bytes over its own node pair's bandwidth plus that pair's
+    latency, checked through the task graph against a machine whose links all move 1 B/ns"""
+    w = W.workload(1)
+    N, G = w.machine.n_nodes, w.machine.gpus_per_node
+    bw, lat = W.ring_node_links(N, 12, 5, 300)
+    mach = dataclasses.replace(w.machine, node_Bpns=bw, node_lat_ns=lat)
+    plain = dataclasses.replace(w.machine, intra_Bpns=1, inter_Bpns=1)
+    D = N * G
+    first_net_row = D + N * G * G
+    n_net = 0
+    for cfg in w.strategies(16):
+        tg, ref = (oracle.build_task_graph(w.ops, w.edges, m, w.cost, cfg) for m in (mach, plain))
+        assert tg.n_tasks == ref.n_tasks and np.array_equal(tg.dev, ref.dev)
+        for t in range(tg.n_compute, tg.n_tasks):
+            n_bytes = int(ref.exe[t])
+            if tg.dev[t] >= first_net_row:
+                a, b = divmod(int(tg.dev[t]) - first_net_row, N)
+                assert a != b
+                assert int(tg.exe[t]) == (n_bytes + int(bw[a, b]) - 1) // int(bw[a, b]) + int(lat[a, b])
+                n_net += 1
+            else:
+                assert int(tg.exe[t]) == (n_bytes + w.machine.intra_Bpns - 1) // w.machine.intra_Bpns
+    assert n_net > 100
+
+
+def test_renaming_the_nodes_with_their_links_changes_nothing():
+    """a permutation of the node numbers applied to every device and to the rows and columns of the
+    node link table describes the same machine"""
+    w = W.workload(1)
+    N, G = w.machine.n_nodes, w.machine.gpus_per_node
+    rng = np.random.default_rng(3)
+    bw = rng.integers(2, 30, size=(N, N)).astype("<u4")
+    lat = rng.integers(0, 500, size=(N, N)).astype("<u4")
+    m1 = dataclasses.replace(w.machine, node_Bpns=bw, node_lat_ns=lat)
+    perm = np.array([2, 0, 3, 1])                                      # old node -> new node
+    inv = np.argsort(perm)
+    m2 = dataclasses.replace(w.machine, node_Bpns=bw[np.ix_(inv, inv)], node_lat_ns=lat[np.ix_(inv, inv)])
+    cfgs = w.strategies(24)
+    maps1 = _formula_maps(cfgs, N * G)
+    maps2 = (perm[maps1 // G] * G + maps1 % G).astype(np.uint16)
+    a = oracle.simulate_batch(w.ops, w.edges, m1, w.cost, cfgs, devmaps=maps1)
+    b = oracle.simulate_batch(w.ops, w.edges, m2, w.cost, cfgs, devmaps=maps2)
+    assert np.array_equal(a, b) and len(set(a.tolist())) > 8

@@ -90,6 +90,12 @@ MISTAKES = [
      "owner = owner * c.deg[d] + (((x.param_dims[i] >> d) & 1) ? idx[d] : 0);", "owner = owner * c.deg[d] + (((x.param_dims[i] >> d) & 1) ? 0 : idx[d]);"),
     ("link table indexed by (to, from)",
      "const size_t pair = (size_t)(from % G) * G + to % G;", "const size_t pair = (size_t)(to % G) * G + from % G;"),
+    ("node link table indexed by (to, from)",
+     "const size_t pair = (size_t)(from / G) * m.n_nodes + to / G;", "const size_t pair = (size_t)(to / G) * m.n_nodes + from / G;"),
+    ("node link table ignored",
+     "if (!same_node && x.node_bw) {", "if (false && x.node_bw) {"),
+    ("node link table used inside a node as well",
+     "if (!same_node && x.node_bw) {", "if (x.node_bw) {"),
     ("explicit device map ignored",
      "dev = x.devmap[(size_t)i * MAX_PARTS + k];", "dev = dev;"),
     ("tuple cost list: first entry of the op instead of the matching one",
