@@ -182,6 +182,20 @@ typedef struct {
 } ff_linktable_t;
 int ff_sim_set_links(ff_sim_t* sim, const ff_linktable_t* links);
 
+/* Network links between nodes that are not all alike (Section 3, as above): Bpns[a * n_nodes + b] /
+ * lat_ns[...] describe the link from node a to node b; entries with a == b are not used; lat_ns may
+ * be null (0 ns).  They replace machine.inter_Bpns / inter_lat_ns for every later call; each ordered
+ * node pair keeps its one link, shared by all GPU pairs of the two nodes.  links == NULL returns to
+ * the machine's single figures.  Independent of ff_sim_set_links; otherwise the same rules (HOST
+ * pointers, deep-copied, waits for the device, invalidates chain sets created before).  FF_EINVAL if
+ * n_nodes differs from the machine's or if a bandwidth is 0. */
+typedef struct {
+    uint32_t n_nodes;
+    const uint32_t* Bpns;
+    const uint32_t* lat_ns;
+} ff_nodelinks_t;
+int ff_sim_set_node_links(ff_sim_t* sim, const ff_nodelinks_t* links);
+
 /* Parameter synchronisation (Section 8 compares strategies by the data they move to keep the
  * replicas of an op's parameters in step; Section 5.1 has no construction for it).  Reading
  * taken: op i holds param_bytes[i] bytes of parameters (0: none), indexed by the output dims in

@@ -34,7 +34,7 @@ class ff_costtable_t(C.Structure):
     _fields_ = [("n_ops", C.c_uint32), ("n_cols", C.c_uint32), ("ns", C.c_void_p)]
 
 
-EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_params",
+EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_node_links", "ff_sim_set_params",
            "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search", "ff_sim_accept_table",
@@ -98,6 +98,8 @@ def lib():
         L.ff_sim_batch_devmaps.argtypes = [vp, vp, vp, u32, vp, vp]
         L.ff_sim_set_links.restype = C.c_int
         L.ff_sim_set_links.argtypes = [vp, vp]
+        L.ff_sim_set_node_links.restype = C.c_int
+        L.ff_sim_set_node_links.argtypes = [vp, vp]
         L.ff_sim_set_params.restype = C.c_int
         L.ff_sim_set_params.argtypes = [vp, vp, vp]
         L.ff_sim_chains_create.restype = C.c_int
@@ -185,6 +187,20 @@ def ff_sim_set_links(sim, gpus_per_node=0, Bpns=None, lat_ns=None):
         raise ValueError("link tables must be [gpus_per_node][gpus_per_node]")
     lt = ff_linktable_t(gpus_per_node, Bpns.ctypes.data, None if lat is None else lat.ctypes.data)
     _check(lib().ff_sim_set_links(sim, C.byref(lt)), "ff_sim_set_links")
+
+
+def ff_sim_set_node_links(sim, n_nodes=0, Bpns=None, lat_ns=None):
+    """Bpns / lat_ns: [n_nodes][n_nodes] (from node, to node); Bpns None: back to the machine's single
+    inter-node figures."""
+    if Bpns is None:
+        _check(lib().ff_sim_set_node_links(sim, None), "ff_sim_set_node_links")
+        return
+    Bpns = np.ascontiguousarray(Bpns, "<u4")
+    lat = None if lat_ns is None else np.ascontiguousarray(lat_ns, "<u4")
+    if Bpns.size != n_nodes * n_nodes or (lat is not None and lat.size != Bpns.size):
+        raise ValueError("node link tables must be [n_nodes][n_nodes]")
+    lt = ff_linktable_t(n_nodes, Bpns.ctypes.data, None if lat is None else lat.ctypes.data)   # same layout as ff_nodelinks_t
+    _check(lib().ff_sim_set_node_links(sim, C.byref(lt)), "ff_sim_set_node_links")
 
 
 def ff_sim_set_params(sim, n_ops, param_bytes=None, param_dims=None):
@@ -317,6 +333,11 @@ class Simulator:
             if lat is None:
                 lat = np.full((machine.gpus_per_node,) * 2, machine.intra_lat_ns, "<u4")
             ff_sim_set_links(self.handle, machine.gpus_per_node, machine.link_Bpns, lat)
+        if getattr(machine, "node_Bpns", None) is not None:
+            lat = machine.node_lat_ns
+            if lat is None:
+                lat = np.full((machine.n_nodes,) * 2, machine.inter_lat_ns, "<u4")
+            ff_sim_set_node_links(self.handle, machine.n_nodes, machine.node_Bpns, lat)
         if params is not None:
             ff_sim_set_params(self.handle, self.n_ops, params[0], params[1])
         self._ws = None

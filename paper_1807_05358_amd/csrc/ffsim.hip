@@ -44,6 +44,7 @@ struct ff_sim {
     ff_machine_t mach{};
     uint32_t links_gen = 0;       // counts ff_sim_set_links / ff_sim_set_params calls (a chain set's stored timelines depend on both)
     std::vector<DOp> h_ops;       // host copy of the op records (ff_sim_set_params rewrites two fields)
+    std::vector<uint32_t> intra_bw, intra_lat, node_bw, node_lat;   // the link tables in force (empty: the machine's single figures)
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
     // the batch kernel may keep the per-edge set-up of a candidate (all extents must fit 16 bits):
@@ -116,13 +117,13 @@ static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = fals
 // chains keep the per-edge set-up in their own memory whenever the extents allow it
 static chain_kernel_t chain_kernel(const ff_sim* s) {
     const KernelChoice k = choice(s, s->chain_cache);
-    const bool ext = s->dev.link_table || s->dev.sync;
+    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync;
     if (s->dev.gpus_per_node == 4) return ext ? chain_kernels<true, 4>(k) : chain_kernels<false, 4>(k);
     return ext ? chain_kernels<true, 0>(k) : chain_kernels<false, 0>(k);
 }
 static try_kernel_t try_kernel(const ff_sim* s) {
     const KernelChoice k = choice(s, s->chain_cache);
-    const bool ext = s->dev.link_table || s->dev.sync;
+    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync;
     if (s->dev.gpus_per_node == 4) return ext ? try_kernels<true, 4>(k) : try_kernels<false, 4>(k);
     return ext ? try_kernels<true, 0>(k) : try_kernels<false, 0>(k);
 }
@@ -160,15 +161,28 @@ const char* ff_sim_strerror(int code) {
 // number of parts.  n_cols == 0: costs keyed by the degree tuple, packed as ptr[n_ops+1], then the
 // tuples of all ops, then their exeTimes.
 // the constants buffer of the kernels (layout: LINK_TABLE_AT in ffsim_device.h)
-static std::vector<uint32_t> constants_image(const ff_linktable_t* links, uint32_t G) {
-    std::vector<uint32_t> c(LINK_TABLE_AT + 4 * (links ? (size_t)G * G : 1), 0);
+// intra: per ordered pair of local GPUs (G*G entries) or empty; inter: per ordered pair of nodes (N*N) or empty;
+// an area that is not given is filled with the machine's single figures (it is then not read)
+static std::vector<uint32_t> constants_image(const ff_machine_t& m, const std::vector<uint32_t>& intra_bw, const std::vector<uint32_t>& intra_lat,
+                                             const std::vector<uint32_t>& node_bw, const std::vector<uint32_t>& node_lat) {
+    const size_t G2 = (size_t)m.gpus_per_node * m.gpus_per_node, N2 = (size_t)m.n_nodes * m.n_nodes;
+    const bool any = !intra_bw.empty() || !node_bw.empty();
+    std::vector<uint32_t> c(LINK_TABLE_AT + 4 * (any ? G2 + N2 : 1), 0);
     for (uint32_t d = 2; d <= 64; d++) c[d] = magic_plus1(d);
-    if (links)
-        for (uint32_t p = 0; p < G * G; p++) {
-            c[LINK_TABLE_AT + 4 * p + 0] = links->Bpns[p];
-            c[LINK_TABLE_AT + 4 * p + 1] = magic_floor(links->Bpns[p]);
-            c[LINK_TABLE_AT + 4 * p + 2] = links->lat_ns ? links->lat_ns[p] : 0;
+    if (any) {
+        for (size_t p = 0; p < G2; p++) {
+            const uint32_t bw = intra_bw.empty() ? m.intra_Bpns : intra_bw[p];
+            c[LINK_TABLE_AT + 4 * p + 0] = bw;
+            c[LINK_TABLE_AT + 4 * p + 1] = magic_floor(bw);
+            c[LINK_TABLE_AT + 4 * p + 2] = intra_bw.empty() ? m.intra_lat_ns : intra_lat[p];
         }
+        for (size_t p = 0; p < N2; p++) {
+            const uint32_t bw = node_bw.empty() ? m.inter_Bpns : node_bw[p];
+            c[LINK_TABLE_AT + 4 * (G2 + p) + 0] = bw;
+            c[LINK_TABLE_AT + 4 * (G2 + p) + 1] = magic_floor(bw);
+            c[LINK_TABLE_AT + 4 * (G2 + p) + 2] = node_bw.empty() ? m.inter_lat_ns : node_lat[p];
+        }
+    }
     return c;
 }
 
@@ -259,7 +273,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         }
         for (uint32_t k = 0; k < g->n_edges; k++) in_edges[ops[edges[k].dst].in_end++] = edges[k];
     }
-    std::vector<uint32_t> magic = constants_image(nullptr, 0);
+    std::vector<uint32_t> magic = constants_image(*m, {}, {}, {}, {});
 
     ff_sim* s = new (std::nothrow) ff_sim;
     if (!s) return FF_ENOMEM;
@@ -295,7 +309,11 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
     // small graphs keep a candidate's task words in LDS, as long as four wavefronts (one per
     // SIMD) still fit in a CU's 160 KB
     const size_t lds_with_words = ((slot_bytes(S.n_ops, S.n_ops_pad) + 15) & ~(size_t)15) + s->lds_common;
+#ifdef FFSIM_FORCE_HBM
+    s->lds_words = false;
+#else
     s->lds_words = lds_with_words <= 40 * 1024;
+#endif
     s->lds = s->lds_words ? lds_with_words : s->lds_common;
     s->cache_ok = max_extent <= ECACHE_MAX_EXTENT && g->n_edges > 0;
     s->chain_cache = s->cache_ok;
@@ -386,33 +404,73 @@ int ff_sim_set_params(ff_sim_t* s, const uint32_t* param_bytes, const uint8_t* p
     return FF_OK;
 }
 
-int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
-    if (!s) return FF_EINVAL;
+// uploads the constants for the link tables in force and re-derives what depends on them
+static int apply_link_tables(ff_sim_t* s) {
     const ff_machine_t& m = s->mach;
-    const uint32_t G = m.gpus_per_node;
-    uint32_t bw_min = std::min(m.intra_Bpns, m.inter_Bpns), lat_max = std::max(m.intra_lat_ns, m.inter_lat_ns);
-    if (links) {
-        if (!links->Bpns || links->gpus_per_node != G) return FF_EINVAL;
-        bw_min = m.inter_Bpns; lat_max = m.inter_lat_ns;
+    const uint32_t G = m.gpus_per_node, N = m.n_nodes;
+    uint32_t bw_min = 0xffffffffu, lat_max = 0;
+    if (s->intra_bw.empty()) { bw_min = std::min(bw_min, m.intra_Bpns); lat_max = std::max(lat_max, m.intra_lat_ns); }
+    else
         for (uint32_t a = 0; a < G; a++)
-            for (uint32_t b = 0; b < G; b++) {
-                if (a == b) continue;                                  // a device needs no link to itself
-                if (links->Bpns[a * G + b] < 1) return FF_EINVAL;
-                bw_min = std::min(bw_min, links->Bpns[a * G + b]);
-                lat_max = std::max(lat_max, links->lat_ns ? links->lat_ns[a * G + b] : 0u);
-            }
-    }
-    std::vector<uint32_t> image = constants_image(links, G);
+            for (uint32_t b = 0; b < G; b++)
+                if (a != b) { bw_min = std::min(bw_min, s->intra_bw[a * G + b]); lat_max = std::max(lat_max, s->intra_lat[a * G + b]); }
+    if (s->node_bw.empty()) { bw_min = std::min(bw_min, m.inter_Bpns); lat_max = std::max(lat_max, m.inter_lat_ns); }
+    else
+        for (uint32_t a = 0; a < N; a++)
+            for (uint32_t b = 0; b < N; b++)
+                if (a != b) { bw_min = std::min(bw_min, s->node_bw[a * N + b]); lat_max = std::max(lat_max, s->node_lat[a * N + b]); }
+    std::vector<uint32_t> image = constants_image(m, s->intra_bw, s->intra_lat, s->node_bw, s->node_lat);
     uint32_t* d_new = nullptr;
     int rc = upload(image, &d_new);
     if (rc) return rc;
     if (hipDeviceSynchronize() != hipSuccess) { hipFree(d_new); return FF_EHIP; }   // no launch may still read the old table
     hipFree(s->d_magic);
     s->d_magic = d_new;
-    s->dev.link_table = links ? 1u : 0u;
+    s->dev.link_table = s->intra_bw.empty() ? 0u : 1u;
+    s->dev.node_table = s->node_bw.empty() ? 0u : 1u;
     s->links_gen++;
     s->wide = needs_wide(s->big_tensors, bw_min, lat_max, G);
     return FF_OK;
+}
+
+int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
+    if (!s) return FF_EINVAL;
+    const uint32_t G = s->mach.gpus_per_node;
+    std::vector<uint32_t> bw, lat;
+    if (links) {
+        if (!links->Bpns || links->gpus_per_node != G) return FF_EINVAL;
+        bw.assign(links->Bpns, links->Bpns + (size_t)G * G);
+        lat.assign((size_t)G * G, 0);
+        if (links->lat_ns) lat.assign(links->lat_ns, links->lat_ns + (size_t)G * G);
+        for (uint32_t a = 0; a < G; a++)
+            for (uint32_t b = 0; b < G; b++) {
+                if (a == b) { bw[a * G + b] = std::max(bw[a * G + b], 1u); continue; }   // a device needs no link to itself
+                if (bw[a * G + b] < 1) return FF_EINVAL;
+            }
+    }
+    s->intra_bw.swap(bw);
+    s->intra_lat.swap(lat);
+    return apply_link_tables(s);
+}
+
+int ff_sim_set_node_links(ff_sim_t* s, const ff_nodelinks_t* links) {
+    if (!s) return FF_EINVAL;
+    const uint32_t N = s->mach.n_nodes;
+    std::vector<uint32_t> bw, lat;
+    if (links) {
+        if (!links->Bpns || links->n_nodes != N) return FF_EINVAL;
+        bw.assign(links->Bpns, links->Bpns + (size_t)N * N);
+        lat.assign((size_t)N * N, 0);
+        if (links->lat_ns) lat.assign(links->lat_ns, links->lat_ns + (size_t)N * N);
+        for (uint32_t a = 0; a < N; a++)
+            for (uint32_t b = 0; b < N; b++) {
+                if (a == b) { bw[a * N + b] = std::max(bw[a * N + b], 1u); continue; }   // not used
+                if (bw[a * N + b] < 1) return FF_EINVAL;
+            }
+    }
+    s->node_bw.swap(bw);
+    s->node_lat.swap(lat);
+    return apply_link_tables(s);
 }
 
 size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {
@@ -448,7 +506,7 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
                       void* hip_stream) {
     if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
     if (B == 0) return FF_OK;
-    const bool ext = s->dev.link_table || s->dev.sync || d_devmaps;
+    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync || d_devmaps;
     const bool cached = batch_cached(s, B);
     const uint32_t slots = batch_slots(s, B);
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
@@ -463,7 +521,7 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
 
 int ff_sim_batch_kernel_name(const ff_sim_t* s, uint32_t B, char* buf, size_t len) {
     if (!s || !buf || len < 1) return FF_EINVAL;
-    const bool ext = s->dev.link_table || s->dev.sync;
+    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync;
     const KernelChoice k = choice(s, batch_cached(s, B));
     const int n = snprintf(buf, len, "k_sim_batch<%s, %s, %s, %d, %s, %s, %d>", k.wide ? "true" : "false", k.lds_words ? "true" : "false",
                            k.stats ? "true" : "false", batch_queue_shape(k), k.cache ? "true" : "false", ext ? "true" : "false",

@@ -261,7 +261,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     meta.tag = first_u32(meta.tag);
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
     SimT<false, EXT, GPN> m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
-    if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
+    if (EXT) { m.links = (const uint4*)(magic + LINK_TABLE_AT); m.node_links = m.links + (size_t)S.gpus_per_node * S.gpus_per_node; }
     m.want_sort = true;          // a later step may make the strategy a general one: the kept set-up is always complete
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
             const uint2 ocfg = cm.cfgs[op];
             SimT<true, EXT, GPN> m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
                               CACHE ? cm.ecache : nullptr, false};
-            if (EXT) m.links = (const uint4*)(magic + LINK_TABLE_AT);
+            if (EXT) { m.links = (const uint4*)(magic + LINK_TABLE_AT); m.node_links = m.links + (size_t)S.gpus_per_node * S.gpus_per_node; }
             m.want_sort = true;
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {

@@ -63,11 +63,14 @@ struct SimDev {
     uint32_t n_groups;                 // n_ops_pad / 64  (<= 64)
     uint32_t link_table;               // 1: links inside a node differ per ordered GPU pair (see LINK_TABLE_AT)
     uint32_t sync;                     // 1: parameter synchronisation transfers are simulated (DOp::param_bytes)
+    uint32_t node_table;               // 1: links between nodes differ per ordered node pair (table behind the one above)
 };
 // The constants buffer every kernel receives: words 0..64 are division constants
 // (floor(2^32/d)+1 for d = 2..64); if SimDev::link_table is set, four words per ordered pair of
 // local GPUs (from * gpus_per_node + to) follow at word LINK_TABLE_AT: bandwidth (B/ns),
-// floor(2^32 / bandwidth), latency (ns), 0.
+// floor(2^32 / bandwidth), latency (ns), 0.  Behind that area (which is always gpus_per_node^2 entries
+// long once any table is set), if SimDev::node_table is set, the same four words per ordered pair of
+// nodes (from * n_nodes + to).
 constexpr uint32_t LINK_TABLE_AT = 128;
 
 // the per-lane condition "my bit of this lane mask is set" (the mask is used as it is)

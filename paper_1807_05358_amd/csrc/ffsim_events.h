@@ -524,6 +524,13 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                                 bw = t.x; m_bw = t.y; lat = t.z;
                             }
                         }
+                        if (SimX::kExt && S.node_table) {
+                            // network links that are not all alike: the node pair's own figures
+                            if (comm && !same_node) {
+                                const uint4 t = m.node_links[node_a * S.n_nodes + node_c];
+                                bw = t.x; m_bw = t.y; lat = t.z;
+                            }
+                        }
                         u64 ns;
                         if (WIDE) {
                             const u64 bytes = elems * S.elem_bytes;
@@ -658,6 +665,12 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         if (S.link_table) {
                             if (act && same_node) {
                                 const uint4 t = m.links[m.local_of(dev_p, node_p) * G + local_o];
+                                bw = t.x; m_bw = t.y; lat = t.z;
+                            }
+                        }
+                        if (S.node_table) {
+                            if (act && !same_node) {
+                                const uint4 t = m.node_links[node_p * S.n_nodes + node_o];
                                 bw = t.x; m_bw = t.y; lat = t.z;
                             }
                         }

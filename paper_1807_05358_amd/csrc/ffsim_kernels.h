@@ -95,6 +95,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
         SimT<false, EXT, GPN> m{S, T, strategies + (size_t)b * S.n_ops, words, exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), ecache, true};
         if (EXT) {
             m.links = (const uint4*)(magic + LINK_TABLE_AT);
+            m.node_links = m.links + (size_t)S.gpus_per_node * S.gpus_per_node;
             if (devmaps) m.devmap = devmaps + (size_t)b * S.n_ops * WAVE;
         }
         const u64 mk = simulate_candidate<WIDE, false, STATS, Q, CACHE>(m, cnt, none);

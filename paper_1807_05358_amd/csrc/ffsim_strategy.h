@@ -230,6 +230,7 @@ struct SimT {
     uint32_t* ecache;        // per (edge, consumer part) values kept from the set-up (see EdgeLane), or null
     bool ecache_fill;        // init_state writes them (false: ecache is someone else's and only read)
     const uint4* links = nullptr;        // per ordered pair of local GPUs: bandwidth, its magic, latency (S.link_table)
+    const uint4* node_links = nullptr;   // per ordered pair of nodes: the same three figures (S.node_table)
     const uint16_t* devmap = nullptr;    // [n_ops][64] device of every part given explicitly, or null
     bool want_sort = false;              // the set-up of an edge includes the consumer's parts in (node, part) order (general event loop)
     static constexpr bool kOvr = OVR;

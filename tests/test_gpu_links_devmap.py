@@ -202,3 +202,82 @@ def test_explicit_devices_with_unequal_links_on_random_graphs(B):
         want = oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8, devmaps=maps)
         assert np.array_equal(got, want), f"seed {seed} maps: {np.nonzero(got != want)[0][:5]}"
         sim.close()
+
+
+# ---- network links between nodes that differ per node pair (ff_sim_set_node_links) --------------------
+
+def _with_node_links(machine, seed=0):
+    N = machine.n_nodes
+    bw, lat = W.ring_node_links(N, 12, 5, 300)
+    rng = np.random.default_rng(seed)
+    bw = (bw + rng.integers(0, 4, size=bw.shape)).astype("<u4")        # no two directions alike
+    lat = (lat + rng.integers(0, 90, size=lat.shape)).astype("<u4")
+    return dataclasses.replace(machine, node_Bpns=bw, node_lat_ns=lat)
+
+
+@pytest.mark.parametrize("config_id,n,both", [(1, 320, False), (1, 200, True), (2, 48, False), (3, 16, True), (4, 3, False)])
+def test_unequal_node_links_match_the_oracle(B, config_id, n, both):
+    """batch results, transfer counters, a mutation chain, trial proposals and a search with the links
+    between nodes priced per node pair (alone, or together with unequal links inside the nodes)"""
+    w = W.workload(config_id)
+    mach = _with_node_links(w.machine, seed=config_id)
+    if both:
+        mach = _with_links(mach, seed=config_id + 7)
+    cfgs = _mixed_strategies(w, n, 70 + config_id)
+    want = oracle.simulate_batch(w.ops, w.edges, mach, w.cost, cfgs, n_threads=16)
+    plain = oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfgs, n_threads=16)
+    assert (want != plain).mean() > 0.5
+    sim = B.Simulator(w.ops, w.edges, mach, w.cost)
+    got, st = sim.simulate(cfgs, stats=True)
+    assert not st["exit_code"].any() and not st["n_stuck"].any()
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+    assert np.array_equal(sim.simulate(cfgs), want)                 # the kernel without the counters
+    for b in range(min(n, 3)):
+        tg = oracle.build_task_graph(w.ops, w.edges, mach, w.cost, cfgs[b])
+        assert int(st["sum_comm_ns"][b]) == int(tg.exe[tg.n_compute:].sum())
+    if config_id <= 2:
+        C, steps = 2, 16
+        muts = w.mutations(steps, C)
+        ch = B.Chains(sim, cfgs[:C])
+        d = ch.delta(ch.upload_mutations(muts), steps).cpu().numpy().view("<u8")
+        cur = cfgs[:C].copy()
+        for c in range(C):
+            assert np.array_equal(d[:, c], oracle.simulate_delta_chain(w.ops, w.edges, mach, w.cost, cfgs[c], muts[:, c]))
+            for s in range(steps):
+                cur[c, int(muts[s, c]["op"])] = muts[s, c]["cfg"]
+        props = w.mutations(steps + 12, C)[steps:]
+        tried = ch.try_mutations(ch.upload_mutations(props), 12).cpu().numpy().view("<u8")
+        for c in range(C):
+            cand = np.repeat(cur[c][None], 12, 0)
+            for p in range(12):
+                cand[p, int(props[p, c]["op"])] = props[p, c]["cfg"]
+            assert np.array_equal(tried[:, c], oracle.simulate_batch(w.ops, w.edges, mach, w.cost, cand, n_threads=8))
+        tp, tu = w.search_space()
+        t0 = int(oracle.simulate_batch(w.ops, w.edges, mach, w.cost, cur[:1])[0])
+        table = osearch.metropolis_table(30.0 / t0, max(1, t0 // 256), 64)
+        ch.search_setup(tp, tu, table, max(1, t0 // 256), 9)
+        tr = ch.search(14).cpu().numpy().view("<u8")
+        for c in range(C):
+            ref = osearch.metropolis_chain(w.ops, w.edges, mach, w.cost, cur[c], tp, tu, table, max(1, t0 // 256), 9, c, 0, 14)[0]
+            assert np.array_equal(tr[:, c], ref)
+        ch.close()
+    # back to the machine's single figures between nodes (the links inside the nodes stay as they are)
+    B.ff_sim_set_node_links(sim.handle)
+    back = dataclasses.replace(mach, node_Bpns=None, node_lat_ns=None)
+    assert np.array_equal(sim.simulate(cfgs), oracle.simulate_batch(w.ops, w.edges, back, w.cost, cfgs, n_threads=16))
+    sim.close()
+
+
+def test_node_link_argument_errors(B):
+    w = W.workload(1)
+    h = B.ff_sim_create(w.ops, w.edges, w.machine, w.cost)
+    N = w.machine.n_nodes
+    with pytest.raises(B.FFSimError):                       # wrong node count
+        B.ff_sim_set_node_links(h, N + 1, np.ones((N + 1, N + 1), "<u4"))
+    z = np.full((N, N), 5, "<u4"); z[1, 2] = 0
+    with pytest.raises(B.FFSimError):                       # a link without bandwidth
+        B.ff_sim_set_node_links(h, N, z)
+    z[1, 2] = 5; z[2, 2] = 0                                # the diagonal is not used
+    B.ff_sim_set_node_links(h, N, z)
+    B.ff_sim_destroy(h)

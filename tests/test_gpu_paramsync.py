@@ -63,6 +63,9 @@ def test_parameter_dims_and_sizes_of_all_kinds_on_random_graphs(B):
         if seed % 2:
             mach = dataclasses.replace(mach, link_Bpns=rng.integers(1, 40, size=(gpn, gpn)).astype("<u4"),
                                        link_lat_ns=rng.integers(0, 300, size=(gpn, gpn)).astype("<u4"))
+        if seed >= 2:                                           # network links per node pair as well
+            mach = dataclasses.replace(mach, node_Bpns=rng.integers(1, 40, size=(n_nodes, n_nodes)).astype("<u4"),
+                                       node_lat_ns=rng.integers(0, 300, size=(n_nodes, n_nodes)).astype("<u4"))
         cost = rng.integers(1, 3000, size=(n_ops, 64)).astype("<u4")
         pb = rng.integers(0, 200000, size=n_ops).astype("<u4")
         pb[rng.random(n_ops) < 0.4] = 0
