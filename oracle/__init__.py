@@ -38,7 +38,7 @@ def lib():
         L = C.CDLL(build())
         vp, u32, u64p, u32p = C.c_void_p, C.c_uint32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)
         L.ffo_build.restype = vp
-        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.ffo_build.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.ffo_graph_ok.restype = C.c_int
         L.ffo_graph_ok.argtypes = [u32, u32, vp]
         L.ffo_from_arrays.restype = vp
@@ -52,7 +52,7 @@ def lib():
         L.ffo_free.restype = None
         L.ffo_free.argtypes = [vp]
         L.ffo_batch.restype = None
-        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp]
+        L.ffo_batch.argtypes = [u32, vp, u32, vp, vp, vp, u32, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -153,7 +153,16 @@ class TaskGraph:
             self._h = None
 
 
-def build_task_graph(ops, edges, machine, cost, cfg, devmap=None, params=None):
+def _tie_args(ties, n_ops):
+    """ties: None, or leader [n_ops] uint32: op i takes the configuration of op leader[i]."""
+    if ties is None:
+        return (), (None,)
+    t = np.ascontiguousarray(ties, "<u4")
+    assert t.shape == (n_ops,)
+    return (t,), (_ptr(t),)
+
+
+def build_task_graph(ops, edges, machine, cost, cfg, devmap=None, params=None, ties=None):
     """Section 5.1 for one strategy (cfg: [n_ops] configs). None if the strategy is invalid.
     devmap [n_ops][64] uint16: the device of every part given explicitly (the configs' offset
     and stride are then not used)."""
@@ -167,8 +176,9 @@ def build_task_graph(ops, edges, machine, cost, cfg, devmap=None, params=None):
         assert devmap.shape == (len(ops), 64)
     keep_p, pargs = _param_args(params, len(ops))
     keep_n, nargs = _node_link_args(machine)
+    keep_t, targs = _tie_args(ties, len(ops))
     h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs,
-                        None if devmap is None else _ptr(devmap), *pargs, *nargs)
+                        None if devmap is None else _ptr(devmap), *pargs, *nargs, *targs)
     return TaskGraph(h) if h else None
 
 
@@ -180,7 +190,7 @@ def build_and_discard(ops, edges, machine, cost, cfg):
     keep, cargs = _cost_args(cost)
     keep_l, largs = _link_args(machine)
     keep_n, nargs = _node_link_args(machine)
-    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None, None, None, *nargs)
+    h = lib().ffo_build(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs, _ptr(cfg), *largs, None, None, None, *nargs, None)
     if h:
         lib().ffo_free(h)
     return bool(h)
@@ -194,7 +204,7 @@ def task_graph_from_arrays(exe, dev, n_rows, dep_src, dep_dst):
     return TaskGraph(lib().ffo_from_arrays(len(exe), _ptr(exe), _ptr(dev), n_rows, len(ds), _ptr(ds), _ptr(dd)))
 
 
-def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None, params=None):
+def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None, params=None, ties=None):
     """makespan (ns) of every strategy in cfgs [B][n_ops]; 2^64-1 for an invalid one.
     devmaps [B][n_ops][64] uint16: explicit devices of all parts (see build_task_graph)."""
     ops, edges, cfgs = map(np.ascontiguousarray, (ops, edges, cfgs))
@@ -209,13 +219,14 @@ def simulate_batch(ops, edges, machine, cost, cfgs, n_threads=1, devmaps=None, p
         assert devmaps.shape == (cfgs.shape[0], len(ops), 64)
     keep_p, pargs = _param_args(params, len(ops))
     keep_n, nargs = _node_link_args(machine)
+    keep_t, targs = _tie_args(ties, len(ops))
     lib().ffo_batch(len(ops), _ptr(ops), len(edges), _ptr(edges), _ptr(m), *cargs,
                     _ptr(cfgs), cfgs.shape[0], _ptr(out), n_threads, *largs,
-                    None if devmaps is None else _ptr(devmaps), *pargs, *nargs)
+                    None if devmaps is None else _ptr(devmaps), *pargs, *nargs, *targs)
     return out
 
 
-def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None, params=None):
+def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None, params=None, ties=None):
     """oracle for delta simulation: apply the single-op mutations cumulatively and fully
     re-simulate (the definition of the delta result, Section 5.3).  mutations: [n_steps]
     records (op, cfg).  `steps` selects which steps (0-based) to evaluate; returns their
@@ -230,4 +241,4 @@ def simulate_delta_chain(ops, edges, machine, cost, cfg0, mutations, steps=None,
             snaps.append(cur.copy())
     if not snaps:
         return np.zeros(0, "<u8")
-    return simulate_batch(ops, edges, machine, cost, np.stack(snaps), params=params)
+    return simulate_batch(ops, edges, machine, cost, np.stack(snaps), params=params, ties=ties)

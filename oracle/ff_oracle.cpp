@@ -43,7 +43,7 @@
 
 namespace {
 
-struct DimMap { int8_t src_dim; uint8_t pad; uint16_t stride; int32_t a, b; };
+struct DimMap { int8_t src_dim; uint8_t kind; uint16_t stride; int32_t a, b; };   // kind: 0 the consumer reads, 1 the producer contributes
 struct Op { uint8_t ndim; uint8_t par_mask; uint16_t type; uint32_t extent[4]; };
 struct Edge { uint32_t src_op, dst_op; DimMap map[4]; };
 struct Cfg { uint8_t deg[4]; uint16_t dev_offset; uint16_t dev_stride; };
@@ -95,19 +95,32 @@ Box part_box(const Op& op, const Cfg& c, uint32_t k) {
     return b;
 }
 
-// elements of the producer's tensor that consumer box `cb` reads and producer box `pb` holds
-uint64_t shared_elems(const Op& prod, const Edge& e, const Box& pb, const Box& cb) {
+// The sub-tensor two tasks share through an edge, in elements (0: none).
+// A reading edge (kind 0, the forward pass): map[d] belongs to dim d of the PRODUCER's tensor; the consumer
+// part with box `cb` reads the range [cb.lo*stride + a, (cb.hi-1)*stride + b + 1) of it (along the consumer
+// dim src_dim; the whole extent if src_dim < 0), clamped to the tensor; shared = what of that lies in the
+// producer part's box `pb`.
+// A contributing edge (kind 1, gradients flowing back along a forward edge): the same map with the roles
+// exchanged.  map[d] belongs to dim d of the CONSUMER's tensor; the producer part with box `pb` contributes to
+// the range [pb.lo*stride + a, (pb.hi-1)*stride + b + 1) of it (along the producer dim src_dim); shared =
+// what of that lies in the consumer part's box `cb`.  The pairs and sizes are those of the forward edge,
+// transposed.
+uint64_t shared_elems(const Op& prod, const Op& cons, const Edge& e, const Box& pb, const Box& cb) {
+    const bool contributes = e.map[0].kind != 0;
+    const Op& space = contributes ? cons : prod;          // the tensor the ranges are taken in
+    const Box& driving = contributes ? pb : cb;           // the part whose box goes through the map
+    const Box& owning = contributes ? cb : pb;            // the part that holds a box of `space`
     uint64_t elems = 1;
-    for (int d = 0; d < prod.ndim; d++) {
+    for (int d = 0; d < space.ndim; d++) {
         const DimMap& m = e.map[d];
-        int64_t need_lo = 0, need_hi = prod.extent[d];
+        int64_t need_lo = 0, need_hi = space.extent[d];
         if (m.src_dim >= 0) {
-            need_lo = cb.lo[m.src_dim] * (int64_t)m.stride + m.a;
-            need_hi = (cb.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;
+            need_lo = driving.lo[m.src_dim] * (int64_t)m.stride + m.a;
+            need_hi = (driving.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;
             need_lo = std::max<int64_t>(need_lo, 0);
-            need_hi = std::min<int64_t>(need_hi, prod.extent[d]);
+            need_hi = std::min<int64_t>(need_hi, space.extent[d]);
         }
-        int64_t lo = std::max(need_lo, pb.lo[d]), hi = std::min(need_hi, pb.hi[d]);
+        int64_t lo = std::max(need_lo, owning.lo[d]), hi = std::min(need_hi, owning.hi[d]);
         if (hi <= lo) return 0;
         elems *= (uint64_t)(hi - lo);
     }
@@ -146,6 +159,11 @@ bool exe_time(const CostModel& cm, uint32_t i, const Cfg& c, uint32_t parts, uin
 // single intra-node figures -- the device topology's connections need not be alike.
 // node_bw / node_lat [N][N]: bandwidth and latency of the network link from node a to node b (the
 // diagonal is not used) instead of the machine's single inter-node figures.
+// leader [n_ops]: tied configurations.  Section 4 gives every OPERATION one configuration; in a training
+// iteration an operation appears as several ops of the graph (its forward and its backward computation;
+// the unrolled steps of a recurrent layer that share parameters).  Op i then takes the configuration the
+// strategy holds for op leader[i] (leader[leader[i]] == leader[i]); the strategy's entries for other ops
+// are not read.  The configuration must be valid for every op that takes it.
 // devmap [n_ops][64]: the device of every task given one by one (Section 4: a configuration
 // assigns each task its device), instead of offset + k * stride.
 // param_bytes / param_dims [n_ops]: parameter synchronisation.  Section 8 discusses how strategies
@@ -163,6 +181,7 @@ struct Extras {
     const uint32_t* link_bw; const uint32_t* link_lat; const uint16_t* devmap;
     const uint32_t* param_bytes; const uint8_t* param_dims;
     const uint32_t* node_bw; const uint32_t* node_lat;
+    const uint32_t* leader;
 };
 
 uint64_t transfer_ns(const Machine& m, const Extras& x, uint32_t from, uint32_t to, uint64_t bytes) {
@@ -188,6 +207,8 @@ bool graph_ok(uint32_t n_ops, uint32_t n_edges, const Edge* edges) {
     for (uint32_t e = 0; e < n_edges; e++) {
         if (edges[e].src_op >= n_ops || edges[e].dst_op >= n_ops || edges[e].src_op >= edges[e].dst_op) return false;
         if (e > 0 && edges[e - 1].src_op > edges[e].src_op) return false;
+        for (int d = 1; d < 4; d++)
+            if ((edges[e].map[d].kind != 0) != (edges[e].map[0].kind != 0)) return false;   // one kind per edge
     }
     return true;
 }
@@ -200,6 +221,15 @@ bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, c
     tg.n_rows = D + N * G * G + N * N;
     std::vector<uint32_t> first(n_ops), np(n_ops);
     // step 1: compute tasks t_{i:1..|c_i|}
+    std::vector<Cfg> tied;
+    if (x.leader) {
+        tied.resize(n_ops);
+        for (uint32_t i = 0; i < n_ops; i++) {
+            if (x.leader[i] >= n_ops || x.leader[x.leader[i]] != x.leader[i]) return false;
+            tied[i] = cfg[x.leader[i]];
+        }
+        cfg = tied.data();
+    }
     for (uint32_t i = 0; i < n_ops; i++) {
         Cfg c = cfg[i];
         if (x.devmap) { c.dev_offset = 0; c.dev_stride = 1; }     // not used with explicit devices
@@ -228,7 +258,7 @@ bool build(uint32_t n_ops, const Op* ops, uint32_t n_edges, const Edge* edges, c
                 Box pb = part_box(ops[i], cfg[i], kp);
                 for (uint32_t kc = 0; kc < np[j]; kc++) {
                     Box cb = part_box(ops[j], cfg[j], kc);
-                    uint64_t elems = shared_elems(ops[i], edges[e], pb, cb);
+                    uint64_t elems = shared_elems(ops[i], ops[j], edges[e], pb, cb);
                     if (!elems) continue;
                     uint32_t tp = first[i] + kp, tc = first[j] + kc;
                     if (tg.dev[tp] == tg.dev[tc]) { tg.add_dep(tp, tc); continue; }
@@ -320,10 +350,10 @@ void* ffo_build(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* e
                 const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
                 const uint32_t* tuple_ns, const void* cfg, const uint32_t* link_bw, const uint32_t* link_lat,
                 const uint16_t* devmap, const uint32_t* param_bytes, const uint8_t* param_dims,
-                const uint32_t* node_bw, const uint32_t* node_lat) {
+                const uint32_t* node_bw, const uint32_t* node_lat, const uint32_t* leader) {
     TaskGraph* tg = new TaskGraph;
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
-    const Extras x{link_bw, link_lat, devmap, param_bytes, param_dims, node_bw, node_lat};
+    const Extras x{link_bw, link_lat, devmap, param_bytes, param_dims, node_bw, node_lat, leader};
     if (!build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                (const Cfg*)cfg, x, *tg)) { delete tg; return nullptr; }
     return tg;
@@ -368,13 +398,13 @@ void ffo_batch(uint32_t n_ops, const void* ops, uint32_t n_edges, const void* ed
                const uint32_t* cost, uint32_t n_cols, const uint32_t* tuple_ptr, const uint32_t* tuples,
                const uint32_t* tuple_ns, const void* cfgs, uint32_t B, uint64_t* out_ns, uint32_t n_threads,
                const uint32_t* link_bw, const uint32_t* link_lat, const uint16_t* devmaps, const uint32_t* param_bytes,
-               const uint8_t* param_dims, const uint32_t* node_bw, const uint32_t* node_lat) {
+               const uint8_t* param_dims, const uint32_t* node_bw, const uint32_t* node_lat, const uint32_t* leader) {
     const CostModel cm{cost, n_cols, tuple_ptr, tuples, tuple_ns};
     auto work = [&](uint32_t b0, uint32_t b1) {
         for (uint32_t b = b0; b < b1; b++) {
             TaskGraph tg;
             const Extras x{link_bw, link_lat, devmaps ? devmaps + (size_t)b * n_ops * MAX_PARTS : nullptr, param_bytes, param_dims,
-                           node_bw, node_lat};
+                           node_bw, node_lat, leader};
             bool ok = build(n_ops, (const Op*)ops, n_edges, (const Edge*)edges, *(const Machine*)machine, cm,
                             (const Cfg*)cfgs + (size_t)b * n_ops, x, tg);
             out_ns[b] = ok ? simulate(tg, nullptr, nullptr, nullptr) : INVALID;

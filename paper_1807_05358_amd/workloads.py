@@ -17,6 +17,9 @@ of the library boundary):
            drives producer dim d (-1: every consumer part needs the whole extent of d).
            For a consumer part covering [lo, hi) along src_dim the needed producer range is
            [lo*stride + a, (hi-1)*stride + b + 1) clamped to [0, extent_d].
+           pad = 1 on all four maps marks a CONTRIBUTING edge (gradients flowing back along a forward
+           edge): map[] is then indexed by the CONSUMER dim d, src_dim names a PRODUCER dim, and a
+           producer part covering [lo, hi) along src_dim contributes to that range of the consumer's dim d.
   CFG_DT   deg u8[4] | dev_offset u16 | dev_stride u16       (one per op = a configuration c_i, Section 4)
   MUT_DT   op u32 | cfg CFG_DT
 """
@@ -92,6 +95,12 @@ class GraphBuilder:
     def __init__(self):
         self.ops = []     # (ndim, par_mask, type, extent[4], flops)
         self.edges = []   # (src, dst, [map per producer dim])
+        self.group_of = {}   # op -> label of the parameters it shares with other ops (unrolled steps of a layer)
+
+    def shares(self, op, label):
+        """op uses the parameters named `label` (every op with that label uses the same ones)."""
+        self.group_of[op] = label
+        return op
 
     def op(self, typ, extent, par_dims, flops):
         extent = list(extent)
@@ -311,7 +320,7 @@ def graph_resnet101(batch=64):
     return g.finish()
 
 
-def graph_nmt(batch=64, hidden=1024, steps=40, vocab=32768):
+def graph_nmt(batch=64, hidden=1024, steps=40, vocab=32768, with_groups=False):
     """configs[4]: NMT-shaped graph: 2-layer LSTM encoder and decoder unrolled `steps`
     times, attention over the stacked encoder states at every decoder step, output
     projection and softmax over the vocabulary.  Tensors are (sample, channel); the
@@ -325,12 +334,13 @@ def graph_nmt(batch=64, hidden=1024, steps=40, vocab=32768):
         g.edge(src, o, [ident(0)] + [ALL] * (len(ext) - 1))
         return o
 
-    def lstm_cell(x, h_prev, c_prev):
-        mx = matmul(x, 4 * H)
+    def lstm_cell(x, h_prev, c_prev, tag=None):
+        mx = g.shares(matmul(x, 4 * H), (tag, "x"))
         if h_prev is not None:
             mh = matmul(h_prev, 4 * H)
         else:   # first step: the recurrent product has no tensor input
             mh = g.op(T_FC, (N, 4 * H), (0, 1), 2 * N * H * 4 * H)
+        g.shares(mh, (tag, "h"))
         s = g.elementwise([mx, mh])
         gates = []
         for k in range(4):
@@ -345,15 +355,15 @@ def graph_nmt(batch=64, hidden=1024, steps=40, vocab=32768):
         h = g.elementwise([go, tc])
         return h, c
 
-    def embed():
-        return g.op(T_EMBED, (N, H), (0, 1), N * H)
+    def embed(tag=None):
+        return g.shares(g.op(T_EMBED, (N, H), (0, 1), N * H), (tag, "embed"))
 
     enc_state = [(None, None), (None, None)]
     enc_top = []
     for _ in range(steps):
-        x = embed()
+        x = embed("enc")
         for layer in range(2):
-            h, c = lstm_cell(x, *enc_state[layer])
+            h, c = lstm_cell(x, *enc_state[layer], tag=("enc", layer))
             enc_state[layer] = (h, c)
             x = h
         enc_top.append(x)
@@ -363,9 +373,9 @@ def graph_nmt(batch=64, hidden=1024, steps=40, vocab=32768):
         g.edge(h, stack, [ident(0), ident(2)])
     dec_state = list(enc_state)
     for _ in range(steps):
-        x = embed()
+        x = embed("dec")
         for layer in range(2):
-            h, c = lstm_cell(x, *dec_state[layer])
+            h, c = lstm_cell(x, *dec_state[layer], tag=("dec", layer))
             dec_state[layer] = (h, c)
             x = h
         score = g.op(T_ATTN, (N, steps), (0,), 2 * N * steps * H)
@@ -376,10 +386,12 @@ def graph_nmt(batch=64, hidden=1024, steps=40, vocab=32768):
         g.edge(prob, ctx, [ident(0), ALL])
         g.edge(stack, ctx, [ident(0), ALL, ident(1)])
         cat = g.concat([ctx, x], axis=1)
-        lin = matmul(cat, H)
+        lin = g.shares(matmul(cat, H), ("dec", "attention-out"))
         th = g.elementwise([lin])
-        out = matmul(th, vocab)
+        out = g.shares(matmul(th, vocab), ("dec", "vocabulary"))
         g.softmax(out)
+    if with_groups:
+        return g.finish() + (dict(g.group_of),)
     return g.finish()
 
 
@@ -585,6 +597,62 @@ def param_table(ops, flops, bytes_per_param=4):
             pb[i] = min(n_params * bytes_per_param, 2 ** 32 - 1)
             pd[i] = 2
     return pb, pd
+
+
+def training_graph(ops, edges, flops, groups=None, backward_cost=2):
+    """The graph of a whole training iteration, from a forward graph: every forward op i gets a backward op
+    i' (same tensor shape, same parallelizable dims, `backward_cost` times the forward FLOPs), created in reverse
+    order behind the forward ops (i' = 2n - 1 - i).  Edges: the forward edges; i -> i' (the backward computation
+    needs what the forward one kept: one-to-one); and for every forward edge p -> i the CONTRIBUTING edge i' -> p'
+    with the forward edge's maps (the part of i' that belongs to an output part of i produces gradient for exactly
+    the input range that part read).  An operation is one thing to the strategy (Section 4): i' takes the
+    configuration of i (`leader`).  `groups`: {forward op: label}; ops with the same label share their parameters:
+    they all take the configuration of the first of them, and the parameters are synchronised once, after the
+    backward op that runs last (that of the first forward op).  Parameters (param_table's model) sit on the
+    backward op of every convolution / matrix product that owns some, or on the group's last backward op.
+    Returns (ops, edges, flops, leader [2n] uint32, (param_bytes [2n] uint32, param_dims [2n] uint8))."""
+    n = len(ops)
+    bwd = lambda i: 2 * n - 1 - i
+    ops2 = np.zeros(2 * n, OP_DT)
+    ops2[:n] = ops
+    flops2 = np.zeros(2 * n, np.int64)
+    flops2[:n] = flops
+    leader = np.arange(2 * n, dtype=np.uint32)
+    first_of = {}
+    for i in range(n):
+        ops2[bwd(i)] = ops[i]
+        flops2[bwd(i)] = backward_cost * int(flops[i])
+        lead = i
+        if groups and i in groups:
+            lead = first_of.setdefault(groups[i], i)
+            if tuple(ops[lead]["extent"]) != tuple(ops[i]["extent"]) or ops[lead]["par_mask"] != ops[i]["par_mask"]:
+                lead = i                         # (shares parameters but not its shape: keeps its own configuration)
+        leader[i] = leader[bwd(i)] = lead
+    rows = []
+    for e in edges:
+        rows.append((int(e["src_op"]), int(e["dst_op"]), e["map"].copy()))
+        m = e["map"].copy()
+        m["pad"] = 1
+        rows.append((bwd(int(e["dst_op"])), bwd(int(e["src_op"])), m))
+    for i in range(n):
+        m = np.zeros(4, DIMMAP_DT)
+        for d in range(4):
+            m[d] = (d, 0, 1, 0, 0) if d < ops[i]["ndim"] else (-1, 0, 1, 0, 0)
+        rows.append((i, bwd(i), m))
+    rows.sort(key=lambda r: (r[0], r[1]))
+    edges2 = np.zeros(len(rows), EDGE_DT)
+    for k, (a, b, m) in enumerate(rows):
+        assert a < b
+        edges2[k]["src_op"], edges2[k]["dst_op"], edges2[k]["map"] = a, b, m
+    pb_f, pd_f = param_table(ops, flops)
+    pb = np.zeros(2 * n, "<u4")
+    pd = np.zeros(2 * n, np.uint8)
+    for i in range(n):
+        if pb_f[i]:
+            if groups and i in groups and leader[i] != i:
+                continue                         # the group's parameters are synchronised by its first op's backward op
+            pb[bwd(i)], pd[bwd(i)] = pb_f[i], pd_f[i]
+    return ops2, edges2, flops2, leader, (pb, pd)
 
 
 def data_parallel_strategy(ops, n_dev, max_parts=MAX_PARTS):

@@ -23,12 +23,13 @@ def graph_from_golden(g):
     edges = np.zeros(len(g["edges"]), W.EDGE_DT)
     for k, e in enumerate(g["edges"]):
         edges[k]["src_op"], edges[k]["dst_op"] = e["src"], e["dst"]
+        kind = 1 if e.get("contributes") else 0      # a gradient edge: the producer contributes to the consumer's tensor
         for d in range(4):
             if d < len(e["map"]):
                 c, st, a, b = e["map"][d]
-                edges[k]["map"][d] = (c, 0, st, a, b)
+                edges[k]["map"][d] = (c, kind, st, a, b)
             else:
-                edges[k]["map"][d] = (-1, 0, 1, 0, 0)
+                edges[k]["map"][d] = (-1, kind, 1, 0, 0)
     cost = np.full((len(ops), W.MAX_PARTS), 1, "<u4")
     for i, row in g["cost"].items():
         for p, v in row.items():

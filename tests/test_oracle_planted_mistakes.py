@@ -17,7 +17,7 @@ import oracle
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "ff_oracle.cpp")
 PIN_FILES = ["test_oracle_builder.py", "test_oracle_simulator.py", "test_oracle_links_devmap.py",
-             "test_oracle_paramsync.py", "test_oracle_tuplecost.py"]
+             "test_oracle_paramsync.py", "test_oracle_tuplecost.py", "test_oracle_training_graph.py"]
 
 # (name, text in the source, replacement); every `text` occurs exactly once
 MISTAKES = [
@@ -31,16 +31,16 @@ MISTAKES = [
      "for (int d = 3; d >= 0; d--) { idx[d] = rem % c.deg[d]; rem /= c.deg[d]; }\n    for (int d = 0; d < 4; d++) {\n        int64_t E",
      "for (int d = 0; d < 4; d++) { idx[d] = rem % c.deg[d]; rem /= c.deg[d]; }\n    for (int d = 0; d < 4; d++) {\n        int64_t E"),
     ("window offsets a and b swapped",
-     "need_lo = cb.lo[m.src_dim] * (int64_t)m.stride + m.a;\n            need_hi = (cb.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;",
-     "need_lo = cb.lo[m.src_dim] * (int64_t)m.stride + m.b;\n            need_hi = (cb.hi[m.src_dim] - 1) * (int64_t)m.stride + m.a + 1;"),
+     "need_lo = driving.lo[m.src_dim] * (int64_t)m.stride + m.a;\n            need_hi = (driving.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;",
+     "need_lo = driving.lo[m.src_dim] * (int64_t)m.stride + m.b;\n            need_hi = (driving.hi[m.src_dim] - 1) * (int64_t)m.stride + m.a + 1;"),
     ("window end without its + 1",
      "(int64_t)m.stride + m.b + 1;", "(int64_t)m.stride + m.b;"),
     ("window stride dropped",
-     "need_lo = cb.lo[m.src_dim] * (int64_t)m.stride + m.a;\n            need_hi = (cb.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;",
-     "need_lo = cb.lo[m.src_dim] + m.a;\n            need_hi = (cb.hi[m.src_dim] - 1) + m.b + 1;"),
+     "need_lo = driving.lo[m.src_dim] * (int64_t)m.stride + m.a;\n            need_hi = (driving.hi[m.src_dim] - 1) * (int64_t)m.stride + m.b + 1;",
+     "need_lo = driving.lo[m.src_dim] + m.a;\n            need_hi = (driving.hi[m.src_dim] - 1) + m.b + 1;"),
     ("needed range not clamped to the producer's extent, shared volume counted outside the producer part",
-     "int64_t lo = std::max(need_lo, pb.lo[d]), hi = std::min(need_hi, pb.hi[d]);",
-     "int64_t lo = std::max(need_lo, pb.lo[d]), hi = need_hi;"),
+     "int64_t lo = std::max(need_lo, owning.lo[d]), hi = std::min(need_hi, owning.hi[d]);",
+     "int64_t lo = std::max(need_lo, owning.lo[d]), hi = need_hi;"),
     ("pairs enumerated consumer part first",
      "for (uint32_t kp = 0; kp < np[i]; kp++) {\n                Box pb = part_box(ops[i], cfg[i], kp);\n                for (uint32_t kc = 0; kc < np[j]; kc++) {\n                    Box cb = part_box(ops[j], cfg[j], kc);",
      "for (uint32_t kc = 0; kc < np[j]; kc++) {\n                Box cb = part_box(ops[j], cfg[j], kc);\n                for (uint32_t kp = 0; kp < np[i]; kp++) {\n                    Box pb = part_box(ops[i], cfg[i], kp);"),
@@ -96,6 +96,14 @@ MISTAKES = [
      "if (!same_node && x.node_bw) {", "if (false && x.node_bw) {"),
     ("node link table used inside a node as well",
      "if (!same_node && x.node_bw) {", "if (x.node_bw) {"),
+    ("a contributing edge treated as a reading edge",
+     "const bool contributes = e.map[0].kind != 0;", "const bool contributes = false;"),
+    ("a contributing edge with the boxes of a reading edge",
+     "const Box& owning = contributes ? cb : pb;", "const Box& owning = pb;"),
+    ("a contributing edge whose ranges are taken in the producer's tensor",
+     "const Op& space = contributes ? cons : prod;", "const Op& space = prod;"),
+    ("tied configurations ignored",
+     "tied[i] = cfg[x.leader[i]];", "tied[i] = cfg[i];"),
     ("explicit device map ignored",
      "dev = x.devmap[(size_t)i * MAX_PARTS + k];", "dev = dev;"),
     ("tuple cost list: first entry of the op instead of the matching one",
