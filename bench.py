@@ -551,6 +551,49 @@ def main():
                     ref[name]["bit_exact_on_sample"] = bool(np.array_equal(out_r.cpu().numpy().view("<u8")[:64], want))
                 sim_r.close()
             line["refinements_on_configs1"] = ref
+        # whole training iterations: forward and backward ops, gradient edges, tied configurations, parameter traffic
+        train = []
+        for cid in (1, 2):
+            if cid not in results:
+                continue
+            w_t = results[cid][2]
+            t_ops, t_edges, t_flops, leader, t_params = W.training_graph(w_t.ops, w_t.edges, w_t.flops)
+            t_cost = np.ascontiguousarray(W.cost_table(cid, t_flops, w_t.seed)[:, :w_t.max_parts])
+            sim_t = binding.Simulator(t_ops, t_edges, w_t.machine, t_cost, params=t_params, ties=leader)
+            n_t = w_t.n_candidates
+            cfgs_t = W.strategies(t_ops, n_t, w_t.seed, w_t.machine.n_devices, w_t.max_parts, w_t.choices)
+            d_t = sim_t.upload_strategies(cfgs_t)
+            k_ms, w_ms, out_t = time_batches(sim_t, d_t, n_t, 5, 1)
+            t = {"workload": f"configs[{cid}] {w_t.name}: training iteration ({len(t_ops)} ops, {len(t_edges)} edges, "
+                             "backward ops tied to their forward ops, gradients of conv / fc parameters synchronised)",
+                 "B": n_t, "kernel_ms": k_ms, "strategies_per_s": n_t / (w_ms * 1e-3),
+                 "kernel": binding.ff_sim_batch_kernel_name(sim_t.handle, n_t)}
+            if not args.no_cpu:
+                import oracle
+                idx = np.linspace(0, n_t - 1, 64).astype(np.int64)
+                want = oracle.simulate_batch(t_ops, t_edges, w_t.machine, t_cost, cfgs_t[idx], n_threads=threads, ties=leader, params=t_params)
+                t["bit_exact_on_sample"] = bool(np.array_equal(out_t.cpu().numpy().view("<u8")[idx], want))
+            if cid == 1:
+                from paper_1807_05358_amd import search as driver
+                C, n_steps = 256, 512
+                cfg0 = driver.starting_strategies(t_ops, w_t.machine, w_t.max_parts, w_t.choices, C, 1807)
+                cfg0[:C // 2] = W.data_parallel_strategy(t_ops, w_t.machine.n_devices, w_t.max_parts)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                res = driver.find_strategy(sim_t, t_ops, w_t.machine, w_t.max_parts, w_t.choices, steps=n_steps, accept_scale=0.005,
+                                           seed=1807, start=cfg0)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                t["search"] = {"chains": C, "steps": n_steps, "wall_s": dt, "proposals_per_s": C * n_steps / dt,
+                               "data_parallel_ns": int(res.start_ns[0]), "best_found_ns": res.best_ns,
+                               "speedup_over_data_parallel": int(res.start_ns[0]) / res.best_ns,
+                               "best_degrees_per_forward_op": res.best["deg"][:len(w_t.ops)].tolist()}
+                if not args.no_cpu:
+                    t["search"]["best_confirmed_by_oracle"] = bool(int(oracle.simulate_batch(
+                        t_ops, t_edges, w_t.machine, t_cost, res.best[None], ties=leader, params=t_params)[0]) == res.best_ns)
+            sim_t.close()
+            train.append(t)
+        line["training_iteration"] = train
         # neighbour sweep (local-optimality check): all single-op neighbours of one strategy
         if 1 in results:
             _, sim_n, w_n, cfgs_n = results[1]

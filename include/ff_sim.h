@@ -62,10 +62,18 @@ enum {
  * [lo*stride + a, (hi-1)*stride + b + 1), clamped to [0, extent).  stride >= 1. */
 typedef struct {
     int8_t src_dim;
-    uint8_t reserved;
+    uint8_t kind;   /* 0: the consumer reads (above); 1: the producer contributes (below); the same on all four maps of an edge */
     uint16_t stride;
     int32_t a, b;
 } ff_dimmap_t;
+/* kind = 1 marks a CONTRIBUTING edge: the gradient that flows back along a forward edge in a training
+ * iteration (Sections 2 and 8 are about training iterations; Section 5.1's construction is stated for
+ * tensor edges in general).  It is the forward edge with the roles exchanged: map[] is indexed by the
+ * CONSUMER's dims, src_dim names a PRODUCER dim, and a producer part covering [lo, hi) along src_dim
+ * contributes to [lo*stride + a, (hi-1)*stride + b + 1) of the consumer's dim, clamped to its extent.  A
+ * producer part and a consumer part share the elements of that range that lie in the consumer part's
+ * box.  With the backward ops cut like their forward ops, the pairs and sizes are the forward edge's,
+ * transposed. */
 
 /* One operation o_i of the operator graph (Section 3.1): the shape of its single output
  * tensor and which output dims may be partitioned (Table 1; bit d of par_mask). */
@@ -195,6 +203,17 @@ typedef struct {
     const uint32_t* lat_ns;
 } ff_nodelinks_t;
 int ff_sim_set_node_links(ff_sim_t* sim, const ff_nodelinks_t* links);
+
+/* Tied configurations (Section 4 gives every OPERATION one configuration; in the graph of a training
+ * iteration an operation appears as several ops: its forward and its backward computation, or the
+ * unrolled steps of a recurrent layer that share parameters).  leader[i] = the op whose entry of the
+ * strategy op i takes (leader[leader[i]] == leader[i], else FF_EINVAL); entries of ops that lead
+ * nobody are not read; a strategy is invalid unless the configuration is valid for every op that takes
+ * it.  HOST pointer [n_ops], deep-copied; NULL: every op takes its own entry.  Waits for the device;
+ * invalidates chain sets created before, as ff_sim_set_links does.  With ties a mutation changes several
+ * ops at once: ff_sim_delta, ff_sim_delta_try, ff_sim_search and the neighbour sweeps stay exact but
+ * simulate every step from time 0 (mutations of ops that lead nobody change nothing). */
+int ff_sim_set_ties(ff_sim_t* sim, const uint32_t* leader);
 
 /* Parameter synchronisation (Section 8 compares strategies by the data they move to keep the
  * replicas of an op's parameters in step; Section 5.1 has no construction for it).  Reading

@@ -34,7 +34,7 @@ class ff_costtable_t(C.Structure):
     _fields_ = [("n_ops", C.c_uint32), ("n_cols", C.c_uint32), ("ns", C.c_void_p)]
 
 
-EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_node_links", "ff_sim_set_params",
+EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_node_links", "ff_sim_set_ties", "ff_sim_set_params",
            "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
            "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search", "ff_sim_accept_table",
@@ -100,6 +100,8 @@ def lib():
         L.ff_sim_set_links.argtypes = [vp, vp]
         L.ff_sim_set_node_links.restype = C.c_int
         L.ff_sim_set_node_links.argtypes = [vp, vp]
+        L.ff_sim_set_ties.restype = C.c_int
+        L.ff_sim_set_ties.argtypes = [vp, vp]
         L.ff_sim_set_params.restype = C.c_int
         L.ff_sim_set_params.argtypes = [vp, vp, vp]
         L.ff_sim_chains_create.restype = C.c_int
@@ -201,6 +203,17 @@ def ff_sim_set_node_links(sim, n_nodes=0, Bpns=None, lat_ns=None):
         raise ValueError("node link tables must be [n_nodes][n_nodes]")
     lt = ff_linktable_t(n_nodes, Bpns.ctypes.data, None if lat is None else lat.ctypes.data)   # same layout as ff_nodelinks_t
     _check(lib().ff_sim_set_node_links(sim, C.byref(lt)), "ff_sim_set_node_links")
+
+
+def ff_sim_set_ties(sim, n_ops, leader=None):
+    """leader [n_ops] uint32: op i takes the configuration of op leader[i]; None: every op its own."""
+    if leader is None:
+        _check(lib().ff_sim_set_ties(sim, None), "ff_sim_set_ties")
+        return
+    t = np.ascontiguousarray(leader, "<u4")
+    if t.shape != (n_ops,):
+        raise ValueError("one leader per op")
+    _check(lib().ff_sim_set_ties(sim, t.ctypes.data), "ff_sim_set_ties")
 
 
 def ff_sim_set_params(sim, n_ops, param_bytes=None, param_dims=None):
@@ -318,7 +331,7 @@ def ff_sim_batch_kernel_name(sim, B):
 class Simulator:
     """owns a handle, its workspace and result buffers (all torch-allocated)."""
 
-    def __init__(self, ops, edges, machine, cost, params=None):
+    def __init__(self, ops, edges, machine, cost, params=None, ties=None):
         """cost: [n_ops][n_cols] table by number of parts, or a triple (tuple_ptr, tuples, ns)
         keyed by the degree tuple.  params: (param_bytes, param_dims) per op, to simulate the
         parameter-synchronisation transfers as well."""
@@ -340,6 +353,8 @@ class Simulator:
             ff_sim_set_node_links(self.handle, machine.n_nodes, machine.node_Bpns, lat)
         if params is not None:
             ff_sim_set_params(self.handle, self.n_ops, params[0], params[1])
+        if ties is not None:
+            ff_sim_set_ties(self.handle, self.n_ops, ties)
         self._ws = None
         self._stats = None
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 HOST_UNIT = "ffsim.hip"
 KERNEL_UNITS = ["ffsim_k_batch.hip", "ffsim_k_chain.hip", "ffsim_k_try.hip"]   # each compiled per (EXT, GPN)
-VARIANTS = [(0, 4), (0, 0), (1, 4), (1, 0)]
+VARIANTS = [(0, 4), (0, 0), (1, 4), (1, 0), (2, 4), (2, 0)]
 UNITS = [HOST_UNIT] + KERNEL_UNITS
 HEADERS = ["ffsim_select.h", "ffsim_sweep.h", "ffsim_kernels.h", "ffsim_chain.h", "ffsim_events.h", "ffsim_strategy.h",
            "ffsim_device.h"]

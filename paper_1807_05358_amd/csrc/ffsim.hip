@@ -45,6 +45,8 @@ struct ff_sim {
     uint32_t links_gen = 0;       // counts ff_sim_set_links / ff_sim_set_params calls (a chain set's stored timelines depend on both)
     std::vector<DOp> h_ops;       // host copy of the op records (ff_sim_set_params rewrites two fields)
     std::vector<uint32_t> intra_bw, intra_lat, node_bw, node_lat;   // the link tables in force (empty: the machine's single figures)
+    std::vector<uint32_t> ties;   // per op the op whose configuration it takes (empty: its own)
+    bool has_contributing = false;   // the graph has contributing (gradient) edges: served by the kernels with the refinements
     bool lds_words = false;       // task words of a candidate fit in LDS (small graphs)
     size_t slot_bytes = 0;        // HBM scratch per resident wavefront (also used by chains)
     // the batch kernel may keep the per-edge set-up of a candidate (all extents must fit 16 bits):
@@ -107,25 +109,30 @@ static_assert(CHAIN_SNAPSHOTS <= MAX_SNAPSHOTS, "one bit per snapshot in ChainMe
 static KernelChoice choice(const ff_sim* s, bool cache) {
     return KernelChoice{s->wide, s->lds_words, s->d_stats != nullptr, cache, s->dev.n_ops, s->dev.n_groups, s->dev.max_parts};
 }
-// ext: the launch uses the link table or explicit devices.  Machines with four GPUs per node (all
-// benchmark configurations) have kernels compiled for that node size.
-static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, bool ext = false) {
+// ext: which refinements the launch needs (0 none; 1 link tables, explicit devices, parameter traffic; 2 also
+// contributing edges or tied configurations).  Machines with four GPUs per node (all benchmark configurations)
+// have kernels compiled for that node size.
+static int ext_level(const ff_sim* s, bool devmaps = false) {
+    if (s->dev.ties || s->has_contributing) return 2;
+    return (s->dev.link_table || s->dev.node_table || s->dev.sync || devmaps) ? 1 : 0;
+}
+static batch_kernel_t batch_kernel(const ff_sim* s, bool cached, int ext = 0) {
     const KernelChoice k = choice(s, cached);
-    if (s->dev.gpus_per_node == 4) return ext ? batch_kernels<true, 4>(k) : batch_kernels<false, 4>(k);
-    return ext ? batch_kernels<true, 0>(k) : batch_kernels<false, 0>(k);
+    if (s->dev.gpus_per_node == 4) return ext == 2 ? batch_kernels<2, 4>(k) : (ext == 1 ? batch_kernels<1, 4>(k) : batch_kernels<0, 4>(k));
+    return ext == 2 ? batch_kernels<2, 0>(k) : (ext == 1 ? batch_kernels<1, 0>(k) : batch_kernels<0, 0>(k));
 }
 // chains keep the per-edge set-up in their own memory whenever the extents allow it
 static chain_kernel_t chain_kernel(const ff_sim* s) {
     const KernelChoice k = choice(s, s->chain_cache);
-    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync;
-    if (s->dev.gpus_per_node == 4) return ext ? chain_kernels<true, 4>(k) : chain_kernels<false, 4>(k);
-    return ext ? chain_kernels<true, 0>(k) : chain_kernels<false, 0>(k);
+    const int ext = ext_level(s);
+    if (s->dev.gpus_per_node == 4) return ext == 2 ? chain_kernels<2, 4>(k) : (ext == 1 ? chain_kernels<1, 4>(k) : chain_kernels<0, 4>(k));
+    return ext == 2 ? chain_kernels<2, 0>(k) : (ext == 1 ? chain_kernels<1, 0>(k) : chain_kernels<0, 0>(k));
 }
 static try_kernel_t try_kernel(const ff_sim* s) {
     const KernelChoice k = choice(s, s->chain_cache);
-    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync;
-    if (s->dev.gpus_per_node == 4) return ext ? try_kernels<true, 4>(k) : try_kernels<false, 4>(k);
-    return ext ? try_kernels<true, 0>(k) : try_kernels<false, 0>(k);
+    const int ext = ext_level(s);
+    if (s->dev.gpus_per_node == 4) return ext == 2 ? try_kernels<2, 4>(k) : (ext == 1 ? try_kernels<1, 4>(k) : try_kernels<0, 4>(k));
+    return ext == 2 ? try_kernels<2, 0>(k) : (ext == 1 ? try_kernels<1, 0>(k) : try_kernels<0, 0>(k));
 }
 
 // A launch with more than 64 KB of dynamic LDS (gfx950 allows a workgroup up to 160 KB) has to be
@@ -161,28 +168,29 @@ const char* ff_sim_strerror(int code) {
 // number of parts.  n_cols == 0: costs keyed by the degree tuple, packed as ptr[n_ops+1], then the
 // tuples of all ops, then their exeTimes.
 // the constants buffer of the kernels (layout: LINK_TABLE_AT in ffsim_device.h)
-// intra: per ordered pair of local GPUs (G*G entries) or empty; inter: per ordered pair of nodes (N*N) or empty;
-// an area that is not given is filled with the machine's single figures (it is then not read)
+// intra: per ordered pair of local GPUs (G*G entries) or empty; inter: per ordered pair of nodes (N*N) or empty
+// (an area that is not given is filled with the machine's single figures; it is then not read); ties: per op the
+// op whose configuration it takes, or empty.  Layout: ffsim_device.h.
 static std::vector<uint32_t> constants_image(const ff_machine_t& m, const std::vector<uint32_t>& intra_bw, const std::vector<uint32_t>& intra_lat,
-                                             const std::vector<uint32_t>& node_bw, const std::vector<uint32_t>& node_lat) {
+                                             const std::vector<uint32_t>& node_bw, const std::vector<uint32_t>& node_lat,
+                                             const std::vector<uint32_t>& ties) {
     const size_t G2 = (size_t)m.gpus_per_node * m.gpus_per_node, N2 = (size_t)m.n_nodes * m.n_nodes;
-    const bool any = !intra_bw.empty() || !node_bw.empty();
-    std::vector<uint32_t> c(LINK_TABLE_AT + 4 * (any ? G2 + N2 : 1), 0);
+    const size_t tie_at = tie_table_at(m.gpus_per_node, m.n_nodes);
+    std::vector<uint32_t> c(tie_at + std::max<size_t>(ties.size(), 1), 0);
     for (uint32_t d = 2; d <= 64; d++) c[d] = magic_plus1(d);
-    if (any) {
-        for (size_t p = 0; p < G2; p++) {
-            const uint32_t bw = intra_bw.empty() ? m.intra_Bpns : intra_bw[p];
-            c[LINK_TABLE_AT + 4 * p + 0] = bw;
-            c[LINK_TABLE_AT + 4 * p + 1] = magic_floor(bw);
-            c[LINK_TABLE_AT + 4 * p + 2] = intra_bw.empty() ? m.intra_lat_ns : intra_lat[p];
-        }
-        for (size_t p = 0; p < N2; p++) {
-            const uint32_t bw = node_bw.empty() ? m.inter_Bpns : node_bw[p];
-            c[LINK_TABLE_AT + 4 * (G2 + p) + 0] = bw;
-            c[LINK_TABLE_AT + 4 * (G2 + p) + 1] = magic_floor(bw);
-            c[LINK_TABLE_AT + 4 * (G2 + p) + 2] = node_bw.empty() ? m.inter_lat_ns : node_lat[p];
-        }
+    for (size_t p = 0; p < G2; p++) {
+        const uint32_t bw = intra_bw.empty() ? m.intra_Bpns : intra_bw[p];
+        c[LINK_TABLE_AT + 4 * p + 0] = bw;
+        c[LINK_TABLE_AT + 4 * p + 1] = magic_floor(bw);
+        c[LINK_TABLE_AT + 4 * p + 2] = intra_bw.empty() ? m.intra_lat_ns : intra_lat[p];
     }
+    for (size_t p = 0; p < N2; p++) {
+        const uint32_t bw = node_bw.empty() ? m.inter_Bpns : node_bw[p];
+        c[LINK_TABLE_AT + 4 * (G2 + p) + 0] = bw;
+        c[LINK_TABLE_AT + 4 * (G2 + p) + 1] = magic_floor(bw);
+        c[LINK_TABLE_AT + 4 * (G2 + p) + 2] = node_bw.empty() ? m.inter_lat_ns : node_lat[p];
+    }
+    std::copy(ties.begin(), ties.end(), c.begin() + tie_at);
     return c;
 }
 
@@ -226,6 +234,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
 
     std::vector<DEdge> edges(g->n_edges);
     std::vector<uint32_t> in_count(g->n_ops, 0);
+    bool has_contributing = false;
     for (uint32_t k = 0; k < g->n_edges; k++) {
         const ff_edge_t& e = g->edges[k];
         if (e.src_op >= g->n_ops || e.dst_op >= g->n_ops || e.src_op >= e.dst_op) return FF_EINVAL;
@@ -236,18 +245,25 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         DEdge& de = edges[k];
         de.src = e.src_op;
         de.dst = e.dst_op;
-        de.src_ndim = ops[e.src_op].ndim;
+        // a contributing edge exchanges the roles: the maps belong to the consumer's dims and name producer dims
+        const bool contributes = e.map[0].kind != 0;
+        for (int d = 0; d < 4; d++)
+            if (e.map[d].kind > 1 || (e.map[d].kind != 0) != contributes) return FF_EINVAL;
+        has_contributing = has_contributing || contributes;
+        const uint32_t space_op = contributes ? e.dst_op : e.src_op, driving_op = contributes ? e.src_op : e.dst_op;
+        de.src_ndim = ops[space_op].ndim;
         de.eid = k;
+        de.kind = contributes ? 1u : 0u;
+        de.unused[0] = de.unused[1] = de.unused[2] = 0;
         for (int d = 0; d < 4; d++) {
-            de.src_extent[d] = ops[e.src_op].extent[d];
-            de.dst_extent[d] = ops[e.dst_op].extent[d];
+            de.src_extent[d] = ops[space_op].extent[d];
             DMap& dm = de.map[d];
             const ff_dimmap_t& sm = e.map[d];
-            if (d >= g->ops[e.src_op].ndim || sm.src_dim < 0) { dm = DMap{-1, 1, 0, 0, 1}; continue; }
-            if (sm.src_dim >= g->ops[e.dst_op].ndim || sm.stride < 1) return FF_EINVAL;
+            if (d >= g->ops[space_op].ndim || sm.src_dim < 0) { dm = DMap{-1, 1, 0, 0, 1}; continue; }
+            if (sm.src_dim >= g->ops[driving_op].ndim || sm.stride < 1) return FF_EINVAL;
             if (sm.stride > FF_MAX_MAP_STRIDE || sm.a > FF_MAX_MAP_OFFSET || sm.a < -FF_MAX_MAP_OFFSET ||
                 sm.b > FF_MAX_MAP_OFFSET || sm.b < -FF_MAX_MAP_OFFSET) return FF_ERANGE;
-            dm = DMap{sm.src_dim, sm.stride, sm.a, sm.b, ops[e.dst_op].extent[sm.src_dim]};
+            dm = DMap{sm.src_dim, sm.stride, sm.a, sm.b, ops[driving_op].extent[sm.src_dim]};
         }
         in_count[e.dst_op]++;
     }
@@ -273,7 +289,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         }
         for (uint32_t k = 0; k < g->n_edges; k++) in_edges[ops[edges[k].dst].in_end++] = edges[k];
     }
-    std::vector<uint32_t> magic = constants_image(*m, {}, {}, {}, {});
+    std::vector<uint32_t> magic = constants_image(*m, {}, {}, {}, {}, {});
 
     ff_sim* s = new (std::nothrow) ff_sim;
     if (!s) return FF_ENOMEM;
@@ -282,6 +298,7 @@ static int create_impl(const ff_opgraph_t* g, const ff_machine_t* m, std::vector
         (rc = upload(cost, &s->d_cost)) || (rc = upload(magic, &s->d_magic))) { release(s); return rc; }
 
     s->h_ops = ops;
+    s->has_contributing = has_contributing;
     SimDev& S = s->dev;
     S.n_ops = g->n_ops; S.n_edges = g->n_edges; S.n_cols = n_cols;
     S.max_parts = n_cols ? std::min<uint32_t>(FF_MAX_PARTS, n_cols) : FF_MAX_PARTS;
@@ -404,7 +421,7 @@ int ff_sim_set_params(ff_sim_t* s, const uint32_t* param_bytes, const uint8_t* p
     return FF_OK;
 }
 
-// uploads the constants for the link tables in force and re-derives what depends on them
+// uploads the constants for the link tables and ties in force and re-derives what depends on them
 static int apply_link_tables(ff_sim_t* s) {
     const ff_machine_t& m = s->mach;
     const uint32_t G = m.gpus_per_node, N = m.n_nodes;
@@ -419,7 +436,7 @@ static int apply_link_tables(ff_sim_t* s) {
         for (uint32_t a = 0; a < N; a++)
             for (uint32_t b = 0; b < N; b++)
                 if (a != b) { bw_min = std::min(bw_min, s->node_bw[a * N + b]); lat_max = std::max(lat_max, s->node_lat[a * N + b]); }
-    std::vector<uint32_t> image = constants_image(m, s->intra_bw, s->intra_lat, s->node_bw, s->node_lat);
+    std::vector<uint32_t> image = constants_image(m, s->intra_bw, s->intra_lat, s->node_bw, s->node_lat, s->ties);
     uint32_t* d_new = nullptr;
     int rc = upload(image, &d_new);
     if (rc) return rc;
@@ -428,6 +445,7 @@ static int apply_link_tables(ff_sim_t* s) {
     s->d_magic = d_new;
     s->dev.link_table = s->intra_bw.empty() ? 0u : 1u;
     s->dev.node_table = s->node_bw.empty() ? 0u : 1u;
+    s->dev.ties = s->ties.empty() ? 0u : 1u;
     s->links_gen++;
     s->wide = needs_wide(s->big_tensors, bw_min, lat_max, G);
     return FF_OK;
@@ -450,6 +468,19 @@ int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
     }
     s->intra_bw.swap(bw);
     s->intra_lat.swap(lat);
+    return apply_link_tables(s);
+}
+
+int ff_sim_set_ties(ff_sim_t* s, const uint32_t* leader) {
+    if (!s) return FF_EINVAL;
+    std::vector<uint32_t> t;
+    if (leader) {
+        const uint32_t n = s->dev.n_ops;
+        t.assign(leader, leader + n);
+        for (uint32_t i = 0; i < n; i++)
+            if (t[i] >= n || t[t[i]] != t[i]) return FF_EINVAL;      // a leader leads itself
+    }
+    s->ties.swap(t);
     return apply_link_tables(s);
 }
 
@@ -506,7 +537,7 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
                       void* hip_stream) {
     if (!s || (B && (!d_strategies || !d_out_ns))) return FF_EINVAL;
     if (B == 0) return FF_OK;
-    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync || d_devmaps;
+    const int ext = ext_level(s, d_devmaps != nullptr);
     const bool cached = batch_cached(s, B);
     const uint32_t slots = batch_slots(s, B);
     if (!s->lds_words && (!s->ws || s->ws_bytes < (size_t)slots * s->batch_slot_bytes)) return FF_EWORKSPACE;
@@ -521,10 +552,10 @@ static int batch_impl(ff_sim_t* s, const ff_opcfg_t* d_strategies, const uint16_
 
 int ff_sim_batch_kernel_name(const ff_sim_t* s, uint32_t B, char* buf, size_t len) {
     if (!s || !buf || len < 1) return FF_EINVAL;
-    const bool ext = s->dev.link_table || s->dev.node_table || s->dev.sync;
+    const int ext = ext_level(s);
     const KernelChoice k = choice(s, batch_cached(s, B));
-    const int n = snprintf(buf, len, "k_sim_batch<%s, %s, %s, %d, %s, %s, %d>", k.wide ? "true" : "false", k.lds_words ? "true" : "false",
-                           k.stats ? "true" : "false", batch_queue_shape(k), k.cache ? "true" : "false", ext ? "true" : "false",
+    const int n = snprintf(buf, len, "k_sim_batch<%s, %s, %s, %d, %s, %d, %d>", k.wide ? "true" : "false", k.lds_words ? "true" : "false",
+                           k.stats ? "true" : "false", batch_queue_shape(k), k.cache ? "true" : "false", ext,
                            s->dev.gpus_per_node == 4 ? 4 : 0);
     return (n < 0 || (size_t)n >= len) ? FF_ERANGE : FF_OK;
 }

@@ -102,7 +102,7 @@ __device__ __forceinline__ uint32_t resume_point(const SimX& m, const u64* end_o
         const uint32_t digits = part_digits(co, lane, m.magic_v);
         for (uint32_t q = in_begin; q < in_end; q++) {
             const DEdge e = m.T.in_edges[q];
-            pend_old += count_inputs(e, m.cfg(e.src), co.x, digits, m.magic_v);
+            pend_old += count_inputs<SimX::kTrain>(e, m.cfg(e.src), co.x, digits, m.magic_v);
         }
     }
     if (ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
@@ -130,8 +130,8 @@ __device__ __forceinline__ void patch_state_for_op(const SimX& m, u64* words, u6
         const uint32_t j = e.dst;
         const OpCfg cj = m.cfg(j);
         const uint32_t digits = part_digits(cj, lane, m.magic_v);
-        const uint32_t was = count_inputs(e, co, cj.x, digits, m.magic_v);
-        const uint32_t is = count_inputs(e, cn, cj.x, digits, m.magic_v);
+        const uint32_t was = count_inputs<SimX::kTrain>(e, co, cj.x, digits, m.magic_v);
+        const uint32_t is = count_inputs<SimX::kTrain>(e, cn, cj.x, digits, m.magic_v);
         if (!ballot((uint32_t)lane < cj.parts && was != is)) continue;
         const u64 w = words[j * WAVE + lane];
         // a part of op j that reads op mo at all is still waiting in such a state
@@ -192,6 +192,14 @@ __device__ __forceinline__ void refresh_ecache_for_op(const SimX& m, uint32_t j)
     wave_sync();
 }
 
+// the same for every op that takes the configuration of op `lead` (tied configurations)
+template <class SimX>
+__device__ __forceinline__ void refresh_ecache_for_group(const SimX& m, uint32_t lead) {
+    if (!(SimX::kTrain && m.tie)) { refresh_ecache_for_op(m, lead); return; }
+    for (uint32_t j = 0; j < m.S.n_ops; j++)
+        if (first_u32(m.tie[j]) == lead) refresh_ecache_for_op(m, j);
+}
+
 // Makes a recorded run the chain's accepted timeline: the snapshots it wrote (first..next-1)
 // take the place of the old ones, the endTimes it wrote are copied over the old ones.
 // converged: the run stopped where it re-joined the accepted timeline, whose later snapshots and
@@ -223,8 +231,8 @@ __device__ __forceinline__ void commit_run(const ChainMem& cm, ChainMeta& meta, 
 // later results are RESULT_INVALID.  out_ns[s][c] is the time of the chain's strategy after
 // step s.
 // CACHE: the chain keeps the per-edge set-up of its current strategy (all extents fit 16 bits).
-// EXT: with the table of links inside a node.  GPN: compiled for this many GPUs per node (0 = any).
-template <bool WIDE, bool TREE, bool CACHE, bool EXT, int GPN>
+// EXT: 0 plain, 1 with the refinements of the inputs, 2 also training-iteration graphs.  GPN: compiled for this many GPUs per node (0 = any).
+template <bool WIDE, bool TREE, bool CACHE, int EXT, int GPN>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                           const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                           const uint32_t* __restrict__ magic, unsigned char* chain_mem,
@@ -262,6 +270,9 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
     Recorder rec{cm.end_try, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, meta.loc, n_snaps, 1, 0, 0};
     SimT<false, EXT, GPN> m{S, T, cfg_lds, cm.words, cm.exe_of, L, magic_v, 0, false, NO_OVERRIDE, make_uint2(0, 0), CACHE ? cm.ecache : nullptr, true};
     if (EXT) { m.links = (const uint4*)(magic + LINK_TABLE_AT); m.node_links = m.links + (size_t)S.gpus_per_node * S.gpus_per_node; }
+    if (EXT >= 2 && S.ties) m.tie = magic + tie_table_at(S.gpus_per_node, S.n_nodes);
+    // With tied configurations a mutation changes several ops at once: such steps are simulated from time 0.
+    const bool tied = EXT >= 2 && S.ties;
     m.want_sort = true;          // a later step may make the strategy a general one: the kept set-up is always complete
     u64 best = search.enabled ? first_u64(search.best_ns[c]) : 0;
     if (search.enabled && !poisoned && !meta.stale && meta.cur_ns < best) {
@@ -323,7 +334,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         } else if (!poisoned && valid) {
             // where the simulation may start (0 = time 0)
             uint32_t k = 0, pend_new = 0;
-            if (changed && !meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
+            if (changed && !meta.stale && meta.n_valid > 1 && meta.step != 0 && !tied) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
             const uint32_t capacity = n_snaps;
             // phase 1: makespan only, to fix the snapshot spacing (no snapshots yet);
             // phase 2: the recorded simulation
@@ -406,7 +417,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
                 wave_sync();
                 if (lane == 0) cfg_lds[op] = ocfg;
                 wave_sync();
-                if (CACHE) refresh_ecache_for_op(m, op);
+                if (CACHE) refresh_ecache_for_group(m, op);
                 mk = meta.cur_ns;
             } else {
                 // a forced step whose simulation failed (overflow): no timeline for this strategy
@@ -441,7 +452,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
 // single-op mutations per chain, each against the chain's current strategy and stored
 // timeline, without changing the chain.  One wavefront per (proposal, chain); its task words
 // live in a private workspace slot, the chain's snapshots are only read.
-template <bool WIDE, bool TREE, bool CACHE, bool EXT, int GPN>
+template <bool WIDE, bool TREE, bool CACHE, int EXT, int GPN>
 __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                         const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                         const uint32_t* __restrict__ magic, const unsigned char* __restrict__ chain_mem,
@@ -479,13 +490,14 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_try(SimDev S, const DOp* __r
             SimT<true, EXT, GPN> m{S, T, cm.cfgs, words, exe_of, L, magic_v, 0, false, op, make_uint2(first_u32(mu[1]), first_u32(mu[2])),
                               CACHE ? cm.ecache : nullptr, false};
             if (EXT) { m.links = (const uint4*)(magic + LINK_TABLE_AT); m.node_links = m.links + (size_t)S.gpus_per_node * S.gpus_per_node; }
+            if (EXT >= 2 && S.ties) m.tie = magic + tie_table_at(S.gpus_per_node, S.n_nodes);
             m.want_sort = true;
             const StrategyClass cls = validate_strategy(m);
             if (cls != STRATEGY_INVALID) {
                 Counters cnt = {};
                 Recorder rec{nullptr, cm.snap_words, cm.snap_l1, cm.snap_free, meta.step, 0, first_u32(meta.loc), n_snaps, 1, 0, 0};
                 uint32_t k = 0, pend_new = 0;
-                if (!meta.stale && meta.n_valid > 1 && meta.step != 0) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
+                if (!meta.stale && meta.n_valid > 1 && meta.step != 0 && !(EXT >= 2 && S.ties)) k = resume_point(m, cm.end_of, meta, op, ocfg, pend_new);
                 if (k == 0) {
                     init_state(m, cnt);
                 } else {

@@ -34,11 +34,17 @@ constexpr u64 RESULT_OVERFLOW = ~0ull - 2;   // a simulated time reached TIME_LI
 struct DMap { int32_t src_dim; uint32_t stride; int32_t a, b; uint32_t cext; };
 // a tensor edge with the shapes of both ends inlined, so that releasing the successors of
 // a finished producer needs no second table lookup
+// A READING edge (kind 0): map[d] belongs to dim d of the producer's tensor, src_dim names a consumer dim,
+// src_ndim / src_extent are the producer's.  A CONTRIBUTING edge (kind 1, a gradient flowing back along a forward
+// edge): the roles are exchanged -- map[d] belongs to dim d of the CONSUMER's tensor, src_dim names a producer
+// dim (cext = the producer's extent there), and src_ndim / src_extent hold the consumer's shape: they always
+// describe the tensor in which the ranges of the two parts are intersected.
 struct DEdge {
     uint32_t src, dst, src_ndim, eid;   // eid: index of the record in the producer-sorted array
     uint32_t src_extent[4];
-    uint32_t dst_extent[4];
-    DMap map[4];                 // indexed by producer dim
+    uint32_t kind;               // 0 reading, 1 contributing
+    uint32_t unused[3];
+    DMap map[4];
 };
 struct DOp {
     uint32_t extent[4];          // 1 beyond ndim
@@ -64,14 +70,18 @@ struct SimDev {
     uint32_t link_table;               // 1: links inside a node differ per ordered GPU pair (see LINK_TABLE_AT)
     uint32_t sync;                     // 1: parameter synchronisation transfers are simulated (DOp::param_bytes)
     uint32_t node_table;               // 1: links between nodes differ per ordered node pair (table behind the one above)
+    uint32_t ties;                     // 1: op i takes the configuration of op tie[i] (table behind the link tables)
 };
 // The constants buffer every kernel receives: words 0..64 are division constants
 // (floor(2^32/d)+1 for d = 2..64); if SimDev::link_table is set, four words per ordered pair of
 // local GPUs (from * gpus_per_node + to) follow at word LINK_TABLE_AT: bandwidth (B/ns),
-// floor(2^32 / bandwidth), latency (ns), 0.  Behind that area (which is always gpus_per_node^2 entries
-// long once any table is set), if SimDev::node_table is set, the same four words per ordered pair of
-// nodes (from * n_nodes + to).
+// floor(2^32 / bandwidth), latency (ns), 0.  Behind that area (always gpus_per_node^2 entries long), if
+// SimDev::node_table is set, the same four words per ordered pair of nodes (from * n_nodes + to; always
+// n_nodes^2 entries).  Behind that, if SimDev::ties is set, one word per op: the op whose configuration it takes.
 constexpr uint32_t LINK_TABLE_AT = 128;
+__host__ __device__ inline uint32_t tie_table_at(uint32_t gpus_per_node, uint32_t n_nodes) {
+    return LINK_TABLE_AT + 4u * (gpus_per_node * gpus_per_node + n_nodes * n_nodes);
+}
 
 // the per-lane condition "my bit of this lane mask is set" (the mask is used as it is)
 __device__ __forceinline__ bool lanes_of(u64 mask) { return __builtin_amdgcn_inverse_ballot_w64(mask); }

@@ -96,7 +96,9 @@ __device__ __forceinline__ void rebuild_l2(const SimX& m) {
 }
 
 // count_inputs (ffsim_strategy.h) from ranges that are already known
-__device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg& cp, const EdgeLane& el) {
+template <bool TRAIN = false>
+__device__ __forceinline__ uint32_t count_inputs_of(const DEdge& e, const OpCfg& cp, const EdgeLane& el, uint32_t magic_v) {
+    if (TRAIN && e.kind) return count_contributors(e, cp, el.nlo, el.nhi, magic_v);   // (the kept ranges are the part's own box)
     uint32_t n = 1;
 #pragma unroll
     for (int d = 0; d < 4; d++) {
@@ -133,7 +135,7 @@ __device__ __forceinline__ void init_state(SimX& m, Counters& cnt) {
                 const DEdge e = m.T.in_edges[q];
                 const EdgeLane el = edge_lane(m, e, cj);
                 ecache_store(m.ecache, m.S.n_edges, e.eid, el);
-                pending += count_inputs_of(e, m.cfg(e.src), el);
+                pending += count_inputs_of<SimX::kTrain>(e, m.cfg(e.src), el, m.magic_v);
             }
         } else {
             pending = count_pending(m, j, cj);
@@ -432,11 +434,33 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         } else {
             // the parts in `mask` finished at `now`: release their successors edge by edge
             DEdge e = opi_p->first;
-            const Box pb = part_box(e.src_extent, ci, lane, magic_v);
+            // the box of every part of the producer (what a reading edge intersects), from the op's own shape
+            // (a contributing edge brings its own ranges, below)
+            Box pb = {};
+            bool pb_is_own = false;
+            if (!(SimX::kTrain && e.kind)) {
+                pb = part_box(e.src_extent, ci, lane, magic_v);
+                pb_is_own = true;
+            }
             const uint32_t node_p = m.node_of(dev_p);
             for (uint32_t ei = out_begin; ei < out_end; ei++) {
                 if (ei != out_begin) e = edges[ei];
                 const uint32_t j = e.dst;
+                // a contributing edge intersects, instead, the range of the consumer's tensor that every producer part
+                // contributes to (the range that follows the part's box through the edge's maps)
+                if (SimX::kTrain && e.kind) {
+                    const uint32_t digits_p = part_digits(ci, lane, magic_v);
+#pragma unroll
+                    for (int d = 0; d < 4; d++) {
+                        int32_t lo = 0, hi = 1;
+                        if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], ci.x, digits_p, magic_v, lo, hi);
+                        pb.lo[d] = (uint32_t)lo; pb.hi[d] = (uint32_t)hi;
+                    }
+                    pb_is_own = false;
+                } else if (SimX::kTrain && !pb_is_own) {
+                    pb = part_box(e.src_extent, ci, lane, magic_v);      // (a reading edge after a contributing one)
+                    pb_is_own = true;
+                }
                 u64 w = words[j * WAVE + lane];
                 // REG: consumer parts sit on consecutive, distinct devices, so the transfers from
                 // one producer part can share a link row only when their consumers sit on the
@@ -445,7 +469,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 // around).  The FIFO order on every shared row is then a running sum along the
                 // run, and no search for lanes with equal rows is needed.
                 // (the op of a trial mutation differs from what the chain's kept set-up describes)
-                const EdgeLane el = (CACHE && !(SimX::kOvr && j == m.ov_op)) ? ecache_load(m.ecache, ei) : edge_lane(m, e, m.cfg(j));
+                const EdgeLane el = (CACHE && !m.overridden(j)) ? ecache_load(m.ecache, ei) : edge_lane(m, e, m.cfg(j));
                 const bool mine = el.mine;
                 int32_t nlo[4], nhi[4];
 #pragma unroll
@@ -457,7 +481,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 const bool wrapped = el.wrapped;
                 const u64 run_end_m = REG ? ballot(el.run_end) : 0;
                 // (general form: the consumer's parts in (node, part) order, and which of them share a GPU)
-                const uint32_t sortw = (REG || WIDE) ? 0u : ((CACHE && !(SimX::kOvr && j == m.ov_op)) ? ecache_sort_word(m.ecache, S.n_edges, ei) : el.sortw);
+                const uint32_t sortw = (REG || WIDE) ? 0u : ((CACHE && !m.overridden(j)) ? ecache_sort_word(m.ecache, S.n_edges, ei) : el.sortw);
                 const u64 dup_m = (REG || WIDE) ? 0 : ballot((sortw >> 23) & 1u);
                 u64 ready = w & (TIME_LIMIT - 1);
                 uint32_t pending = (uint32_t)(w >> 48) & PENDING_LIMIT;

@@ -2,14 +2,14 @@
 #include "ffsim_select.h"
 
 #if !defined(FFSIM_EXT) || !defined(FFSIM_GPN)
-#error "define FFSIM_EXT (0/1) and FFSIM_GPN (0/4)"
+#error "define FFSIM_EXT (0/1/2) and FFSIM_GPN (0/4)"
 #endif
 
 namespace ffsim {
 
 template <bool WIDE, bool STATS, bool CACHE>
 static batch_kernel_t batch_kernel_of(const KernelChoice& k) {
-    constexpr bool EXT = FFSIM_EXT;
+    constexpr int EXT = FFSIM_EXT;
     constexpr int GPN = FFSIM_GPN;
     switch (batch_queue_shape(k)) {
         case Q_ONE16: return k_sim_batch<WIDE, true, STATS, Q_ONE16, CACHE, EXT, GPN>;

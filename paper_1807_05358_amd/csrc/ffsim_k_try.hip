@@ -3,14 +3,14 @@
 #include "ffsim_select.h"
 
 #if !defined(FFSIM_EXT) || !defined(FFSIM_GPN)
-#error "define FFSIM_EXT (0/1) and FFSIM_GPN (0/4)"
+#error "define FFSIM_EXT (0/1/2) and FFSIM_GPN (0/4)"
 #endif
 
 namespace ffsim {
 
 template <bool CACHE>
 static try_kernel_t try_kernel_of(const KernelChoice& k) {
-    constexpr bool EXT = FFSIM_EXT;
+    constexpr int EXT = FFSIM_EXT;
     constexpr int GPN = FFSIM_GPN;
     const bool tree = k.n_groups > FLAT_GROUPS;
     if (k.wide) return tree ? k_sim_chain_try<true, true, CACHE, EXT, GPN> : k_sim_chain_try<true, false, CACHE, EXT, GPN>;

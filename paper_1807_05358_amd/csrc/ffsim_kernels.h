@@ -62,7 +62,7 @@ __device__ __forceinline__ void store_counters(Counters c, Counters* out) {
 // CACHE: the per-edge set-up is kept (after the task words: in LDS if LDSW, else in the slot).
 // EXT: with the link table and / or explicit devices (devmaps, else null and never read).
 // GPN: compiled for machines with this many GPUs per node (0 = any).
-template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE, bool EXT, int GPN>
+template <bool WIDE, bool LDSW, bool STATS, int Q, bool CACHE, int EXT, int GPN>
 __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restrict__ ops, const DEdge* __restrict__ edges,
                                                     const DEdge* __restrict__ in_edges, const uint32_t* __restrict__ cost,
                                                     const uint32_t* __restrict__ magic, const uint2* __restrict__ strategies,
@@ -96,6 +96,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_batch(SimDev S, const DOp* __restr
         if (EXT) {
             m.links = (const uint4*)(magic + LINK_TABLE_AT);
             m.node_links = m.links + (size_t)S.gpus_per_node * S.gpus_per_node;
+            if (EXT >= 2 && S.ties) m.tie = magic + tie_table_at(S.gpus_per_node, S.n_nodes);
             if (devmaps) m.devmap = devmaps + (size_t)b * S.n_ops * WAVE;
         }
         const u64 mk = simulate_candidate<WIDE, false, STATS, Q, CACHE>(m, cnt, none);

@@ -28,10 +28,11 @@ inline int batch_queue_shape(const KernelChoice& k) {
     if (k.lds_words) return k.n_ops <= 64 ? Q_ONE : Q_FLAT;
     return k.n_groups > FLAT_GROUPS ? Q_TREE : Q_FLAT;
 }
-// EXT: the refinements of the inputs (link table, explicit devices); GPN: GPUs per node the
+// EXT: 0 plain; 1 the refinements of the inputs (link tables, explicit devices, parameter traffic); 2 also
+// training-iteration graphs (contributing edges, tied configurations).  GPN: GPUs per node the
 // kernels are compiled for (4, or 0 = any).  One explicit specialisation per object.
-template <bool EXT, int GPN> batch_kernel_t batch_kernels(const KernelChoice& k);
-template <bool EXT, int GPN> chain_kernel_t chain_kernels(const KernelChoice& k);
-template <bool EXT, int GPN> try_kernel_t try_kernels(const KernelChoice& k);
+template <int EXT, int GPN> batch_kernel_t batch_kernels(const KernelChoice& k);
+template <int EXT, int GPN> chain_kernel_t chain_kernels(const KernelChoice& k);
+template <int EXT, int GPN> try_kernel_t try_kernels(const KernelChoice& k);
 
 }  // namespace ffsim

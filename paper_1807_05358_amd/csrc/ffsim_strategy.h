@@ -207,13 +207,13 @@ __device__ __forceinline__ uint32_t owner_part(uint32_t x, uint32_t E, uint32_t 
 // from it must not be treated as invariant.
 // OVR: one op's configuration may be overridden (trial mutations); the plain form does not
 // pay for the comparison.
-// EXT: the refinements of the inputs that only some callers use -- links inside a node that
+// EXT: 0, 1 or 2.  From 1 on: the refinements of the inputs that only some callers use -- links inside a node that
 // differ per pair, explicit devices per task -- are compiled into kernels of their own; the
 // plain kernels carry none of it.
 // GPN: the machine's number of GPUs per node when the kernel is compiled for one (4: node and
 // local index of a device are a shift and a mask, and three scalars fewer stay alive in the
 // event loop), 0 = any.
-template <bool OVR, bool EXT = false, int GPN = 0>
+template <bool OVR, int EXT = 0, int GPN = 0>
 struct SimT {
     const SimDev& S;
     const Tables& T;
@@ -232,9 +232,11 @@ struct SimT {
     const uint4* links = nullptr;        // per ordered pair of local GPUs: bandwidth, its magic, latency (S.link_table)
     const uint4* node_links = nullptr;   // per ordered pair of nodes: the same three figures (S.node_table)
     const uint16_t* devmap = nullptr;    // [n_ops][64] device of every part given explicitly, or null
+    const uint32_t* tie = nullptr;       // [n_ops] tied configurations (S.ties), or null
     bool want_sort = false;              // the set-up of an edge includes the consumer's parts in (node, part) order (general event loop)
     static constexpr bool kOvr = OVR;
-    static constexpr bool kExt = EXT;
+    static constexpr bool kExt = EXT >= 1;      // refinements of the inputs: link tables, explicit devices, parameter traffic
+    static constexpr bool kTrain = EXT >= 2;    // training-iteration graphs: contributing edges, tied configurations
     static_assert(GPN == 0 || GPN == 4, "compiled node sizes");
     __device__ __forceinline__ uint32_t gpn() const { return GPN ? (uint32_t)GPN : S.gpus_per_node; }
     __device__ __forceinline__ uint32_t node_of(uint32_t dev) const {
@@ -243,7 +245,12 @@ struct SimT {
     __device__ __forceinline__ uint32_t local_of(uint32_t dev, uint32_t node) const {
         return GPN == 4 ? (dev & 3u) : dev - node * S.gpus_per_node;
     }
+    // the op whose configuration op j takes (Section 4: one configuration per operation; the forward and the
+    // backward computation of an operation are two ops of the graph)
+    __device__ __forceinline__ uint32_t leader_of(uint32_t j) const { return (kTrain && tie) ? tie[j] : j; }
+    __device__ __forceinline__ bool overridden(uint32_t j) const { return OVR && leader_of(j) == ov_op; }
     __device__ __forceinline__ uint2 cfg_raw(uint32_t j) const {
+        j = leader_of(j);
         uint2 c = cfgs[j];
         if (OVR && j == ov_op) c = ov_cfg;
         return c;
@@ -292,10 +299,20 @@ __device__ __forceinline__ EdgeLane edge_lane(const SimX& m, const DEdge& e, con
     EdgeLane el;
     el.mine = (uint32_t)lane < cj.parts;
     const uint32_t digits = part_digits(cj, lane, m.magic_v);
+    if (SimX::kTrain && e.kind) {
+        // a contributing edge: the ranges are taken in the consumer's own tensor, of which this lane's part holds a box
+        const Box cb = part_box(e.src_extent, cj, lane, m.magic_v);
 #pragma unroll
-    for (int d = 0; d < 4; d++) {
-        el.nlo[d] = 0; el.nhi[d] = 1;
-        if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, m.magic_v, el.nlo[d], el.nhi[d]);
+        for (int d = 0; d < 4; d++) {
+            el.nlo[d] = (uint32_t)d < e.src_ndim ? (int32_t)cb.lo[d] : 0;
+            el.nhi[d] = (uint32_t)d < e.src_ndim ? (int32_t)cb.hi[d] : 1;
+        }
+    } else {
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            el.nlo[d] = 0; el.nhi[d] = 1;
+            if ((uint32_t)d < e.src_ndim) needed_range(e.map[d], e.src_extent[d], cj.x, digits, m.magic_v, el.nlo[d], el.nhi[d]);
+        }
     }
     const uint32_t G = m.gpn();
     // the run fields only depend on the consumer's own configuration: filled whenever it puts its
@@ -367,7 +384,55 @@ __device__ __forceinline__ uint32_t ecache_sort_word(const uint32_t* ecache, uin
 
 // how many parts of the producer (configuration cp) a consumer part reads through edge e:
 // the product over the producer's dims of the number of producer parts its range touches
+// The same count for a contributing edge: how many producer parts contribute to the box [blo, bhi) of the
+// consumer's tensor.  Every dim of that tensor follows one producer dim (or none), so the count is a product
+// over the PRODUCER's dims of the number of indices along that dim whose range meets the box in every dim that
+// follows it (all indices, if none does).  Loops over the producer's degrees; runs once per edge and candidate.
+__device__ __forceinline__ uint32_t count_contributors(const DEdge& e, const OpCfg& cp, const int32_t blo[4], const int32_t bhi[4], uint32_t magic_v) {
+    uint32_t n = 1;
+    for (int c = 0; c < 4; c++) {
+        const uint32_t deg = cp.deg[c];
+        uint32_t followers = 0;
+        for (int d = 0; d < 4; d++) followers |= ((uint32_t)d < e.src_ndim && e.map[d].src_dim == c) ? (1u << d) : 0u;
+        if (!followers) { n *= deg; continue; }
+        const Divisor dv = divisor(deg, magic_v);
+        uint32_t cnt = 0;
+        for (uint32_t idx = 0; idx < deg; idx++) {
+            bool meets = true;
+            for (int d = 0; d < 4; d++) {
+                if (!((followers >> d) & 1u)) continue;
+                const DMap mp = e.map[d];
+                const int32_t E = (int32_t)e.src_extent[d];
+                const int32_t plo = (int32_t)div_by(idx * mp.cext, dv), phi = (int32_t)div_by((idx + 1) * mp.cext, dv);
+                int32_t l = plo * (int32_t)mp.stride + mp.a, h = (phi - 1) * (int32_t)mp.stride + mp.b + 1;
+                l = l < 0 ? 0 : (l > E ? E : l);
+                h = h < 0 ? 0 : (h > E ? E : h);
+                meets = meets && h > l && h > blo[d] && l < bhi[d];
+            }
+            cnt += meets ? 1u : 0u;
+        }
+        n *= cnt;
+    }
+    return n;
+}
+
+template <bool TRAIN = false>
 __device__ __forceinline__ uint32_t count_inputs(const DEdge& e, const OpCfg& cp, uint32_t cons_cfg_x, uint32_t digits, uint32_t magic_v) {
+    if (TRAIN && e.kind) {
+        // this lane's box of the consumer's tensor
+        int32_t blo[4], bhi[4];
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            const uint32_t deg = (cons_cfg_x >> (8 * d)) & 0xff, idx = (digits >> (8 * d)) & 0xff;
+            blo[d] = 0; bhi[d] = (uint32_t)d < e.src_ndim ? (int32_t)e.src_extent[d] : 1;
+            if (deg != 1) {
+                const Divisor dv = divisor(deg, magic_v);
+                blo[d] = (int32_t)div_by(idx * e.src_extent[d], dv);
+                bhi[d] = (int32_t)div_by((idx + 1) * e.src_extent[d], dv);
+            }
+        }
+        return count_contributors(e, cp, blo, bhi, magic_v);
+    }
     uint32_t n = 1;
 #pragma unroll
     for (int d = 0; d < 4; d++) {
@@ -395,7 +460,7 @@ __device__ __forceinline__ uint32_t count_pending(const SimX& m, uint32_t j, con
     for (uint32_t q = in_begin; q < in_end; q++) {
         const DEdge e = m.T.in_edges[q];
         const OpCfg ci = m.cfg(e.src);
-        pending += count_inputs(e, ci, cj.x, digits, m.magic_v);
+        pending += count_inputs<SimX::kTrain>(e, ci, cj.x, digits, m.magic_v);
     }
     return pending;
 }

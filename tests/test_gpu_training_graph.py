@@ -1,0 +1,254 @@
+"""GPU parity for training-iteration graphs: contributing (gradient) edges and tied configurations
+(ff_sim_set_ties), bit for bit against the CPU oracle: batch simulation with counters, mutation chains,
+trial proposals and the search loop, with and without parameter traffic."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import search as osearch
+from helpers import graph_from_golden, load_golden
+from paper_1807_05358_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_1807_05358_amd import binding
+    return binding
+
+
+def _training(config_id):
+    w = W.workload(config_id)
+    ops, edges, flops, leader, params = W.training_graph(w.ops, w.edges, w.flops)
+    cost = np.ascontiguousarray(W.cost_table(config_id, flops, w.seed)[:, :w.max_parts])
+    return w, ops, edges, cost, leader, params
+
+
+def _mixed(ops, w, n, seed):
+    cfgs = W.strategies(ops, n, w.seed, w.machine.n_devices, w.max_parts, w.choices)
+    rng = np.random.default_rng(seed)
+    irregular = rng.random(n) < 0.3
+    cfgs["dev_stride"][irregular] = rng.integers(0, 6, size=(int(irregular.sum()), cfgs.shape[1]))
+    return cfgs
+
+
+def test_hand_computed_contributing_window(B, golden_dir):
+    g = load_golden(golden_dir, "build_contributing_window_pairs.json")
+    ops, edges, mach, cost, cfg = graph_from_golden(g)
+    sim = B.Simulator(ops, edges, mach, cost)
+    out, st = sim.simulate(cfg[None], stats=True)
+    assert int(out[0]) == g["makespan"]
+    assert int(st[0]["n_comm"]) == 3 and int(st[0]["n_pairs"]) == 3 and int(st[0]["sum_comm_ns"]) == 9
+    sim.close()
+
+
+@pytest.mark.parametrize("config_id,n,with_params", [(0, 64, False), (1, 320, False), (1, 200, True), (2, 48, True), (3, 12, False)])
+def test_training_iteration_matches_the_oracle(B, config_id, n, with_params):
+    w, ops, edges, cost, leader, params = _training(config_id)
+    params = params if with_params else None
+    cfgs = _mixed(ops, w, n, 90 + config_id)
+    cfgs[0] = W.data_parallel_strategy(ops, w.machine.n_devices, w.max_parts)
+    want = oracle.simulate_batch(ops, edges, w.machine, cost, cfgs, n_threads=16, ties=leader, params=params)
+    assert want.max() < oracle.INVALID
+    sim = B.Simulator(ops, edges, w.machine, cost, params=params, ties=leader)
+    got, st = sim.simulate(cfgs, stats=True)
+    assert not st["exit_code"].any() and not st["n_stuck"].any()
+    for b in range(min(n, 3)):
+        tg = oracle.build_task_graph(ops, edges, w.machine, cost, cfgs[b], ties=leader, params=params)
+        n_comm = tg.n_tasks - tg.n_compute
+        assert int(st[b]["n_compute"]) == tg.n_compute and int(st[b]["n_comm"]) == n_comm
+        assert int(st[b]["sum_comm_ns"]) == int(tg.exe[tg.n_compute:].sum())
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} of {n} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+    assert np.array_equal(sim.simulate(cfgs), want)                      # and the kernel without the counters
+    # without the ties every op takes its own entry again
+    B.ff_sim_set_ties(sim.handle, len(ops))
+    assert np.array_equal(sim.simulate(cfgs[:32]), oracle.simulate_batch(ops, edges, w.machine, cost, cfgs[:32], n_threads=16, params=params))
+    sim.close()
+
+
+def test_invalid_for_a_tied_op_is_invalid(B):
+    w, ops, edges, cost, leader, _ = _training(0)
+    cfgs = W.strategies(ops, 8, w.seed, w.machine.n_devices, w.max_parts, w.choices)
+    lead = leader.copy()
+    lead[5] = 4                                 # softmax (sample dim only) takes the fc's configuration
+    lead[len(ops) - 1 - 5] = 4
+    cfgs[:, 4]["deg"] = (1, 2, 1, 1)
+    want = oracle.simulate_batch(ops, edges, w.machine, cost, cfgs, ties=lead)
+    assert (want == oracle.INVALID).all()
+    sim = B.Simulator(ops, edges, w.machine, cost, ties=lead)
+    assert np.array_equal(sim.simulate(cfgs), want)
+    bad = lead.copy(); bad[0] = 1; bad[1] = 0   # leaders that do not lead themselves
+    with pytest.raises(B.FFSimError):
+        B.ff_sim_set_ties(sim.handle, len(ops), bad)
+    sim.close()
+
+
+def test_shared_parameters_on_the_nmt_shaped_training_graph(B):
+    ops, edges, flops, groups = W.graph_nmt(steps=8, with_groups=True)
+    t_ops, t_edges, t_flops, leader, params = W.training_graph(ops, edges, flops, groups=groups)
+    assert (leader != np.arange(len(t_ops))).sum() > len(ops)             # backward ops and the later steps follow a leader
+    cost = np.ascontiguousarray(W.cost_table(4, t_flops, 9)[:, :64])
+    mach = W.Machine(16, 4)
+    cfgs = W.strategies(t_ops, 24, 9, mach.n_devices, 64, (1, 2, 4, 8, 16, 32, 64))
+    want = oracle.simulate_batch(t_ops, t_edges, mach, cost, cfgs, n_threads=16, ties=leader, params=params)
+    sim = B.Simulator(t_ops, t_edges, mach, cost, params=params, ties=leader)
+    got = sim.simulate(cfgs)
+    bad = np.nonzero(got != want)[0]
+    assert len(bad) == 0, f"{len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+    sim.close()
+
+
+@pytest.mark.parametrize("config_id,tied", [(1, True), (1, False), (2, False), (0, True)])
+def test_chains_trials_and_search_on_a_training_graph(B, config_id, tied):
+    """mutation chains (with ties every step is simulated from time 0; without them contributing edges go through
+    the resumed simulation and its patched input counts), trial proposals and the search loop"""
+    w, ops, edges, cost, leader, params = _training(config_id)
+    ties = leader if tied else None
+    C, steps = 2, 20
+    cfgs = W.strategies(ops, C, w.seed + 1, w.machine.n_devices, w.max_parts, w.choices)
+    muts = W.mutation_chains(ops, steps, C, w.seed, w.machine.n_devices, w.max_parts, w.choices)
+    muts["op"][0] = 0
+    muts["op"][1] = len(ops) - 1
+    sim = B.Simulator(ops, edges, w.machine, cost, ties=ties)
+    ch = B.Chains(sim, cfgs)
+    assert np.array_equal(ch.start_ns(), oracle.simulate_batch(ops, edges, w.machine, cost, cfgs, ties=ties))
+    d = ch.delta(ch.upload_mutations(muts), steps).cpu().numpy().view("<u8")
+    cur = cfgs.copy()
+    for c in range(C):
+        ref = oracle.simulate_delta_chain(ops, edges, w.machine, cost, cfgs[c], muts[:, c], ties=ties)
+        bad = np.nonzero(d[:, c] != ref)[0]
+        assert len(bad) == 0, f"chain {c}: first differing step {bad[0]} (op {int(muts[bad[0], c]['op'])})"
+        for s in range(steps):
+            cur[c, int(muts[s, c]["op"])] = muts[s, c]["cfg"]
+    M = 10
+    props = W.mutation_chains(ops, steps + M, C, w.seed, w.machine.n_devices, w.max_parts, w.choices)[steps:]
+    tried = ch.try_mutations(ch.upload_mutations(props), M).cpu().numpy().view("<u8")
+    for c in range(C):
+        cand = np.repeat(cur[c][None], M, 0)
+        for p in range(M):
+            cand[p, int(props[p, c]["op"])] = props[p, c]["cfg"]
+        assert np.array_equal(tried[:, c], oracle.simulate_batch(ops, edges, w.machine, cost, cand, n_threads=8, ties=ties))
+    tp, tu = W.search_space(ops, w.max_parts, w.choices)
+    t0 = int(oracle.simulate_batch(ops, edges, w.machine, cost, cur[:1], ties=ties)[0])
+    table = osearch.metropolis_table(30.0 / t0, max(1, t0 // 256), 64)
+    ch.search_setup(tp, tu, table, max(1, t0 // 256), 21)
+    tr = ch.search(16).cpu().numpy().view("<u8")
+    for c in range(C):
+        ref = _oracle_chain(ops, edges, w.machine, cost, cur[c], tp, tu, table, max(1, t0 // 256), 21, c, 16, ties)
+        assert np.array_equal(tr[:, c], ref), f"search chain {c}"
+    ch.close()
+    sim.close()
+
+
+def _oracle_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept, bucket_ns, seed, chain, n_steps, ties):
+    """oracle/search.py's chain, with the simulator told about the ties (the search itself does not know them:
+    it proposes for every op, and a proposal for an op that leads nobody changes nothing)"""
+    n_ops, n_dev = len(ops), int(machine.n_devices)
+    sim1 = lambda c: int(oracle.simulate_batch(ops, edges, machine, cost, c[None], ties=ties)[0])
+    cur = np.array(cfg0, copy=True)
+    cur_ns = sim1(cur)
+    trace = np.zeros(n_steps, "<u8")
+    for s in range(n_steps):
+        op = osearch.draw(seed, osearch.OP, chain, s) % n_ops
+        t0, t1 = int(tuple_ptr[op]), int(tuple_ptr[op + 1])
+        if t1 > t0:
+            word = int(tuples[t0 + osearch.draw(seed, osearch.TUPLE, chain, s) % (t1 - t0)])
+            prop = cur.copy()
+            prop[op]["deg"] = [(word >> (8 * d)) & 0xFF for d in range(4)]
+            prop[op]["dev_offset"] = osearch.draw(seed, osearch.OFFSET, chain, s) % n_dev
+            prop[op]["dev_stride"] = 1
+            new_ns = sim1(prop)
+            ok = False
+            if new_ns < oracle.INVALID - 2:
+                if new_ns <= cur_ns:
+                    ok = True
+                else:
+                    b = min((new_ns - cur_ns) // int(bucket_ns), len(accept) - 1)
+                    ok = (osearch.draw(seed, osearch.ACCEPT, chain, s) >> 32) < int(accept[b])
+            if ok:
+                cur, cur_ns = prop, new_ns
+        trace[s] = cur_ns
+    return trace
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_graphs_with_contributing_edges(B, seed):
+    """random DAGs whose edges are reading or contributing at random, random affine maps, general and regular
+    strategies, random ties among ops of equal shape"""
+    rng = np.random.default_rng(4400 + seed)
+    n_ops = int(rng.integers(4, 60))
+    g = W.GraphBuilder()
+    kinds = []
+    for i in range(n_ops):
+        ndim = int(rng.integers(1, 5))
+        ext = [int(rng.choice([1, 2, 3, 5, 8, 12, 17, 32, 64])) for _ in range(ndim)]
+        par = [d for d in range(ndim) if rng.random() < 0.8] or [0]
+        g.op(W.T_ELEM, ext, par, 1)
+        n_in = 0 if i == 0 else int(rng.integers(0, min(i, 3) + 1))
+        for src in sorted(rng.choice(i, size=n_in, replace=False).tolist()) if n_in else []:
+            contributes = rng.random() < 0.5
+            space, driving = (g.extent(i), g.extent(src)) if contributes else (g.extent(src), g.extent(i))
+            maps = []
+            for d in range(len(space)):
+                if rng.random() < 0.3:
+                    maps.append(W.ALL)
+                else:
+                    c = int(rng.integers(0, len(driving)))
+                    a = int(rng.integers(-3, 4))
+                    maps.append((c, int(rng.choice([1, 1, 1, 2, 3])), a, a + int(rng.integers(0, 4))))
+            g.edges.append((src, i, maps))
+            kinds.append(((src, i), contributes))
+    ops, edges, _ = g.finish()
+    kind_of = dict(kinds)                           # (at most one edge per op pair here)
+    for e in edges:
+        if kind_of[(int(e["src_op"]), int(e["dst_op"]))]:
+            e["map"]["pad"] = 1
+    mach = W.Machine(int(rng.integers(1, 5)), int(rng.choice([1, 2, 4, 4])), int(rng.integers(1, 30)), int(rng.integers(1, 30)),
+                     int(rng.integers(0, 50)), int(rng.integers(0, 50)), int(rng.choice([1, 2, 4])))
+    cost = rng.integers(1, 3000, size=(n_ops, 64)).astype("<u4")
+    # ties among ops of equal shape and parallelizable dims
+    leader = np.arange(n_ops, dtype=np.uint32)
+    for i in range(n_ops):
+        for j in range(i):
+            if leader[j] == j and rng.random() < 0.3 and tuple(ops[i]["extent"]) == tuple(ops[j]["extent"]) and \
+                    ops[i]["ndim"] == ops[j]["ndim"] and ops[i]["par_mask"] == ops[j]["par_mask"]:
+                leader[i] = j
+                break
+    n = 120
+    cfgs = np.zeros((n, n_ops), W.CFG_DT)
+    for i in range(n_ops):
+        t = W.valid_degree_tuples(ops[i], min(64, max(1, mach.n_devices * 2)), (1, 2, 3, 4, 5, 7, 8, 16, 32, 64))
+        cfgs["deg"][:, i] = t[rng.integers(len(t), size=n)]
+    cfgs["dev_offset"] = rng.integers(0, mach.n_devices, size=(n, n_ops))
+    cfgs["dev_stride"] = 1
+    cfgs["dev_stride"][n // 2:] = rng.integers(0, 4, size=(n - n // 2, n_ops))
+    print(f"seed {seed}: {n_ops} ops, {len(edges)} edges ({int(edges['map']['pad'][:, 0].sum())} contributing), "
+          f"{int((leader != np.arange(n_ops)).sum())} tied, machine {mach.as_tuple()}", flush=True)
+    for ties in (None, leader):
+        want = oracle.simulate_batch(ops, edges, mach, cost, cfgs, n_threads=8, ties=ties)
+        sim = B.Simulator(ops, edges, mach, cost, ties=ties)
+        got, st = sim.simulate(cfgs, stats=True)
+        ok = want != oracle.INVALID
+        assert not st["exit_code"][ok].any() and not st["n_stuck"][ok].any()
+        bad = np.nonzero(got != want)[0]
+        assert len(bad) == 0, f"ties {ties is not None}: {len(bad)} differ, first {bad[:5]}: gpu {got[bad[:5]]} oracle {want[bad[:5]]}"
+        # a mutation chain (resumed simulations patch the input counts through both kinds of edges)
+        muts = np.zeros((24, 2), W.MUT_DT)
+        muts["op"] = rng.integers(0, n_ops, size=(24, 2))
+        for s in range(24):
+            for c in range(2):
+                i = int(muts[s, c]["op"])
+                t = W.valid_degree_tuples(ops[i], min(64, max(1, mach.n_devices * 2)), (1, 2, 3, 4, 8, 16))
+                muts[s, c]["cfg"]["deg"] = t[rng.integers(len(t))]
+                muts[s, c]["cfg"]["dev_offset"] = rng.integers(0, mach.n_devices)
+                muts[s, c]["cfg"]["dev_stride"] = rng.integers(0, 3)
+        start = np.nonzero(ok)[0][:2]
+        ch = B.Chains(sim, cfgs[start])
+        d = ch.delta(ch.upload_mutations(muts), 24).cpu().numpy().view("<u8")
+        for c in range(2):
+            ref = oracle.simulate_delta_chain(ops, edges, mach, cost, cfgs[start[c]], muts[:, c], ties=ties)
+            assert np.array_equal(d[:, c], ref), f"ties {ties is not None} chain {c}: steps {np.nonzero(d[:, c] != ref)[0][:5]}"
+        ch.close()
+        sim.close()
