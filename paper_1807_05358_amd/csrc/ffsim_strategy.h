@@ -382,9 +382,7 @@ __device__ __forceinline__ uint32_t ecache_sort_word(const uint32_t* ecache, uin
     return ecache[(size_t)n_edges * (ECACHE_WORDS * WAVE) + (size_t)eid * WAVE + lane_id()];
 }
 
-// how many parts of the producer (configuration cp) a consumer part reads through edge e:
-// the product over the producer's dims of the number of producer parts its range touches
-// The same count for a contributing edge: how many producer parts contribute to the box [blo, bhi) of the
+// The number of inputs a consumer part has through a contributing edge: how many producer parts contribute to the box [blo, bhi) of the
 // consumer's tensor.  Every dim of that tensor follows one producer dim (or none), so the count is a product
 // over the PRODUCER's dims of the number of indices along that dim whose range meets the box in every dim that
 // follows it (all indices, if none does).  Loops over the producer's degrees; runs once per edge and candidate.
@@ -416,6 +414,8 @@ __device__ __forceinline__ uint32_t count_contributors(const DEdge& e, const OpC
     return n;
 }
 
+// how many parts of the producer (configuration cp) a consumer part reads through edge e:
+// the product over the producer's dims of the number of producer parts its range touches
 template <bool TRAIN = false>
 __device__ __forceinline__ uint32_t count_inputs(const DEdge& e, const OpCfg& cp, uint32_t cons_cfg_x, uint32_t digits, uint32_t magic_v) {
     if (TRAIN && e.kind) {
