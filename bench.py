@@ -251,6 +251,41 @@ def long_chain(n_steps, check, threads):
     return 0 if not bad else 1
 
 
+SECTIONS = ["set-up (validate, initial state, kept per-edge set-up)", "queue pop", "wait for the popped op's words",
+            "dequeue of READY tasks", "release: before the loop over producer parts", "wait for the edge's loads",
+            "release: loop over producer parts", "consumer words and queue update"]
+
+
+def sections():
+    """Where the time of one wavefront (= one candidate) goes: the diagnostic build of the library accumulates shader
+    clock ticks per section of the event loop (Algorithm 1) and returns them in the optional per-candidate record."""
+    import numpy as np
+    from paper_1807_05358_amd import binding, build, workloads as W
+    if not os.path.exists(build.SECTIONS_LIB):
+        print(f"bench.py --sections: {build.SECTIONS_LIB} is missing; build it with "
+              "`python -m paper_1807_05358_amd.build --sections`", file=sys.stderr)
+        return 2
+    # queue steps per candidate come from the ordinary library (the diagnostic build reuses that field)
+    steps = {}
+    for c in range(5):
+        w = W.workload(c)
+        sim = binding.Simulator(w.ops, w.edges, w.machine, w.cost)
+        steps[c] = float(sim.simulate(w.strategies(w.n_candidates), stats=True)[1]["n_events"].mean())
+        sim.close()
+    binding.load_library(build.SECTIONS_LIB)
+    fields = ["n_compute", "n_pairs", "n_comm", "sum_comm_ns", "n_events", "exit_code", "n_stuck", "reserved"]
+    for c in range(5):
+        w = W.workload(c)
+        sim = binding.Simulator(w.ops, w.edges, w.machine, w.cost)
+        st = sim.simulate(w.strategies(w.n_candidates), stats=True)[1]
+        sim.close()
+        t = np.array([st[f] for f in fields], dtype=np.float64).mean(1)
+        print(f"configs[{c}] {w.name}: B = {w.n_candidates}, {steps[c]:.0f} queue steps and {t.sum():.0f} clock ticks per candidate")
+        for name, v in zip(SECTIONS, t):
+            print(f"    {name:58s} {v:12.0f}  {100 * v / t.sum():5.1f} %  {v / steps[c]:8.1f} per queue step")
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -266,6 +301,10 @@ def main():
     ap.add_argument("--long-chain", type=int, default=0, metavar="N",
                     help="run only the N-step mutation chain of configs[4] (10000 in the configuration list)")
     ap.add_argument("--check", type=int, default=200, help="with --long-chain: steps compared with the oracle")
+    ap.add_argument("--sections", action="store_true",
+                    help="print where a wavefront's time goes inside the batch kernel (clock ticks per section of the "
+                         "event loop, mean per candidate) for the five workloads; needs the diagnostic build "
+                         "(python -m paper_1807_05358_amd.build --sections)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (candidates are independent: several GPUs would each take a "
@@ -276,6 +315,8 @@ def main():
     import torch
     from paper_1807_05358_amd import binding, workloads as W
 
+    if args.sections:
+        sys.exit(sections())
     threads, logical_cpus, usable_cpus = host_cores()
     if args.long_chain:
         sys.exit(long_chain(args.long_chain, args.check, threads))

@@ -64,6 +64,14 @@ class ff_search_t(C.Structure):
 _lib = None
 
 
+def load_library(path):
+    """use another build of the library (the diagnostic build with section timers) for everything created from now
+    on; handles made with the previous one must have been closed."""
+    global _lib, LIB_PATH
+    LIB_PATH = path
+    _lib = None
+
+
 def lib():
     """the loaded library; raises if it has not been built (no fallback)."""
     global _lib

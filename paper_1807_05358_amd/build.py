@@ -15,6 +15,10 @@ HEADERS = ["ffsim_select.h", "ffsim_sweep.h", "ffsim_kernels.h", "ffsim_chain.h"
            "ffsim_device.h"]
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libffsim.so")
+# the same sources with the event loop's section timers compiled in (a diagnostic build: the optional per-candidate
+# record then holds clock ticks per section instead of its counters; `bench.py --sections` reads it)
+SECTIONS_OBJ_DIR = os.path.join(HERE, "_build_sections")
+SECTIONS_LIB = os.path.join(HERE, "libffsim_sections.so")
 DEPS = [os.path.join(CSRC, f) for f in UNITS + HEADERS] + [os.path.join(os.path.dirname(HERE), "include", "ff_sim.h")]
 
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -23,17 +27,20 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Wno-unused-value"]
 
 
-def build_library(force: bool = True) -> str:
-    """compile libffsim.so; with force=False only if it is missing or older than a source."""
-    if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS):
-        return LIB
+def build_library(force: bool = True, sections: bool = False) -> str:
+    """compile libffsim.so (sections=True: libffsim_sections.so, the build with section timers);
+    with force=False only if it is missing or older than a source."""
+    lib_path, obj_dir = (SECTIONS_LIB, SECTIONS_OBJ_DIR) if sections else (LIB, OBJ_DIR)
+    extra = ["-DFFSIM_PROFILE"] if sections else []
+    if not force and os.path.exists(lib_path) and all(os.path.getmtime(lib_path) >= os.path.getmtime(d) for d in DEPS):
+        return lib_path
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    os.makedirs(OBJ_DIR, exist_ok=True)
-    jobs = [(HOST_UNIT, [], "ffsim.o")]
+    os.makedirs(obj_dir, exist_ok=True)
+    jobs = [(HOST_UNIT, extra, "ffsim.o")]
     for ext, gpn in VARIANTS:
         for u in KERNEL_UNITS:
-            jobs.append((u, [f"-DFFSIM_EXT={ext}", f"-DFFSIM_GPN={gpn}"], f"{os.path.splitext(u)[0]}_e{ext}_g{gpn}.o"))
-    objs = [os.path.join(OBJ_DIR, o) for _, _, o in jobs]
+            jobs.append((u, [f"-DFFSIM_EXT={ext}", f"-DFFSIM_GPN={gpn}", *extra], f"{os.path.splitext(u)[0]}_e{ext}_g{gpn}.o"))
+    objs = [os.path.join(obj_dir, o) for _, _, o in jobs]
     workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1))))
     running, failed, todo = [], [], list(zip(jobs, objs))
     while todo or running:
@@ -45,9 +52,10 @@ def build_library(force: bool = True) -> str:
             failed.append(name)
     if failed:
         raise RuntimeError("hipcc failed on " + ", ".join(failed))
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
-    return LIB
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs])
+    return lib_path
 
 
 if __name__ == "__main__":
-    print(build_library())
+    import sys
+    print(build_library(sections="--sections" in sys.argv[1:]))

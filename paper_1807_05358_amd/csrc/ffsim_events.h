@@ -357,6 +357,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
         const OpCfg ci = m.cfg(i);
         const u64 exe = m.exe_of[i];
         const uint32_t dev_p = m.template device_of<REG>(i, ci);   // (with explicit devices a load: requested with the words)
+        PROF_MARK(1)
+        PROF_VMWAIT(2)
         const u64 mask_same = ballot(k0 == kmin);       // parts of op i that hold the minimum
         if (!mask_same) { cnt.exit_code = 2; return RESULT_INTERNAL; }
         cnt.n_events++;
@@ -430,7 +432,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const bool releases = out_end > out_begin || (SimX::kExt && S.sync && opi_p->param_bytes != 0);
             if (in_mask) k0 = releases ? end << 1 : W_NONE;
             if (RECORD) { if (in_mask && rec.end_try) rec.end_try[i * WAVE + lane] = rec.tag | end; }
-            PROF_MARK(2)
+            PROF_MARK(3)
         } else {
             // the parts in `mask` finished at `now`: release their successors edge by edge
             DEdge e = opi_p->first;
@@ -490,7 +492,8 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                 const u64 mine_m = ballot(mine);
                 u64 touched_m = 0;
                 u64 todo = mask;
-                PROF_MARK(3)
+                PROF_MARK(4)
+                PROF_VMWAIT(5)
                 while (todo) {
                     // next producer part: by part index; in a run of releases by (time, part index)
                     int kp = __builtin_ctzll(todo);
@@ -635,7 +638,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                     touched_m |= hit_m;
                     if (STATS) cnt.n_pairs += __popcll(hit_m);
                 }
-                PROF_MARK(4)
+                PROF_MARK(6)
                 const bool touched = lanes_of(touched_m);
                 overflow = overflow || (touched && ready >= TIME_LIMIT);
                 const bool now_ready = touched && pending == 0;
@@ -653,7 +656,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
                         if (TREE && (j >> 6) == (i >> 6) && nmin < row_rest) row_rest = nmin;
                     }
                 }
-                PROF_MARK(5)
+                PROF_MARK(7)
             }
             if (SimX::kExt && S.sync) {
                 // Parameter synchronisation (a refinement of the inputs; Section 8 discusses the traffic,
@@ -725,7 +728,7 @@ __device__ u64 run_events(SimX& m, Counters& cnt, Recorder& rec) {
             const u64 new_l2 = new_l1 < row_rest ? new_l1 : row_rest;
             if ((uint32_t)lane == (i >> 6)) qreg = new_l2;
         }
-        PROF_MARK(6)
+        PROF_MARK(7)
     }
     m.last_key = last_key;
     PROF_STORE(cnt)

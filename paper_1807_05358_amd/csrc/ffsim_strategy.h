@@ -12,17 +12,24 @@ constexpr uint32_t FLAT_GROUPS = 8;
 // along consecutive lanes (one shift per GPU); beyond, the general search for equal rows runs
 constexpr uint32_t MAX_RUN = 8;
 
-// Section timing for development builds (-DFFSIM_PROFILE): shader-clock ticks per section are
-// accumulated in a register array and reported through the stats record instead of the
-// usual counters.  Compiled out otherwise.
+// Section timing for diagnostic builds (-DFFSIM_PROFILE): shader-clock ticks per section of the
+// event loop are accumulated in registers and reported through the optional per-candidate record
+// INSTEAD of its usual counters (section k in field k: 0 set-up, 1 queue pop, 2 wait for the popped
+// op's words, 3 dequeue of READY tasks, 4 release: before the loop over producer parts, 5 wait
+// for the edge's loads, 6 loop over producer parts, 7 consumer words and queue update).  Every mark
+// reads the clock through the scalar memory path and waits for it, so LDS and scalar loads in
+// flight are charged to the section that issued them; sections 2 and 5 wait for the vector loads.
+// Compiled out otherwise.
 #ifdef FFSIM_PROFILE
 #define PROF_DECL u64 prof_t[8] = {cnt.exit_code, 0, 0, 0, 0, 0, 0, 0}; u64 prof_last = __builtin_readcyclecounter();
 #define PROF_MARK(k) { const u64 prof_now = __builtin_readcyclecounter(); prof_t[k] += prof_now - prof_last; prof_last = prof_now; }
+#define PROF_VMWAIT(k) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); PROF_MARK(k) }
 #define PROF_STORE(c) { c.n_compute = prof_t[0]; c.n_pairs = prof_t[1]; c.n_comm = prof_t[2]; c.sum_comm_ns = lane_id() == 0 ? prof_t[3] : 0; \
-                        c.exit_code = prof_t[4]; c.n_stuck = prof_t[5]; c.want_check = prof_t[6]; }
+                        c.n_events = prof_t[4]; c.exit_code = prof_t[5]; c.n_stuck = prof_t[6]; c.want_check = prof_t[7]; }
 #else
 #define PROF_DECL
 #define PROF_MARK(k)
+#define PROF_VMWAIT(k)
 #define PROF_STORE(c)
 #endif
 
