@@ -261,8 +261,9 @@ int ff_sim_batch_kernel_name(const ff_sim_t* sim, uint32_t B, char* buf, size_t 
 /* The same with the device of every task given one by one (Section 4: a configuration assigns
  * each of its tasks a device) instead of dev_offset + k * dev_stride: d_devmaps is
  * [B][n_ops][FF_MAX_PARTS], entry k of an op = device of its part k (< n_devices, else the
- * strategy is invalid); entries beyond the op's number of parts and the configurations'
- * dev_offset / dev_stride are not read.  Device memory, read only.  Workspace, stats and
+ * strategy is invalid); entries beyond the op's number of parts have no meaning (all FF_MAX_PARTS
+ * entries of an op must be readable), and the configurations' dev_offset / dev_stride are not
+ * read.  Device memory, read only.  Workspace, stats and
  * results as for ff_sim_batch. */
 int ff_sim_batch_devmaps(ff_sim_t* sim, const ff_opcfg_t* d_strategies, const uint16_t* d_devmaps, uint32_t B,
                          uint64_t* d_out_ns, void* hip_stream);

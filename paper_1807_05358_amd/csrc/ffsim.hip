@@ -408,14 +408,16 @@ void ff_sim_destroy(ff_sim_t* s) { release(s); }
 int ff_sim_set_params(ff_sim_t* s, const uint32_t* param_bytes, const uint8_t* param_dims) {
     if (!s || (param_bytes && !param_dims)) return FF_EINVAL;
     bool any = false;
+    std::vector<DOp> ops = s->h_ops;
     for (uint32_t i = 0; i < s->dev.n_ops; i++) {
-        DOp& o = s->h_ops[i];
+        DOp& o = ops[i];
         o.param_bytes = param_bytes ? param_bytes[i] : 0;
         o.param_dims = param_bytes ? (param_dims[i] & ((1u << o.ndim) - 1)) : 0;
         any = any || o.param_bytes;
     }
     if (hipDeviceSynchronize() != hipSuccess) return FF_EHIP;       // no launch may still read the old records
-    if (hipMemcpy(s->d_ops, s->h_ops.data(), s->h_ops.size() * sizeof(DOp), hipMemcpyHostToDevice) != hipSuccess) return FF_EHIP;
+    if (hipMemcpy(s->d_ops, ops.data(), ops.size() * sizeof(DOp), hipMemcpyHostToDevice) != hipSuccess) return FF_EHIP;
+    s->h_ops.swap(ops);
     s->dev.sync = any ? 1u : 0u;
     s->links_gen++;
     return FF_OK;
@@ -468,7 +470,9 @@ int ff_sim_set_links(ff_sim_t* s, const ff_linktable_t* links) {
     }
     s->intra_bw.swap(bw);
     s->intra_lat.swap(lat);
-    return apply_link_tables(s);
+    const int rc = apply_link_tables(s);
+    if (rc) { s->intra_bw.swap(bw); s->intra_lat.swap(lat); }     // nothing changed on the device: keep the old table
+    return rc;
 }
 
 int ff_sim_set_ties(ff_sim_t* s, const uint32_t* leader) {
@@ -481,7 +485,9 @@ int ff_sim_set_ties(ff_sim_t* s, const uint32_t* leader) {
             if (t[i] >= n || t[t[i]] != t[i]) return FF_EINVAL;      // a leader leads itself
     }
     s->ties.swap(t);
-    return apply_link_tables(s);
+    const int rc = apply_link_tables(s);
+    if (rc) s->ties.swap(t);
+    return rc;
 }
 
 int ff_sim_set_node_links(ff_sim_t* s, const ff_nodelinks_t* links) {
@@ -501,7 +507,9 @@ int ff_sim_set_node_links(ff_sim_t* s, const ff_nodelinks_t* links) {
     }
     s->node_bw.swap(bw);
     s->node_lat.swap(lat);
-    return apply_link_tables(s);
+    const int rc = apply_link_tables(s);
+    if (rc) { s->node_bw.swap(bw); s->node_lat.swap(lat); }
+    return rc;
 }
 
 size_t ff_sim_workspace_bytes(const ff_sim_t* s, uint32_t B) {

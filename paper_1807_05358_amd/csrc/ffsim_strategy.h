@@ -269,7 +269,11 @@ struct SimT {
     // the same for part k of op j (k may differ per lane)
     template <bool REG>
     __device__ __forceinline__ uint32_t device_of_part(uint32_t j, const OpCfg& c, uint32_t k) const {
-        if (EXT && !REG && devmap) return k < c.parts ? devmap[(size_t)j * WAVE + k] : 0u;
+        if (EXT && !REG && devmap) {
+            // (the entry is requested before the number of parts is known; one beyond the parts is dropped)
+            const uint32_t d = devmap[(size_t)j * WAVE + (k & (WAVE - 1))];
+            return k < c.parts ? d : 0u;
+        }
         return part_device<REG>(c, k, S);
     }
 };
