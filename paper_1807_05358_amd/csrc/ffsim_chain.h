@@ -106,6 +106,22 @@ __device__ __forceinline__ uint32_t resume_point(const SimX& m, const u64* end_o
         }
     }
     if (ballot(((uint32_t)lane < cn.parts && pend_new == 0) || ((uint32_t)lane < co.parts && pend_old == 0))) tau = 0;
+    if (SimX::kTrain) {
+        // Which consumer parts a part of op mo contributes to depends on how op mo is cut (a coarser part also
+        // covers what lies between the ranges of finer ones), unlike which consumer parts READ op mo at all.  A
+        // consumer part that takes a contribution from op mo under one of the two configurations and none
+        // under the other may be dequeued at any time in one of the two timelines: start from time 0.
+        const uint32_t ob = m.T.ops[mo].out_begin, oe = m.T.ops[mo].out_end;
+        for (uint32_t ei = ob; ei < oe; ei++) {
+            const DEdge e = m.T.edges[ei];
+            if (!e.kind) continue;
+            const OpCfg cj = m.cfg(e.dst);
+            const uint32_t digits = part_digits(cj, lane, m.magic_v);
+            const uint32_t was = count_inputs<true>(e, co, cj.x, digits, m.magic_v);
+            const uint32_t is = count_inputs<true>(e, cn, cj.x, digits, m.magic_v);
+            if (ballot((uint32_t)lane < cj.parts && (was == 0) != (is == 0))) tau = 0;
+        }
+    }
     u64 k64 = (2 * tau) / meta.step;
     if (k64 > meta.n_valid - 1) k64 = meta.n_valid - 1;
     return (uint32_t)k64;

@@ -173,7 +173,70 @@ def _oracle_chain(ops, edges, machine, cost, cfg0, tuple_ptr, tuples, accept, bu
     return trace
 
 
-@pytest.mark.parametrize("seed", range(4))
+def _gap_graph():
+    """op 2 (4 elements) contributes to op 3 (12 elements) with stride 3: cut into four parts it reaches elements
+    0, 3, 6, 9 only; as one part it reaches 0..9.  Parts of op 3 that lie between take a contribution from op 2
+    under the second configuration and none under the first.  Op 0 (slow) keeps op 2 late; op 1 (fast) feeds op 3."""
+    g = W.GraphBuilder()
+    g.op(W.T_ELEM, [4], [0], 1)
+    g.op(W.T_ELEM, [12], [0], 1)
+    g.op(W.T_ELEM, [4], [0], 1)
+    g.op(W.T_ELEM, [12], [0], 1)
+    g.op(W.T_ELEM, [12], [0], 1)
+    g.edge(0, 2, [(0, 1, 0, 0)])
+    g.edge(1, 3, [(0, 1, 0, 0)])
+    g.edges.append((2, 3, [(0, 3, 0, 0)]))
+    g.edge(3, 4, [(0, 1, 0, 0)])
+    ops, edges, _ = g.finish()
+    edges[2]["map"]["pad"] = 1                      # 2 -> 3 is the contributing edge
+    mach = W.Machine(2, 4, 16, 8, 5, 20, 4)
+    cost = np.zeros((5, 64), "<u4")
+    cost[0] = 60000; cost[1] = 700; cost[2] = 900; cost[3] = 1100; cost[4] = 1300
+    cost -= (np.arange(64, dtype=np.uint32) * 7)[None, :]
+    return ops, edges, mach, cost
+
+
+def test_chain_when_a_consumer_part_gains_or_loses_a_contribution(B):
+    """Section 5.3 on a contributing edge: which consumer parts a producer contributes to depends on how the PRODUCER is
+    cut, so a mutation of the producer can give a consumer part, that ran long ago in the accepted timeline, a new
+    input (and take one away): such steps cannot resume from a late snapshot."""
+    ops, edges, mach, cost = _gap_graph()
+    cfg0 = np.zeros((2, 5), W.CFG_DT)
+    cfg0["deg"] = 1
+    cfg0["dev_stride"] = 1
+    cfg0["deg"][:, 0, 0] = 2; cfg0["deg"][:, 1, 0] = 6; cfg0["deg"][:, 3, 0] = 12; cfg0["deg"][:, 4, 0] = 3
+    cfg0["deg"][0, 2, 0] = 4                        # chain 0 starts fine-grained, chain 1 with op 2 in one part
+    cfg0["dev_offset"] = np.array([0, 3, 5, 1, 6])[None, :]
+    tg_fine = oracle.build_task_graph(ops, edges, mach, cost, cfg0[0])
+    tg_one = oracle.build_task_graph(ops, edges, mach, cost, cfg0[1])
+    assert tg_one.n_deps > tg_fine.n_deps           # the one-part producer reaches consumer parts the four parts do not
+    steps = [(2, 1, 5), (2, 4, 5), (2, 2, 0), (3, 6, 2), (2, 1, 7), (0, 4, 1), (2, 4, 2), (4, 12, 0), (2, 2, 3), (2, 1, 1), (2, 4, 4)]
+    muts = np.zeros((len(steps), 2), W.MUT_DT)
+    for s, (op, deg, off) in enumerate(steps):
+        for c in range(2):
+            muts[s, c]["op"] = op
+            muts[s, c]["cfg"]["deg"] = [deg if c == 0 else {1: 4, 4: 1}.get(deg, deg) if op == 2 else deg, 1, 1, 1]
+            muts[s, c]["cfg"]["dev_offset"] = off
+            muts[s, c]["cfg"]["dev_stride"] = 1
+    sim = B.Simulator(ops, edges, mach, cost)
+    ch = B.Chains(sim, cfg0)
+    assert np.array_equal(ch.start_ns(), oracle.simulate_batch(ops, edges, mach, cost, cfg0))
+    got = ch.delta(ch.upload_mutations(muts), len(steps)).cpu().numpy().view("<u8")
+    for c in range(2):
+        ref = oracle.simulate_delta_chain(ops, edges, mach, cost, cfg0[c], muts[:, c])
+        assert np.array_equal(got[:, c], ref), f"chain {c}: steps {np.nonzero(got[:, c] != ref)[0]}"
+    # the same mutations as proposals against the unchanged chains
+    ch2 = B.Chains(sim, cfg0)
+    tried = ch2.try_mutations(ch2.upload_mutations(muts), len(steps)).cpu().numpy().view("<u8")
+    for c in range(2):
+        for s in range(len(steps)):
+            cfg = cfg0[c].copy()
+            cfg[int(muts[s, c]["op"])] = muts[s, c]["cfg"]
+            assert int(tried[s, c]) == int(oracle.simulate_batch(ops, edges, mach, cost, cfg[None])[0]), (c, s)
+    ch.close(); ch2.close(); sim.close()
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3, 28, 39])
 def test_random_graphs_with_contributing_edges(B, seed):
     """random DAGs whose edges are reading or contributing at random, random affine maps, general and regular
     strategies, random ties among ops of equal shape"""
