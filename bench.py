@@ -531,6 +531,41 @@ def main():
                            "median_start_ns": float(np.median(start)), "median_best_ns": float(np.median(best_ns))})
             ch.close()
         line["search"] = search
+        # one chain is one wavefront in ff_sim_search; ff_sim_search_ahead simulates the proposals of the coming
+        # steps side by side (the same chain, step for step).  It pays when few proposals are accepted.
+        few = []
+        for cid, n_steps, start_kind in ((1, 4000, "data parallelism"), (1, 2000, "random strategy"), (2, 600, "data parallelism")):
+            if cid not in results:
+                continue
+            _, sim_s, w_s, cfgs_s = results[cid]
+            cfg0 = cfgs_s[:1].copy()
+            if start_kind == "data parallelism":
+                cfg0[0] = W.data_parallel_strategy(w_s.ops, w_s.machine.n_devices, w_s.max_parts)
+            tp, tu = w_s.search_space()
+            rec = {"workload": f"configs[{cid}] {w_s.name}", "chains": 1, "steps": n_steps, "start": start_kind}
+            traces = []
+            for ahead in (0, 4096):
+                ch = binding.Chains(sim_s, cfg0)
+                t_start = float(ch.start_ns()[0])
+                bucket = max(1, int(t_start * 0.02 * 8 / 256))
+                ch.search_setup(tp, tu, binding.ff_sim_accept_table(1.0 / (t_start * 0.02), bucket, 256), bucket, 1807)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                tr = ch.search(n_steps, ahead=ahead)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                traces.append(tr.cpu().numpy().view("<u8"))
+                if ahead:
+                    rec["ahead_steps_per_s"] = n_steps / dt
+                    rec["ahead_rounds"], rec["ahead_proposals_simulated"] = int(ch.ahead_stats[0]), int(ch.ahead_stats[1])
+                else:
+                    rec["one_by_one_steps_per_s"] = n_steps / dt
+                ch.close()
+            rec["same_trace"] = bool(np.array_equal(traces[0], traces[1]))
+            rec["steps_that_changed_the_time"] = int((np.diff(np.concatenate([[t_start], traces[0][:, 0].astype(np.float64)])) != 0).sum())
+            rec["speedup"] = rec["ahead_steps_per_s"] / rec["one_by_one_steps_per_s"]
+            few.append(rec)
+        line["search_with_one_chain"] = few
         # the whole search with parameter-synchronisation traffic simulated (ff_sim_set_params): can it
         # beat data parallelism, as Section 8 reports?  (a simulator of its own, the timed kernels above
         # never see the refinement)

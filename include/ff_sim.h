@@ -368,6 +368,31 @@ typedef struct {
 int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_steps, uint64_t* d_trace_ns,
                   void* hip_stream);
 
+/* The same search, with the same result in every respect that ff_sim_search documents (trace, best
+ * times and strategies, the chains' strategies afterwards), for callers with FEWER chains than the
+ * GPU has room for: one chain is one wavefront in ff_sim_search, whatever the size of the device.
+ * Section 6.2's proposal for a step depends on the step's random draws alone, not on the chain's
+ * strategy, and a rejected proposal leaves the strategy as it was (Section 6.1).  So the proposals of
+ * the next K steps of every chain are simulated side by side, each against the chain's current
+ * strategy (the trial kernel of ff_sim_delta_try); a chain then walks through them in order, takes
+ * the decisions of ff_sim_search with the same draws, and stops at the first proposal it accepts,
+ * which is simulated once more and committed; what was simulated for the steps after it is dropped,
+ * and the next round starts from there.  A round costs about two simulations and takes a chain to
+ * its first accepted proposal, so it pays when few proposals are accepted (the later, longer part
+ * of a search): the call measures the share of accepted proposals as it goes, simulates ahead
+ * (K about two over that share, at most max_ahead and at most what the trial kernel has wavefronts
+ * for) while the share is below a quarter, and otherwise -- or when the chains alone fill the
+ * device -- simulates the steps one by one in stretches (8 steps, then 32, 128, ...: between
+ * stretches the chains wait for each other, which costs when their steps differ in length).
+ * Needs the handle's workspace to hold ff_sim_delta_try_workspace_bytes(chains, max_ahead) bytes
+ * (FF_EWORKSPACE otherwise).  NOT asynchronous: the call allocates its buffers on first use and waits
+ * for hip_stream after every round (it copies C integers back to see how far the chains are), so
+ * it cannot be captured into a graph.  h_stats (HOST, may be null): rounds taken, proposals
+ * simulated ahead, steps made (n_steps * C when the call returns FF_OK). */
+typedef struct { uint64_t rounds, proposals_simulated, steps; } ff_ahead_stats_t;
+int ff_sim_search_ahead(ff_chains_t* chains, const ff_search_t* params, uint32_t n_steps, uint32_t max_ahead,
+                        uint64_t* d_trace_ns, void* hip_stream, ff_ahead_stats_t* h_stats);
+
 /* The acceptance table of ff_sim_search for the Metropolis rule of Section 6.1 with a given beta:
  * out[b] = floor(2^32 * exp(-beta_per_ns * b * bucket_ns)), capped at 2^32 - 1 -- the probability
  * of accepting a proposal that is slower by b * bucket_ns, the lower edge of bucket b (so a

@@ -37,13 +37,17 @@ class ff_costtable_t(C.Structure):
 EXPORTS = ["ff_sim_create", "ff_sim_create_tuplecost", "ff_sim_destroy", "ff_sim_set_links", "ff_sim_set_node_links", "ff_sim_set_ties", "ff_sim_set_params",
            "ff_sim_workspace_bytes", "ff_sim_set_workspace", "ff_sim_set_stats",
            "ff_sim_batch", "ff_sim_batch_devmaps", "ff_sim_chains_create", "ff_sim_delta", "ff_sim_chains_destroy", "ff_sim_chains_get_stats",
-           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search", "ff_sim_accept_table",
+           "ff_sim_delta_try", "ff_sim_delta_try_workspace_bytes", "ff_sim_search", "ff_sim_search_ahead", "ff_sim_accept_table",
            "ff_sim_batch_kernel_name",
            "ff_sim_neighbour_count", "ff_sim_neighbours", "ff_sim_neighbours_noalloc",
            "ff_sim_strerror"]
 CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events", "<u8"), ("n_events_full", "<u8"),
                            ("n_converged", "<u8")])
 
+
+
+class ff_ahead_stats_t(C.Structure):
+    _fields_ = [("rounds", C.c_uint64), ("proposals_simulated", C.c_uint64), ("steps", C.c_uint64)]
 
 
 class ff_linktable_t(C.Structure):
@@ -124,6 +128,8 @@ def lib():
         L.ff_sim_delta_try_workspace_bytes.argtypes = [vp, u32]
         L.ff_sim_search.restype = C.c_int
         L.ff_sim_search.argtypes = [vp, C.POINTER(ff_search_t), u32, vp, vp]
+        L.ff_sim_search_ahead.restype = C.c_int
+        L.ff_sim_search_ahead.argtypes = [vp, C.POINTER(ff_search_t), u32, u32, vp, vp, C.POINTER(ff_ahead_stats_t)]
         L.ff_sim_accept_table.restype = C.c_int
         L.ff_sim_accept_table.argtypes = [C.c_double, C.c_uint64, u32, vp]
         L.ff_sim_batch_kernel_name.restype = C.c_int
@@ -281,6 +287,13 @@ def ff_sim_delta_try(chains, d_muts, M, d_out_ns, stream=None):
 
 def ff_sim_search(chains, params, n_steps, d_trace_ns, stream=None):
     _check(lib().ff_sim_search(chains, C.byref(params), n_steps, d_trace_ns, stream), "ff_sim_search")
+
+
+def ff_sim_search_ahead(chains, params, n_steps, max_ahead, d_trace_ns, stream=None):
+    """returns (rounds, proposals simulated ahead, steps made)"""
+    st = ff_ahead_stats_t()
+    _check(lib().ff_sim_search_ahead(chains, C.byref(params), n_steps, max_ahead, d_trace_ns, stream, C.byref(st)), "ff_sim_search_ahead")
+    return st.rounds, st.proposals_simulated, st.steps
 
 
 def ff_sim_neighbour_count(chains, d_tuple_ptr, n_tuples, op_begin, op_end):
@@ -490,9 +503,11 @@ class Chains:
             n_tuples=len(tuples), n_buckets=len(accept), bucket_ns=int(bucket_ns), seed=int(seed), step=0,
             patience=int(patience))
 
-    def search(self, n_steps, d_trace=None):
+    def search(self, n_steps, d_trace=None, ahead=0):
         """n_steps Metropolis steps on every chain; returns the device tensor [n_steps][C] of the
-        chains' times after each step (asynchronous apart from the argument check)."""
+        chains' times after each step (asynchronous apart from the argument check).
+        ahead > 0: ff_sim_search_ahead with up to that many proposals per chain simulated side by side (same
+        results; synchronous; self.ahead_stats then holds (rounds, proposals simulated, steps))."""
         torch = _torch()
         sp = self._sp
         if d_trace is None:
@@ -500,7 +515,12 @@ class Chains:
         p = ff_search_t(sp["seed"], sp["step"], sp["bucket_ns"], sp["patience"], sp["n_buckets"], sp["n_tuples"],
                         sp["accept"].data_ptr(), sp["tuple_ptr"].data_ptr(), sp["tuples"].data_ptr(),
                         sp["best_ns"].data_ptr(), sp["best"].data_ptr())
-        ff_sim_search(self.handle, p, n_steps, d_trace.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        stream = torch.cuda.current_stream().cuda_stream
+        if ahead:
+            self._ensure_try_workspace(ahead)
+            self.ahead_stats = ff_sim_search_ahead(self.handle, p, n_steps, ahead, d_trace.data_ptr(), stream)
+        else:
+            ff_sim_search(self.handle, p, n_steps, d_trace.data_ptr(), stream)
         sp["step"] += n_steps
         return d_trace
 

@@ -77,6 +77,11 @@ struct ff_chains {
     uint32_t links_gen = 0;        // sim->links_gen when the chains were created
     const uint32_t* checked_ptr = nullptr;   // the proposal ranges ff_sim_search has checked last
     uint32_t checked_n = 0;
+    // ff_sim_search_ahead: proposals [K][C], their simulated times [K][C], steps done per chain [C]; K <= ahead_cap
+    uint32_t* d_ahead_muts = nullptr;
+    uint64_t* d_ahead_ns = nullptr;
+    uint32_t* d_ahead_done = nullptr;
+    uint32_t ahead_cap = 0;
 };
 
 // Scratch of ff_sim_neighbours_noalloc: the index of every op's first neighbour (one entry per op of the
@@ -637,12 +642,11 @@ int ff_sim_delta(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t n_steps, 
     return launch_chain_steps(c, d_muts, n_steps, d_out_ns, (hipStream_t)hip_stream, SearchDev{});
 }
 
-int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64_t* d_trace_ns, void* hip_stream) {
-    if (!c || !p || (n_steps && !d_trace_ns)) return FF_EINVAL;
+// checks the search parameters and fills what the kernels take of them
+static int search_params(ff_chains_t* c, const ff_search_t* p, SearchDev* out) {
     if (c->links_gen != c->sim->links_gen) return FF_EINVAL;
     if (!p->d_accept || !p->d_tuple_ptr || !p->d_tuples || !p->d_best_ns || !p->d_best || p->n_buckets < 1 || p->bucket_ns < 1 ||
         p->n_tuples < 1) return FF_EINVAL;
-    if (n_steps == 0) return FF_OK;
     // the per-op ranges index the tuple list on the device: they are read back and checked when a
     // chain set sees a list for the first time; later calls with the same list only launch
     if (c->checked_ptr != p->d_tuple_ptr || c->checked_n != p->n_tuples) {
@@ -659,7 +663,93 @@ int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64
     sd.accept = p->d_accept; sd.tuple_ptr = p->d_tuple_ptr; sd.tuples = p->d_tuples;
     sd.n_buckets = p->n_buckets; sd.enabled = 1; sd.patience = p->patience; sd.n_tuples = p->n_tuples;
     sd.best_ns = (u64*)p->d_best_ns; sd.best_cfgs = (uint2*)p->d_best;
+    *out = sd;
+    return FF_OK;
+}
+
+int ff_sim_search(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint64_t* d_trace_ns, void* hip_stream) {
+    if (!c || !p || (n_steps && !d_trace_ns)) return FF_EINVAL;
+    if (n_steps == 0) return c->links_gen != c->sim->links_gen ? FF_EINVAL : FF_OK;
+    SearchDev sd{};
+    const int rc = search_params(c, p, &sd);
+    if (rc) return rc;
     return launch_chain_steps(c, nullptr, n_steps, d_trace_ns, (hipStream_t)hip_stream, sd);
+}
+
+// the trial kernel on M proposals per chain (d_muts [M][C]); the caller has checked the workspace
+static int launch_trials(ff_chains* c, const uint32_t* d_muts, uint32_t M, uint64_t* d_out_ns, hipStream_t st) {
+    ff_sim* s = c->sim;
+    const uint32_t total = M * c->C;
+    const uint32_t slots = std::min(total, s->max_try_slots);
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(WAVE), 0, st, c->d_counter);
+    if (!allow_lds((const void*)try_kernel(s), s->lds_common)) return FF_EHIP;
+    hipLaunchKernelGGL(try_kernel(s), dim3(slots), dim3(WAVE), s->lds_common, st, s->dev, s->d_ops, s->d_edges,
+                       s->d_in_edges, s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, d_muts, M,
+                       (u64*)d_out_ns, c->d_flags, c->d_counter, (unsigned char*)s->ws, s->slot_bytes);
+    return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
+}
+
+int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint32_t max_ahead, uint64_t* d_trace_ns,
+                        void* hip_stream, ff_ahead_stats_t* h_stats) {
+    if (!c || !p || (n_steps && !d_trace_ns) || max_ahead < 1) return FF_EINVAL;
+    if (h_stats) *h_stats = ff_ahead_stats_t{0, 0, 0};
+    if (n_steps == 0) return c->links_gen != c->sim->links_gen ? FF_EINVAL : FF_OK;
+    SearchDev sd{};
+    int rc = search_params(c, p, &sd);
+    if (rc) return rc;
+    ff_sim* s = c->sim;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // no more proposals in flight than the trial kernel has wavefronts for
+    const uint64_t fit = std::max<uint64_t>(1, (uint64_t)s->max_try_slots / c->C);
+    const uint32_t cap = (uint32_t)std::min<uint64_t>(std::min<uint64_t>(max_ahead, fit), n_steps);
+    {
+        const uint32_t slots = (uint32_t)std::min<uint64_t>((uint64_t)cap * c->C, s->max_try_slots);
+        if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
+    }
+    if (c->ahead_cap < cap) {
+        hipFree(c->d_ahead_muts); hipFree(c->d_ahead_ns); hipFree(c->d_ahead_done);
+        c->d_ahead_muts = nullptr; c->d_ahead_ns = nullptr; c->d_ahead_done = nullptr; c->ahead_cap = 0;
+        if (hipMalloc((void**)&c->d_ahead_muts, (size_t)cap * c->C * 12) != hipSuccess ||
+            hipMalloc((void**)&c->d_ahead_ns, (size_t)cap * c->C * 8) != hipSuccess ||
+            hipMalloc((void**)&c->d_ahead_done, (size_t)c->C * 8) != hipSuccess) return FF_ENOMEM;   // positions, then counts
+        c->ahead_cap = cap;
+    }
+    hipLaunchKernelGGL(k_zero_words, dim3((2 * c->C + 255) / 256), dim3(256), 0, st, c->d_ahead_done, 2 * c->C);
+    sd.done = c->d_ahead_done;
+    sd.n_accepted = c->d_ahead_done + c->C;
+    std::vector<uint32_t> now(2 * (size_t)c->C, 0), before;
+    // Simulating ahead pays when few proposals are taken: a round costs about two simulations (the proposals side
+    // by side, then the one that is taken) and advances a chain to its first accepted proposal.  The share of
+    // accepted proposals is measured as the search goes (it falls as the chains settle); while it is high, or when
+    // the chains alone fill the device, the steps are simulated one by one as in ff_sim_search.
+    uint32_t block = 8;                    // steps of a stretch without look-ahead: four times longer after each in a row
+    double taken_share = 1.0;
+    for (;;) {
+        uint32_t K = 0;
+        if (cap >= 4 && taken_share < 0.25) K = (uint32_t)std::min<double>(cap, std::max(4.0, 2.0 / std::max(taken_share, 1e-3)));
+        sd.ahead_ns = K ? (const u64*)c->d_ahead_ns : nullptr;
+        sd.n_ahead = K ? K : block;
+        block = K ? 8 : (block > n_steps / 4 ? n_steps : block * 4);
+        if (K) {
+            const uint32_t n = K * c->C;
+            hipLaunchKernelGGL(k_search_ahead_proposals, dim3((n + 255) / 256), dim3(256), 0, st, sd, s->dev.n_ops, s->dev.n_dev, c->C,
+                               n_steps, c->d_ahead_muts);
+            if ((rc = launch_trials(c, c->d_ahead_muts, K, c->d_ahead_ns, st))) return rc;
+        }
+        if ((rc = launch_chain_steps(c, nullptr, n_steps, d_trace_ns, st, sd))) return rc;
+        before = now;
+        if (hipMemcpyAsync(now.data(), c->d_ahead_done, now.size() * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+            hipStreamSynchronize(st) != hipSuccess) return FF_EHIP;
+        uint64_t advanced = 0, active = 0, unfinished = 0, taken = 0;
+        for (uint32_t k = 0; k < c->C; k++) {
+            if (before[k] < n_steps) { active++; advanced += now[k] - before[k]; taken += now[c->C + k] - before[c->C + k]; }
+            if (now[k] < n_steps) unfinished++;
+        }
+        if (h_stats) { h_stats->rounds++; h_stats->proposals_simulated += K ? (uint64_t)K * active : advanced; h_stats->steps += advanced; }
+        if (!unfinished) break;
+        if (advanced) taken_share = 0.5 * taken_share + 0.5 * (double)taken / (double)advanced;
+    }
+    return FF_OK;
 }
 
 // host copy of the per-op tuple ranges, validated; first[o - op_begin] = index of op o's first neighbour
@@ -764,12 +854,7 @@ int ff_sim_delta_try(ff_chains_t* c, const ff_mutation_t* d_muts, uint32_t M, ui
     const uint32_t total = M * c->C;
     const uint32_t slots = std::min(total, s->max_try_slots);
     if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(WAVE), 0, (hipStream_t)hip_stream, c->d_counter);
-    if (!allow_lds((const void*)try_kernel(s), s->lds_common)) return FF_EHIP;
-    hipLaunchKernelGGL(try_kernel(s), dim3(slots), dim3(WAVE), s->lds_common, (hipStream_t)hip_stream, s->dev, s->d_ops, s->d_edges,
-                       s->d_in_edges, s->d_cost, s->d_magic, c->d_mem, c->stride, c->n_snaps, c->C, (const uint32_t*)d_muts, M,
-                       (u64*)d_out_ns, c->d_flags, c->d_counter, (unsigned char*)s->ws, s->slot_bytes);
-    return hipGetLastError() == hipSuccess ? FF_OK : FF_EHIP;
+    return launch_trials(c, (const uint32_t*)d_muts, M, d_out_ns, (hipStream_t)hip_stream);
 }
 
 int ff_sim_chains_get_stats(ff_chains_t* c, ff_chain_stats_t* h_out) {
@@ -793,6 +878,9 @@ void ff_sim_chains_destroy(ff_chains_t* c) {
     hipFree(c->d_mem);
     hipFree(c->d_flags);
     hipFree(c->d_counter);
+    hipFree(c->d_ahead_muts);
+    hipFree(c->d_ahead_ns);
+    hipFree(c->d_ahead_done);
     delete c;
 }
 

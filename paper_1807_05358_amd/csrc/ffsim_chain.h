@@ -193,7 +193,46 @@ struct SearchDev {
     u64 patience;                // a chain stops proposing after this many steps without a new best (0 = never)
     u64* best_ns;                // [C] best simulated time seen (in/out)
     uint2* best_cfgs;            // [C][n_ops] the strategy that achieved it (in/out)
+    // ff_sim_search_ahead: every chain has its own position in the call's steps, and a launch takes it at most
+    // n_ahead steps further.
+    // Look-ahead (ahead_ns given).  The proposal of a step does not depend on the chain's strategy, and a
+    // rejected proposal leaves it unchanged: the proposals of the next n_ahead steps of every chain have been
+    // simulated beforehand, each against the chain's current strategy (ahead_ns[j][c] for step done[c] + j), and
+    // are valid for as long as everything before them is rejected.  A chain walks through them without
+    // simulating, and stops for this launch after the first one it accepts.
+    const u64* ahead_ns;         // [n_ahead][C] or null (every proposal is simulated in its turn)
+    uint32_t* done;              // [C] steps of the call that the chain has finished (in/out), or null (all chains in step)
+    uint32_t* n_accepted;        // [C] proposals taken so far (in/out; with done)
+    uint32_t n_ahead;
 };
+
+// The proposal of step st of chain c (Section 6.2): a random op, one of its listed degree tuples, a random
+// device offset, stride 1.  false if the op has no list.  The same draws whoever asks.
+__device__ __forceinline__ bool search_proposal(const SearchDev& search, uint32_t n_ops, uint32_t n_dev, uint32_t c, u64 st,
+                                                uint32_t& op, uint2& cfg) {
+    op = (uint32_t)(draw64(search.seed, 10, c, st) % n_ops);
+    // (the host has checked the ranges; the clamp keeps the read inside the list even if the
+    // caller changed them afterwards)
+    const uint32_t t0 = search.tuple_ptr[op];
+    const uint32_t t1r = search.tuple_ptr[op + 1];
+    const uint32_t t1 = t1r < search.n_tuples ? t1r : search.n_tuples;
+    if (t1 <= t0) return false;
+    const uint32_t deg = search.tuples[t0 + (uint32_t)(draw64(search.seed, 11, c, st) % (t1 - t0))];
+    const uint32_t off = (uint32_t)(draw64(search.seed, 12, c, st) % n_dev);
+    cfg = make_uint2(deg, off | (1u << 16));   // stride 1
+    return true;
+}
+
+// Section 6.1 with tabulated probabilities: is a proposal with simulated time mk taken by a chain whose
+// strategy takes cur?  (mk: a time, or one of the RESULT_* codes, which are never taken)
+__device__ __forceinline__ bool search_accepts(const SearchDev& search, uint32_t c, u64 st, u64 mk, u64 cur) {
+    if (mk >= RESULT_OVERFLOW) return false;
+    if (mk <= cur) return true;
+    u64 b = (mk - cur) / search.bucket_ns;
+    if (b >= search.n_buckets) b = search.n_buckets - 1;
+    const uint32_t u = (uint32_t)(draw64(search.seed, 13, c, st) >> 32);
+    return u < search.accept[b];
+}
 
 // the kept set-up of op j's in-edges follows its configuration
 template <class SimX>
@@ -297,28 +336,37 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         for (uint32_t i = lane; i < S.n_ops; i += WAVE) search.best_cfgs[(size_t)c * S.n_ops + i] = cfg_lds[i];
     }
 
-    for (uint32_t s = 0; s < n_steps; s++) {
+    // look-ahead: this launch takes the chain from step done[c] up to its first accepted proposal, at most n_ahead steps
+    const bool own_position = search.enabled && search.done != nullptr;
+    const bool ahead = own_position && search.ahead_ns != nullptr;
+    uint32_t s_begin = 0, s_end = n_steps, n_taken = 0;
+    if (own_position) {
+        s_begin = first_u32(search.done[c]);
+        s_begin = s_begin < n_steps ? s_begin : n_steps;
+        s_end = n_steps - s_begin < search.n_ahead ? n_steps : s_begin + search.n_ahead;
+    }
+    uint32_t s = s_begin;
+    for (; s < s_end; s++) {
         Counters cnt = {};
         bool proposal = false, valid = true;
+        bool known_rejected = false;     // look-ahead: simulated beforehand and not taken
         uint32_t op = 0;
         uint2 ocfg = make_uint2(0, 0);
         if (search.enabled) {
             if (!poisoned && !meta.stale && !(search.patience && meta.idle_steps >= search.patience)) {
                 const u64 st = search.first_step + s;
-                op = first_u32((uint32_t)(draw64(search.seed, 10, c, st) % S.n_ops));
-                // (the host has checked the ranges; the clamp keeps the read inside the list even if the
-                // caller changed them afterwards)
-                const uint32_t t0 = first_u32(search.tuple_ptr[op]);
-                const uint32_t t1r = first_u32(search.tuple_ptr[op + 1]);
-                const uint32_t t1 = t1r < search.n_tuples ? t1r : search.n_tuples;
-                if (t1 > t0) {   // an op without a list gets no proposals
-                    const uint32_t deg = search.tuples[t0 + (uint32_t)(draw64(search.seed, 11, c, st) % (t1 - t0))];
-                    const uint32_t off = (uint32_t)(draw64(search.seed, 12, c, st) % S.n_dev);
-                    ocfg = cfg_lds[op];
-                    wave_sync();
-                    if (lane == 0) cfg_lds[op] = make_uint2(first_u32(deg), first_u32(off) | (1u << 16));   // stride 1
-                    wave_sync();
-                    proposal = true;
+                uint2 ncfg;
+                if (search_proposal(search, S.n_ops, S.n_dev, c, st, op, ncfg)) {   // an op without a list gets no proposals
+                    op = first_u32(op);
+                    if (ahead && !search_accepts(search, c, st, first_u64(search.ahead_ns[(size_t)(s - s_begin) * C + c]), meta.cur_ns)) {
+                        known_rejected = true;
+                    } else {
+                        ocfg = cfg_lds[op];
+                        wave_sync();
+                        if (lane == 0) cfg_lds[op] = make_uint2(first_u32(ncfg.x), first_u32(ncfg.y));
+                        wave_sync();
+                        proposal = true;
+                    }
                 }
             }
         } else if (muts) {
@@ -338,11 +386,12 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         }
         u64 mk = RESULT_INVALID;
         StrategyClass cls = STRATEGY_INVALID;
-        if (!poisoned) cls = validate_strategy(m);
-        valid = cls != STRATEGY_INVALID;
+        // (a proposal known to be rejected changes nothing: the strategy in force was validated when it was taken)
+        if (!poisoned && !known_rejected) cls = validate_strategy(m);
+        valid = known_rejected || cls != STRATEGY_INVALID;
         if (!poisoned && !valid && !proposal) { meta.stale = 1; meta.cur_ns = RESULT_INVALID; }
         const bool changed = muts != nullptr || proposal;
-        if (changed && !poisoned) meta.n_steps++;
+        if ((changed || known_rejected) && !poisoned) meta.n_steps++;
         bool accepted = false;
 
         if (search.enabled && !proposal && !poisoned && !meta.stale) {
@@ -401,15 +450,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
             if (changed) meta.n_events += cnt.n_events;
             // the decision: forced mutations and the starting strategy are always taken; a proposal
             // by the Metropolis rule (Section 6.1) with tabulated probabilities
-            if (!rc) {
-                accepted = true;
-                if (proposal && mk > meta.cur_ns) {
-                    u64 b = (mk - meta.cur_ns) / search.bucket_ns;
-                    if (b >= search.n_buckets) b = search.n_buckets - 1;
-                    const uint32_t u = (uint32_t)(draw64(search.seed, 13, c, search.first_step + s) >> 32);
-                    accepted = u < search.accept[b];
-                }
-            }
+            if (!rc) accepted = proposal ? search_accepts(search, c, search.first_step + s, mk, meta.cur_ns) : true;
             if (accepted) {
                 if (proposal && lane == 0) cm.cfgs[op] = cfg_lds[op];
                 if (k > 0) {
@@ -456,11 +497,15 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         }
         if (lane == 0) out_ns[(size_t)s * C + c] = mk;
         wave_sync();
+        // what was simulated ahead for the later steps assumed the strategy this step has just replaced
+        if (proposal && accepted) n_taken++;
+        if (ahead && proposal && accepted) { s++; break; }
     }
     if (lane == 0) {
         chain_flags[c] = poisoned ? 1u : 0u;
         *cm.meta = meta;
         if (search.enabled) search.best_ns[c] = best;
+        if (own_position) { search.done[c] = s; search.n_accepted[c] += n_taken; }
     }
 }
 

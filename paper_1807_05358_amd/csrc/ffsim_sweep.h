@@ -100,6 +100,28 @@ __global__ __launch_bounds__(WAVE) void k_best_of(const u64* __restrict__ ns, ui
 }
 
 // clears the work counter of k_sim_chain_try (a kernel, so that a captured stream sees a node)
+// the proposals of the steps done[c] .. done[c] + n_ahead - 1 of every chain, as mutation records
+// [n_ahead][C] {op, cfg.x, cfg.y}; op = all ones where there is none (no list, or beyond the call's steps)
+__global__ void k_search_ahead_proposals(SearchDev search, uint32_t n_ops, uint32_t n_dev, uint32_t C, uint32_t n_steps, uint32_t* muts) {
+    const uint32_t idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= search.n_ahead * C) return;
+    const uint32_t j = idx / C, c = idx % C;
+    const uint32_t s = search.done[c] + j;
+    uint32_t op = 0xffffffffu;
+    uint2 cfg = make_uint2(0, 0);
+    if (s < n_steps) {
+        uint32_t o;
+        if (search_proposal(search, n_ops, n_dev, c, search.first_step + s, o, cfg)) op = o;
+    }
+    muts[(size_t)idx * 3 + 0] = op;
+    muts[(size_t)idx * 3 + 1] = cfg.x;
+    muts[(size_t)idx * 3 + 2] = cfg.y;
+}
+
 __global__ void k_zero_u32(uint32_t* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
+__global__ void k_zero_words(uint32_t* p, uint32_t n) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
 
 }  // namespace ffsim

@@ -40,10 +40,11 @@ def starting_strategies(ops, machine, max_parts, choices, n_chains, seed):
 
 
 def find_strategy(sim: B.Simulator, ops, machine, max_parts, choices, n_chains=64, steps=256, steps_per_call=64,
-                  accept_scale=0.02, n_buckets=256, seed=1, start=None) -> SearchResult:
+                  accept_scale=0.02, n_buckets=256, seed=1, start=None, ahead=0) -> SearchResult:
     """runs n_chains independent Markov chains for `steps` steps each and returns the best
     strategy any of them has seen.  `start`: [n_chains][n_ops] starting strategies (default: see
-    starting_strategies)."""
+    starting_strategies).  `ahead`: with few chains, let ff_sim_search_ahead simulate up to that many
+    proposals per chain side by side (the same chains, step for step; only faster)."""
     cfg0 = starting_strategies(ops, machine, max_parts, choices, n_chains, seed) if start is None else np.ascontiguousarray(start, W.CFG_DT)
     n_chains = len(cfg0)
     chains = B.Chains(sim, cfg0)
@@ -61,7 +62,7 @@ def find_strategy(sim: B.Simulator, ops, machine, max_parts, choices, n_chains=6
         done = 0
         while done < steps:
             n = min(steps_per_call, steps - done)
-            traces.append(chains.search(n).cpu().numpy().view("<u8"))
+            traces.append(chains.search(n, ahead=ahead).cpu().numpy().view("<u8"))
             done += n
         best_ns, best = chains.best()
     finally:

@@ -16,7 +16,7 @@ def B():
     return binding
 
 
-def _run_both(B, config_id, C, calls, beta_rel, seed, n_buckets=64):
+def _run_both(B, config_id, C, calls, beta_rel, seed, n_buckets=64, ahead=0):
     """beta_rel: beta * (start time of chain 0); the bucket is 1/256 of that time."""
     w = W.workload(config_id)
     sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
@@ -27,7 +27,7 @@ def _run_both(B, config_id, C, calls, beta_rel, seed, n_buckets=64):
     table = S.metropolis_table(beta_rel / t0, bucket, n_buckets)
     ch = B.Chains(sim, cfg0)
     ch.search_setup(tp, tu, table, bucket, seed)
-    got = np.concatenate([ch.search(n).cpu().numpy().view("<u8") for n in calls])
+    got = np.concatenate([ch.search(n, ahead=ahead).cpu().numpy().view("<u8") for n in calls])
     best_ns, best = ch.best()
     n_acc_total = 0
     for c in range(C):
@@ -59,6 +59,73 @@ def test_search_matches_oracle(B, config_id, C, calls, beta_rel):
     assert n_acc > 0
     if n >= 24:
         assert n_acc < n      # the case exercises both outcomes
+
+
+@pytest.mark.parametrize("config_id,C,calls,beta_rel,ahead", [
+    (0, 4, (40, 25), 20.0, 1),
+    (0, 4, (40, 25), 20.0, 7),
+    (1, 6, (50, 30), 40.0, 3),
+    (1, 2, (81,), 40.0, 500),
+    (2, 3, (14, 10), 60.0, 5),
+    (3, 2, (12,), 60.0, 16),
+    (4, 1, (6,), 100.0, 4),
+])
+def test_search_ahead_matches_oracle(B, config_id, C, calls, beta_rel, ahead):
+    """ff_sim_search_ahead: proposals of the coming steps simulated side by side, the same chain step for step
+    (Sections 6.1, 6.2: a proposal does not depend on the current strategy, a rejection leaves it unchanged)"""
+    got, n_acc, st = _run_both(B, config_id, C, calls, beta_rel, seed=4242 + config_id, ahead=ahead)
+    assert n_acc > 0
+
+
+def test_search_ahead_equals_search_over_a_long_run(B):
+    """the two entry points on 600 steps with a stopping rule that strikes on the way, continued by 40 steps of the
+    other kind: traces, best times and best strategies agree"""
+    w = W.workload(1)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    cfg0 = w.strategies(3)
+    tp, tu = w.search_space()
+    t0 = int(oracle.simulate_batch(w.ops, w.edges, w.machine, w.cost, cfg0[:1])[0])
+    bucket = max(1, t0 // 256)
+    table = B.ff_sim_accept_table(120.0 / t0, bucket, 64)
+    out = []
+    for first, second in ((0, 200), (200, 0)):
+        ch = B.Chains(sim, cfg0)
+        ch.search_setup(tp, tu, table, bucket, 77, patience=150)
+        a = ch.search(600, ahead=first).cpu().numpy().view("<u8")
+        if first:
+            rounds, simulated, steps = ch.ahead_stats
+            assert steps == 600 * 3 and rounds < 600 and simulated >= steps
+            print(f"look-ahead: {rounds} rounds, {simulated} proposals simulated for {steps} steps", flush=True)
+        b = ch.search(40, ahead=second).cpu().numpy().view("<u8")
+        out.append((np.concatenate([a, b]),) + ch.best())
+        ch.close()
+    assert np.array_equal(out[0][0], out[1][0])
+    assert np.array_equal(out[0][1], out[1][1]) and np.array_equal(out[0][2], out[1][2])
+    assert len(np.unique(out[0][0][:, 0])) > 5                        # the chains did move
+    sim.close()
+
+
+def test_search_ahead_argument_errors(B):
+    torch = pytest.importorskip("torch")
+    w = W.workload(1)
+    sim = B.Simulator(w.ops, w.edges, w.machine, w.cost)
+    ch = B.Chains(sim, w.strategies(2))
+    tp, tu = w.search_space()
+    ch.search_setup(tp, tu, np.full(4, 1000, np.uint32), 1000, 5)
+    sp = ch._sp
+    p = B.ff_search_t(sp["seed"], 0, sp["bucket_ns"], 0, sp["n_buckets"], sp["n_tuples"], sp["accept"].data_ptr(),
+                      sp["tuple_ptr"].data_ptr(), sp["tuples"].data_ptr(), sp["best_ns"].data_ptr(), sp["best"].data_ptr())
+    trace = torch.empty((8, 2), dtype=torch.int64, device="cuda")
+    with pytest.raises(B.FFSimError) as e:
+        B.ff_sim_search_ahead(ch.handle, p, 8, 0, trace.data_ptr())
+    assert e.value.code == B.FF_EINVAL
+    B.ff_sim_set_workspace(sim.handle, None, 0)
+    with pytest.raises(B.FFSimError) as e:
+        B.ff_sim_search_ahead(ch.handle, p, 8, 4, trace.data_ptr())
+    assert e.value.code == B.FF_EWORKSPACE
+    assert B.ff_sim_search_ahead(ch.handle, p, 0, 4, None) == (0, 0, 0)
+    ch.close()
+    sim.close()
 
 
 def test_pure_descent_and_always_accept(B):
