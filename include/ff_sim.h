@@ -384,11 +384,14 @@ int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_ste
  * for) while the share is below a quarter, and otherwise -- or when the chains alone fill the
  * device -- simulates the steps one by one in stretches (8 steps, then 32, 128, ...: between
  * stretches the chains wait for each other, which costs when their steps differ in length).
+ * max_ahead | FF_AHEAD_ALWAYS switches the measuring off: every round simulates ahead, with K =
+ * max_ahead (or what fits), for callers who know that few proposals will be taken.
  * Needs the handle's workspace to hold ff_sim_delta_try_workspace_bytes(chains, max_ahead) bytes
  * (FF_EWORKSPACE otherwise).  NOT asynchronous: the call allocates its buffers on first use and waits
  * for hip_stream after every round (it copies C integers back to see how far the chains are), so
  * it cannot be captured into a graph.  h_stats (HOST, may be null): rounds taken, proposals
  * simulated ahead, steps made (n_steps * C when the call returns FF_OK). */
+#define FF_AHEAD_ALWAYS 0x80000000u
 typedef struct { uint64_t rounds, proposals_simulated, steps; } ff_ahead_stats_t;
 int ff_sim_search_ahead(ff_chains_t* chains, const ff_search_t* params, uint32_t n_steps, uint32_t max_ahead,
                         uint64_t* d_trace_ns, void* hip_stream, ff_ahead_stats_t* h_stats);

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libffsim.so")
 
 FF_OK, FF_EINVAL, FF_ENOMEM, FF_EWORKSPACE, FF_ERANGE, FF_EHIP = 0, -1, -2, -3, -4, -5
+FF_AHEAD_ALWAYS = 0x80000000
 FF_INVALID_NS = 2 ** 64 - 1
 FF_INTERNAL_NS = 2 ** 64 - 2
 FF_OVERFLOW_NS = 2 ** 64 - 3
@@ -517,7 +518,7 @@ class Chains:
                         sp["best_ns"].data_ptr(), sp["best"].data_ptr())
         stream = torch.cuda.current_stream().cuda_stream
         if ahead:
-            self._ensure_try_workspace(ahead)
+            self._ensure_try_workspace(ahead & ~FF_AHEAD_ALWAYS)
             self.ahead_stats = ff_sim_search_ahead(self.handle, p, n_steps, ahead, d_trace.data_ptr(), stream)
         else:
             ff_sim_search(self.handle, p, n_steps, d_trace.data_ptr(), stream)

@@ -691,6 +691,8 @@ static int launch_trials(ff_chains* c, const uint32_t* d_muts, uint32_t M, uint6
 
 int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, uint32_t max_ahead, uint64_t* d_trace_ns,
                         void* hip_stream, ff_ahead_stats_t* h_stats) {
+    const bool always = (max_ahead & FF_AHEAD_ALWAYS) != 0;
+    max_ahead &= ~FF_AHEAD_ALWAYS;
     if (!c || !p || (n_steps && !d_trace_ns) || max_ahead < 1) return FF_EINVAL;
     if (h_stats) *h_stats = ff_ahead_stats_t{0, 0, 0};
     if (n_steps == 0) return c->links_gen != c->sim->links_gen ? FF_EINVAL : FF_OK;
@@ -705,6 +707,14 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
     {
         const uint32_t slots = (uint32_t)std::min<uint64_t>((uint64_t)cap * c->C, s->max_try_slots);
         if (!s->ws || s->ws_bytes < (size_t)slots * s->slot_bytes) return FF_EWORKSPACE;
+    }
+    if (cap < 4 && !always) {
+        // the chains alone fill the device (or the caller allows no look-ahead worth a round): ff_sim_search
+        rc = launch_chain_steps(c, nullptr, n_steps, d_trace_ns, st, sd);
+        if (rc) return rc;
+        if (hipStreamSynchronize(st) != hipSuccess) return FF_EHIP;
+        if (h_stats) *h_stats = ff_ahead_stats_t{1, (uint64_t)n_steps * c->C, (uint64_t)n_steps * c->C};
+        return FF_OK;
     }
     if (c->ahead_cap < cap) {
         hipFree(c->d_ahead_muts); hipFree(c->d_ahead_ns); hipFree(c->d_ahead_done);
@@ -726,7 +736,8 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
     double taken_share = 1.0;
     for (;;) {
         uint32_t K = 0;
-        if (cap >= 4 && taken_share < 0.25) K = (uint32_t)std::min<double>(cap, std::max(4.0, 2.0 / std::max(taken_share, 1e-3)));
+        if (always) K = cap;
+        else if (taken_share < 0.25) K = (uint32_t)std::min<double>(cap, std::max(4.0, 2.0 / std::max(taken_share, 1e-3)));
         sd.ahead_ns = K ? (const u64*)c->d_ahead_ns : nullptr;
         sd.n_ahead = K ? K : block;
         block = K ? 8 : (block > n_steps / 4 ? n_steps : block * 4);

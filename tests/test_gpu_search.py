@@ -73,8 +73,11 @@ def test_search_matches_oracle(B, config_id, C, calls, beta_rel):
 def test_search_ahead_matches_oracle(B, config_id, C, calls, beta_rel, ahead):
     """ff_sim_search_ahead: proposals of the coming steps simulated side by side, the same chain step for step
     (Sections 6.1, 6.2: a proposal does not depend on the current strategy, a rejection leaves it unchanged)"""
-    got, n_acc, st = _run_both(B, config_id, C, calls, beta_rel, seed=4242 + config_id, ahead=ahead)
+    got, n_acc, st = _run_both(B, config_id, C, calls, beta_rel, seed=4242 + config_id, ahead=ahead | B.FF_AHEAD_ALWAYS)
     assert n_acc > 0
+    if config_id <= 2:      # and with the call deciding by itself when to simulate ahead
+        again, _, _ = _run_both(B, config_id, C, calls, beta_rel, seed=4242 + config_id, ahead=ahead)
+        assert np.array_equal(got, again)
 
 
 def test_search_ahead_equals_search_over_a_long_run(B):
