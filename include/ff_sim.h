@@ -382,8 +382,8 @@ int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_ste
  * of a search): the call measures the share of accepted proposals as it goes, simulates ahead
  * (K about two over that share, at most max_ahead and at most what the trial kernel has wavefronts
  * for) while the share is below a quarter, and otherwise -- or when the chains alone fill the
- * device -- simulates the steps one by one in stretches (8 steps, then 32, 128, ...: between
- * stretches the chains wait for each other, which costs when their steps differ in length).
+ * device -- simulates the steps one by one in stretches: 8 steps, then stretches that end by the
+ * device's clock, each four times as long as the one before, every chain stopping where it is.
  * max_ahead | FF_AHEAD_ALWAYS switches the measuring off: every round simulates ahead, with K =
  * max_ahead (or what fits), for callers who know that few proposals will be taken.
  * Needs the handle's workspace to hold ff_sim_delta_try_workspace_bytes(chains, max_ahead) bytes

@@ -1,6 +1,7 @@
 // Host side of the C boundary declared in include/ff_sim.h: validation, upload of the
 // constant tables, workspace bookkeeping and kernel launches.  No torch types here.
 #include "../../include/ff_sim.h"
+#include <chrono>
 
 #include <hip/hip_runtime.h>
 
@@ -732,15 +733,26 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
     // by side, then the one that is taken) and advances a chain to its first accepted proposal.  The share of
     // accepted proposals is measured as the search goes (it falls as the chains settle); while it is high, or when
     // the chains alone fill the device, the steps are simulated one by one as in ff_sim_search.
-    uint32_t block = 8;                    // steps of a stretch without look-ahead: four times longer after each in a row
+    // A stretch without look-ahead: the first of a row is 8 steps, timed; the following ones end by the device's
+    // clock, each four times as long as the one before (no chain waits for a slower one: each stops where it is).
+    int clock_khz = 0;
+    int dev_id = 0;
+    if (hipGetDevice(&dev_id) != hipSuccess || hipDeviceGetAttribute(&clock_khz, hipDeviceAttributeWallClockRate, dev_id) != hipSuccess)
+        clock_khz = 0;
+    double stretch_ms = 0.0;               // length of the last stretch of the current row (0: none yet)
     double taken_share = 1.0;
     for (;;) {
         uint32_t K = 0;
         if (always) K = cap;
         else if (taken_share < 0.25) K = (uint32_t)std::min<double>(cap, std::max(4.0, 2.0 / std::max(taken_share, 1e-3)));
         sd.ahead_ns = K ? (const u64*)c->d_ahead_ns : nullptr;
-        sd.n_ahead = K ? K : block;
-        block = K ? 8 : (block > n_steps / 4 ? n_steps : block * 4);
+        sd.n_ahead = K ? K : 8;
+        sd.time_limit = 0;
+        if (!K && stretch_ms > 0.0 && clock_khz > 0) {
+            sd.n_ahead = n_steps;
+            sd.time_limit = (u64)(4.0 * stretch_ms * clock_khz);
+        }
+        const auto t_begin = std::chrono::steady_clock::now();
         if (K) {
             const uint32_t n = K * c->C;
             hipLaunchKernelGGL(k_search_ahead_proposals, dim3((n + 255) / 256), dim3(256), 0, st, sd, s->dev.n_ops, s->dev.n_dev, c->C,
@@ -759,6 +771,7 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
         if (h_stats) { h_stats->rounds++; h_stats->proposals_simulated += K ? (uint64_t)K * active : advanced; h_stats->steps += advanced; }
         if (!unfinished) break;
         if (advanced) taken_share = 0.5 * taken_share + 0.5 * (double)taken / (double)advanced;
+        stretch_ms = K ? 0.0 : std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();
     }
     return FF_OK;
 }

@@ -204,6 +204,9 @@ struct SearchDev {
     uint32_t* done;              // [C] steps of the call that the chain has finished (in/out), or null (all chains in step)
     uint32_t* n_accepted;        // [C] proposals taken so far (in/out; with done)
     uint32_t n_ahead;
+    // without look-ahead: a launch may also end by the clock (ticks of the constant-rate counter, 0 = no limit): every
+    // chain then stops after the step during which the time ran out, wherever it is, and no chain waits for a slower one
+    u64 time_limit;
 };
 
 // The proposal of step st of chain c (Section 6.2): a random op, one of its listed degree tuples, a random
@@ -345,6 +348,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         s_begin = s_begin < n_steps ? s_begin : n_steps;
         s_end = n_steps - s_begin < search.n_ahead ? n_steps : s_begin + search.n_ahead;
     }
+    const u64 clock_begin = (own_position && search.time_limit) ? wall_clock64() : 0;
     uint32_t s = s_begin;
     for (; s < s_end; s++) {
         Counters cnt = {};
@@ -500,6 +504,7 @@ __global__ __launch_bounds__(WAVE) void k_sim_chain_steps(SimDev S, const DOp* _
         // what was simulated ahead for the later steps assumed the strategy this step has just replaced
         if (proposal && accepted) n_taken++;
         if (ahead && proposal && accepted) { s++; break; }
+        if (own_position && search.time_limit && first_u64(wall_clock64() - clock_begin) >= search.time_limit) { s++; break; }
     }
     if (lane == 0) {
         chain_flags[c] = poisoned ? 1u : 0u;
