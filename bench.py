@@ -547,8 +547,9 @@ def main():
             for ahead in (0, 4096):
                 ch = binding.Chains(sim_s, cfg0)
                 t_start = float(ch.start_ns()[0])
-                bucket = max(1, int(t_start * 0.02 * 8 / 256))
-                ch.search_setup(tp, tu, binding.ff_sim_accept_table(1.0 / (t_start * 0.02), bucket, 256), bucket, 1807)
+                scale = 0.25 / len(w_s.ops)            # the search driver's default tolerance
+                bucket = max(1, int(t_start * scale * 8 / 256))
+                ch.search_setup(tp, tu, binding.ff_sim_accept_table(1.0 / (t_start * scale), bucket, 256), bucket, 1807)
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
                 tr = ch.search(n_steps, ahead=ahead)
@@ -558,6 +559,7 @@ def main():
                 if ahead:
                     rec["ahead_steps_per_s"] = n_steps / dt
                     rec["ahead_rounds"], rec["ahead_proposals_simulated"] = int(ch.ahead_stats[0]), int(ch.ahead_stats[1])
+                    rec["proposals_accepted"] = int(ch.ahead_stats[3])
                 else:
                     rec["one_by_one_steps_per_s"] = n_steps / dt
                 ch.close()

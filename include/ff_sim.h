@@ -390,9 +390,9 @@ int ff_sim_search(ff_chains_t* chains, const ff_search_t* params, uint32_t n_ste
  * (FF_EWORKSPACE otherwise).  NOT asynchronous: the call allocates its buffers on first use and waits
  * for hip_stream after every round (it copies C integers back to see how far the chains are), so
  * it cannot be captured into a graph.  h_stats (HOST, may be null): rounds taken, proposals
- * simulated ahead, steps made (n_steps * C when the call returns FF_OK). */
+ * simulated ahead, steps made (n_steps * C when the call returns FF_OK), proposals accepted. */
 #define FF_AHEAD_ALWAYS 0x80000000u
-typedef struct { uint64_t rounds, proposals_simulated, steps; } ff_ahead_stats_t;
+typedef struct { uint64_t rounds, proposals_simulated, steps, accepted; } ff_ahead_stats_t;
 int ff_sim_search_ahead(ff_chains_t* chains, const ff_search_t* params, uint32_t n_steps, uint32_t max_ahead,
                         uint64_t* d_trace_ns, void* hip_stream, ff_ahead_stats_t* h_stats);
 

@@ -48,7 +48,7 @@ CHAIN_STATS_DT = np.dtype([("n_steps", "<u8"), ("n_resumed", "<u8"), ("n_events"
 
 
 class ff_ahead_stats_t(C.Structure):
-    _fields_ = [("rounds", C.c_uint64), ("proposals_simulated", C.c_uint64), ("steps", C.c_uint64)]
+    _fields_ = [("rounds", C.c_uint64), ("proposals_simulated", C.c_uint64), ("steps", C.c_uint64), ("accepted", C.c_uint64)]
 
 
 class ff_linktable_t(C.Structure):
@@ -291,10 +291,11 @@ def ff_sim_search(chains, params, n_steps, d_trace_ns, stream=None):
 
 
 def ff_sim_search_ahead(chains, params, n_steps, max_ahead, d_trace_ns, stream=None):
-    """returns (rounds, proposals simulated ahead, steps made)"""
+    """returns (rounds, proposals simulated ahead, steps made, proposals accepted; the last is not counted when the call
+    runs as plain ff_sim_search because no look-ahead fits)"""
     st = ff_ahead_stats_t()
     _check(lib().ff_sim_search_ahead(chains, C.byref(params), n_steps, max_ahead, d_trace_ns, stream, C.byref(st)), "ff_sim_search_ahead")
-    return st.rounds, st.proposals_simulated, st.steps
+    return st.rounds, st.proposals_simulated, st.steps, st.accepted
 
 
 def ff_sim_neighbour_count(chains, d_tuple_ptr, n_tuples, op_begin, op_end):

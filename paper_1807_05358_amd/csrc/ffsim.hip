@@ -695,7 +695,7 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
     const bool always = (max_ahead & FF_AHEAD_ALWAYS) != 0;
     max_ahead &= ~FF_AHEAD_ALWAYS;
     if (!c || !p || (n_steps && !d_trace_ns) || max_ahead < 1) return FF_EINVAL;
-    if (h_stats) *h_stats = ff_ahead_stats_t{0, 0, 0};
+    if (h_stats) *h_stats = ff_ahead_stats_t{0, 0, 0, 0};
     if (n_steps == 0) return c->links_gen != c->sim->links_gen ? FF_EINVAL : FF_OK;
     SearchDev sd{};
     int rc = search_params(c, p, &sd);
@@ -714,7 +714,7 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
         rc = launch_chain_steps(c, nullptr, n_steps, d_trace_ns, st, sd);
         if (rc) return rc;
         if (hipStreamSynchronize(st) != hipSuccess) return FF_EHIP;
-        if (h_stats) *h_stats = ff_ahead_stats_t{1, (uint64_t)n_steps * c->C, (uint64_t)n_steps * c->C};
+        if (h_stats) *h_stats = ff_ahead_stats_t{1, (uint64_t)n_steps * c->C, (uint64_t)n_steps * c->C, 0};
         return FF_OK;
     }
     if (c->ahead_cap < cap) {
@@ -768,7 +768,7 @@ int ff_sim_search_ahead(ff_chains_t* c, const ff_search_t* p, uint32_t n_steps, 
             if (before[k] < n_steps) { active++; advanced += now[k] - before[k]; taken += now[c->C + k] - before[c->C + k]; }
             if (now[k] < n_steps) unfinished++;
         }
-        if (h_stats) { h_stats->rounds++; h_stats->proposals_simulated += K ? (uint64_t)K * active : advanced; h_stats->steps += advanced; }
+        if (h_stats) { h_stats->rounds++; h_stats->proposals_simulated += K ? (uint64_t)K * active : advanced; h_stats->steps += advanced; h_stats->accepted += taken; }
         if (!unfinished) break;
         if (advanced) taken_share = 0.5 * taken_share + 0.5 * (double)taken / (double)advanced;
         stretch_ms = K ? 0.0 : std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_begin).count();

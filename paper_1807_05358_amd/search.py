@@ -9,7 +9,7 @@ way Section 6.2 describes them and calls it until the budget is spent:
   budget without improving on its best strategy;
 * acceptance: the Metropolis rule of Section 6.1 with beta chosen relative to the starting
   time (a proposal that is slower by `accept_scale` times the starting time is accepted with
-  probability 1/e), tabulated for the integer rule the kernel applies.
+  probability 1/e; default 0.25 / number of ops), tabulated for the integer rule the kernel applies.
 """
 from __future__ import annotations
 
@@ -40,11 +40,14 @@ def starting_strategies(ops, machine, max_parts, choices, n_chains, seed):
 
 
 def find_strategy(sim: B.Simulator, ops, machine, max_parts, choices, n_chains=64, steps=256, steps_per_call=64,
-                  accept_scale=0.02, n_buckets=256, seed=1, start=None, ahead=0) -> SearchResult:
+                  accept_scale=None, n_buckets=256, seed=1, start=None, ahead=0) -> SearchResult:
     """runs n_chains independent Markov chains for `steps` steps each and returns the best
     strategy any of them has seen.  `start`: [n_chains][n_ops] starting strategies (default: see
     starting_strategies).  `ahead`: with few chains, let ff_sim_search_ahead simulate up to that many
     proposals per chain side by side (the same chains, step for step; only faster)."""
+    if accept_scale is None:
+        # one op moves the iteration time by about its share of it: the tolerance follows the number of ops
+        accept_scale = 0.25 / max(1, len(ops))
     cfg0 = starting_strategies(ops, machine, max_parts, choices, n_chains, seed) if start is None else np.ascontiguousarray(start, W.CFG_DT)
     n_chains = len(cfg0)
     chains = B.Chains(sim, cfg0)
