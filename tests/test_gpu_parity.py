@@ -598,6 +598,26 @@ def test_costs_keyed_by_degree_tuple(B, config_id, n):
     sim.close()
 
 
+def test_costs_from_the_measurement_cache(B):
+    """cost lists built through the (operation type, output size) cache of Section 5.1 (costcache.tuple_costs) on the
+    Inception-shaped graph: batch and a mutation chain against the oracle with the same lists"""
+    from paper_1807_05358_amd import costcache
+    w = W.workload(2)
+    tc = costcache.tuple_costs(w.ops, w.max_parts, w.choices, costcache.ExeTimeCache(costcache.model_measure))
+    sim = B.Simulator(w.ops, w.edges, w.machine, tc)
+    cfgs = w.strategies(96)
+    want = oracle.simulate_batch(w.ops, w.edges, w.machine, tc, cfgs, n_threads=8)
+    assert (want != oracle.INVALID).all()
+    assert np.array_equal(sim.simulate(cfgs), want)
+    muts = w.mutations(16, 2)
+    ch = B.Chains(sim, cfgs[:2])
+    d = ch.delta(ch.upload_mutations(muts), 16).cpu().numpy().view("<u8")
+    for c in range(2):
+        assert np.array_equal(d[:, c], oracle.simulate_delta_chain(w.ops, w.edges, w.machine, tc, cfgs[c], muts[:, c]))
+    ch.close()
+    sim.close()
+
+
 def test_tuple_cost_argument_errors(B):
     w = W.workload(0)
     ptr, tup, ns = w.tuple_costs()
