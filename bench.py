@@ -501,6 +501,23 @@ def main():
                     ref = oracle.simulate_batch(w4.ops, w4.edges, w4.machine, w4.cost, cand, n_threads=threads)
                     t["bit_exact_on_sampled_proposals"] = bool(np.array_equal(tried.cpu().numpy().view("<u8")[sel, 0], ref))
                 delta.append(t)
+                # with one proposal per wavefront the launch lasts as long as its slowest proposal (one that has to
+                # start from time 0); with several per wavefront, handed out from a counter, the launch follows the
+                # MEAN cost of a proposal, which is where the kept timeline shows
+                M8 = 8192
+                props8 = w4.mutations(n_steps + M8, 1)[n_steps:]
+                d_p8 = ch.upload_mutations(props8)
+                ch.try_mutations(d_p8, 8)
+                torch.cuda.synchronize()
+                a.record()
+                ch.try_mutations(d_p8, M8)
+                b.record()
+                torch.cuda.synchronize()
+                ms8 = a.elapsed_time(b)
+                delta.append({"workload": "configs[4] nmt", "chains": 1, "proposals": M8, "ms": ms8,
+                              "kind": "trial mutations (ff_sim_delta_try), eight times as many as wavefronts fit",
+                              "delta_sims_per_s": M8 / (ms8 * 1e-3),
+                              "against_full_simulations_per_s": (M8 / (ms8 * 1e-3)) / line["value"]})
             ch.close()
         line["delta"] = delta
         # the search loop on the device (ff_sim_search): independent Metropolis chains
