@@ -432,7 +432,8 @@ def main():
         # delta simulation on configs[4]: one chain, and 256 independent chains
         r4, sim4, w4, cfgs4 = results[4]
         delta = []
-        for C, n_steps in ((1, 256), (256, 32)):
+        # (the last: as many chains as the device holds at once -- three per compute unit, by the LDS a chain needs)
+        for C, n_steps in ((1, 256), (256, 32), (768, 8)):
             muts = w4.mutations(n_steps, C)
             ch = binding.Chains(sim4, cfgs4[:C])
             d_m = ch.upload_mutations(muts)
@@ -466,7 +467,7 @@ def main():
                 d["algorithmic_bytes_per_step"] = items * 34.0   # 20 B per task written + read, 14 B per record, as in the byte model
                 d["algorithmic_GBps"] = items * 34.0 * n_steps / (ms * 1e-3) / 1e9
             if not args.no_cpu and C > 1:
-                chains_checked = [0, 31, 64, 100, 127, 200, 254, 255]
+                chains_checked = [0, 31, 64, 100, 127, 200, 254, 255] if C == 256 else [0, 383, 767]
                 ok = True
                 for cc in chains_checked:
                     ref = oracle_chain_steps(w4, cfgs4[cc], muts[:, cc], [n_steps // 2, n_steps - 1], threads)
