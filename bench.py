@@ -433,7 +433,7 @@ def main():
         r4, sim4, w4, cfgs4 = results[4]
         delta = []
         # (the last: as many chains as the device holds at once -- three per compute unit, by the LDS a chain needs)
-        for C, n_steps in ((1, 256), (256, 32), (768, 8)):
+        for C, n_steps in ((1, 256), (256, 32), (768, 32)):
             muts = w4.mutations(n_steps, C)
             ch = binding.Chains(sim4, cfgs4[:C])
             d_m = ch.upload_mutations(muts)
